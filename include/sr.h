@@ -1,0 +1,202 @@
+/*
+ * libsr -- streaming-rollout frame update on one AMD MI355X (gfx950).
+ *
+ * A network is a directed graph whose nodes are layers and whose edges are
+ * transformations (Sec. 3 of "The streaming rollout of deep networks").  A
+ * rollout pattern R gives every edge a bridging bit: R(e) = 1 means the edge
+ * reads its source at frame t-1, R(e) = 0 at frame t (Sec. 3, definition of
+ * rollout pattern and window, Eq. 2).  One frame update computes, for every
+ * node v that has incoming edges,
+ *
+ *     x_v(t) = sigma_v( b_v + sum_{e=(u,v)} f_e(theta_e, x_u(t - R(e))) )     (App. A1.2)
+ *
+ * With R == 1 everywhere (the streaming rollout) all nodes of a frame are
+ * independent and are computed by one launch; otherwise a frame takes F(R)
+ * dependent launches, one per value of the inference tableau (Eq. 5, Eq. 6).
+ * Inference chains windows of size W = 1: the frame just computed is frame 0 of
+ * the next window (Sec. 4, Sec. 5), so the library keeps two copies of every
+ * state and alternates between them.
+ *
+ * General conventions
+ *  - plain C ABI; every call returns an sr_status and never throws or aborts;
+ *    output arguments are written only when SR_OK is returned.
+ *  - "host" pointers are ordinary CPU memory, read during the call only.
+ *    "device" pointers are HIP device memory owned by the caller, which must
+ *    stay valid until the work enqueued by the call has finished on the
+ *    graph's stream.
+ *  - all tensors at the boundary are dense NHWC, [B][H][W][C], in the graph's
+ *    dtype (float for SR_F32, bfloat16 bit patterns for SR_BF16).
+ *  - the library owns the graph object, both copies of every node state, the
+ *    packed weights and its HIP graph objects; sr_graph_destroy frees them.
+ *  - all device work is enqueued on the HIP stream given at creation and is
+ *    asynchronous with respect to the host unless stated otherwise.
+ *  - node and edge ids are 0-based indices into the arrays given at creation;
+ *    nodes need not be listed in any particular order.
+ *  - calls on one graph object must not overlap in time (no internal locking).
+ */
+#ifndef SR_H_
+#define SR_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct sr_graph sr_graph; /* opaque */
+
+typedef enum {
+  SR_OK = 0,
+  SR_ERR_ARG = 1,     /* null pointer, negative size, unknown enum value, R(e) not in {0,1} */
+  SR_ERR_GRAPH = 2,   /* not a network: no edges, bad node id, or a node not reachable from the input set */
+  SR_ERR_ROLLOUT = 3, /* invalid pattern: the edges with R(e)=0 contain a cycle (a self-edge with R=0 is one) */
+  SR_ERR_SHAPE = 4,   /* an edge's result does not have the shape of its target node */
+  SR_ERR_STATE = 5,   /* call order: weights missing, stepping before sr_reset, ... */
+  SR_ERR_OOM = 6,     /* host or device allocation failed */
+  SR_ERR_DEVICE = 7   /* a HIP call failed (no device, launch error); see sr_last_error */
+} sr_status;
+
+typedef enum { SR_F32 = 0, SR_BF16 = 1 } sr_dtype;
+typedef enum { SR_ACT_IDENTITY = 0, SR_ACT_RELU = 1 } sr_act;
+
+typedef enum {
+  SR_EDGE_CONV = 0,     /* cross-correlation kh x kw, stride, zero padding pad, then nearest upsampling by `upsample` */
+  SR_EDGE_DENSE = 1,    /* dense map over the flattened (h,w,c) source; target is 1x1; kh,kw = source H,W */
+  SR_EDGE_GAP_DENSE = 2 /* mean over (h,w) of the source, then a dense map over channels; target is 1x1 */
+} sr_edge_kind;
+
+/* A node (layer): state x_v of shape [B][height][width][channels]; `act` is sigma_v.
+ * Nodes without incoming edges are the network's inputs (Eq. 1); their `act` is ignored. */
+typedef struct {
+  int32_t channels, height, width;
+  int32_t act; /* sr_act */
+} sr_node_desc;
+
+/* An edge (transformation) f_e from node src to node dst (App. A1.2).
+ * conv:  y[b,ho,wo,co] = sum_{i,j,ci} theta[i,j,ci,co] * x[b, ho*stride+i-pad, wo*stride+j-pad, ci]
+ *        (zero outside the source), then y_up[b,h,w,c] = y[b, h/upsample, w/upsample, c].
+ * bridge is R(e): 1 reads the source at frame t-1, 0 at frame t. */
+typedef struct {
+  int32_t src, dst;
+  int32_t kind; /* sr_edge_kind */
+  int32_t kh, kw, stride, pad, upsample;
+  uint8_t bridge;
+} sr_edge_desc;
+
+/* Option keys for sr_graph_configure. */
+typedef enum {
+  SR_OPT_USE_HIPGRAPH = 0,  /* 1 (default): frames are replayed from a captured HIP graph; 0: plain launches */
+  SR_OPT_FORCE_DIRECT = 1,  /* 1: every node is computed by the plain one-thread-per-output kernel (no MFMA); default 0 */
+  SR_OPT_FRAMES_PER_GRAPH = 2 /* number of frames captured into one HIP graph for sr_rollout (default 8, >= 1) */
+} sr_option;
+
+/* ---------------------------------------------------------------------------
+ * Host-only analysis (Sec. 3).  Touches no device.
+ * Validates that (nodes, edges) is a network and that the bridging bits form a
+ * valid rollout pattern, and returns
+ *   levels[v]          (host, n_nodes ints, may be NULL): value of the inference tableau of the
+ *                      size-1 window at (1, v): the update step of a frame at which v is computed;
+ *                      0 for input nodes (Eq. 5)
+ *   inference_factor   (host, may be NULL): F(R) = max_v levels[v] (Eq. 6); 1 iff the pattern is
+ *                      equally model-parallel to the streaming rollout (Theorem 1)
+ * Errors: SR_ERR_ARG, SR_ERR_GRAPH, SR_ERR_ROLLOUT.  Shapes are not checked here
+ * (n_nodes is enough; node descriptors are not needed). */
+sr_status sr_analyze(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
+                     int32_t* levels, int32_t* inference_factor);
+
+/* Number of valid rollout patterns of a network by exhaustive enumeration (Lemma 1
+ * bounds this number); n_edges <= 24.  The bridge fields of `edges` are ignored.
+ * count (host) receives the number.  Errors: SR_ERR_ARG, SR_ERR_GRAPH. */
+sr_status sr_count_valid_patterns(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
+                                  uint64_t* count);
+
+/* ---------------------------------------------------------------------------
+ * Create the device-side representation of a network and its rollout pattern
+ * (Sec. 3: network, rollout pattern; App. A1.2: node and edge maps).
+ *   nodes, edges   host arrays, copied
+ *   batch          B >= 1
+ *   dtype          storage/arithmetic type: SR_F32 (float everywhere) or SR_BF16 (states and
+ *                  weights bfloat16, products accumulated in float, bias float, result rounded to
+ *                  nearest-even bfloat16 after sigma)
+ *   hip_stream     a hipStream_t (NULL = the default stream); all work goes there
+ *   out            receives the graph handle
+ * Allocates both state copies (zero-filled), biases (zero) and weight storage on the current
+ * device.  Errors: SR_ERR_ARG, SR_ERR_GRAPH, SR_ERR_ROLLOUT, SR_ERR_SHAPE (checked in this order,
+ * all before any device call), SR_ERR_OOM, SR_ERR_DEVICE. */
+sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes,
+                          const sr_edge_desc* edges, int32_t n_edges,
+                          int32_t batch, sr_dtype dtype, void* hip_stream, sr_graph** out);
+
+/* theta_e of one edge, host float array [kh][kw][Cin][Cout] (dense: [Hsrc][Wsrc][Cin][Cout];
+ * GAP+dense: [Cin][Cout]); count must equal the product.  The library rounds to the graph's dtype
+ * (nearest even) and repacks; synchronous with respect to the host copy. Every edge needs weights
+ * before the first frame.  Errors: SR_ERR_ARG, SR_ERR_OOM, SR_ERR_DEVICE. */
+sr_status sr_graph_set_weights(sr_graph* g, int32_t edge, const float* host_w, size_t count);
+
+/* Channel-wise bias b_v of a node, host float [C]; default 0; kept in float. */
+sr_status sr_graph_set_bias(sr_graph* g, int32_t node, const float* host_b, size_t count);
+
+/* Options (see sr_option); must be called before the first sr_reset. */
+sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value);
+
+/* Inference factor and tableau of the graph's pattern (as sr_analyze), plus the number of
+ * kernel launches one frame takes (launches_per_frame, may be NULL). */
+sr_status sr_graph_info(const sr_graph* g, int32_t* inference_factor, int32_t* levels,
+                        int32_t* launches_per_frame);
+
+/* Frame 0 (initial state of Sec. 3; zero initial state per App. A2, training details):
+ * every node with incoming edges is set to zero; input node i (i-th node without incoming
+ * edges, in node order) is set to input_frame0[i] (device, NHWC, graph dtype), or to zero if that
+ * pointer or the whole array is NULL.  The frame counter becomes 0. */
+sr_status sr_reset(sr_graph* g, const void* const* input_frame0);
+
+/* Advance one frame (one window of size 1 chained to the previous one, Sec. 4):
+ * inputs_t[i] (device, NHWC, graph dtype) is the state of the i-th input node at the new frame t;
+ * every other node is updated by the node map above.  Asynchronous.
+ * Errors: SR_ERR_ARG, SR_ERR_STATE (no sr_reset yet, weights missing), SR_ERR_DEVICE. */
+sr_status sr_frame_step(sr_graph* g, const void* const* inputs_t);
+
+/* sr_reset(frame 0) followed by T calls of sr_frame_step(frame t), t = 1..T, without returning to
+ * the host in between.
+ *   inputs[i]   device pointer to [T+1][B][H][W][C] of the i-th input node, frame 0 first
+ *   out_node    node whose state is recorded after every frame (ignored if outputs is NULL)
+ *   outputs     device [T][B][H][W][C] of out_node (frames 1..T), or NULL
+ * Asynchronous.  Errors as sr_frame_step. */
+sr_status sr_rollout(sr_graph* g, const void* const* inputs, int32_t T, int32_t out_node, void* outputs);
+
+/* Copy the current frame's state of a node to / from dense NHWC device memory of `bytes` bytes
+ * (must equal B*H*W*C*sizeof(dtype)); enqueued on the graph's stream.  Together with the frame
+ * counter these states are all the memory the stream has (Sec. 5), so get/set of every node is a
+ * checkpoint.  sr_set_state on an input node is overwritten by the next frame's input. */
+sr_status sr_get_state(const sr_graph* g, int32_t node, void* dst_device, size_t bytes);
+sr_status sr_set_state(sr_graph* g, int32_t node, const void* src_device, size_t bytes);
+
+/* Number of frames computed since the last sr_reset (host value). */
+sr_status sr_frame_index(const sr_graph* g, int64_t* frame);
+
+/* Run one frame with plain launches, bracketing every kernel of the frame with HIP events on
+ * the graph's stream, and wait for it.  kernel_ms (host, capacity `cap`) receives the
+ * duration of each launch in launch order, kernel_kind (host, may be NULL) a tag per launch:
+ * 0 input staging, 1 MFMA convolution tiles, 2 direct (one thread per output) nodes, 3 GAP+dense
+ * head, 4 bookkeeping; n_launches the number written.  Synchronous. */
+sr_status sr_frame_step_timed(sr_graph* g, const void* const* inputs_t, float* kernel_ms,
+                              int32_t* kernel_kind, int32_t cap, int32_t* n_launches);
+
+/* Work of one frame as the library counts it: nominal multiply-adds * 2 over all edges
+ * (padding taps counted, channel padding not), number of MFMA tiles, and bytes of both state
+ * copies plus packed weights resident on the device.  Any pointer may be NULL. */
+sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfma_tiles,
+                        int64_t* device_bytes);
+
+void sr_graph_destroy(sr_graph* g);
+
+const char* sr_status_str(sr_status s);
+/* Human-readable detail of the last error on this graph (or of the last failed
+ * sr_graph_create / sr_analyze on this thread if g is NULL). */
+const char* sr_last_error(const sr_graph* g);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SR_H_ */

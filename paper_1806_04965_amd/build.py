@@ -1,0 +1,35 @@
+"""Build libsr.so (the C-ABI library) for gfx950 with hipcc, in-tree."""
+from __future__ import annotations
+
+import os
+import subprocess
+import sys
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+CSRC = os.path.join(HERE, "csrc")
+LIB = os.path.join(HERE, "libsr.so")
+SOURCES = ["sr_kernels.hip", "sr_host.cpp"]
+
+
+def build(verbose: bool = False) -> str:
+    """Compile every source of the library; returns the path of the shared object."""
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [hipcc, "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+           "-Wno-unused-value",
+           # packed fp32 arithmetic stays off (plain float code only)
+           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           "-I", CSRC, "-I", os.path.join(HERE, "..", "include")]
+    cmd += [os.path.join(CSRC, s) for s in SOURCES]
+    cmd += ["-o", LIB + ".tmp"]
+    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    out = "\n".join(l for l in res.stdout.splitlines() if "is not a recognized feature" not in l)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + out)
+    os.replace(LIB + ".tmp", LIB)
+    if verbose and out.strip():
+        print(out, file=sys.stderr)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build(verbose=True))

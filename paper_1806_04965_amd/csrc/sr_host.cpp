@@ -1,0 +1,1043 @@
+// Host side of libsr: the C ABI of include/sr.h, rollout analysis (Sec. 3), the frame planner
+// (levels, tile work-lists, descriptor tables, weight packing) and the HIP-graph frame loop.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "../../include/sr.h"
+#include "sr_internal.h"
+
+namespace {
+
+thread_local std::string g_last_error;
+
+// ---------------------------------------------------------------------------
+// rollout analysis (host only)
+// ---------------------------------------------------------------------------
+struct Analysis {
+  std::vector<int> is_input;   // node has no incoming edge (Eq. 1)
+  std::vector<int> level;      // tableau value of (1, v) in the size-1 window (Eq. 5)
+  int factor = 0;              // F(R), Eq. 6
+};
+
+sr_status fail(std::string* err, sr_status st, const std::string& msg) {
+  if (err) *err = msg;
+  g_last_error = msg;
+  return st;
+}
+
+// Definition of a network (Sec. 3): at least one edge, valid ids, every node reachable from I_N.
+sr_status check_network(int n_nodes, const sr_edge_desc* edges, int n_edges, std::vector<int>* is_input,
+                        std::string* err) {
+  if (n_nodes <= 0 || n_edges < 0 || (n_edges > 0 && !edges)) return fail(err, SR_ERR_ARG, "bad node/edge arrays");
+  if (n_edges == 0) return fail(err, SR_ERR_GRAPH, "a network needs at least one edge");
+  for (int e = 0; e < n_edges; ++e) {
+    if (edges[e].src < 0 || edges[e].src >= n_nodes || edges[e].dst < 0 || edges[e].dst >= n_nodes)
+      return fail(err, SR_ERR_GRAPH, "edge " + std::to_string(e) + " names a node that does not exist");
+  }
+  is_input->assign(n_nodes, 1);
+  for (int e = 0; e < n_edges; ++e) (*is_input)[edges[e].dst] = 0;
+  std::vector<int> reached(*is_input), stack;
+  for (int v = 0; v < n_nodes; ++v)
+    if (reached[v]) stack.push_back(v);
+  while (!stack.empty()) {
+    int u = stack.back();
+    stack.pop_back();
+    for (int e = 0; e < n_edges; ++e)
+      if (edges[e].src == u && !reached[edges[e].dst]) {
+        reached[edges[e].dst] = 1;
+        stack.push_back(edges[e].dst);
+      }
+  }
+  for (int v = 0; v < n_nodes; ++v)
+    if (!reached[v]) return fail(err, SR_ERR_GRAPH, "node " + std::to_string(v) + " is not reachable from an input node");
+  return SR_OK;
+}
+
+// Validity (Sec. 3): rollout windows are acyclic iff the edges that stay inside a frame
+// (R = 0) contain no cycle, since no window edge points backwards in time.  Levels: longest
+// chain of R = 0 edges into v inside frame 1, where a chain may start with any edge whose
+// source is already known (an input node, or a frame-0 node reached over an R = 1 edge).
+sr_status analyse_pattern(int n_nodes, const sr_edge_desc* edges, int n_edges, const uint8_t* bits,
+                          const std::vector<int>& is_input, Analysis* out, std::string* err) {
+  std::vector<int> indeg(n_nodes, 0);
+  for (int e = 0; e < n_edges; ++e) {
+    if (bits[e] > 1) return fail(err, SR_ERR_ARG, "R(e) must be 0 or 1 (edge " + std::to_string(e) + ")");
+    if (bits[e] == 0) indeg[edges[e].dst]++;
+  }
+  // Kahn's algorithm over the R = 0 sub-graph, carrying the longest-path value
+  std::vector<int> level(n_nodes, 0), order;
+  for (int v = 0; v < n_nodes; ++v) {
+    level[v] = is_input[v] ? 0 : 1;   // every non-input node has an incoming edge: path length >= 1
+    if (indeg[v] == 0) order.push_back(v);
+  }
+  for (size_t i = 0; i < order.size(); ++i) {
+    int u = order[i];
+    for (int e = 0; e < n_edges; ++e) {
+      if (bits[e] != 0 || edges[e].src != u) continue;
+      int v = edges[e].dst;
+      level[v] = std::max(level[v], level[u] + 1);
+      if (--indeg[v] == 0) order.push_back(v);
+    }
+  }
+  if ((int)order.size() != n_nodes)
+    return fail(err, SR_ERR_ROLLOUT, "the edges with R(e)=0 contain a cycle: rollout windows would be cyclic");
+  out->is_input = is_input;
+  out->level = level;
+  out->factor = *std::max_element(level.begin(), level.end());
+  return SR_OK;
+}
+
+inline int conv_out(int size, int k, int stride, int pad) { return (size + 2 * pad - k) / stride + 1; }
+
+inline uint16_t f2bf(float f) {
+  uint32_t u;
+  std::memcpy(&u, &f, 4);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+inline float bf2f(uint16_t h) {
+  uint32_t u = ((uint32_t)h) << 16;
+  float f;
+  std::memcpy(&f, &u, 4);
+  return f;
+}
+
+inline uint32_t magic_for(uint32_t d) { return (uint32_t)((((uint64_t)1 << 32) + d - 1) / d); }
+// largest x for which umulhi(x, magic_for(d)) == x / d is guaranteed
+inline uint64_t magic_range(uint32_t d) {
+  uint64_t m = magic_for(d);
+  uint64_t e = m * d - ((uint64_t)1 << 32);   // 0 <= e < d
+  if (e == 0) return ((uint64_t)1 << 32) - 1;
+  return (((uint64_t)1 << 32) / e) - 1;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// the graph object
+// ---------------------------------------------------------------------------
+struct NodeRt {
+  sr_node_desc d{};
+  int Cp = 0;                 // channel pitch of the stored state
+  size_t state_bytes = 0;
+  void* state[2] = {nullptr, nullptr};
+  float* bias_dev = nullptr;  // [Cp] float
+  std::vector<float> bias;
+  int kind = 0;               // 0 input, 1 mfma, 2 direct, 3 head
+  int input_slot = -1;
+};
+
+struct EdgeRt {
+  sr_edge_desc d{};
+  int kh = 0, kw = 0;              // effective kernel (dense: source H, W; GAP: 1)
+  size_t w_count = 0;
+  bool has_w = false;
+  std::vector<float> w_host;       // rounded to the graph dtype, [kh][kw][Cin][Cout]
+  float* w_dev = nullptr;          // same, float, for the direct and head kernels
+  void* wpk_dev = nullptr;         // packed bf16 for the MFMA kernel
+};
+
+struct LevelPlan {
+  int tile_begin = 0, n_tiles = 0;
+  int block_begin = 0, n_blocks = 0;
+  int head_begin = 0, n_heads = 0, head_max_splits = 1, head_max_cin = 0;
+};
+
+struct sr_graph {
+  int n_nodes = 0, n_edges = 0, batch = 0;
+  sr_dtype dtype = SR_F32;
+  hipStream_t stream = nullptr;
+  std::vector<NodeRt> nodes;
+  std::vector<EdgeRt> edges;
+  Analysis an;
+  std::vector<int> inputs;    // node ids of the input set, in node order
+  std::string err;
+
+  // options
+  bool use_hipgraph = true, force_direct = false;
+  int frames_per_graph = 8;
+
+  // plan
+  bool finalized = false, was_reset = false;
+  int64_t host_frame = 0;
+  std::vector<LevelPlan> levels;
+  std::vector<void*> dev_allocs;     // everything to free
+  SrCtx* ctx = nullptr;
+  SrStageNode* stage_nodes = nullptr;
+  int stage_max_elems = 0;
+  SrDirectNode* d_nodes = nullptr;
+  SrDirectEdge* d_edges = nullptr;
+  SrDirectBlock* d_blocks = nullptr;
+  SrMfmaNode* m_nodes = nullptr;
+  SrMfmaEdge* m_edges = nullptr;
+  SrMfmaTile* m_tiles = nullptr;
+  SrHead* heads = nullptr;
+  int lds_bytes = 0;
+  int64_t n_mfma_tiles = 0;
+  double flops = 0;
+  int64_t device_bytes = 0;
+  int launches_per_frame = 0;
+
+  // rollout output recording (set per call)
+  int rec_node = -1;
+
+  hipGraph_t graph1 = nullptr, graphN = nullptr;
+  hipGraphExec_t exec1 = nullptr, execN = nullptr;
+  int graph_rec_node = -2;   // out_node the captured graphs record
+};
+
+namespace {
+
+sr_status gfail(sr_graph* g, sr_status st, const std::string& msg) {
+  if (g) g->err = msg;
+  g_last_error = msg;
+  return st;
+}
+
+#define SR_HIP(g, call)                                                                              \
+  do {                                                                                               \
+    hipError_t e_ = (call);                                                                          \
+    if (e_ != hipSuccess)                                                                            \
+      return gfail((g), e_ == hipErrorOutOfMemory ? SR_ERR_OOM : SR_ERR_DEVICE,                      \
+                   std::string(#call) + ": " + hipGetErrorString(e_));                               \
+  } while (0)
+
+size_t elem_size(const sr_graph* g) { return g->dtype == SR_BF16 ? 2 : 4; }
+
+sr_status dev_alloc(sr_graph* g, void** p, size_t bytes) {
+  *p = nullptr;
+  if (bytes == 0) bytes = 16;
+  SR_HIP(g, hipMalloc(p, bytes));
+  g->dev_allocs.push_back(*p);
+  g->device_bytes += (int64_t)bytes;
+  return SR_OK;
+}
+
+template <typename T>
+sr_status upload(sr_graph* g, T** dev, const std::vector<T>& host) {
+  void* p = nullptr;
+  sr_status st = dev_alloc(g, &p, host.size() * sizeof(T));
+  if (st != SR_OK) return st;
+  if (!host.empty()) SR_HIP(g, hipMemcpy(p, host.data(), host.size() * sizeof(T), hipMemcpyHostToDevice));
+  *dev = (T*)p;
+  return SR_OK;
+}
+
+// shape of f_e's result (App. A1.2: must be summable at the target)
+void edge_result_shape(const sr_graph* g, const EdgeRt& e, int* h, int* w) {
+  const sr_node_desc& s = g->nodes[e.d.src].d;
+  if (e.d.kind == SR_EDGE_CONV) {
+    *h = conv_out(s.height, e.d.kh, e.d.stride, e.d.pad) * e.d.upsample;
+    *w = conv_out(s.width, e.d.kw, e.d.stride, e.d.pad) * e.d.upsample;
+  } else {
+    *h = 1;
+    *w = 1;
+  }
+}
+
+// ---------------------------------------------------------------------------
+// planner
+// ---------------------------------------------------------------------------
+struct MfmaChoice {
+  int waves_m, waves_n, wn_tiles;
+};
+
+bool mfma_eligible(const sr_graph* g, int v) {
+  if (g->dtype != SR_BF16 || g->force_direct) return false;
+  const NodeRt& n = g->nodes[v];
+  if (n.d.channels % 32 != 0) return false;
+  bool any = false;
+  for (const EdgeRt& e : g->edges) {
+    if (e.d.dst != v) continue;
+    any = true;
+    if (e.d.kind != SR_EDGE_CONV) return false;
+    if (e.d.stride != 1 && e.d.stride != 2 && e.d.stride != 4) return false;
+  }
+  return any;
+}
+
+// Patch geometry of one (node tiling, edge): maximum number of LDS slots over all tiles.
+int64_t max_patch_slots(const sr_graph* g, int v, const EdgeRt& e, int BM) {
+  const sr_node_desc& dn = g->nodes[v].d;
+  const sr_node_desc& sn = g->nodes[e.d.src].d;
+  const int Ho = dn.height, Wo = dn.width, HoWo = Ho * Wo;
+  const int64_t M = (int64_t)g->batch * HoWo;
+  const int s = e.d.stride, up = e.d.upsample;
+  const int PH = sn.height + 2 * e.d.pad, PW = sn.width + 2 * e.d.pad;
+  const int PWs = (PW + s - 1) / s, RP = s * PWs;
+  (void)PW;
+  int64_t worst = 0;
+  for (int64_t m0 = 0; m0 < M; m0 += BM) {
+    int64_t m1 = std::min<int64_t>(m0 + BM, M) - 1;
+    int64_t b0 = m0 / HoWo, oy0 = (m0 % HoWo) / Wo;
+    int64_t b1 = m1 / HoWo, oy1 = (m1 % HoWo) / Wo;
+    int64_t Q0 = b0 * PH + (oy0 / up) * s;
+    int64_t Q1 = b1 * PH + (oy1 / up) * s + e.d.kh - 1;
+    worst = std::max(worst, (Q1 - Q0 + 1) * RP);
+  }
+  return worst;
+}
+
+sr_status finalize(sr_graph* g) {
+  if (g->finalized) return SR_OK;
+  for (int e = 0; e < g->n_edges; ++e)
+    if (!g->edges[e].has_w) return gfail(g, SR_ERR_STATE, "edge " + std::to_string(e) + " has no weights");
+  const int B = g->batch;
+  const bool bf16 = g->dtype == SR_BF16;
+  const int F = g->an.factor;
+
+  // classify nodes
+  for (int v = 0; v < g->n_nodes; ++v) {
+    NodeRt& n = g->nodes[v];
+    if (g->an.is_input[v]) { n.kind = 0; continue; }
+    int n_in = 0, n_gap = 0;
+    for (const EdgeRt& e : g->edges)
+      if (e.d.dst == v) { ++n_in; n_gap += (e.d.kind == SR_EDGE_GAP_DENSE); }
+    if (mfma_eligible(g, v)) n.kind = 1;
+    else if (n_in == 1 && n_gap == 1 && !g->force_direct) n.kind = 3;
+    else n.kind = 2;
+  }
+
+  std::vector<SrStageNode> stage;
+  for (size_t i = 0; i < g->inputs.size(); ++i) {
+    NodeRt& n = g->nodes[g->inputs[i]];
+    SrStageNode s{};
+    s.state[0] = n.state[0];
+    s.state[1] = n.state[1];
+    s.elems_px = B * n.d.height * n.d.width;
+    s.C = n.d.channels;
+    s.Cp = n.Cp;
+    s.input_slot = (int)i;
+    stage.push_back(s);
+    g->stage_max_elems = std::max(g->stage_max_elems, s.elems_px * s.Cp);
+  }
+
+  std::vector<SrDirectNode> dn;
+  std::vector<SrDirectEdge> de;
+  std::vector<SrDirectBlock> db;
+  std::vector<SrMfmaNode> mn;
+  std::vector<SrMfmaEdge> me;
+  std::vector<SrMfmaTile> mt;
+  std::vector<SrHead> hd;
+  g->levels.assign(F + 1, LevelPlan());
+  const int lds_cap = sr_mfma_max_lds_bytes();
+  g->lds_bytes = 0;
+  g->flops = 0;
+
+  for (const EdgeRt& e : g->edges) {
+    const sr_node_desc& s = g->nodes[e.d.src].d;
+    const sr_node_desc& d = g->nodes[e.d.dst].d;
+    double macs;
+    if (e.d.kind == SR_EDGE_CONV)
+      macs = (double)(d.height / e.d.upsample) * (d.width / e.d.upsample) * d.channels * s.channels * e.d.kh * e.d.kw;
+    else if (e.d.kind == SR_EDGE_DENSE)
+      macs = (double)s.height * s.width * s.channels * d.channels;
+    else
+      macs = (double)s.channels * d.channels;
+    g->flops += 2.0 * B * macs;
+  }
+
+  for (int L = 1; L <= F; ++L) {
+    LevelPlan& lp = g->levels[L];
+    lp.tile_begin = (int)mt.size();
+    lp.block_begin = (int)db.size();
+    lp.head_begin = (int)hd.size();
+    struct TileGroup { int node_index; double cost; std::vector<SrMfmaTile> tiles; };
+    std::vector<TileGroup> groups;
+
+    for (int v = 0; v < g->n_nodes; ++v) {
+      NodeRt& n = g->nodes[v];
+      if (g->an.level[v] != L || n.kind == 0) continue;
+      if (n.kind == 1) {
+        // ---- MFMA node: tile shape, per-edge staging depth, tiles
+        const int Cout = n.d.channels;
+        const int wn_tiles = (Cout % 64 == 0) ? 2 : 1;
+        const int cw = 32 * wn_tiles;
+        int waves_n = 1;
+        for (int cand : {4, 2, 1})
+          if (Cout % (cw * cand) == 0) { waves_n = cand; break; }
+        const int waves_m = 4 / waves_n;
+        const int64_t M = (int64_t)B * n.d.height * n.d.width;
+        const int BM = 128 * waves_m, BN = cw * waves_n;
+        SrMfmaNode node{};
+        node.out[0] = n.state[0];
+        node.out[1] = n.state[1];
+        node.bias = n.bias_dev;
+        node.M = (int)M;
+        node.Ho = n.d.height;
+        node.Wo = n.d.width;
+        node.Cout = Cout;
+        node.Cp = n.Cp;
+        node.act = n.d.act;
+        node.edge_begin = (int)me.size();
+        node.waves_m = waves_m;
+        node.waves_n = waves_n;
+        node.wn_tiles = wn_tiles;
+        double ksum = 0;
+        bool ok = true;
+        for (EdgeRt& e : g->edges) {
+          if (e.d.dst != v) continue;
+          const NodeRt& sn = g->nodes[e.d.src];
+          SrMfmaEdge m{};
+          m.src[0] = sn.state[0];
+          m.src[1] = sn.state[1];
+          m.wpk = e.wpk_dev;
+          m.bridge = e.d.bridge;
+          m.Hs = sn.d.height;
+          m.Ws = sn.d.width;
+          m.Csp = sn.Cp;
+          m.kh = e.d.kh;
+          m.kw = e.d.kw;
+          m.stride = e.d.stride;
+          m.pad = e.d.pad;
+          m.up = e.d.upsample;
+          m.PH = m.Hs + 2 * m.pad;
+          m.PW = m.Ws + 2 * m.pad;
+          m.PWs = (m.PW + m.stride - 1) / m.stride;
+          m.RP = m.stride * m.PWs;
+          m.magicPW = magic_for((uint32_t)m.PW);
+          m.magicPH = magic_for((uint32_t)m.PH);
+          m.wstride8 = (Cout / 32) * 64;
+          const int64_t slots = max_patch_slots(g, v, e, BM);
+          int KC = 0;
+          for (int cand : {64, 32, 16})
+            if (sn.Cp % cand == 0 && slots * (cand * 2 + 16) <= lds_cap) { KC = cand; break; }
+          // the staging loop divides slot indices by PW and padded row indices by PH with a
+          // multiply-high; make sure both stay inside the range where that is exact
+          if (KC == 0 || (uint64_t)slots > magic_range((uint32_t)m.PW) ||
+              (uint64_t)B * m.PH > magic_range((uint32_t)m.PH) || slots * (KC * 2 + 16) > (int64_t)1 << 30) {
+            ok = false;
+            break;
+          }
+          m.KC = KC;
+          m.nchunk = sn.Cp / KC;
+          m.SP = KC * 2 + 16;
+          g->lds_bytes = std::max<int>(g->lds_bytes, (int)(slots * m.SP));
+          ksum += (double)sn.Cp * m.kh * m.kw;
+          me.push_back(m);
+        }
+        if (!ok) {   // patch does not fit: this node goes the direct way
+          me.resize(node.edge_begin);
+          n.kind = 2;
+        } else {
+          node.edge_count = (int)me.size() - node.edge_begin;
+          const int node_index = (int)mn.size();
+          mn.push_back(node);
+          TileGroup grp;
+          grp.node_index = node_index;
+          grp.cost = ksum * BM * BN;
+          const int n_mt = (int)((M + BM - 1) / BM), n_nt = Cout / BN;
+          // order: groups of 8 consecutive pixel tiles (one per XCD when workgroups are dealt
+          // round-robin), all channel tiles of a group back to back, so that the channel tiles of
+          // one pixel tile land on the same XCD and share its L2 copy of the source patch
+          for (int mg = 0; mg < n_mt; mg += 8)
+            for (int nt = 0; nt < n_nt; ++nt)
+              for (int mi = mg; mi < std::min(mg + 8, n_mt); ++mi) {
+                SrMfmaTile t{};
+                t.node = node_index;
+                t.m0 = mi * BM;
+                t.n0 = nt * BN;
+                grp.tiles.push_back(t);
+              }
+          groups.push_back(std::move(grp));
+        }
+      }
+      if (n.kind == 3) {
+        SrHead h{};
+        for (const EdgeRt& e : g->edges) {
+          if (e.d.dst != v) continue;
+          const NodeRt& sn = g->nodes[e.d.src];
+          h.src[0] = sn.state[0];
+          h.src[1] = sn.state[1];
+          h.w = e.w_dev;
+          h.bridge = e.d.bridge;
+          h.HW = sn.d.height * sn.d.width;
+          h.Cin = sn.d.channels;
+          h.Csp = sn.Cp;
+        }
+        h.out[0] = n.state[0];
+        h.out[1] = n.state[1];
+        h.bias = n.bias_dev;
+        h.act = n.d.act;
+        h.B = B;
+        h.Cout = n.d.channels;
+        h.Cp = n.Cp;
+        h.splits = std::max(1, std::min(64, (h.HW + 63) / 64));
+        h.bf16 = bf16;
+        void* part = nullptr;
+        sr_status st = dev_alloc(g, &part, (size_t)B * h.splits * h.Cin * sizeof(float));
+        if (st != SR_OK) return st;
+        h.partial = (float*)part;
+        hd.push_back(h);
+        lp.head_max_splits = std::max(lp.head_max_splits, h.splits);
+        lp.head_max_cin = std::max(lp.head_max_cin, h.Cin);
+      }
+      if (n.kind == 2) {
+        SrDirectNode node{};
+        node.out[0] = n.state[0];
+        node.out[1] = n.state[1];
+        node.bias = n.bias_dev;
+        node.H = n.d.height;
+        node.W = n.d.width;
+        node.C = n.d.channels;
+        node.Cp = n.Cp;
+        node.act = n.d.act;
+        node.edge_begin = (int)de.size();
+        for (const EdgeRt& e : g->edges) {
+          if (e.d.dst != v) continue;
+          const NodeRt& sn = g->nodes[e.d.src];
+          SrDirectEdge d{};
+          d.src[0] = sn.state[0];
+          d.src[1] = sn.state[1];
+          d.w = e.w_dev;
+          d.bridge = e.d.bridge;
+          d.kind = (e.d.kind == SR_EDGE_GAP_DENSE) ? 2 : 0;
+          d.Hs = sn.d.height;
+          d.Ws = sn.d.width;
+          d.Cin = sn.d.channels;
+          d.Csp = sn.Cp;
+          d.kh = e.kh;
+          d.kw = e.kw;
+          d.stride = (e.d.kind == SR_EDGE_CONV) ? e.d.stride : 1;
+          d.pad = (e.d.kind == SR_EDGE_CONV) ? e.d.pad : 0;
+          d.up = (e.d.kind == SR_EDGE_CONV) ? e.d.upsample : 1;
+          de.push_back(d);
+        }
+        node.edge_count = (int)de.size() - node.edge_begin;
+        const int node_index = (int)dn.size();
+        dn.push_back(node);
+        const int64_t total = (int64_t)B * node.H * node.W * node.C;
+        for (int64_t first = 0; first < total; first += 256) {
+          SrDirectBlock blk{node_index, (int)first};
+          db.push_back(blk);
+        }
+      }
+    }
+    // longest tiles first, so that the tail of the launch is made of short ones
+    std::stable_sort(groups.begin(), groups.end(),
+                     [](const TileGroup& a, const TileGroup& b) { return a.cost > b.cost; });
+    for (const TileGroup& grp : groups) mt.insert(mt.end(), grp.tiles.begin(), grp.tiles.end());
+    lp.n_tiles = (int)mt.size() - lp.tile_begin;
+    lp.n_blocks = (int)db.size() - lp.block_begin;
+    lp.n_heads = (int)hd.size() - lp.head_begin;
+  }
+  g->n_mfma_tiles = (int64_t)mt.size();
+
+  sr_status st;
+  if ((st = upload(g, &g->stage_nodes, stage)) != SR_OK) return st;
+  if ((st = upload(g, &g->d_nodes, dn)) != SR_OK) return st;
+  if ((st = upload(g, &g->d_edges, de)) != SR_OK) return st;
+  if ((st = upload(g, &g->d_blocks, db)) != SR_OK) return st;
+  if ((st = upload(g, &g->m_nodes, mn)) != SR_OK) return st;
+  if ((st = upload(g, &g->m_edges, me)) != SR_OK) return st;
+  if ((st = upload(g, &g->m_tiles, mt)) != SR_OK) return st;
+  if ((st = upload(g, &g->heads, hd)) != SR_OK) return st;
+
+  int launches = 1;   // input staging
+  for (int L = 1; L <= F; ++L) {
+    const LevelPlan& lp = g->levels[L];
+    launches += (lp.n_tiles > 0) + (lp.n_blocks > 0) + 2 * (lp.n_heads > 0);
+  }
+  g->launches_per_frame = launches + 1;   // + frame counter
+  g->finalized = true;
+  return SR_OK;
+}
+
+// Enqueue the kernels of one frame.  If `times` is given, every launch is bracketed by events.
+struct FrameTimer {
+  std::vector<hipEvent_t> ev;
+  std::vector<int> kind;
+};
+
+sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
+  hipStream_t s = g->stream;
+  const int bf16 = g->dtype == SR_BF16;
+  auto mark = [&](int kind) -> hipError_t {
+    if (!ft) return hipSuccess;
+    hipEvent_t e;
+    hipError_t r = hipEventCreate(&e);
+    if (r != hipSuccess) return r;
+    r = hipEventRecord(e, s);
+    ft->ev.push_back(e);
+    ft->kind.push_back(kind);
+    return r;
+  };
+  SR_HIP(g, mark(0));
+  SR_HIP(g, sr_launch_stage_inputs(s, g->ctx, g->stage_nodes, (int)g->inputs.size(), g->stage_max_elems, bf16));
+  for (int L = 1; L <= g->an.factor; ++L) {
+    const LevelPlan& lp = g->levels[L];
+    if (lp.n_tiles > 0) {
+      SR_HIP(g, mark(1));
+      SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes));
+    }
+    if (lp.n_blocks > 0) {
+      SR_HIP(g, mark(2));
+      SR_HIP(g, sr_launch_direct(s, g->ctx, g->d_nodes, g->d_edges, g->d_blocks + lp.block_begin, lp.n_blocks, bf16, g->batch));
+    }
+    if (lp.n_heads > 0) {
+      SR_HIP(g, mark(3));
+      SR_HIP(g, sr_launch_head(s, g->ctx, g->heads + lp.head_begin, lp.n_heads, g->batch, lp.head_max_splits,
+                               lp.head_max_cin, bf16));
+    }
+  }
+  SR_HIP(g, mark(4));
+  if (record && g->rec_node >= 0) {
+    const NodeRt& n = g->nodes[g->rec_node];
+    SR_HIP(g, sr_launch_record_output(s, g->ctx, n.state[0], n.state[1], g->batch * n.d.height * n.d.width,
+                                      n.d.channels, n.Cp, bf16));
+  }
+  SR_HIP(g, sr_launch_tick(s, g->ctx));
+  SR_HIP(g, mark(-1));
+  return SR_OK;
+}
+
+void drop_graphs(sr_graph* g) {
+  if (g->exec1) hipGraphExecDestroy(g->exec1);
+  if (g->execN) hipGraphExecDestroy(g->execN);
+  if (g->graph1) hipGraphDestroy(g->graph1);
+  if (g->graphN) hipGraphDestroy(g->graphN);
+  g->exec1 = g->execN = nullptr;
+  g->graph1 = g->graphN = nullptr;
+  g->graph_rec_node = -2;
+}
+
+sr_status capture(sr_graph* g, int frames, hipGraph_t* graph, hipGraphExec_t* exec) {
+  SR_HIP(g, hipStreamBeginCapture(g->stream, hipStreamCaptureModeThreadLocal));
+  sr_status st = SR_OK;
+  for (int f = 0; f < frames && st == SR_OK; ++f) st = enqueue_frame(g, true, nullptr);
+  hipError_t e = hipStreamEndCapture(g->stream, graph);
+  if (st != SR_OK) return st;
+  SR_HIP(g, e);
+  SR_HIP(g, hipGraphInstantiate(exec, *graph, nullptr, nullptr, 0));
+  return SR_OK;
+}
+
+sr_status ensure_graphs(sr_graph* g) {
+  if (g->exec1 && g->graph_rec_node == g->rec_node) return SR_OK;
+  drop_graphs(g);
+  sr_status st = capture(g, 1, &g->graph1, &g->exec1);
+  if (st != SR_OK) return st;
+  if (g->frames_per_graph > 1) {
+    st = capture(g, g->frames_per_graph, &g->graphN, &g->execN);
+    if (st != SR_OK) return st;
+  }
+  g->graph_rec_node = g->rec_node;
+  return SR_OK;
+}
+
+sr_status run_frames(sr_graph* g, int64_t frames) {
+  if (!g->use_hipgraph) {
+    for (int64_t f = 0; f < frames; ++f) {
+      sr_status st = enqueue_frame(g, true, nullptr);
+      if (st != SR_OK) return st;
+    }
+  } else {
+    sr_status st = ensure_graphs(g);
+    if (st != SR_OK) return st;
+    int64_t left = frames;
+    while (g->execN && left >= g->frames_per_graph) {
+      SR_HIP(g, hipGraphLaunch(g->execN, g->stream));
+      left -= g->frames_per_graph;
+    }
+    for (; left > 0; --left) SR_HIP(g, hipGraphLaunch(g->exec1, g->stream));
+  }
+  g->host_frame += frames;
+  return SR_OK;
+}
+
+sr_status do_reset(sr_graph* g, const void* const* input_frame0) {
+  sr_status st = finalize(g);
+  if (st != SR_OK) return st;
+  const int bf16 = g->dtype == SR_BF16;
+  for (int v = 0; v < g->n_nodes; ++v) {
+    NodeRt& n = g->nodes[v];
+    int slot = n.input_slot;
+    const void* src = (slot >= 0 && input_frame0) ? input_frame0[slot] : nullptr;
+    if (src)
+      SR_HIP(g, sr_launch_pack(g->stream, n.state[0], src, g->batch * n.d.height * n.d.width, n.d.channels, n.Cp, bf16, 0));
+    else
+      SR_HIP(g, sr_launch_fill_zero(g->stream, n.state[0], n.state_bytes));
+  }
+  SrCtx c{};
+  c.frame = 1;
+  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 1));
+  g->host_frame = 0;
+  g->was_reset = true;
+  return SR_OK;
+}
+
+}  // namespace
+
+// ---------------------------------------------------------------------------
+// C ABI
+// ---------------------------------------------------------------------------
+extern "C" {
+
+const char* sr_status_str(sr_status s) {
+  switch (s) {
+    case SR_OK: return "SR_OK";
+    case SR_ERR_ARG: return "SR_ERR_ARG";
+    case SR_ERR_GRAPH: return "SR_ERR_GRAPH";
+    case SR_ERR_ROLLOUT: return "SR_ERR_ROLLOUT";
+    case SR_ERR_SHAPE: return "SR_ERR_SHAPE";
+    case SR_ERR_STATE: return "SR_ERR_STATE";
+    case SR_ERR_OOM: return "SR_ERR_OOM";
+    case SR_ERR_DEVICE: return "SR_ERR_DEVICE";
+  }
+  return "SR_ERR_?";
+}
+
+const char* sr_last_error(const sr_graph* g) { return g ? g->err.c_str() : g_last_error.c_str(); }
+
+sr_status sr_analyze(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges, int32_t* levels,
+                     int32_t* inference_factor) {
+  std::vector<int> is_input;
+  std::string err;
+  sr_status st = check_network(n_nodes, edges, n_edges, &is_input, &err);
+  if (st != SR_OK) return st;
+  std::vector<uint8_t> bits(n_edges);
+  for (int e = 0; e < n_edges; ++e) bits[e] = edges[e].bridge;
+  Analysis an;
+  st = analyse_pattern(n_nodes, edges, n_edges, bits.data(), is_input, &an, &err);
+  if (st != SR_OK) return st;
+  if (levels)
+    for (int v = 0; v < n_nodes; ++v) levels[v] = an.level[v];
+  if (inference_factor) *inference_factor = an.factor;
+  return SR_OK;
+}
+
+sr_status sr_count_valid_patterns(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges, uint64_t* count) {
+  if (!count) return fail(nullptr, SR_ERR_ARG, "count is null");
+  std::vector<int> is_input;
+  sr_status st = check_network(n_nodes, edges, n_edges, &is_input, nullptr);
+  if (st != SR_OK) return st;
+  if (n_edges > 24) return fail(nullptr, SR_ERR_ARG, "enumeration is limited to 24 edges");
+  uint64_t valid = 0;
+  std::vector<uint8_t> bits(n_edges);
+  Analysis an;
+  for (uint64_t mask = 0; mask < ((uint64_t)1 << n_edges); ++mask) {
+    for (int e = 0; e < n_edges; ++e) bits[e] = (uint8_t)((mask >> e) & 1);
+    if (analyse_pattern(n_nodes, edges, n_edges, bits.data(), is_input, &an, nullptr) == SR_OK) ++valid;
+  }
+  *count = valid;
+  return SR_OK;
+}
+
+sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
+                          int32_t batch, sr_dtype dtype, void* hip_stream, sr_graph** out) {
+  if (!out || !nodes || n_nodes <= 0 || batch <= 0 || (dtype != SR_F32 && dtype != SR_BF16))
+    return fail(nullptr, SR_ERR_ARG, "bad argument to sr_graph_create");
+  for (int v = 0; v < n_nodes; ++v) {
+    if (nodes[v].channels <= 0 || nodes[v].height <= 0 || nodes[v].width <= 0 ||
+        (nodes[v].act != SR_ACT_IDENTITY && nodes[v].act != SR_ACT_RELU))
+      return fail(nullptr, SR_ERR_ARG, "node " + std::to_string(v) + ": bad shape or activation");
+  }
+  std::vector<int> is_input;
+  std::string err;
+  sr_status st = check_network(n_nodes, edges, n_edges, &is_input, &err);
+  if (st != SR_OK) return st;
+  for (int e = 0; e < n_edges; ++e) {
+    const sr_edge_desc& d = edges[e];
+    if (d.kind != SR_EDGE_CONV && d.kind != SR_EDGE_DENSE && d.kind != SR_EDGE_GAP_DENSE)
+      return fail(nullptr, SR_ERR_ARG, "edge " + std::to_string(e) + ": unknown kind");
+    if (d.kind == SR_EDGE_CONV && (d.kh <= 0 || d.kw <= 0 || d.stride <= 0 || d.pad < 0 || d.upsample <= 0))
+      return fail(nullptr, SR_ERR_ARG, "edge " + std::to_string(e) + ": bad convolution geometry");
+  }
+  std::vector<uint8_t> bits(n_edges);
+  for (int e = 0; e < n_edges; ++e) bits[e] = edges[e].bridge;
+  Analysis an;
+  st = analyse_pattern(n_nodes, edges, n_edges, bits.data(), is_input, &an, &err);
+  if (st != SR_OK) return st;
+
+  sr_graph* g = new (std::nothrow) sr_graph();
+  if (!g) return fail(nullptr, SR_ERR_OOM, "out of host memory");
+  g->n_nodes = n_nodes;
+  g->n_edges = n_edges;
+  g->batch = batch;
+  g->dtype = dtype;
+  g->stream = (hipStream_t)hip_stream;
+  if (!hip_stream) g->use_hipgraph = false;   // the legacy default stream cannot be captured
+  g->an = an;
+  g->nodes.resize(n_nodes);
+  g->edges.resize(n_edges);
+  for (int v = 0; v < n_nodes; ++v) {
+    NodeRt& n = g->nodes[v];
+    n.d = nodes[v];
+    n.Cp = (dtype == SR_BF16) ? ((n.d.channels + 15) / 16) * 16 : n.d.channels;
+    n.state_bytes = (size_t)batch * n.d.height * n.d.width * n.Cp * elem_size(g);
+    n.bias.assign(n.Cp, 0.f);
+    if (is_input[v]) {
+      n.input_slot = (int)g->inputs.size();
+      g->inputs.push_back(v);
+    }
+  }
+  if ((int)g->inputs.size() > SR_MAX_INPUTS) {
+    delete g;
+    return fail(nullptr, SR_ERR_ARG, "more than 16 input nodes");
+  }
+  // shapes (App. A1.2: results of incoming transformations must be summable)
+  for (int e = 0; e < n_edges; ++e) {
+    EdgeRt& er = g->edges[e];
+    er.d = edges[e];
+    const sr_node_desc& s = g->nodes[er.d.src].d;
+    const sr_node_desc& d = g->nodes[er.d.dst].d;
+    if (er.d.kind == SR_EDGE_CONV) { er.kh = er.d.kh; er.kw = er.d.kw; }
+    else if (er.d.kind == SR_EDGE_DENSE) { er.kh = s.height; er.kw = s.width; }
+    else { er.kh = 1; er.kw = 1; }
+    er.w_count = (size_t)er.kh * er.kw * s.channels * d.channels;
+    int h, w;
+    edge_result_shape(g, er, &h, &w);
+    if (h != d.height || w != d.width) {
+      std::string msg = "edge " + std::to_string(e) + ": result " + std::to_string(h) + "x" + std::to_string(w) +
+                        " does not match node " + std::to_string(er.d.dst) + " (" + std::to_string(d.height) + "x" +
+                        std::to_string(d.width) + ")";
+      delete g;
+      return fail(nullptr, SR_ERR_SHAPE, msg);
+    }
+  }
+  // device memory
+  auto bail = [&](sr_status s2) {
+    std::string m = g->err;
+    sr_graph_destroy(g);
+    g_last_error = m;
+    return s2;
+  };
+  for (int v = 0; v < n_nodes; ++v) {
+    NodeRt& n = g->nodes[v];
+    for (int p = 0; p < 2; ++p) {
+      if ((st = dev_alloc(g, &n.state[p], n.state_bytes)) != SR_OK) return bail(st);
+      hipError_t he = sr_launch_fill_zero(g->stream, n.state[p], n.state_bytes);
+      if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
+    }
+    void* b = nullptr;
+    if ((st = dev_alloc(g, &b, n.Cp * sizeof(float))) != SR_OK) return bail(st);
+    n.bias_dev = (float*)b;
+    hipError_t he = sr_launch_fill_zero(g->stream, b, n.Cp * sizeof(float));
+    if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
+  }
+  void* c = nullptr;
+  if ((st = dev_alloc(g, &c, sizeof(SrCtx))) != SR_OK) return bail(st);
+  g->ctx = (SrCtx*)c;
+  {
+    hipError_t he = sr_launch_fill_zero(g->stream, c, sizeof(SrCtx));
+    if (he == hipSuccess) he = hipStreamSynchronize(g->stream);
+    if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
+  }
+  *out = g;
+  return SR_OK;
+}
+
+sr_status sr_graph_set_weights(sr_graph* g, int32_t edge, const float* host_w, size_t count) {
+  if (!g || !host_w || edge < 0 || edge >= g->n_edges) return gfail(g, SR_ERR_ARG, "bad argument to sr_graph_set_weights");
+  EdgeRt& e = g->edges[edge];
+  if (count != e.w_count)
+    return gfail(g, SR_ERR_ARG, "edge " + std::to_string(edge) + ": expected " + std::to_string(e.w_count) + " weights");
+  const bool bf16 = g->dtype == SR_BF16;
+  e.w_host.assign(host_w, host_w + count);
+  if (bf16)
+    for (float& x : e.w_host) x = bf2f(f2bf(x));
+  if (!e.w_dev) {
+    void* p = nullptr;
+    sr_status st = dev_alloc(g, &p, count * sizeof(float));
+    if (st != SR_OK) return st;
+    e.w_dev = (float*)p;
+  }
+  SR_HIP(g, hipMemcpy(e.w_dev, e.w_host.data(), count * sizeof(float), hipMemcpyHostToDevice));
+  if (bf16 && e.d.kind == SR_EDGE_CONV && g->nodes[e.d.dst].d.channels % 32 == 0) {
+    // B operand of the tile kernel: [tap][Cin_p/16][Cout/32][lane 0..63][8]; lane l of a
+    // (tap, k16 block, channel tile) holds channel tile*32 + l%32 and input channels
+    // block*16 + (l/32)*8 + 0..7
+    const int Cin = g->nodes[e.d.src].d.channels, Cinp = g->nodes[e.d.src].Cp;
+    const int Cout = g->nodes[e.d.dst].d.channels;
+    const int taps = e.kh * e.kw, kb = Cinp / 16, nt = Cout / 32;
+    std::vector<uint16_t> pk((size_t)taps * kb * nt * 512, 0);
+    for (int t = 0; t < taps; ++t)
+      for (int k = 0; k < kb; ++k)
+        for (int n = 0; n < nt; ++n)
+          for (int l = 0; l < 64; ++l)
+            for (int i = 0; i < 8; ++i) {
+              const int ci = k * 16 + (l / 32) * 8 + i, co = n * 32 + (l % 32);
+              if (ci < Cin)
+                pk[((((size_t)t * kb + k) * nt + n) * 64 + l) * 8 + i] = f2bf(host_w[((size_t)t * Cin + ci) * Cout + co]);
+            }
+    if (!e.wpk_dev) {
+      sr_status st = dev_alloc(g, &e.wpk_dev, pk.size() * 2);
+      if (st != SR_OK) return st;
+    }
+    SR_HIP(g, hipMemcpy(e.wpk_dev, pk.data(), pk.size() * 2, hipMemcpyHostToDevice));
+  }
+  e.has_w = true;
+  return SR_OK;
+}
+
+sr_status sr_graph_set_bias(sr_graph* g, int32_t node, const float* host_b, size_t count) {
+  if (!g || !host_b || node < 0 || node >= g->n_nodes) return gfail(g, SR_ERR_ARG, "bad argument to sr_graph_set_bias");
+  NodeRt& n = g->nodes[node];
+  if (count != (size_t)n.d.channels) return gfail(g, SR_ERR_ARG, "bias length differs from the node's channels");
+  std::copy(host_b, host_b + count, n.bias.begin());
+  SR_HIP(g, hipMemcpy(n.bias_dev, n.bias.data(), n.Cp * sizeof(float), hipMemcpyHostToDevice));
+  return SR_OK;
+}
+
+sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value) {
+  if (!g) return fail(nullptr, SR_ERR_ARG, "null graph");
+  if (g->finalized) return gfail(g, SR_ERR_STATE, "options must be set before the first sr_reset");
+  switch (option) {
+    case SR_OPT_USE_HIPGRAPH: g->use_hipgraph = value != 0; return SR_OK;
+    case SR_OPT_FORCE_DIRECT: g->force_direct = value != 0; return SR_OK;
+    case SR_OPT_FRAMES_PER_GRAPH:
+      if (value < 1 || value > 1024) return gfail(g, SR_ERR_ARG, "frames per graph must be in 1..1024");
+      g->frames_per_graph = (int)value;
+      return SR_OK;
+  }
+  return gfail(g, SR_ERR_ARG, "unknown option");
+}
+
+sr_status sr_graph_info(const sr_graph* g, int32_t* inference_factor, int32_t* levels, int32_t* launches_per_frame) {
+  if (!g) return fail(nullptr, SR_ERR_ARG, "null graph");
+  if (inference_factor) *inference_factor = g->an.factor;
+  if (levels)
+    for (int v = 0; v < g->n_nodes; ++v) levels[v] = g->an.level[v];
+  if (launches_per_frame) {
+    sr_status st = finalize(const_cast<sr_graph*>(g));
+    if (st != SR_OK) return st;
+    *launches_per_frame = g->launches_per_frame;
+  }
+  return SR_OK;
+}
+
+sr_status sr_reset(sr_graph* g, const void* const* input_frame0) {
+  if (!g) return fail(nullptr, SR_ERR_ARG, "null graph");
+  return do_reset(g, input_frame0);
+}
+
+sr_status sr_frame_step(sr_graph* g, const void* const* inputs_t) {
+  if (!g || !inputs_t) return gfail(g, SR_ERR_ARG, "bad argument to sr_frame_step");
+  if (!g->was_reset) return gfail(g, SR_ERR_STATE, "sr_frame_step before sr_reset");
+  SrCtx c{};
+  for (size_t i = 0; i < g->inputs.size(); ++i) {
+    if (!inputs_t[i]) return gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
+    c.in_ptr[i] = inputs_t[i];
+    c.in_stride[i] = 0;
+  }
+  c.out_ptr = nullptr;
+  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  return run_frames(g, 1);
+}
+
+sr_status sr_rollout(sr_graph* g, const void* const* inputs, int32_t T, int32_t out_node, void* outputs) {
+  if (!g || !inputs || T < 0) return gfail(g, SR_ERR_ARG, "bad argument to sr_rollout");
+  if (outputs && (out_node < 0 || out_node >= g->n_nodes)) return gfail(g, SR_ERR_ARG, "bad out_node");
+  const void* frame0[SR_MAX_INPUTS] = {nullptr};
+  for (size_t i = 0; i < g->inputs.size(); ++i) {
+    if (!inputs[i]) return gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
+    frame0[i] = inputs[i];
+  }
+  sr_status st = do_reset(g, frame0);
+  if (st != SR_OK) return st;
+  SrCtx c{};
+  for (size_t i = 0; i < g->inputs.size(); ++i) {
+    const sr_node_desc& d = g->nodes[g->inputs[i]].d;
+    c.in_ptr[i] = inputs[i];
+    c.in_stride[i] = (int64_t)g->batch * d.height * d.width * d.channels * (int64_t)elem_size(g);
+  }
+  c.in_base = 0;    // frame t reads inputs[t]
+  c.out_base = 1;   // frame t is recorded in slot t-1
+  g->rec_node = outputs ? out_node : -1;
+  if (outputs) {
+    const sr_node_desc& d = g->nodes[out_node].d;
+    c.out_ptr = outputs;
+    c.out_stride = (int64_t)g->batch * d.height * d.width * d.channels * (int64_t)elem_size(g);
+  }
+  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  return run_frames(g, T);
+}
+
+sr_status sr_get_state(const sr_graph* g, int32_t node, void* dst_device, size_t bytes) {
+  if (!g || !dst_device || node < 0 || node >= g->n_nodes) return fail(nullptr, SR_ERR_ARG, "bad argument to sr_get_state");
+  sr_graph* gm = const_cast<sr_graph*>(g);
+  const NodeRt& n = g->nodes[node];
+  const size_t want = (size_t)g->batch * n.d.height * n.d.width * n.d.channels * elem_size(g);
+  if (bytes != want) return gfail(gm, SR_ERR_ARG, "sr_get_state: expected " + std::to_string(want) + " bytes");
+  SR_HIP(gm, sr_launch_pack(g->stream, dst_device, n.state[g->host_frame & 1], g->batch * n.d.height * n.d.width,
+                            n.d.channels, n.Cp, g->dtype == SR_BF16, 1));
+  return SR_OK;
+}
+
+sr_status sr_set_state(sr_graph* g, int32_t node, const void* src_device, size_t bytes) {
+  if (!g || !src_device || node < 0 || node >= g->n_nodes) return gfail(g, SR_ERR_ARG, "bad argument to sr_set_state");
+  const NodeRt& n = g->nodes[node];
+  const size_t want = (size_t)g->batch * n.d.height * n.d.width * n.d.channels * elem_size(g);
+  if (bytes != want) return gfail(g, SR_ERR_ARG, "sr_set_state: expected " + std::to_string(want) + " bytes");
+  SR_HIP(g, sr_launch_pack(g->stream, n.state[g->host_frame & 1], src_device, g->batch * n.d.height * n.d.width,
+                           n.d.channels, n.Cp, g->dtype == SR_BF16, 0));
+  return SR_OK;
+}
+
+sr_status sr_frame_index(const sr_graph* g, int64_t* frame) {
+  if (!g || !frame) return fail(nullptr, SR_ERR_ARG, "bad argument to sr_frame_index");
+  *frame = g->host_frame;
+  return SR_OK;
+}
+
+sr_status sr_frame_step_timed(sr_graph* g, const void* const* inputs_t, float* kernel_ms, int32_t* kernel_kind,
+                              int32_t cap, int32_t* n_launches) {
+  if (!g || !inputs_t || !kernel_ms || !n_launches || cap <= 0) return gfail(g, SR_ERR_ARG, "bad argument to sr_frame_step_timed");
+  if (!g->was_reset) return gfail(g, SR_ERR_STATE, "sr_frame_step_timed before sr_reset");
+  SrCtx c{};
+  for (size_t i = 0; i < g->inputs.size(); ++i) {
+    if (!inputs_t[i]) return gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
+    c.in_ptr[i] = inputs_t[i];
+  }
+  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  const int keep = g->rec_node;
+  g->rec_node = -1;
+  FrameTimer ft;
+  sr_status st = enqueue_frame(g, false, &ft);
+  g->rec_node = keep;
+  hipError_t he = hipStreamSynchronize(g->stream);
+  int n = 0;
+  if (st == SR_OK && he == hipSuccess) {
+    for (size_t i = 0; i + 1 < ft.ev.size() && n < cap; ++i, ++n) {
+      float ms = 0.f;
+      hipEventElapsedTime(&ms, ft.ev[i], ft.ev[i + 1]);
+      kernel_ms[n] = ms;
+      if (kernel_kind) kernel_kind[n] = ft.kind[i];
+    }
+  }
+  for (hipEvent_t e : ft.ev) hipEventDestroy(e);
+  if (st != SR_OK) return st;
+  SR_HIP(g, he);
+  g->host_frame += 1;
+  *n_launches = n;
+  return SR_OK;
+}
+
+sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfma_tiles, int64_t* device_bytes) {
+  if (!g) return fail(nullptr, SR_ERR_ARG, "null graph");
+  sr_status st = finalize(const_cast<sr_graph*>(g));
+  if (st != SR_OK) return st;
+  if (flops_per_frame) *flops_per_frame = g->flops;
+  if (mfma_tiles) *mfma_tiles = g->n_mfma_tiles;
+  if (device_bytes) *device_bytes = g->device_bytes;
+  return SR_OK;
+}
+
+void sr_graph_destroy(sr_graph* g) {
+  if (!g) return;
+  if (g->stream || !g->dev_allocs.empty()) hipStreamSynchronize(g->stream);
+  drop_graphs(g);
+  for (void* p : g->dev_allocs) hipFree(p);
+  delete g;
+}
+
+}  // extern "C"

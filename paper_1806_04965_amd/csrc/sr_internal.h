@@ -1,0 +1,129 @@
+// Shared between the host planner (sr_host.cpp) and the kernels (sr_kernels.hip):
+// device-resident descriptor tables and the launch wrappers.
+#pragma once
+#include <hip/hip_runtime_api.h>
+#include <stdint.h>
+
+#define SR_MAX_INPUTS 16
+
+// One per graph, in device memory.  Kernels read the frame counter from here, so
+// the same captured HIP graph serves every frame: the buffer written at frame t
+// is t & 1, the buffer holding frame t-1 is the other one.
+struct SrCtx {
+  int32_t frame;      // index of the frame being computed (>= 1)
+  int32_t in_base;    // input frame read = in_ptr[i] + (frame - in_base) * in_stride[i]
+  int32_t out_base;   // output slot = frame - out_base
+  int32_t out_node_elems;  // unused by kernels (kept for debugging)
+  const void* in_ptr[SR_MAX_INPUTS];
+  int64_t in_stride[SR_MAX_INPUTS];   // bytes between consecutive frames (0: always the same buffer)
+  void* out_ptr;                      // may be null
+  int64_t out_stride;                 // bytes per recorded frame
+};
+
+// ---------------------------------------------------------------------------
+// direct path: one thread per output element
+// ---------------------------------------------------------------------------
+struct SrDirectEdge {
+  const void* src[2];   // source state, both copies
+  const float* w;       // [kh][kw][Cin][Cout] float (already rounded to the graph dtype)
+  int32_t bridge, kind; // kind: 0 conv (dense is a conv as large as its source), 2 GAP+dense
+  int32_t Hs, Ws, Cin, Csp;   // source height, width, channels, channel pitch
+  int32_t kh, kw, stride, pad, up;
+  int32_t pad_;
+};
+
+struct SrDirectNode {
+  void* out[2];
+  const float* bias;    // [C]
+  int32_t H, W, C, Cp;  // Cp: channel pitch of the stored state
+  int32_t act;
+  int32_t edge_begin, edge_count;
+  int32_t pad_;
+};
+
+struct SrDirectBlock {   // one workgroup of 256 outputs
+  int32_t node;
+  int32_t first;         // first linear output element (over [B*H*W][C]) of this block
+};
+
+// ---------------------------------------------------------------------------
+// MFMA path: node-centric implicit-GEMM tiles
+// ---------------------------------------------------------------------------
+struct SrMfmaEdge {
+  const void* src[2];    // bf16 source state [B][Hs][Ws][Csp], both copies
+  const void* wpk;       // packed bf16 weights [tap][Cin_p/16][Cout/32][64 lanes][8]
+  int32_t bridge;
+  int32_t Hs, Ws, Csp;   // source geometry and channel pitch
+  int32_t kh, kw, stride, pad, up;
+  int32_t KC;            // channels staged per LDS fill (16, 32 or 64)
+  int32_t nchunk;        // Csp / KC
+  int32_t PH;            // padded source rows per image: Hs + 2*pad
+  int32_t PW;            // padded source width: Ws + 2*pad
+  int32_t PWs;           // ceil(PW / stride): width of one column-phase plane
+  int32_t RP;            // slots per patch row: stride * PWs
+  int32_t SP;            // bytes per slot: KC*2 + 16
+  uint32_t magicPW;      // ceil(2^32 / PW)  -> x / PW == umulhi(x, magic) for x < 2^16 (checked on host)
+  uint32_t magicPH;      // ceil(2^32 / PH)
+  int32_t wstride8;      // 16-byte units between consecutive k16 blocks in wpk: (Cout/32)*64
+  int32_t pad_;
+};
+
+struct SrMfmaNode {
+  void* out[2];          // bf16 state [M][Cp]
+  const float* bias;     // [Cout]
+  int32_t M;             // B*Ho*Wo
+  int32_t Ho, Wo;
+  int32_t Cout, Cp;
+  int32_t act;
+  int32_t edge_begin, edge_count;
+  int32_t waves_m, waves_n;   // 4 waves arranged waves_m x waves_n; BM = 128*waves_m
+  int32_t wn_tiles;           // 32-wide MFMA column tiles per wave: 1 or 2; BN = 32*wn_tiles*waves_n
+  uint32_t magicHoWo, magicWo;
+  int32_t pad_;
+};
+
+struct SrMfmaTile {
+  int32_t node;
+  int32_t m0;    // first output pixel (linear over [B][Ho][Wo])
+  int32_t n0;    // first output channel
+  int32_t pad_;
+};
+
+// ---------------------------------------------------------------------------
+// GAP + dense head (node with a single GAP+dense incoming edge)
+// ---------------------------------------------------------------------------
+struct SrHead {
+  const void* src[2];
+  void* out[2];
+  const float* w;        // [Cin][Cout] float
+  const float* bias;
+  float* partial;        // [B][splits][Cin] float scratch
+  int32_t bridge, act;
+  int32_t B, HW, Cin, Csp, Cout, Cp;
+  int32_t splits, bf16;
+};
+
+// input staging / state packing
+struct SrStageNode {
+  void* state[2];
+  int32_t elems_px;   // B*H*W
+  int32_t C, Cp;
+  int32_t input_slot; // index into SrCtx::in_ptr
+};
+
+// launch wrappers (sr_kernels.hip); each returns the hipError_t of the launch
+hipError_t sr_launch_set_ctx(hipStream_t s, SrCtx* ctx, const SrCtx& values, int set_frame);
+hipError_t sr_launch_tick(hipStream_t s, SrCtx* ctx);
+hipError_t sr_launch_fill_zero(hipStream_t s, void* p, size_t bytes);
+hipError_t sr_launch_stage_inputs(hipStream_t s, const SrCtx* ctx, const SrStageNode* nodes, int n_nodes,
+                                  int max_elems, int bf16);
+hipError_t sr_launch_pack(hipStream_t s, void* dst, const void* src, int px, int C, int Cp, int bf16, int unpack);
+hipError_t sr_launch_record_output(hipStream_t s, const SrCtx* ctx, const void* state0, const void* state1,
+                                   int px, int C, int Cp, int bf16);
+hipError_t sr_launch_direct(hipStream_t s, const SrCtx* ctx, const SrDirectNode* nodes, const SrDirectEdge* edges,
+                            const SrDirectBlock* blocks, int n_blocks, int bf16, int batch);
+hipError_t sr_launch_mfma(hipStream_t s, const SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
+                          const SrMfmaTile* tiles, int n_tiles, int lds_bytes);
+hipError_t sr_launch_head(hipStream_t s, const SrCtx* ctx, const SrHead* heads, int n_heads, int max_B,
+                          int max_splits, int max_cin, int bf16);
+int sr_mfma_max_lds_bytes();

@@ -1,0 +1,140 @@
+"""GPU parity: the HIP library (through its C ABI) against the CPU oracle, element by element, on
+the same seeded inputs.  Tolerances: max-abs-rel <= 1e-4 for fp32 graphs (oracle in float64),
+<= 2e-2 for bf16 graphs (oracle emulating the bf16 storage points)."""
+import numpy as np
+import pytest
+
+import workloads as W
+from workloads.graphs import Node, Edge, Graph, ACT_IDENTITY, ACT_RELU
+from gpu_util import (gpu_states_by_steps, gpu_rollout, oracle_states, compare_all, max_abs_rel)
+
+pytestmark = pytest.mark.gpu
+
+TOL = {"f32": 1e-4, "bf16": 2e-2}
+MODE = {"f32": "f64", "bf16": "bf16"}
+OPT_DIRECT = {1: 1}
+OPT_EAGER = {0: 0}
+
+
+def check(g, seed=0, T=None, options=None, bias_scale=0.1, label=None):
+    T = g.frames if T is None else T
+    w, b, x = W.make_case(g, seed=seed, bias_scale=bias_scale, frames=T)
+    got, info, work = gpu_states_by_steps(g, w, b, x, T, options)
+    ref = oracle_states(g, w, b, x, T, MODE[g.dtype])
+    worst = compare_all(got, ref, TOL[g.dtype], label or g.name)
+    print(f"[parity] {label or g.name}: worst max-abs-rel {worst:.3e} (tol {TOL[g.dtype]}), "
+          f"F(R)={info['inference_factor']}, mfma tiles={work['mfma_tiles']}", flush=True)
+    return info, work
+
+
+def test_tiny_sr_fp32_streaming_all_nodes_all_frames():
+    g = W.tiny_sr()
+    info, _ = check(g)
+    assert info["inference_factor"] == 1
+
+
+@pytest.mark.parametrize("pattern", ["sequential", "hybrid"])
+def test_tiny_sr_fp32_other_patterns(pattern):
+    g = W.tiny_sr()
+    bits = W.sequential_pattern(g) if pattern == "sequential" else W.hybrid_pattern(g)
+    check(g.with_pattern(bits), label=f"tiny_sr/{pattern}")
+
+
+def test_mnist_sr_net_fp32_conv7_stride4_and_dense_edges():
+    check(W.mnist_net("SR", batch=3, frames=5))
+
+
+def test_cifar_small_bf16_direct_kernel():
+    g = W.cifar_sr(batch=2, frames=4)
+    _, work = check(g, options=OPT_DIRECT, label="cifar_sr/direct")
+    assert work["mfma_tiles"] == 0
+
+
+def test_cifar_small_bf16_mfma_streaming():
+    g = W.cifar_sr(batch=4, frames=6)
+    info, work = check(g)
+    assert work["mfma_tiles"] > 0 and info["inference_factor"] == 1
+
+
+def test_cifar_ragged_batch_bf16_mfma():
+    # B=3: nodes 5 and 6 have 192 pixels, less than one 256-pixel tile; nodes 3, 4 end in a partial tile
+    check(W.cifar_sr(batch=3, frames=4), seed=3, label="cifar_sr/B3")
+
+
+@pytest.mark.parametrize("pattern", ["sequential", "hybrid"])
+def test_cifar_patterns_bf16_mfma(pattern):
+    g = W.cifar_patterns(batch=4, frames=5)[pattern]
+    info, work = check(g, label=g.name)
+    assert work["mfma_tiles"] > 0
+    assert info["inference_factor"] == (7 if pattern == "sequential" else info["inference_factor"])
+
+
+def test_gtsrb_small_bf16_mfma_feedback_and_long_skips():
+    check(W.gtsrb_sr(batch=2, frames=4), seed=1)
+
+
+def test_dsr2_bf16_conv5_and_stride4():
+    check(W.dsr_net(2, batch=2, frames=5), seed=2)
+
+
+def test_hires_reduced_bf16_mfma():
+    # the high-resolution graph at 64x64 input (same nodes, edges and channel schedule)
+    g = W.hires_sr(batch=1, frames=3)
+    nodes = []
+    for n in g.nodes:
+        if n.name == "out":
+            nodes.append(n)
+        else:
+            nodes.append(Node(n.name, n.channels, n.height // 4, n.width // 4, n.act))
+    g2 = Graph("hires_sr", nodes, g.edges, 1, 3, "bf16", g.out_node)
+    check(g2, seed=4, label="hires_sr/64x64")
+
+
+def test_rollout_equals_frame_steps_and_hipgraph_equals_eager():
+    g = W.cifar_sr(batch=2, frames=11)       # 11 frames: one 8-frame graph + 3 single frames
+    w, b, x = W.make_case(g, seed=5, bias_scale=0.1)
+    T = g.frames
+    a = gpu_rollout(g, w, b, x, T)
+    c = gpu_rollout(g, w, b, x, T, options=OPT_EAGER)
+    steps, _, _ = gpu_states_by_steps(g, w, b, x, T, nodes=[g.out_node])
+    np.testing.assert_array_equal(a, c)
+    np.testing.assert_array_equal(a, np.stack(steps[g.out_node]))
+    ref = oracle_states(g, w, b, x, T, "bf16", nodes=[g.out_node])[g.out_node]
+    for t in range(T):
+        assert max_abs_rel(a[t], ref[t]) <= 2e-2
+
+
+def test_checkpoint_restore_continues_bit_exactly():
+    import paper_1806_04965_amd as sr
+    from gpu_util import to_device
+    g = W.cifar_sr(batch=2, frames=6)
+    w, b, x = W.make_case(g, seed=6)
+    xd = to_device(x[0], "bf16")
+    full, _, _ = gpu_states_by_steps(g, w, b, x, 6, nodes=range(len(g.nodes)))
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    dev.reset([xd[0]])
+    for t in range(1, 4):
+        dev.frame_step([xd[t]])
+    saved = [dev.get_state(v) for v in range(len(g.nodes))]
+    dev.close()
+    dev2 = sr.SrGraph(g)
+    dev2.set_parameters(w, b)
+    dev2.reset(None)
+    for v, s in enumerate(saved):
+        dev2.set_state(v, s)
+    for t in range(4, 7):
+        dev2.frame_step([xd[t]])
+    for v in range(1, len(g.nodes)):
+        np.testing.assert_array_equal(dev2.get_state(v).float().cpu().numpy(), full[v][-1])
+    dev2.close()
+
+
+def test_first_response_frame_on_gpu():
+    # exact zeros at the output until shortest-path-many frames have passed (zero bias)
+    g = W.cifar_sr(batch=2, frames=7)
+    w, b, x = W.make_case(g, seed=7)
+    out = gpu_rollout(g, w, b, x, 7)
+    for t in range(1, 5):
+        assert np.all(out[t - 1] == 0.0)
+    assert np.any(out[4] != 0.0)
