@@ -1,0 +1,163 @@
+#!/usr/bin/env python3
+"""Benchmark of the streaming-rollout hot path on one MI355X.
+
+A step is one sr_rollout: T frame updates of the whole batch, inputs already resident in HBM,
+every frame's output-node state recorded.  Prints ONE JSON line: rollout frames/s
+(= batch * T * steps / time), per-frame latency, the roofline position of the dominant kernel
+(the MFMA convolution tiles: algorithmic FLOP of one launch / its average duration from HIP events
+taken on the library's stream) and the CPU oracle timed on a bounded sample of the same workload.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gtsrb_sr|cifar_sr|hires_sr|tiny_sr]
+                    [--pattern streaming|sequential|hybrid] [--no-cpu-baseline]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
+PEAK_FP32_VALU_TFLOPS = 157.3  # fp32 vector peak (the fp32 graph runs on plain ALUs)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="gtsrb_sr")
+    ap.add_argument("--pattern", default="streaming")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-hipgraph", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(the path shards by batch or by node partition, see DESIGN.md)", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_1806_04965_amd as sr
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    torch.cuda.set_device(0)
+    g = W.BENCH_CONFIGS[args.workload]()
+    bits = {"streaming": W.streaming_pattern, "sequential": W.sequential_pattern,
+            "hybrid": W.hybrid_pattern}[args.pattern](g)
+    g = g.with_pattern(bits)
+    T, B = g.frames, g.batch
+    w, b, x = W.make_case(g, seed=0)
+
+    opts = {0: 0} if args.no_hipgraph else None
+    dev = sr.SrGraph(g, options=opts)
+    dev.set_parameters(w, b)
+    tdt = torch.bfloat16 if g.dtype == "bf16" else torch.float32
+    ins = g.input_nodes()
+    xin = [torch.from_numpy(x[v]).to("cuda").to(tdt).contiguous() for v in ins]
+    n_out = g.nodes[g.out_node]
+    out = torch.empty((T, B, n_out.height, n_out.width, n_out.channels), dtype=tdt, device="cuda")
+    info = dev.info()
+    work = dev.work()
+
+    for _ in range(args.warmup):
+        dev.rollout(xin, T, g.out_node, out)
+    dev.synchronize()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        dev.rollout(xin, T, g.out_node, out)
+    dev.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    frames_per_s = B * T * args.steps / dt
+
+    # dominant kernel, timed live with HIP events on the library's stream (plain launches)
+    dev.reset([xi[0] for xi in xin])
+    for t in range(1, min(T, 4) + 1):
+        dev.frame_step([xi[t] for xi in xin])
+    dev.synchronize()
+    kind_ms = {}
+    reps = min(T, 12)
+    for r in range(reps):
+        for kind, ms in dev.frame_step_timed([xi[1 + (r % T)] for xi in xin]):
+            kind_ms.setdefault(kind, []).append(ms)
+    conv_flops = 0
+    for e in g.edges:
+        if e.kind == "conv":
+            s, d = g.nodes[e.src], g.nodes[e.dst]
+            conv_flops += 2 * B * (d.height // e.up) * (d.width // e.up) * d.channels * s.channels * e.kh * e.kw
+    mfma_launch_ms = None
+    if g.dtype == "bf16" and 1 in kind_ms:
+        per_frame = info["inference_factor"]       # one tile launch per level
+        mfma_launch_ms = float(np.sum(kind_ms[1]) / (len(kind_ms[1])))
+        launches_per_frame = len(kind_ms[1]) / reps
+        frame_conv_ms = mfma_launch_ms * launches_per_frame
+        achieved = conv_flops / (frame_conv_ms * 1e-3) / 1e12
+        roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "kernel": "sr_mfma_kernel", "launch_ms": round(mfma_launch_ms, 4),
+                    "launches_per_frame": launches_per_frame, "flop_per_frame": conv_flops}
+        del per_frame
+    else:
+        d_ms = float(np.mean(kind_ms.get(2, [float("nan")])))
+        achieved = work["flops_per_frame"] / (d_ms * 1e-3) / 1e12
+        roofline = {"bound": "alu", "achieved": round(achieved, 5), "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
+                    "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 6), "traffic": None,
+                    "kernel": "sr_direct_kernel", "launch_ms": round(d_ms, 4)}
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import rollout as orc
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        mode = "bf16" if g.dtype == "bf16" else "f64"
+        sample_frames = 2 if work["flops_per_frame"] > 5e10 else min(T, 8)
+        r = orc.Rollout(g, w, b, mode)
+        r.reset({v: x[v][0] for v in ins})
+        c0 = time.perf_counter()
+        for t in range(1, sample_frames + 1):
+            r.step({v: x[v][t] for v in ins})
+        cdt = time.perf_counter() - c0
+        cpu = {"value": round(B * sample_frames / cdt, 3), "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"{sample_frames} frame updates of the full batch ({mode} mode), {cdt:.1f} s",
+               "ms_per_frame": round(cdt / sample_frames * 1e3, 1)}
+
+    line = {
+        "metric": "rollout frames/sec (batch x frames / s)",
+        "value": round(frames_per_s, 1),
+        "unit": "frames/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": g.dtype,
+        "data": "synthetic",
+        "config": {"workload": f"{args.workload} ({args.pattern} rollout)", "batch": B, "frames_per_step": T,
+                   "nodes": len(g.nodes), "edges": len(g.edges), "inference_factor": info["inference_factor"],
+                   "launches_per_frame": info["launches_per_frame"], "hipgraph": not args.no_hipgraph},
+        "us_per_frame": round(ms_per_step * 1e3 / T, 2),
+        "gflop_per_frame": round(work["flops_per_frame"] / 1e9, 3),
+        "frame_tflops": round(work["flops_per_frame"] * T / (ms_per_step * 1e-3) / 1e12, 2),
+        "roofline": roofline,
+        "cpu_baseline": cpu,
+    }
+    dev.close()
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -181,6 +181,7 @@ struct sr_graph {
   SrMfmaEdge* m_edges = nullptr;
   SrMfmaTile* m_tiles = nullptr;
   SrHead* heads = nullptr;
+  void* zero_page = nullptr;
   int lds_bytes = 0;
   int64_t n_mfma_tiles = 0;
   double flops = 0;
@@ -382,6 +383,7 @@ sr_status finalize(sr_graph* g) {
         node.waves_m = waves_m;
         node.waves_n = waves_n;
         node.wn_tiles = wn_tiles;
+        node.zero_page = g->zero_page;
         double ksum = 0;
         bool ok = true;
         for (EdgeRt& e : g->edges) {
@@ -404,7 +406,8 @@ sr_status finalize(sr_graph* g) {
           m.PW = m.Ws + 2 * m.pad;
           m.PWs = (m.PW + m.stride - 1) / m.stride;
           m.RP = m.stride * m.PWs;
-          m.magicPW = magic_for((uint32_t)m.PW);
+          m.magicRP = magic_for((uint32_t)m.RP);
+          m.magicPWs = magic_for((uint32_t)m.PWs);
           m.magicPH = magic_for((uint32_t)m.PH);
           m.wstride8 = (Cout / 32) * 64;
           const int64_t slots = max_patch_slots(g, v, e, BM);
@@ -413,14 +416,21 @@ sr_status finalize(sr_graph* g) {
             if (sn.Cp % cand == 0 && slots * (cand * 2 + 16) <= lds_cap) { KC = cand; break; }
           // the staging loop divides slot indices by PW and padded row indices by PH with a
           // multiply-high; make sure both stay inside the range where that is exact
-          if (KC == 0 || (uint64_t)slots > magic_range((uint32_t)m.PW) ||
-              (uint64_t)B * m.PH > magic_range((uint32_t)m.PH) || slots * (KC * 2 + 16) > (int64_t)1 << 30) {
+          if (KC == 0 || (uint64_t)slots + 256 > magic_range((uint32_t)m.RP) ||
+              (uint64_t)m.RP > magic_range((uint32_t)m.PWs) ||
+              (uint64_t)B * m.PH + slots > magic_range((uint32_t)m.PH)) {
             ok = false;
             break;
           }
           m.KC = KC;
           m.nchunk = sn.Cp / KC;
           m.SP = KC * 2 + 16;
+          m.magicCH1 = magic_for((uint32_t)(KC / 8 + 1));
+          m.magicKW = (int32_t)((65536 + m.kw - 1) / m.kw);
+          for (int tap = 0; tap < m.kh * m.kw; ++tap)
+            if (((tap * m.magicKW) >> 16) != tap / m.kw) ok = false;
+          if ((uint64_t)slots * (KC / 8 + 1) + 256 > magic_range((uint32_t)(KC / 8 + 1))) ok = false;
+          if (!ok) break;
           g->lds_bytes = std::max<int>(g->lds_bytes, (int)(slots * m.SP));
           ksum += (double)sn.Cp * m.kh * m.kw;
           me.push_back(m);
@@ -822,6 +832,11 @@ sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_e
     if ((st = dev_alloc(g, &b, n.Cp * sizeof(float))) != SR_OK) return bail(st);
     n.bias_dev = (float*)b;
     hipError_t he = sr_launch_fill_zero(g->stream, b, n.Cp * sizeof(float));
+    if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
+  }
+  if ((st = dev_alloc(g, &g->zero_page, 256)) != SR_OK) return bail(st);
+  {
+    hipError_t he = sr_launch_fill_zero(g->stream, g->zero_page, 256);
     if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
   }
   void* c = nullptr;

@@ -61,8 +61,11 @@ struct SrMfmaEdge {
   int32_t PW;            // padded source width: Ws + 2*pad
   int32_t PWs;           // ceil(PW / stride): width of one column-phase plane
   int32_t RP;            // slots per patch row: stride * PWs
-  int32_t SP;            // bytes per slot: KC*2 + 16
-  uint32_t magicPW;      // ceil(2^32 / PW)  -> x / PW == umulhi(x, magic) for x < 2^16 (checked on host)
+  int32_t SP;            // bytes per slot: KC*2 + 16 (one spare 16-byte piece rotates the LDS banks)
+  uint32_t magicRP;      // ceil(2^32 / RP): x / RP == umulhi(x, magic) over the range the host checked
+  uint32_t magicPWs;     // ceil(2^32 / PWs)
+  uint32_t magicCH1;     // ceil(2^32 / (KC/8 + 1))
+  int32_t magicKW;       // ceil(2^16 / kw): tap / kw == (tap * magic) >> 16 for tap < kh*kw (checked on host)
   uint32_t magicPH;      // ceil(2^32 / PH)
   int32_t wstride8;      // 16-byte units between consecutive k16 blocks in wpk: (Cout/32)*64
   int32_t pad_;
@@ -78,8 +81,8 @@ struct SrMfmaNode {
   int32_t edge_begin, edge_count;
   int32_t waves_m, waves_n;   // 4 waves arranged waves_m x waves_n; BM = 128*waves_m
   int32_t wn_tiles;           // 32-wide MFMA column tiles per wave: 1 or 2; BN = 32*wn_tiles*waves_n
-  uint32_t magicHoWo, magicWo;
   int32_t pad_;
+  const void* zero_page; // 256 zero bytes: source of padding pixels for the direct-to-LDS loads
 };
 
 struct SrMfmaTile {

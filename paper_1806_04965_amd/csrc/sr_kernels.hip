@@ -211,45 +211,173 @@ __global__ __launch_bounds__(256) void sr_head_dense_kernel(const SrCtx* __restr
 // supplies row (A) / column (B) l % 32 and 8 consecutive k values selected by l / 32.
 //
 // A operand (pixels x channels of the source): the source patch that the tile's pixels touch is
-// staged once per KC channels in LDS and re-read for every tap.  LDS slot (q, px): q = padded
-// source row relative to the tile's first one, px = padded source column, stored column-phase
-// major for strided edges so that consecutive output pixels read consecutive slots:
-//     slot = q*RP + (px % stride)*PWs + px / stride,   SP = KC*2 + 16 bytes per slot
-// (the 16 spare bytes rotate consecutive slots across the LDS banks).
+// staged once per KC channels in LDS and re-read for every tap.  It is written by direct-to-LDS
+// loads (no registers in between), all issued back to back, so a stage costs one memory latency;
+// a second workgroup on the same CU computes meanwhile.  LDS slot of padded source pixel
+// (row q relative to the tile's first row, column px), column-phase major for strided edges so
+// that consecutive output pixels read consecutive slots:
+//     slot = q*RP + (px % stride)*PWs + px / stride            KC*2 bytes per slot
+// and inside a slot the 16-byte piece p sits at p ^ ((slot >> SH) & (CH-1)), CH = KC/8 pieces,
+// SH = log2(16/CH): sixteen consecutive slots then cover sixteen different 16-byte columns of
+// the 256-byte LDS row, which is what a conflict-free ds_read_b128 needs.
 //
 // B operand (weights): pre-packed on the host in exactly the per-lane order of the instruction,
 // [tap][k16 block][32-channel tile][lane][8], so a wave's fragment is one coalesced 1 KiB load
-// straight into registers; it is prefetched one k-step ahead.
+// straight into registers, prefetched a few k-steps ahead through a small ring.
+#define SR_RING 3   // depth of the weight-fragment and A-fragment rings; the step loop is unrolled by it
+
+typedef const __attribute__((address_space(1))) bf16x8_t* sr_gfrag_ptr;   // global memory
+#define SR_UNIFORM(x) __builtin_amdgcn_readfirstlane(x)
+
+// Wave-uniform copy of an edge descriptor, read through the constant address space so that it
+// lives in scalar registers and all per-step address arithmetic stays on the scalar unit.
+struct SrEdgeK {
+  const unsigned char* src;
+  sr_gfrag_ptr wpk;
+  int Hs, Ws, Csp, kw, ntaps, stride, lgs, pad, up, KC, lgK16, nchunk, PH, PW, PWs, RP, SP, CH1;
+  unsigned magicRP, magicPWs, magicPH, magicCH1;
+  int magicKW, wstride8, k16_total;
+};
+
+__device__ __forceinline__ SrEdgeK sr_load_edge(const SrMfmaEdge* edges, int index, int cur) {
+  const __attribute__((address_space(4))) SrMfmaEdge* p =
+      (const __attribute__((address_space(4))) SrMfmaEdge*)(unsigned long long)(edges + index);
+  SrEdgeK k;
+  const int bridge = p->bridge;
+  k.src = (const unsigned char*)p->src[bridge ? (cur ^ 1) : cur];
+  k.wpk = (sr_gfrag_ptr)(unsigned long long)p->wpk;
+  k.Hs = p->Hs; k.Ws = p->Ws; k.Csp = p->Csp;
+  k.kw = p->kw; k.ntaps = p->kh * p->kw;
+  k.stride = p->stride; k.lgs = (k.stride == 1) ? 0 : (k.stride == 2 ? 1 : 2);
+  k.pad = p->pad; k.up = p->up;
+  k.KC = p->KC; k.lgK16 = (k.KC == 16) ? 0 : (k.KC == 32 ? 1 : 2);
+  k.nchunk = p->nchunk;
+  k.PH = p->PH; k.PW = p->PW; k.PWs = p->PWs; k.RP = p->RP; k.SP = p->SP;
+  k.CH1 = (k.KC >> 3) + 1;
+  k.magicRP = p->magicRP; k.magicPWs = p->magicPWs; k.magicPH = p->magicPH; k.magicCH1 = p->magicCH1;
+  k.magicKW = p->magicKW; k.wstride8 = p->wstride8;
+  k.k16_total = k.Csp >> 4;
+  return k;
+}
+
+// Issue the direct-to-LDS loads of one stage: KC channels of every padded source pixel in the
+// tile's patch.  Position P (16-byte units) of the LDS buffer is piece P % (CH+1) of slot
+// P / (CH+1); the last piece of a slot is the spare one and is never written.  Lanes whose pixel
+// is padding or outside the image read a zero page instead.
+__device__ __forceinline__ void sr_stage_dma(const SrEdgeK& e, const unsigned char* __restrict__ zero_page,
+                                             unsigned char* lds, int Q0, int n_pos, int chunk, int tid) {
+  const int lane = tid & 63;
+  for (int P0 = tid - lane; P0 < n_pos; P0 += 256) {   // P0: first position of this wave's 1 KiB piece
+    const int P = P0 + lane;
+    const int slot = __umulhi((unsigned)P, e.magicCH1);
+    const int piece = P - slot * e.CH1;
+    const int q = __umulhi((unsigned)slot, e.magicRP);
+    const int col = slot - q * e.RP;
+    const int phase = __umulhi((unsigned)col, e.magicPWs);
+    const int px = ((col - phase * e.PWs) << e.lgs) + phase;
+    const int Qg = Q0 + q;
+    const int b = __umulhi((unsigned)Qg, e.magicPH);
+    const int iy = Qg - b * e.PH - e.pad;
+    const int ix = px - e.pad;
+    const unsigned char* g = zero_page;
+    if (iy >= 0 && iy < e.Hs && ix >= 0 && ix < e.Ws)
+      g = e.src + (((size_t)(b * e.Hs + iy) * e.Ws + ix) * e.Csp + chunk * e.KC + piece * 8) * 2;
+    if (P < n_pos && px < e.PW && piece < e.CH1 - 1)
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                       (__attribute__((address_space(3))) void*)(lds + (size_t)SR_UNIFORM(P0) * 16),
+                                       16, 0, 0);
+  }
+}
+
+// k-step st of a stage -> byte offset of its A fragments relative to tap (0,0), k = 0, and index
+// of its weight fragment relative to the chunk's first one.  All wave-uniform (scalar unit).
+struct SrStep { int aoff; int boff; };
+__device__ __forceinline__ SrStep sr_step_decode(const SrEdgeK& e, int st) {
+  const int tap = st >> e.lgK16;
+  const int k = st - (tap << e.lgK16);
+  const int ti = (tap * e.magicKW) >> 16;
+  const int tj = tap - ti * e.kw;
+  SrStep r;
+  r.aoff = (ti * e.RP + (tj & (e.stride - 1)) * e.PWs + (tj >> e.lgs)) * e.SP + k * 32;
+  r.boff = (tap * e.k16_total + k) * e.wstride8;
+  return r;
+}
+
+// One stage of the contraction: NS = taps * KC/16 k-steps over the patch in LDS.  Weight fragments
+// run SR_RING steps ahead, A fragments one step ahead; the loop body is SR_RING steps so that
+// every ring slot has a fixed register.
 template <int WN>
-__device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode& nd,
-                                             const SrMfmaEdge* __restrict__ edges, const SrMfmaTile& t,
-                                             unsigned char* lds) {
+__device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
+                                                 sr_gfrag_ptr wchunk, bf16x8_t (&bq)[SR_RING][WN],
+                                                 f32x16_t (&acc)[4][WN], int NS) {
+  bf16x8_t a[SR_RING][4];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) a[0][mi] = *(const bf16x8_t*)(lds + abase[mi]);
+  int st0 = 0;
+  for (; st0 + SR_RING <= NS; st0 += SR_RING) {
+#pragma unroll
+    for (int u = 0; u < SR_RING; ++u) {
+      const int st = st0 + u;
+      if (st + 1 < NS) {
+        const SrStep nx = sr_step_decode(e, st + 1);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) a[(u + 1) % SR_RING][mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < WN; ++nj)
+          acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][mi], bq[u][nj], acc[mi][nj], 0, 0, 0);
+      if (st + SR_RING < NS) {
+        const SrStep nb = sr_step_decode(e, st + SR_RING);
+#pragma unroll
+        for (int nj = 0; nj < WN; ++nj) bq[u][nj] = wchunk[nb.boff + nj * 64];
+      }
+    }
+  }
+  // remaining 0..SR_RING-1 steps (their fragments are already in ring slots 0, 1, ...)
+#pragma unroll
+  for (int u = 0; u < SR_RING - 1; ++u) {
+    const int st = st0 + u;
+    if (st < NS) {
+      if (st + 1 < NS) {
+        const SrStep nx = sr_step_decode(e, st + 1);
+#pragma unroll
+        for (int mi = 0; mi < 4; ++mi) a[u + 1][mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
+      }
+#pragma unroll
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < WN; ++nj)
+          acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][mi], bq[u][nj], acc[mi][nj], 0, 0, 0);
+    }
+  }
+}
+
+template <int WN>
+__device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
+                                             const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
+                                             int tile_n0, unsigned char* lds) {
+  const __attribute__((address_space(4))) SrMfmaNode* nd =
+      (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
-  const int wave = tid >> 6;
-  const int wm = wave / nd.waves_n;
-  const int wn = wave - wm * nd.waves_n;
+  const int wave = SR_UNIFORM(tid >> 6);
+  const int waves_n = nd->waves_n;
+  const int wm = (waves_n == 4) ? 0 : (waves_n == 2 ? (wave >> 1) : wave);
+  const int wn = wave - wm * waves_n;
   const int cur = ctx->frame & 1;
-  const int BM = 128 * nd.waves_m;
-  const int HoWo = nd.Ho * nd.Wo;
-  const int m_first = t.m0;
-  const int m_last = min(t.m0 + BM, nd.M) - 1;
-  const int wave_m0 = t.m0 + wm * 128;
-  const int wave_n0 = t.n0 + wn * (32 * WN);
+  const int M = nd->M, Wo = nd->Wo, HoWo = nd->Ho * Wo;
+  const int BM = 128 * nd->waves_m;
+  const int m_first = tile_m0;
+  const int m_last = min(tile_m0 + BM, M) - 1;
+  const int wave_m0 = tile_m0 + wm * 128;
+  const int wave_n0 = tile_n0 + wn * (32 * WN);
   const int ntile0 = wave_n0 >> 5;
-
-  // pixel coordinates of this lane's 4 rows (clamped to the last valid pixel)
-  int pb[4], py[4], pxo[4];
-#pragma unroll
-  for (int mi = 0; mi < 4; ++mi) {
-    int m = min(wave_m0 + mi * 32 + (lane & 31), nd.M - 1);
-    int b = m / HoWo;
-    int r = m - b * HoWo;
-    int oy = r / nd.Wo;
-    pb[mi] = b; py[mi] = oy; pxo[mi] = r - oy * nd.Wo;
-  }
-  const int b_first = m_first / HoWo, oy_first = (m_first - b_first * HoWo) / nd.Wo;
-  const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / nd.Wo;
+  const int b_first = m_first / HoWo, oy_first = (m_first - b_first * HoWo) / Wo;
+  const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / Wo;
+  const unsigned char* zero_page = (const unsigned char*)nd->zero_page;
+  const int edge_begin = nd->edge_begin, edge_count = nd->edge_count;
 
   f32x16_t acc[4][WN];
 #pragma unroll
@@ -259,107 +387,65 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
 
-  for (int ei = 0; ei < nd.edge_count; ++ei) {
-    const SrMfmaEdge& e = edges[nd.edge_begin + ei];
-    const unsigned char* src = (const unsigned char*)e.src[e.bridge ? (cur ^ 1) : cur];
-    const int s = e.stride, lg = (s == 1) ? 0 : (s == 2 ? 1 : 2);
-    const int Q0 = b_first * e.PH + (oy_first / e.up) * s;
-    const int Q1 = b_last * e.PH + (oy_last / e.up) * s + e.kh - 1;
-    const int n_items_row = e.PW;
-    const int CH = e.KC >> 3;                 // 16-byte pieces per slot
-    const int lgCH = (CH == 2) ? 1 : (CH == 4 ? 2 : 3);
-    const int n_items = (Q1 - Q0 + 1) * n_items_row * CH;
+  for (int ei = 0; ei < edge_count; ++ei) {
+    const SrEdgeK e = sr_load_edge(edges, edge_begin + ei, cur);
+    const int Q0 = b_first * e.PH + (oy_first / e.up) * e.stride;
+    const int Q1 = b_last * e.PH + (oy_last / e.up) * e.stride + e.ntaps / e.kw - 1;
+    const int n_pos = (Q1 - Q0 + 1) * e.RP * e.CH1;
+    // LDS byte address of the tap (0,0), k = 0 fragment of this lane's 4 rows; rows past the end
+    // repeat the last pixel
     int abase[4];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
-      int q = pb[mi] * e.PH + (py[mi] / e.up) * s - Q0;
-      abase[mi] = (q * e.RP + (pxo[mi] / e.up)) * e.SP + (lane >> 5) * 16;
+      const int m = min(wave_m0 + mi * 32 + (lane & 31), M - 1);
+      const int b = m / HoWo;
+      const int r = m - b * HoWo;
+      const int oy = r / Wo;
+      const int ox = r - oy * Wo;
+      abase[mi] = ((b * e.PH + (oy / e.up) * e.stride - Q0) * e.RP + ox / e.up) * e.SP + (lane >> 5) * 16;
     }
-    const int ntaps = e.kh * e.kw;
-    const int k16_per_chunk = e.KC >> 4;
-    const int k16_total = e.Csp >> 4;
-    const bf16x8_t* wlane = (const bf16x8_t*)e.wpk + (size_t)ntile0 * 64 + lane;
-
+    const sr_gfrag_ptr wlane = e.wpk + ntile0 * 64 + lane;
+    const int NS = e.ntaps << e.lgK16;
     for (int chunk = 0; chunk < e.nchunk; ++chunk) {
+      const sr_gfrag_ptr wchunk = wlane + (size_t)(chunk << e.lgK16) * e.wstride8;
       __syncthreads();   // everyone has finished reading the previous patch
-      // ---- stage the patch: KC channels of every padded source pixel the tile touches
-      for (int item0 = tid; item0 < n_items; item0 += 256 * 4) {
-        uint4 v[4];
-        int dst[4];
+      // the first weight fragments go out ahead of the patch so that both are in flight together
+      bf16x8_t bq[SR_RING][WN];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const int item = item0 + u * 256;
-          v[u] = make_uint4(0, 0, 0, 0);
-          dst[u] = -1;
-          if (item < n_items) {
-            const int ch = item & (CH - 1);
-            const int sl = item >> lgCH;
-            const int q = __umulhi((unsigned)sl, e.magicPW);
-            const int px = sl - q * e.PW;
-            const int Qg = Q0 + q;
-            const int b = __umulhi((unsigned)Qg, e.magicPH);
-            const int iy = Qg - b * e.PH - e.pad;
-            const int ix = px - e.pad;
-            if (iy >= 0 && iy < e.Hs && ix >= 0 && ix < e.Ws) {
-              const size_t off = (((size_t)(b * e.Hs + iy) * e.Ws + ix) * e.Csp + chunk * e.KC + ch * 8) * 2;
-              v[u] = *(const uint4*)(src + off);
-            }
-            dst[u] = (q * e.RP + (px & (s - 1)) * e.PWs + (px >> lg)) * e.SP + ch * 16;
-          }
-        }
+      for (int d = 0; d < SR_RING; ++d) {
+        if (d < NS) {
+          const SrStep nb = sr_step_decode(e, d);
 #pragma unroll
-        for (int u = 0; u < 4; ++u)
-          if (dst[u] >= 0) *(uint4*)(lds + dst[u]) = v[u];
-      }
-      __syncthreads();
-      // ---- contract: taps x k16 steps of this chunk
-      const bf16x8_t* wchunk = wlane + (size_t)(chunk * k16_per_chunk) * e.wstride8;
-      bf16x8_t bcur[WN], bnxt[WN];
-#pragma unroll
-      for (int nj = 0; nj < WN; ++nj) bnxt[nj] = bcur[nj] = wchunk[nj * 64];
-      for (int tap = 0; tap < ntaps; ++tap) {
-        const int ti = tap / e.kw, tj = tap - ti * e.kw;
-        const int toff = (ti * e.RP + (tj & (s - 1)) * e.PWs + (tj >> lg)) * e.SP;
-        for (int k = 0; k < k16_per_chunk; ++k) {
-          // prefetch the next step's weights (next k16 of this tap, else first k16 of the next tap)
-          int ntap = tap, nk = k + 1;
-          if (nk == k16_per_chunk) { nk = 0; ntap = tap + 1; }
-          if (ntap < ntaps) {
-            const bf16x8_t* wp = wchunk + ((size_t)ntap * k16_total + nk) * e.wstride8;
-#pragma unroll
-            for (int nj = 0; nj < WN; ++nj) bnxt[nj] = wp[nj * 64];
-          }
-          bf16x8_t a[4];
-#pragma unroll
-          for (int mi = 0; mi < 4; ++mi) a[mi] = *(const bf16x8_t*)(lds + abase[mi] + toff + k * 32);
-#pragma unroll
-          for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-            for (int nj = 0; nj < WN; ++nj)
-              acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mi], bcur[nj], acc[mi][nj], 0, 0, 0);
-#pragma unroll
-          for (int nj = 0; nj < WN; ++nj) bcur[nj] = bnxt[nj];
+          for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[nb.boff + nj * 64];
         }
       }
+      sr_stage_dma(e, zero_page, lds, Q0, n_pos, chunk, tid);
+      asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
+      __syncthreads();                                     // ... and everybody else's
+      sr_stage_compute<WN>(e, lds, abase, wchunk, bq, acc, NS);
     }
   }
 
   // ---- epilogue: bias, activation, round to bf16, NHWC store.
   // Accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-  uint16_t* out = (uint16_t*)nd.out[cur];
+  __attribute__((address_space(1))) uint16_t* out =
+      (__attribute__((address_space(1))) uint16_t*)(unsigned long long)nd->out[cur];
+  const __attribute__((address_space(1))) float* biasp =
+      (const __attribute__((address_space(1))) float*)(unsigned long long)nd->bias;
+  const int Cp = nd->Cp, act = nd->act;
 #pragma unroll
   for (int nj = 0; nj < WN; ++nj) {
     const int col = wave_n0 + nj * 32 + (lane & 31);
-    const float bias = nd.bias[col];
+    const float bias = biasp[col];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
       for (int r = 0; r < 16; ++r) {
         const int row = wave_m0 + mi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < nd.M) {
+        if (row < M) {
           float v = acc[mi][nj][r] + bias;
-          if (nd.act == 1) v = fmaxf(v, 0.f);
-          out[(size_t)row * nd.Cp + col] = float_to_bf16_bits(v);
+          if (act == 1) v = fmaxf(v, 0.f);
+          out[(size_t)row * Cp + col] = float_to_bf16_bits(v);
         }
       }
     }
@@ -372,9 +458,9 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(const SrCtx* __restrict
                                                          const SrMfmaTile* __restrict__ tiles) {
   extern __shared__ __align__(16) unsigned char sr_lds[];
   const SrMfmaTile t = tiles[blockIdx.x];
-  const SrMfmaNode nd = nodes[t.node];
-  if (nd.wn_tiles == 2) sr_mfma_tile<2>(ctx, nd, edges, t, sr_lds);
-  else sr_mfma_tile<1>(ctx, nd, edges, t, sr_lds);
+  const int node_index = SR_UNIFORM(t.node);
+  if (nodes[node_index].wn_tiles == 2) sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), sr_lds);
+  else sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), sr_lds);
 }
 
 // ---------------------------------------------------------------------------
@@ -448,6 +534,13 @@ hipError_t sr_launch_direct(hipStream_t s, const SrCtx* ctx, const SrDirectNode*
 hipError_t sr_launch_mfma(hipStream_t s, const SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
                           const SrMfmaTile* tiles, int n_tiles, int lds_bytes) {
   if (n_tiles == 0) return hipSuccess;
+  static bool attr_set = false;
+  if (!attr_set) {   // dynamic LDS above 64 KiB has to be requested once
+    hipError_t e = hipFuncSetAttribute((const void*)sr_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       sr_mfma_max_lds_bytes());
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
   hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles), dim3(256), lds_bytes, s, ctx, nodes, edges, tiles);
   return hipGetLastError();
 }
@@ -465,4 +558,4 @@ hipError_t sr_launch_head(hipStream_t s, const SrCtx* ctx, const SrHead* heads, 
   return hipGetLastError();
 }
 
-int sr_mfma_max_lds_bytes() { return 64 * 1024; }
+int sr_mfma_max_lds_bytes() { return 80 * 1024; }   // two workgroups per CU share 160 KiB
