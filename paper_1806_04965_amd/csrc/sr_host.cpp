@@ -432,6 +432,7 @@ sr_status finalize(sr_graph* g) {
           if ((uint64_t)slots * (KC / 8 + 1) + 256 > magic_range((uint32_t)(KC / 8 + 1))) ok = false;
           if (!ok) break;
           g->lds_bytes = std::max<int>(g->lds_bytes, (int)(slots * m.SP));
+          g->lds_bytes = std::max<int>(g->lds_bytes, 4 * 64 * (32 * wn_tiles * 2 + 16));
           ksum += (double)sn.Cp * m.kh * m.kw;
           me.push_back(m);
         }

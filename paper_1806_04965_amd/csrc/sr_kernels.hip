@@ -19,6 +19,8 @@
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
+typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
 
 // ---------------------------------------------------------------------------
 // bfloat16 <-> float (round to nearest even)
@@ -224,7 +226,7 @@ __global__ __launch_bounds__(256) void sr_head_dense_kernel(const SrCtx* __restr
 // B operand (weights): pre-packed on the host in exactly the per-lane order of the instruction,
 // [tap][k16 block][32-channel tile][lane][8], so a wave's fragment is one coalesced 1 KiB load
 // straight into registers, prefetched a few k-steps ahead through a small ring.
-#define SR_RING 3   // depth of the weight-fragment and A-fragment rings; the step loop is unrolled by it
+#define SR_RING 4   // depth of the weight-fragment ring; the step loop is unrolled by it
 
 typedef const __attribute__((address_space(1))) bf16x8_t* sr_gfrag_ptr;   // global memory
 #define SR_UNIFORM(x) __builtin_amdgcn_readfirstlane(x)
@@ -260,15 +262,19 @@ __device__ __forceinline__ SrEdgeK sr_load_edge(const SrMfmaEdge* edges, int ind
   return k;
 }
 
-// Issue the direct-to-LDS loads of one stage: KC channels of every padded source pixel in the
-// tile's patch.  Position P (16-byte units) of the LDS buffer is piece P % (CH+1) of slot
-// P / (CH+1); the last piece of a slot is the spare one and is never written.  Lanes whose pixel
-// is padding or outside the image read a zero page instead.
-__device__ __forceinline__ void sr_stage_dma(const SrEdgeK& e, const unsigned char* __restrict__ zero_page,
-                                             unsigned char* lds, int Q0, int n_pos, int chunk, int tid) {
-  const int lane = tid & 63;
-  for (int P0 = tid - lane; P0 < n_pos; P0 += 256) {   // P0: first position of this wave's 1 KiB piece
-    const int P = P0 + lane;
+// Direct-to-LDS staging.  Position P (16-byte units) of the LDS buffer is piece P % (CH+1) of
+// slot P / (CH+1); the last piece of a slot is the spare one and is never written.  Which source
+// bytes a position holds does not depend on the channel chunk, so every thread decodes its
+// positions once per edge (sr_dma_plan) into byte offsets from the source tensor, and a stage
+// only adds the chunk's channel offset (sr_stage_dma).  Padding pixels read a zero page.
+#define SR_DMA_ITEMS 16        // positions per thread: 64 KiB of LDS / 16 bytes / 256 threads
+#define SR_DMA_ZERO (-1)
+#define SR_DMA_SKIP (-2)
+
+__device__ __forceinline__ void sr_dma_plan(const SrEdgeK& e, int Q0, int n_pos, int tid, int (&off)[SR_DMA_ITEMS]) {
+#pragma unroll
+  for (int it = 0; it < SR_DMA_ITEMS; ++it) {
+    const int P = tid + it * 256;
     const int slot = __umulhi((unsigned)P, e.magicCH1);
     const int piece = P - slot * e.CH1;
     const int q = __umulhi((unsigned)slot, e.magicRP);
@@ -279,13 +285,27 @@ __device__ __forceinline__ void sr_stage_dma(const SrEdgeK& e, const unsigned ch
     const int b = __umulhi((unsigned)Qg, e.magicPH);
     const int iy = Qg - b * e.PH - e.pad;
     const int ix = px - e.pad;
-    const unsigned char* g = zero_page;
-    if (iy >= 0 && iy < e.Hs && ix >= 0 && ix < e.Ws)
-      g = e.src + (((size_t)(b * e.Hs + iy) * e.Ws + ix) * e.Csp + chunk * e.KC + piece * 8) * 2;
-    if (P < n_pos && px < e.PW && piece < e.CH1 - 1)
-      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                       (__attribute__((address_space(3))) void*)(lds + (size_t)SR_UNIFORM(P0) * 16),
-                                       16, 0, 0);
+    int o = SR_DMA_ZERO;
+    if (iy >= 0 && iy < e.Hs && ix >= 0 && ix < e.Ws) o = (((b * e.Hs + iy) * e.Ws + ix) * e.Csp + piece * 8) * 2;
+    if (P >= n_pos || px >= e.PW || piece >= e.CH1 - 1) o = SR_DMA_SKIP;
+    off[it] = o;
+  }
+}
+
+__device__ __forceinline__ void sr_stage_dma(const SrEdgeK& e, const unsigned char* __restrict__ zero_page,
+                                             unsigned char* lds, int n_pos, int chunk, int tid,
+                                             const int (&off)[SR_DMA_ITEMS]) {
+  const int wave_pos = SR_UNIFORM(tid & ~63);
+  const unsigned char* srcc = e.src + (size_t)chunk * e.KC * 2;
+#pragma unroll
+  for (int it = 0; it < SR_DMA_ITEMS; ++it) {
+    const int P0 = wave_pos + it * 256;     // first position of this wave's 1 KiB piece
+    if (P0 < n_pos) {
+      const unsigned char* g = (off[it] == SR_DMA_ZERO) ? zero_page : srcc + off[it];
+      if (off[it] != SR_DMA_SKIP)
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
+                                         (__attribute__((address_space(3))) void*)(lds + (size_t)P0 * 16), 16, 0, 0);
+    }
   }
 }
 
@@ -303,55 +323,46 @@ __device__ __forceinline__ SrStep sr_step_decode(const SrEdgeK& e, int st) {
   return r;
 }
 
-// One stage of the contraction: NS = taps * KC/16 k-steps over the patch in LDS.  Weight fragments
-// run SR_RING steps ahead, A fragments one step ahead; the loop body is SR_RING steps so that
-// every ring slot has a fixed register.
+// One k-step: 4 x WN MFMAs.  Each A fragment is reloaded for the next step right after its last
+// use, which leaves the other rows' MFMAs to cover the LDS latency; the weight fragments of ring
+// slot u are replaced by those of step st + SR_RING once all rows have used them.
+template <int WN>
+__device__ __forceinline__ void sr_step(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
+                                        sr_gfrag_ptr wchunk, bf16x8_t (&a)[4], bf16x8_t (&b)[WN],
+                                        f32x16_t (&acc)[4][WN], int st, int NS) {
+  const bool more_a = st + 1 < NS;
+  const SrStep nx = sr_step_decode(e, more_a ? st + 1 : st);
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+    for (int nj = 0; nj < WN; ++nj)
+      acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[nj], a[mi], acc[mi][nj], 0, 0, 0);
+    if (more_a) a[mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
+  }
+  if (st + SR_RING < NS) {
+    const SrStep nb = sr_step_decode(e, st + SR_RING);
+#pragma unroll
+    for (int nj = 0; nj < WN; ++nj) b[nj] = wchunk[nb.boff + nj * 64];
+  }
+}
+
+// One stage of the contraction: NS = taps * KC/16 k-steps over the patch in LDS.
 template <int WN>
 __device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
                                                  sr_gfrag_ptr wchunk, bf16x8_t (&bq)[SR_RING][WN],
                                                  f32x16_t (&acc)[4][WN], int NS) {
-  bf16x8_t a[SR_RING][4];
+  bf16x8_t a[4];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi) a[0][mi] = *(const bf16x8_t*)(lds + abase[mi]);
+  for (int mi = 0; mi < 4; ++mi) a[mi] = *(const bf16x8_t*)(lds + abase[mi]);
   int st0 = 0;
   for (; st0 + SR_RING <= NS; st0 += SR_RING) {
 #pragma unroll
-    for (int u = 0; u < SR_RING; ++u) {
-      const int st = st0 + u;
-      if (st + 1 < NS) {
-        const SrStep nx = sr_step_decode(e, st + 1);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) a[(u + 1) % SR_RING][mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
-      }
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int nj = 0; nj < WN; ++nj)
-          acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][mi], bq[u][nj], acc[mi][nj], 0, 0, 0);
-      if (st + SR_RING < NS) {
-        const SrStep nb = sr_step_decode(e, st + SR_RING);
-#pragma unroll
-        for (int nj = 0; nj < WN; ++nj) bq[u][nj] = wchunk[nb.boff + nj * 64];
-      }
-    }
+    for (int u = 0; u < SR_RING; ++u) sr_step<WN>(e, lds, abase, wchunk, a, bq[u], acc, st0 + u, NS);
   }
-  // remaining 0..SR_RING-1 steps (their fragments are already in ring slots 0, 1, ...)
+  // remaining 0..SR_RING-1 steps (their weight fragments are already in ring slots 0, 1, ...)
 #pragma unroll
-  for (int u = 0; u < SR_RING - 1; ++u) {
-    const int st = st0 + u;
-    if (st < NS) {
-      if (st + 1 < NS) {
-        const SrStep nx = sr_step_decode(e, st + 1);
-#pragma unroll
-        for (int mi = 0; mi < 4; ++mi) a[u + 1][mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
-      }
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int nj = 0; nj < WN; ++nj)
-          acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[u][mi], bq[u][nj], acc[mi][nj], 0, 0, 0);
-    }
-  }
+  for (int u = 0; u < SR_RING - 1; ++u)
+    if (st0 + u < NS) sr_step<WN>(e, lds, abase, wchunk, a, bq[u], acc, st0 + u, NS);
 }
 
 template <int WN>
@@ -404,6 +415,8 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       const int ox = r - oy * Wo;
       abase[mi] = ((b * e.PH + (oy / e.up) * e.stride - Q0) * e.RP + ox / e.up) * e.SP + (lane >> 5) * 16;
     }
+    int dma_off[SR_DMA_ITEMS];
+    sr_dma_plan(e, Q0, n_pos, tid, dma_off);
     const sr_gfrag_ptr wlane = e.wpk + ntile0 * 64 + lane;
     const int NS = e.ntaps << e.lgK16;
     for (int chunk = 0; chunk < e.nchunk; ++chunk) {
@@ -419,7 +432,7 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
           for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[nb.boff + nj * 64];
         }
       }
-      sr_stage_dma(e, zero_page, lds, Q0, n_pos, chunk, tid);
+      sr_stage_dma(e, zero_page, lds, n_pos, chunk, tid, dma_off);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
       __syncthreads();                                     // ... and everybody else's
       sr_stage_compute<WN>(e, lds, abase, wchunk, bq, acc, NS);
@@ -427,27 +440,57 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
   }
 
   // ---- epilogue: bias, activation, round to bf16, NHWC store.
-  // Accumulator layout: register r of lane l holds row 8*(r/4) + 4*(l/32) + r%4, column l%32.
-  __attribute__((address_space(1))) uint16_t* out =
-      (__attribute__((address_space(1))) uint16_t*)(unsigned long long)nd->out[cur];
+  // The weights are the MFMA's row operand, so register r of lane l holds channel
+  // 8*(r/4) + 4*(l/32) + r%4 of pixel l%32: four consecutive channels per register quad.  Each
+  // wave transposes its tile through its own LDS region (64 pixels at a time, rows of 32*WN
+  // channels + 16 spare bytes) so that global stores are 16 bytes per lane and whole pixel rows.
+  __attribute__((address_space(1))) unsigned char* out =
+      (__attribute__((address_space(1))) unsigned char*)(unsigned long long)nd->out[cur];
   const __attribute__((address_space(1))) float* biasp =
       (const __attribute__((address_space(1))) float*)(unsigned long long)nd->bias;
   const int Cp = nd->Cp, act = nd->act;
+  constexpr int EP = 32 * WN * 2 + 16;          // bytes per pixel row in LDS
+  constexpr int PIECES = 32 * WN * 2 / 16;      // 16-byte pieces per pixel row
+  unsigned char* my = lds + wave * (64 * EP);
+  float bias[WN][4][4];
 #pragma unroll
-  for (int nj = 0; nj < WN; ++nj) {
-    const int col = wave_n0 + nj * 32 + (lane & 31);
-    const float bias = biasp[col];
+  for (int nj = 0; nj < WN; ++nj)
 #pragma unroll
-    for (int mi = 0; mi < 4; ++mi) {
+    for (int gq = 0; gq < 4; ++gq)
 #pragma unroll
-      for (int r = 0; r < 16; ++r) {
-        const int row = wave_m0 + mi * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-        if (row < M) {
-          float v = acc[mi][nj][r] + bias;
-          if (act == 1) v = fmaxf(v, 0.f);
-          out[(size_t)row * Cp + col] = float_to_bf16_bits(v);
+      for (int i = 0; i < 4; ++i) bias[nj][gq][i] = biasp[wave_n0 + nj * 32 + 8 * gq + 4 * (lane >> 5) + i];
+  __syncthreads();   // every wave has finished reading the last patch
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int mh = 0; mh < 2; ++mh) {
+      const int mi = half * 2 + mh;
+#pragma unroll
+      for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          uint16_t h[4];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float v = acc[mi][nj][gq * 4 + i] + bias[nj][gq][i];
+            if (act == 1) v = fmaxf(v, 0.f);
+            h[i] = float_to_bf16_bits(v);
+          }
+          u32x2_t pk;
+          pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
+          pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
+          *(u32x2_t*)(my + (mh * 32 + (lane & 31)) * EP + (nj * 32 + 8 * gq + 4 * (lane >> 5)) * 2) = pk;
         }
-      }
+    }
+    // same wave reads what it wrote: LDS operations of one wave complete in order
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int p = it * 64 + lane;
+      const int row = p / PIECES, piece = p - row * PIECES;
+      const int m = wave_m0 + half * 64 + row;
+      const u32x4_t v = *(const u32x4_t*)(my + row * EP + piece * 16);
+      if (m < M)
+        *(__attribute__((address_space(1))) u32x4_t*)(out + ((size_t)m * Cp + wave_n0) * 2 + piece * 16) = v;
     }
   }
 }
@@ -558,4 +601,4 @@ hipError_t sr_launch_head(hipStream_t s, const SrCtx* ctx, const SrHead* heads, 
   return hipGetLastError();
 }
 
-int sr_mfma_max_lds_bytes() { return 80 * 1024; }   // two workgroups per CU share 160 KiB
+int sr_mfma_max_lds_bytes() { return 64 * 1024; }   // two workgroups per CU, 160 KiB in all
