@@ -9,6 +9,7 @@
 #include <cstring>
 #include <new>
 #include <string>
+#include <unordered_map>
 #include <vector>
 
 #include "../../include/sr.h"
@@ -180,6 +181,8 @@ struct sr_graph {
   SrMfmaNode* m_nodes = nullptr;
   SrMfmaEdge* m_edges = nullptr;
   SrMfmaTile* m_tiles = nullptr;
+  int32_t* plan_index = nullptr;
+  int32_t* plan_tables = nullptr;
   SrHead* heads = nullptr;
   void* zero_page = nullptr;
   int lds_bytes = 0;
@@ -262,30 +265,74 @@ bool mfma_eligible(const sr_graph* g, int v) {
     any = true;
     if (e.d.kind != SR_EDGE_CONV) return false;
     if (e.d.stride != 1 && e.d.stride != 2 && e.d.stride != 4) return false;
+    if (e.d.upsample != 1 && e.d.upsample != 2 && e.d.upsample != 4) return false;
   }
+  if (n.d.height > 4095 || n.d.width > 4095) return false;
   return any;
 }
 
-// Patch geometry of one (node tiling, edge): maximum number of LDS slots over all tiles.
-int64_t max_patch_slots(const sr_graph* g, int v, const EdgeRt& e, int BM) {
+// Patch geometry of one (tile, edge): padded source rows Q0..Q1 that the tile's pixels touch.
+struct PatchRows { int64_t b0, oy0, Q0, Q1; };
+PatchRows patch_rows(int64_t m0, int64_t m1, int HoWo, int Wo, int PH, int s, int up, int kh) {
+  PatchRows r;
+  r.b0 = m0 / HoWo;
+  r.oy0 = (m0 % HoWo) / Wo;
+  const int64_t b1 = m1 / HoWo, oy1 = (m1 % HoWo) / Wo;
+  r.Q0 = r.b0 * PH + (r.oy0 / up) * s;
+  r.Q1 = b1 * PH + (oy1 / up) * s + kh - 1;
+  return r;
+}
+
+int64_t max_patch_rows(const sr_graph* g, int v, const EdgeRt& e, int BM) {
   const sr_node_desc& dn = g->nodes[v].d;
   const sr_node_desc& sn = g->nodes[e.d.src].d;
-  const int Ho = dn.height, Wo = dn.width, HoWo = Ho * Wo;
+  const int HoWo = dn.height * dn.width;
   const int64_t M = (int64_t)g->batch * HoWo;
-  const int s = e.d.stride, up = e.d.upsample;
-  const int PH = sn.height + 2 * e.d.pad, PW = sn.width + 2 * e.d.pad;
-  const int PWs = (PW + s - 1) / s, RP = s * PWs;
-  (void)PW;
+  const int PH = sn.height + 2 * e.d.pad;
   int64_t worst = 0;
   for (int64_t m0 = 0; m0 < M; m0 += BM) {
-    int64_t m1 = std::min<int64_t>(m0 + BM, M) - 1;
-    int64_t b0 = m0 / HoWo, oy0 = (m0 % HoWo) / Wo;
-    int64_t b1 = m1 / HoWo, oy1 = (m1 % HoWo) / Wo;
-    int64_t Q0 = b0 * PH + (oy0 / up) * s;
-    int64_t Q1 = b1 * PH + (oy1 / up) * s + e.d.kh - 1;
-    worst = std::max(worst, (Q1 - Q0 + 1) * RP);
+    PatchRows r = patch_rows(m0, std::min<int64_t>(m0 + BM, M) - 1, HoWo, dn.width, PH, e.d.stride, e.d.upsample, e.d.kh);
+    worst = std::max(worst, r.Q1 - r.Q0 + 1);
   }
   return worst;
+}
+
+// Row pitch of the LDS patch in 16-byte units: at least RP slots of CH1 pieces, and chosen so
+// that stepping from the last pixel of an output row to the first pixel of the next one moves
+// by the same number of 16-byte columns (mod 16) as stepping to the next pixel inside a row;
+// sixteen consecutive pixels then always fall into sixteen different LDS columns.
+int row_pitch16(int RP, int CH1, int s, int up, int Wo) {
+  const int base = RP * CH1;
+  if (up != 1) return base;
+  for (int r = base; r < base + 16; ++r)
+    if ((s * r) % 16 == (Wo * CH1) % 16) return r;
+  return base;
+}
+
+// Direct-to-LDS plan of one (tile, edge): for every 16-byte LDS position the byte offset of its
+// source relative to (image b0, source row iy_first), or ZERO (padding) / SKIP (not written).
+void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows& r) {
+  const int CH1 = m.KC / 8 + 1, CH = CH1 - 1;
+  const int RPB16 = m.RPB / 16;
+  const int64_t NQ = r.Q1 - r.Q0 + 1;
+  const int64_t n_pos = NQ * RPB16;
+  const int64_t padded = (n_pos + 255) / 256 * 256;
+  out->assign((size_t)padded, -2);
+  const int64_t iy_first = (r.oy0 / m.up) * m.stride - m.pad;
+  for (int64_t q = 0; q < NQ; ++q) {
+    const int64_t Qg = r.Q0 + q, b = Qg / m.PH, iy = Qg % m.PH - m.pad;
+    for (int col = 0; col < m.RP; ++col) {
+      const int phase = col / m.PWs, px = (col % m.PWs) * m.stride + phase;
+      if (px >= m.PW) continue;
+      const int ix = px - m.pad;
+      const bool valid = iy >= 0 && iy < m.Hs && ix >= 0 && ix < m.Ws;
+      for (int piece = 0; piece < CH; ++piece) {
+        int32_t off = -1;
+        if (valid) off = (int32_t)(((((b - r.b0) * m.Hs + iy - iy_first) * m.Ws + ix) * m.Csp) * 2 + piece * 16);
+        (*out)[(size_t)(q * RPB16 + col * CH1 + piece)] = off;
+      }
+    }
+  }
 }
 
 sr_status finalize(sr_graph* g) {
@@ -329,6 +376,8 @@ sr_status finalize(sr_graph* g) {
   std::vector<SrMfmaEdge> me;
   std::vector<SrMfmaTile> mt;
   std::vector<SrHead> hd;
+  std::vector<int32_t> plan_index, plan_tables, plan_tmp;   // per (tile, edge): offset of its plan
+  std::unordered_map<uint64_t, std::vector<int>> plan_seen;
   g->levels.assign(F + 1, LevelPlan());
   const int lds_cap = sr_mfma_max_lds_bytes();
   g->lds_bytes = 0;
@@ -406,32 +455,28 @@ sr_status finalize(sr_graph* g) {
           m.PW = m.Ws + 2 * m.pad;
           m.PWs = (m.PW + m.stride - 1) / m.stride;
           m.RP = m.stride * m.PWs;
-          m.magicRP = magic_for((uint32_t)m.RP);
-          m.magicPWs = magic_for((uint32_t)m.PWs);
-          m.magicPH = magic_for((uint32_t)m.PH);
           m.wstride8 = (Cout / 32) * 64;
-          const int64_t slots = max_patch_slots(g, v, e, BM);
+          const int64_t rows = max_patch_rows(g, v, e, BM);
           int KC = 0;
-          for (int cand : {64, 32, 16})
-            if (sn.Cp % cand == 0 && slots * (cand * 2 + 16) <= lds_cap) { KC = cand; break; }
-          // the staging loop divides slot indices by PW and padded row indices by PH with a
-          // multiply-high; make sure both stay inside the range where that is exact
-          if (KC == 0 || (uint64_t)slots + 256 > magic_range((uint32_t)m.RP) ||
-              (uint64_t)m.RP > magic_range((uint32_t)m.PWs) ||
-              (uint64_t)B * m.PH + slots > magic_range((uint32_t)m.PH)) {
-            ok = false;
-            break;
+          for (int cand : {64, 32, 16}) {
+            const int pitch = row_pitch16(m.RP, cand / 8 + 1, m.stride, m.up, n.d.width);
+            // a patch must fit the LDS budget (= 20 plan positions for each of the 256 threads)
+            if (sn.Cp % cand == 0 && rows * pitch * 16 <= lds_cap) {
+              KC = cand;
+              m.RPB = pitch * 16;
+              break;
+            }
           }
+          const int64_t imgs_per_tile = BM / ((int64_t)n.d.height * n.d.width) + 2;
+          if (KC == 0 || imgs_per_tile > 255) { ok = false; break; }
           m.KC = KC;
           m.nchunk = sn.Cp / KC;
           m.SP = KC * 2 + 16;
-          m.magicCH1 = magic_for((uint32_t)(KC / 8 + 1));
           m.magicKW = (int32_t)((65536 + m.kw - 1) / m.kw);
           for (int tap = 0; tap < m.kh * m.kw; ++tap)
             if (((tap * m.magicKW) >> 16) != tap / m.kw) ok = false;
-          if ((uint64_t)slots * (KC / 8 + 1) + 256 > magic_range((uint32_t)(KC / 8 + 1))) ok = false;
           if (!ok) break;
-          g->lds_bytes = std::max<int>(g->lds_bytes, (int)(slots * m.SP));
+          g->lds_bytes = std::max<int>(g->lds_bytes, (int)(rows * m.RPB));
           g->lds_bytes = std::max<int>(g->lds_bytes, 4 * 64 * (32 * wn_tiles * 2 + 16));
           ksum += (double)sn.Cp * m.kh * m.kw;
           me.push_back(m);
@@ -457,6 +502,25 @@ sr_status finalize(sr_graph* g) {
                 t.node = node_index;
                 t.m0 = mi * BM;
                 t.n0 = nt * BN;
+                t.plan_begin = (int)plan_index.size();
+                for (int ei = 0; ei < node.edge_count; ++ei) {
+                  const SrMfmaEdge& m = me[node.edge_begin + ei];
+                  const PatchRows r = patch_rows(t.m0, std::min<int64_t>((int64_t)t.m0 + BM, M) - 1,
+                                                 n.d.height * n.d.width, n.d.width, m.PH, m.stride, m.up, m.kh);
+                  build_plan(&plan_tmp, m, r);
+                  uint64_t h = 1469598103934665603ull ^ (uint64_t)(node.edge_begin + ei);
+                  for (int32_t x : plan_tmp) h = (h ^ (uint32_t)x) * 1099511628211ull;
+                  int found = -1;
+                  for (int cand : plan_seen[h])
+                    if (plan_tables.size() >= (size_t)cand + plan_tmp.size() &&
+                        std::equal(plan_tmp.begin(), plan_tmp.end(), plan_tables.begin() + cand)) { found = cand; break; }
+                  if (found < 0) {
+                    found = (int)plan_tables.size();
+                    plan_tables.insert(plan_tables.end(), plan_tmp.begin(), plan_tmp.end());
+                    plan_seen[h].push_back(found);
+                  }
+                  plan_index.push_back(found);
+                }
                 grp.tiles.push_back(t);
               }
           groups.push_back(std::move(grp));
@@ -548,6 +612,9 @@ sr_status finalize(sr_graph* g) {
   if ((st = upload(g, &g->d_nodes, dn)) != SR_OK) return st;
   if ((st = upload(g, &g->d_edges, de)) != SR_OK) return st;
   if ((st = upload(g, &g->d_blocks, db)) != SR_OK) return st;
+  if ((st = upload(g, &g->plan_index, plan_index)) != SR_OK) return st;
+  if ((st = upload(g, &g->plan_tables, plan_tables)) != SR_OK) return st;
+  for (SrMfmaNode& node : mn) { node.plan_index = g->plan_index; node.plan_tables = g->plan_tables; }
   if ((st = upload(g, &g->m_nodes, mn)) != SR_OK) return st;
   if ((st = upload(g, &g->m_edges, me)) != SR_OK) return st;
   if ((st = upload(g, &g->m_tiles, mt)) != SR_OK) return st;

@@ -62,11 +62,8 @@ struct SrMfmaEdge {
   int32_t PWs;           // ceil(PW / stride): width of one column-phase plane
   int32_t RP;            // slots per patch row: stride * PWs
   int32_t SP;            // bytes per slot: KC*2 + 16 (one spare 16-byte piece rotates the LDS banks)
-  uint32_t magicRP;      // ceil(2^32 / RP): x / RP == umulhi(x, magic) over the range the host checked
-  uint32_t magicPWs;     // ceil(2^32 / PWs)
-  uint32_t magicCH1;     // ceil(2^32 / (KC/8 + 1))
+  int32_t RPB;           // bytes per patch row in LDS: >= RP*SP, tuned so that row wraps stay conflict-free
   int32_t magicKW;       // ceil(2^16 / kw): tap / kw == (tap * magic) >> 16 for tap < kh*kw (checked on host)
-  uint32_t magicPH;      // ceil(2^32 / PH)
   int32_t wstride8;      // 16-byte units between consecutive k16 blocks in wpk: (Cout/32)*64
   int32_t pad_;
 };
@@ -74,6 +71,9 @@ struct SrMfmaEdge {
 struct SrMfmaNode {
   void* out[2];          // bf16 state [M][Cp]
   const float* bias;     // [Cout]
+  const void* zero_page; // 256 zero bytes: source of padding pixels for the direct-to-LDS loads
+  const int32_t* plan_index;   // [tile.plan_begin + edge]: offset of that (tile, edge) plan in plan_tables
+  const int32_t* plan_tables;  // per LDS position: source byte offset, -1 zero page, -2 not written
   int32_t M;             // B*Ho*Wo
   int32_t Ho, Wo;
   int32_t Cout, Cp;
@@ -82,14 +82,13 @@ struct SrMfmaNode {
   int32_t waves_m, waves_n;   // 4 waves arranged waves_m x waves_n; BM = 128*waves_m
   int32_t wn_tiles;           // 32-wide MFMA column tiles per wave: 1 or 2; BN = 32*wn_tiles*waves_n
   int32_t pad_;
-  const void* zero_page; // 256 zero bytes: source of padding pixels for the direct-to-LDS loads
 };
 
 struct SrMfmaTile {
   int32_t node;
   int32_t m0;    // first output pixel (linear over [B][Ho][Wo])
   int32_t n0;    // first output channel
-  int32_t pad_;
+  int32_t plan_begin;  // first entry of this tile in plan_index (one per incoming edge)
 };
 
 // ---------------------------------------------------------------------------

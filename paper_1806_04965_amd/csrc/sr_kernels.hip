@@ -21,6 +21,7 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16_t;
 typedef unsigned int u32x4_t __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x2_t __attribute__((ext_vector_type(2)));
+typedef __attribute__((__vector_size__(4 * sizeof(__bf16)))) __bf16 bf16x4_t;
 
 // ---------------------------------------------------------------------------
 // bfloat16 <-> float (round to nearest even)
@@ -236,8 +237,7 @@ typedef const __attribute__((address_space(1))) bf16x8_t* sr_gfrag_ptr;   // glo
 struct SrEdgeK {
   const unsigned char* src;
   sr_gfrag_ptr wpk;
-  int Hs, Ws, Csp, kw, ntaps, stride, lgs, pad, up, KC, lgK16, nchunk, PH, PW, PWs, RP, SP, CH1;
-  unsigned magicRP, magicPWs, magicPH, magicCH1;
+  int Hs, Ws, Csp, kw, kh, ntaps, stride, lgs, lgup, pad, KC, lgK16, nchunk, PH, PWs, SP, RPB;
   int magicKW, wstride8, k16_total;
 };
 
@@ -249,59 +249,48 @@ __device__ __forceinline__ SrEdgeK sr_load_edge(const SrMfmaEdge* edges, int ind
   k.src = (const unsigned char*)p->src[bridge ? (cur ^ 1) : cur];
   k.wpk = (sr_gfrag_ptr)(unsigned long long)p->wpk;
   k.Hs = p->Hs; k.Ws = p->Ws; k.Csp = p->Csp;
-  k.kw = p->kw; k.ntaps = p->kh * p->kw;
+  k.kw = p->kw; k.kh = p->kh; k.ntaps = k.kh * k.kw;
   k.stride = p->stride; k.lgs = (k.stride == 1) ? 0 : (k.stride == 2 ? 1 : 2);
-  k.pad = p->pad; k.up = p->up;
+  const int up = p->up;
+  k.lgup = (up == 1) ? 0 : (up == 2 ? 1 : 2);
+  k.pad = p->pad;
   k.KC = p->KC; k.lgK16 = (k.KC == 16) ? 0 : (k.KC == 32 ? 1 : 2);
   k.nchunk = p->nchunk;
-  k.PH = p->PH; k.PW = p->PW; k.PWs = p->PWs; k.RP = p->RP; k.SP = p->SP;
-  k.CH1 = (k.KC >> 3) + 1;
-  k.magicRP = p->magicRP; k.magicPWs = p->magicPWs; k.magicPH = p->magicPH; k.magicCH1 = p->magicCH1;
+  k.PH = p->PH; k.PWs = p->PWs; k.SP = p->SP; k.RPB = p->RPB;
   k.magicKW = p->magicKW; k.wstride8 = p->wstride8;
   k.k16_total = k.Csp >> 4;
   return k;
 }
 
-// Direct-to-LDS staging.  Position P (16-byte units) of the LDS buffer is piece P % (CH+1) of
-// slot P / (CH+1); the last piece of a slot is the spare one and is never written.  Which source
-// bytes a position holds does not depend on the channel chunk, so every thread decodes its
-// positions once per edge (sr_dma_plan) into byte offsets from the source tensor, and a stage
-// only adds the chunk's channel offset (sr_stage_dma).  Padding pixels read a zero page.
-#define SR_DMA_ITEMS 16        // positions per thread: 64 KiB of LDS / 16 bytes / 256 threads
+// Direct-to-LDS staging.  The LDS patch is an array of 16-byte positions: row q (padded source
+// row relative to the tile's first one) starts at q*RPB, slot c of a row at c*SP, piece p of a
+// slot at p*16; the last piece of a slot is the spare one.  Which source bytes a position holds
+// does not depend on the channel chunk, so the host tabulates it once per (tile, edge) --
+// identical tables are shared -- as a byte offset from the tile's first source row, or ZERO for
+// padding (read from a zero page) or SKIP for positions that are never written.  A thread keeps
+// its table entries in registers for the whole edge; a stage only adds the chunk's offset.
+#define SR_DMA_ITEMS 20        // positions per thread: 80 KiB of LDS / 16 bytes / 256 threads
 #define SR_DMA_ZERO (-1)
 #define SR_DMA_SKIP (-2)
 
-__device__ __forceinline__ void sr_dma_plan(const SrEdgeK& e, int Q0, int n_pos, int tid, int (&off)[SR_DMA_ITEMS]) {
+__device__ __forceinline__ void sr_dma_plan(const __attribute__((address_space(1))) int* __restrict__ table,
+                                            int n_pos, int tid, int (&off)[SR_DMA_ITEMS]) {
 #pragma unroll
   for (int it = 0; it < SR_DMA_ITEMS; ++it) {
-    const int P = tid + it * 256;
-    const int slot = __umulhi((unsigned)P, e.magicCH1);
-    const int piece = P - slot * e.CH1;
-    const int q = __umulhi((unsigned)slot, e.magicRP);
-    const int col = slot - q * e.RP;
-    const int phase = __umulhi((unsigned)col, e.magicPWs);
-    const int px = ((col - phase * e.PWs) << e.lgs) + phase;
-    const int Qg = Q0 + q;
-    const int b = __umulhi((unsigned)Qg, e.magicPH);
-    const int iy = Qg - b * e.PH - e.pad;
-    const int ix = px - e.pad;
-    int o = SR_DMA_ZERO;
-    if (iy >= 0 && iy < e.Hs && ix >= 0 && ix < e.Ws) o = (((b * e.Hs + iy) * e.Ws + ix) * e.Csp + piece * 8) * 2;
-    if (P >= n_pos || px >= e.PW || piece >= e.CH1 - 1) o = SR_DMA_SKIP;
-    off[it] = o;
+    off[it] = SR_DMA_SKIP;
+    if (it * 256 < n_pos) off[it] = table[tid + it * 256];   // tables are padded to 256 entries
   }
 }
 
-__device__ __forceinline__ void sr_stage_dma(const SrEdgeK& e, const unsigned char* __restrict__ zero_page,
-                                             unsigned char* lds, int n_pos, int chunk, int tid,
-                                             const int (&off)[SR_DMA_ITEMS]) {
+__device__ __forceinline__ void sr_stage_dma(const unsigned char* __restrict__ base,
+                                             const unsigned char* __restrict__ zero_page, unsigned char* lds,
+                                             int n_pos, int tid, const int (&off)[SR_DMA_ITEMS]) {
   const int wave_pos = SR_UNIFORM(tid & ~63);
-  const unsigned char* srcc = e.src + (size_t)chunk * e.KC * 2;
 #pragma unroll
   for (int it = 0; it < SR_DMA_ITEMS; ++it) {
     const int P0 = wave_pos + it * 256;     // first position of this wave's 1 KiB piece
     if (P0 < n_pos) {
-      const unsigned char* g = (off[it] == SR_DMA_ZERO) ? zero_page : srcc + off[it];
+      const unsigned char* g = (off[it] == SR_DMA_ZERO) ? zero_page : base + off[it];
       if (off[it] != SR_DMA_SKIP)
         __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
                                          (__attribute__((address_space(3))) void*)(lds + (size_t)P0 * 16), 16, 0, 0);
@@ -318,7 +307,7 @@ __device__ __forceinline__ SrStep sr_step_decode(const SrEdgeK& e, int st) {
   const int ti = (tap * e.magicKW) >> 16;
   const int tj = tap - ti * e.kw;
   SrStep r;
-  r.aoff = (ti * e.RP + (tj & (e.stride - 1)) * e.PWs + (tj >> e.lgs)) * e.SP + k * 32;
+  r.aoff = ti * e.RPB + ((tj & (e.stride - 1)) * e.PWs + (tj >> e.lgs)) * e.SP + k * 32;
   r.boff = (tap * e.k16_total + k) * e.wstride8;
   return r;
 }
@@ -368,7 +357,7 @@ __device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const unsigne
 template <int WN>
 __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
                                              const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
-                                             int tile_n0, unsigned char* lds) {
+                                             int tile_n0, int plan_begin, unsigned char* lds) {
   const __attribute__((address_space(4))) SrMfmaNode* nd =
       (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
   const int tid = threadIdx.x;
@@ -389,6 +378,22 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
   const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / Wo;
   const unsigned char* zero_page = (const unsigned char*)nd->zero_page;
   const int edge_begin = nd->edge_begin, edge_count = nd->edge_count;
+  const __attribute__((address_space(4))) int* plan_index =
+      (const __attribute__((address_space(4))) int*)(unsigned long long)nd->plan_index + plan_begin;
+  const __attribute__((address_space(1))) int* plan_tables =
+      (const __attribute__((address_space(1))) int*)(unsigned long long)nd->plan_tables;
+
+  // pixel coordinates of this lane's 4 rows, packed: ox | oy << 12 | (image - first image) << 24;
+  // rows past the end repeat the last pixel
+  int pix[4];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    const int m = min(wave_m0 + mi * 32 + (lane & 31), M - 1);
+    const int b = m / HoWo;
+    const int r = m - b * HoWo;
+    const int oy = r / Wo;
+    pix[mi] = (r - oy * Wo) | (oy << 12) | ((b - b_first) << 24);
+  }
 
   f32x16_t acc[4][WN];
 #pragma unroll
@@ -400,23 +405,21 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 
   for (int ei = 0; ei < edge_count; ++ei) {
     const SrEdgeK e = sr_load_edge(edges, edge_begin + ei, cur);
-    const int Q0 = b_first * e.PH + (oy_first / e.up) * e.stride;
-    const int Q1 = b_last * e.PH + (oy_last / e.up) * e.stride + e.ntaps / e.kw - 1;
-    const int n_pos = (Q1 - Q0 + 1) * e.RP * e.CH1;
-    // LDS byte address of the tap (0,0), k = 0 fragment of this lane's 4 rows; rows past the end
-    // repeat the last pixel
+    const int row_first = (oy_first >> e.lgup) << e.lgs;          // first padded source row, in its image
+    const int Q0 = b_first * e.PH + row_first;
+    const int Q1 = b_last * e.PH + ((oy_last >> e.lgup) << e.lgs) + e.kh - 1;
+    const int n_pos = (Q1 - Q0 + 1) * (e.RPB >> 4);
+    int dma_off[SR_DMA_ITEMS];
+    sr_dma_plan(plan_tables + plan_index[ei], n_pos, tid, dma_off);
+    // plan offsets count from source row (row_first - pad) of image b_first
+    const unsigned char* dma_base = e.src + ((long long)(b_first * e.Hs + row_first - e.pad) * e.Ws) * e.Csp * 2;
+    // LDS byte address of the tap (0,0), k = 0 fragment of this lane's 4 rows
     int abase[4];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
-      const int m = min(wave_m0 + mi * 32 + (lane & 31), M - 1);
-      const int b = m / HoWo;
-      const int r = m - b * HoWo;
-      const int oy = r / Wo;
-      const int ox = r - oy * Wo;
-      abase[mi] = ((b * e.PH + (oy / e.up) * e.stride - Q0) * e.RP + ox / e.up) * e.SP + (lane >> 5) * 16;
+      const int ox = pix[mi] & 0xfff, oy = (pix[mi] >> 12) & 0xfff, db = pix[mi] >> 24;
+      abase[mi] = (db * e.PH + ((oy >> e.lgup) << e.lgs) - row_first) * e.RPB + (ox >> e.lgup) * e.SP + (lane >> 5) * 16;
     }
-    int dma_off[SR_DMA_ITEMS];
-    sr_dma_plan(e, Q0, n_pos, tid, dma_off);
     const sr_gfrag_ptr wlane = e.wpk + ntile0 * 64 + lane;
     const int NS = e.ntaps << e.lgK16;
     for (int chunk = 0; chunk < e.nchunk; ++chunk) {
@@ -432,7 +435,7 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
           for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[nb.boff + nj * 64];
         }
       }
-      sr_stage_dma(e, zero_page, lds, n_pos, chunk, tid, dma_off);
+      sr_stage_dma(dma_base + (size_t)chunk * e.KC * 2, zero_page, lds, n_pos, tid, dma_off);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
       __syncthreads();                                     // ... and everybody else's
       sr_stage_compute<WN>(e, lds, abase, wchunk, bq, acc, NS);
@@ -469,17 +472,14 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       for (int nj = 0; nj < WN; ++nj)
 #pragma unroll
         for (int gq = 0; gq < 4; ++gq) {
-          uint16_t h[4];
+          bf16x4_t h;
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             float v = acc[mi][nj][gq * 4 + i] + bias[nj][gq][i];
             if (act == 1) v = fmaxf(v, 0.f);
-            h[i] = float_to_bf16_bits(v);
+            h[i] = (__bf16)v;      // round to nearest even
           }
-          u32x2_t pk;
-          pk.x = (uint32_t)h[0] | ((uint32_t)h[1] << 16);
-          pk.y = (uint32_t)h[2] | ((uint32_t)h[3] << 16);
-          *(u32x2_t*)(my + (mh * 32 + (lane & 31)) * EP + (nj * 32 + 8 * gq + 4 * (lane >> 5)) * 2) = pk;
+          *(bf16x4_t*)(my + (mh * 32 + (lane & 31)) * EP + (nj * 32 + 8 * gq + 4 * (lane >> 5)) * 2) = h;
         }
     }
     // same wave reads what it wrote: LDS operations of one wave complete in order
@@ -502,8 +502,10 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(const SrCtx* __restrict
   extern __shared__ __align__(16) unsigned char sr_lds[];
   const SrMfmaTile t = tiles[blockIdx.x];
   const int node_index = SR_UNIFORM(t.node);
-  if (nodes[node_index].wn_tiles == 2) sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), sr_lds);
-  else sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), sr_lds);
+  if (nodes[node_index].wn_tiles == 2)
+    sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
+  else
+    sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
 }
 
 // ---------------------------------------------------------------------------
@@ -601,4 +603,4 @@ hipError_t sr_launch_head(hipStream_t s, const SrCtx* ctx, const SrHead* heads, 
   return hipGetLastError();
 }
 
-int sr_mfma_max_lds_bytes() { return 64 * 1024; }   // two workgroups per CU, 160 KiB in all
+int sr_mfma_max_lds_bytes() { return 80 * 1024; }   // two workgroups per CU share 160 KiB
