@@ -150,7 +150,8 @@ struct EdgeRt {
 struct LevelPlan {
   int tile_begin = 0, n_tiles = 0;
   int block_begin = 0, n_blocks = 0;
-  int head_begin = 0, n_heads = 0, head_max_splits = 1, head_max_cin = 0;
+  int head_begin = 0, n_heads = 0;
+  int aux_begin = 0, n_aux = 0;     // head and input-staging items that ride along in this level's launch
 };
 
 struct sr_graph {
@@ -174,7 +175,12 @@ struct sr_graph {
   std::vector<void*> dev_allocs;     // everything to free
   SrCtx* ctx = nullptr;
   SrStageNode* stage_nodes = nullptr;
-  int stage_max_elems = 0;
+  SrAux* aux = nullptr;
+  bool stage_folded = false;   // input staging rides in level 1's launch (no R=0 edge leaves an input)
+  int stage_aux_begin = 0, n_stage_aux = 0;
+  int aux_smem_bytes = 0;
+  std::vector<int> head_node;   // node id of each head, in head order
+  std::vector<SrHead> heads_host;
   SrDirectNode* d_nodes = nullptr;
   SrDirectEdge* d_edges = nullptr;
   SrDirectBlock* d_blocks = nullptr;
@@ -366,7 +372,6 @@ sr_status finalize(sr_graph* g) {
     s.Cp = n.Cp;
     s.input_slot = (int)i;
     stage.push_back(s);
-    g->stage_max_elems = std::max(g->stage_max_elems, s.elems_px * s.Cp);
   }
 
   std::vector<SrDirectNode> dn;
@@ -396,6 +401,19 @@ sr_status finalize(sr_graph* g) {
     g->flops += 2.0 * B * macs;
   }
 
+  std::vector<SrAux> aux, stage_aux;
+  for (size_t i = 0; i < stage.size(); ++i) {
+    const int total = stage[i].elems_px;
+    for (int c = 0; c * SR_STAGE_CHUNK < total; ++c) stage_aux.push_back(SrAux{SR_AUX_STAGE, (int)i, c, 0});
+  }
+  g->stage_folded = true;
+  for (const EdgeRt& e : g->edges)
+    if (g->an.is_input[e.d.src] && e.d.bridge == 0) g->stage_folded = false;
+  if (!g->stage_folded) {   // staging gets a launch of its own, ahead of level 1
+    g->stage_aux_begin = 0;
+    g->n_stage_aux = (int)stage_aux.size();
+    aux = stage_aux;
+  }
   for (int L = 1; L <= F; ++L) {
     LevelPlan& lp = g->levels[L];
     lp.tile_begin = (int)mt.size();
@@ -403,6 +421,8 @@ sr_status finalize(sr_graph* g) {
     lp.head_begin = (int)hd.size();
     struct TileGroup { int node_index; double cost; std::vector<SrMfmaTile> tiles; };
     std::vector<TileGroup> groups;
+    std::vector<SrAux> level_aux;
+    if (L == 1 && g->stage_folded) level_aux = stage_aux;
 
     for (int v = 0; v < g->n_nodes; ++v) {
       NodeRt& n = g->nodes[v];
@@ -547,14 +567,23 @@ sr_status finalize(sr_graph* g) {
         h.Cout = n.d.channels;
         h.Cp = n.Cp;
         h.splits = std::max(1, std::min(64, (h.HW + 63) / 64));
-        h.bf16 = bf16;
+        h.record = 0;
+        void* cnt = nullptr;
+        {
+          sr_status st2 = dev_alloc(g, &cnt, (size_t)B * sizeof(int32_t));
+          if (st2 != SR_OK) return st2;
+          SR_HIP(g, sr_launch_fill_zero(g->stream, cnt, (size_t)B * sizeof(int32_t)));
+        }
+        h.counters = (int32_t*)cnt;
         void* part = nullptr;
         sr_status st = dev_alloc(g, &part, (size_t)B * h.splits * h.Cin * sizeof(float));
         if (st != SR_OK) return st;
         h.partial = (float*)part;
+        for (int b = 0; b < B; ++b)
+          for (int sp = 0; sp < h.splits; ++sp) level_aux.push_back(SrAux{SR_AUX_HEAD, (int)hd.size(), b, sp});
+        g->head_node.push_back(v);
         hd.push_back(h);
-        lp.head_max_splits = std::max(lp.head_max_splits, h.splits);
-        lp.head_max_cin = std::max(lp.head_max_cin, h.Cin);
+        g->aux_smem_bytes = std::max(g->aux_smem_bytes, (int)(h.Cin * sizeof(float) + 16 + 256 * sizeof(float)));
       }
       if (n.kind == 2) {
         SrDirectNode node{};
@@ -604,6 +633,9 @@ sr_status finalize(sr_graph* g) {
     lp.n_tiles = (int)mt.size() - lp.tile_begin;
     lp.n_blocks = (int)db.size() - lp.block_begin;
     lp.n_heads = (int)hd.size() - lp.head_begin;
+    lp.aux_begin = (int)aux.size();
+    aux.insert(aux.end(), level_aux.begin(), level_aux.end());
+    lp.n_aux = (int)level_aux.size();
   }
   g->n_mfma_tiles = (int64_t)mt.size();
 
@@ -619,13 +651,17 @@ sr_status finalize(sr_graph* g) {
   if ((st = upload(g, &g->m_edges, me)) != SR_OK) return st;
   if ((st = upload(g, &g->m_tiles, mt)) != SR_OK) return st;
   if ((st = upload(g, &g->heads, hd)) != SR_OK) return st;
+  if ((st = upload(g, &g->aux, aux)) != SR_OK) return st;
+  g->heads_host = hd;
+  g->lds_bytes = std::max(g->lds_bytes, g->aux_smem_bytes);
 
-  int launches = 1;   // input staging
+  int launches = g->stage_folded ? 0 : 1;
   for (int L = 1; L <= F; ++L) {
     const LevelPlan& lp = g->levels[L];
-    launches += (lp.n_tiles > 0) + (lp.n_blocks > 0) + 2 * (lp.n_heads > 0);
+    const bool has_tiles = lp.n_tiles > 0, has_blocks = lp.n_blocks > 0;
+    launches += has_tiles + (has_blocks || (!has_tiles && lp.n_aux > 0));
   }
-  g->launches_per_frame = launches + 1;   // + frame counter
+  g->launches_per_frame = launches;
   g->finalized = true;
   return SR_OK;
 }
@@ -635,6 +671,29 @@ struct FrameTimer {
   std::vector<hipEvent_t> ev;
   std::vector<int> kind;
 };
+
+// The recorded node's values go out with the head item that computes them; any other recorded node
+// needs a copy kernel behind the frame (and then the frame counter a launch of its own).
+sr_status set_record_node(sr_graph* g, int node) {
+  if (g->rec_node == node) return SR_OK;
+  g->rec_node = node;
+  bool changed = false;
+  for (size_t i = 0; i < g->heads_host.size(); ++i) {
+    const int want = (g->head_node[i] == node) ? 1 : 0;
+    if (g->heads_host[i].record != want) { g->heads_host[i].record = want; changed = true; }
+  }
+  if (changed)
+    SR_HIP(g, hipMemcpyAsync(g->heads, g->heads_host.data(), g->heads_host.size() * sizeof(SrHead),
+                             hipMemcpyHostToDevice, g->stream));
+  return SR_OK;
+}
+
+bool record_needs_copy(const sr_graph* g) {
+  if (g->rec_node < 0) return false;
+  for (int v : g->head_node)
+    if (v == g->rec_node) return false;
+  return true;
+}
 
 sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
   hipStream_t s = g->stream;
@@ -649,31 +708,46 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
     ft->kind.push_back(kind);
     return r;
   };
-  SR_HIP(g, mark(0));
-  SR_HIP(g, sr_launch_stage_inputs(s, g->ctx, g->stage_nodes, (int)g->inputs.size(), g->stage_max_elems, bf16));
+  const bool copy_out = record && record_needs_copy(g);
+  // which launch is the frame's last one (it advances the frame counter)
+  int last_level = 0, last_is_direct = 0;
   for (int L = 1; L <= g->an.factor; ++L) {
     const LevelPlan& lp = g->levels[L];
-    if (lp.n_tiles > 0) {
+    const bool has_tiles = lp.n_tiles > 0;
+    const bool direct_launch = lp.n_blocks > 0 || (!has_tiles && lp.n_aux > 0);
+    if (has_tiles || direct_launch) { last_level = L; last_is_direct = direct_launch; }
+  }
+  if (!g->stage_folded) {
+    SR_HIP(g, mark(0));
+    SR_HIP(g, sr_launch_aux(s, g->ctx, g->aux + g->stage_aux_begin, g->n_stage_aux, g->heads, g->stage_nodes,
+                            g->aux_smem_bytes, bf16, 0));
+  }
+  for (int L = 1; L <= g->an.factor; ++L) {
+    const LevelPlan& lp = g->levels[L];
+    const bool has_tiles = lp.n_tiles > 0;
+    const bool direct_launch = lp.n_blocks > 0 || (!has_tiles && lp.n_aux > 0);
+    if (has_tiles) {
+      const int is_last = (!copy_out && L == last_level && !last_is_direct) ? 1 : 0;
       SR_HIP(g, mark(1));
-      SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes));
+      SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes,
+                               g->aux + lp.aux_begin, lp.n_aux, g->heads, g->stage_nodes, is_last));
     }
-    if (lp.n_blocks > 0) {
+    if (direct_launch) {
+      const int is_last = (!copy_out && L == last_level) ? 1 : 0;
+      const int n_aux = has_tiles ? 0 : lp.n_aux;   // aux items already went with the tiles
       SR_HIP(g, mark(2));
-      SR_HIP(g, sr_launch_direct(s, g->ctx, g->d_nodes, g->d_edges, g->d_blocks + lp.block_begin, lp.n_blocks, bf16, g->batch));
-    }
-    if (lp.n_heads > 0) {
-      SR_HIP(g, mark(3));
-      SR_HIP(g, sr_launch_head(s, g->ctx, g->heads + lp.head_begin, lp.n_heads, g->batch, lp.head_max_splits,
-                               lp.head_max_cin, bf16));
+      SR_HIP(g, sr_launch_direct(s, g->ctx, g->d_nodes, g->d_edges, g->d_blocks + lp.block_begin, lp.n_blocks, bf16,
+                                 g->batch, g->aux + lp.aux_begin, n_aux, g->heads, g->stage_nodes,
+                                 g->aux_smem_bytes, is_last));
     }
   }
-  SR_HIP(g, mark(4));
-  if (record && g->rec_node >= 0) {
+  if (copy_out) {
+    SR_HIP(g, mark(4));
     const NodeRt& n = g->nodes[g->rec_node];
     SR_HIP(g, sr_launch_record_output(s, g->ctx, n.state[0], n.state[1], g->batch * n.d.height * n.d.width,
                                       n.d.channels, n.Cp, bf16));
+    SR_HIP(g, sr_launch_tick(s, g->ctx));
   }
-  SR_HIP(g, sr_launch_tick(s, g->ctx));
   SR_HIP(g, mark(-1));
   return SR_OK;
 }
@@ -1035,7 +1109,10 @@ sr_status sr_rollout(sr_graph* g, const void* const* inputs, int32_t T, int32_t 
   }
   c.in_base = 0;    // frame t reads inputs[t]
   c.out_base = 1;   // frame t is recorded in slot t-1
-  g->rec_node = outputs ? out_node : -1;
+  {
+    sr_status st2 = set_record_node(g, outputs ? out_node : -1);
+    if (st2 != SR_OK) return st2;
+  }
   if (outputs) {
     const sr_node_desc& d = g->nodes[out_node].d;
     c.out_ptr = outputs;
@@ -1082,11 +1159,8 @@ sr_status sr_frame_step_timed(sr_graph* g, const void* const* inputs_t, float* k
     c.in_ptr[i] = inputs_t[i];
   }
   SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
-  const int keep = g->rec_node;
-  g->rec_node = -1;
   FrameTimer ft;
   sr_status st = enqueue_frame(g, false, &ft);
-  g->rec_node = keep;
   hipError_t he = hipStreamSynchronize(g->stream);
   int n = 0;
   if (st == SR_OK && he == hipSuccess) {

@@ -13,7 +13,7 @@ struct SrCtx {
   int32_t frame;      // index of the frame being computed (>= 1)
   int32_t in_base;    // input frame read = in_ptr[i] + (frame - in_base) * in_stride[i]
   int32_t out_base;   // output slot = frame - out_base
-  int32_t out_node_elems;  // unused by kernels (kept for debugging)
+  int32_t done;       // workgroups of the frame's last launch that have finished (returns to 0)
   const void* in_ptr[SR_MAX_INPUTS];
   int64_t in_stride[SR_MAX_INPUTS];   // bytes between consecutive frames (0: always the same buffer)
   void* out_ptr;                      // may be null
@@ -100,9 +100,10 @@ struct SrHead {
   const float* w;        // [Cin][Cout] float
   const float* bias;
   float* partial;        // [B][splits][Cin] float scratch
+  int32_t* counters;     // [B] slabs finished per image (return to 0)
   int32_t bridge, act;
   int32_t B, HW, Cin, Csp, Cout, Cp;
-  int32_t splits, bf16;
+  int32_t splits, record;   // record: also write the result to the rollout output
 };
 
 // input staging / state packing
@@ -113,19 +114,27 @@ struct SrStageNode {
   int32_t input_slot; // index into SrCtx::in_ptr
 };
 
+// work items other than tiles and direct blocks that ride along in a level's launch
+#define SR_AUX_HEAD 1        // a = head index, b = image, c = pixel slab
+#define SR_AUX_STAGE 2       // a = input node index (in stage order), b = chunk of SR_STAGE_CHUNK pixels
+#define SR_STAGE_CHUNK 1024
+struct SrAux {
+  int32_t kind, a, b, c;
+};
+
 // launch wrappers (sr_kernels.hip); each returns the hipError_t of the launch
 hipError_t sr_launch_set_ctx(hipStream_t s, SrCtx* ctx, const SrCtx& values, int set_frame);
 hipError_t sr_launch_tick(hipStream_t s, SrCtx* ctx);
 hipError_t sr_launch_fill_zero(hipStream_t s, void* p, size_t bytes);
-hipError_t sr_launch_stage_inputs(hipStream_t s, const SrCtx* ctx, const SrStageNode* nodes, int n_nodes,
-                                  int max_elems, int bf16);
 hipError_t sr_launch_pack(hipStream_t s, void* dst, const void* src, int px, int C, int Cp, int bf16, int unpack);
 hipError_t sr_launch_record_output(hipStream_t s, const SrCtx* ctx, const void* state0, const void* state1,
                                    int px, int C, int Cp, int bf16);
-hipError_t sr_launch_direct(hipStream_t s, const SrCtx* ctx, const SrDirectNode* nodes, const SrDirectEdge* edges,
-                            const SrDirectBlock* blocks, int n_blocks, int bf16, int batch);
-hipError_t sr_launch_mfma(hipStream_t s, const SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
-                          const SrMfmaTile* tiles, int n_tiles, int lds_bytes);
-hipError_t sr_launch_head(hipStream_t s, const SrCtx* ctx, const SrHead* heads, int n_heads, int max_B,
-                          int max_splits, int max_cin, int bf16);
+hipError_t sr_launch_aux(hipStream_t s, SrCtx* ctx, const SrAux* aux, int n_aux, const SrHead* heads,
+                         const SrStageNode* stage_nodes, int smem_bytes, int bf16, int is_last);
+hipError_t sr_launch_direct(hipStream_t s, SrCtx* ctx, const SrDirectNode* nodes, const SrDirectEdge* edges,
+                            const SrDirectBlock* blocks, int n_blocks, int bf16, int batch, const SrAux* aux, int n_aux,
+                            const SrHead* heads, const SrStageNode* stage_nodes, int smem_bytes, int is_last);
+hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
+                          const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
+                          const SrHead* heads, const SrStageNode* stage_nodes, int is_last);
 int sr_mfma_max_lds_bytes();

@@ -60,27 +60,26 @@ __global__ void sr_tick_kernel(SrCtx* ctx) {
   if (threadIdx.x == 0 && blockIdx.x == 0) ctx->frame = ctx->frame + 1;
 }
 
+// Called by every workgroup of the last launch of a frame once its work is stored: the workgroup
+// that arrives last advances the frame counter (all others have read it long before).
+__device__ __forceinline__ void sr_block_done(SrCtx* ctx, int n_blocks) {
+  // no fence: the counter only orders "everyone has read the frame counter" (done at kernel start)
+  // before its update, and the next launch sees the update through the kernel boundary
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const int old = __hip_atomic_fetch_add(&ctx->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    if (old == n_blocks - 1) {
+      ctx->done = 0;
+      ctx->frame = ctx->frame + 1;
+    }
+  }
+}
+
 __global__ void sr_fill_zero_kernel(uint4* p, size_t n16, unsigned char* tail, size_t ntail) {
   size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   size_t stride = (size_t)gridDim.x * blockDim.x;
   for (; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
   if (blockIdx.x == 0 && threadIdx.x < ntail) tail[threadIdx.x] = 0;
-}
-
-// state[frame & 1] of every input node := this frame's input, channel pitch C -> Cp
-template <typename T>
-__global__ void sr_stage_inputs_kernel(const SrCtx* __restrict__ ctx, const SrStageNode* __restrict__ nodes) {
-  const SrStageNode nd = nodes[blockIdx.y];
-  const int frame = ctx->frame;
-  const char* base = (const char*)ctx->in_ptr[nd.input_slot];
-  if (base == nullptr) return;
-  const T* in = (const T*)(base + (int64_t)(frame - ctx->in_base) * ctx->in_stride[nd.input_slot]);
-  T* out = (T*)nd.state[frame & 1];
-  const int total = nd.elems_px * nd.Cp;
-  for (int idx = blockIdx.x * blockDim.x + threadIdx.x; idx < total; idx += gridDim.x * blockDim.x) {
-    int p = idx / nd.Cp, c = idx - p * nd.Cp;
-    out[idx] = (c < nd.C) ? in[(size_t)p * nd.C + c] : (T)0;
-  }
 }
 
 // dense [px][C]  <->  pitched [px][Cp]
@@ -113,17 +112,123 @@ __global__ void sr_record_output_kernel(const SrCtx* __restrict__ ctx, const T* 
 }
 
 // ---------------------------------------------------------------------------
+// auxiliary work items that ride along in a level's launch
+// ---------------------------------------------------------------------------
+// input staging: state[frame & 1] of an input node := this frame's input, channel pitch C -> Cp;
+// one item covers SR_STAGE_CHUNK pixels, one pixel per thread and pass, 16-byte stores when the
+// stored pixel is a whole number of them
+template <typename T>
+__device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, const SrStageNode& nd, int chunk) {
+  const int frame = ctx->frame;
+  const char* base = (const char*)ctx->in_ptr[nd.input_slot];
+  if (base == nullptr) return;
+  const T* in = (const T*)(base + (int64_t)(frame - ctx->in_base) * ctx->in_stride[nd.input_slot]);
+  T* out = (T*)nd.state[frame & 1];
+  const int end = min(nd.elems_px, (chunk + 1) * SR_STAGE_CHUNK);
+  constexpr int V = 16 / sizeof(T);
+  if ((nd.Cp % V) == 0) {
+    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += blockDim.x) {
+      const T* ip = in + (size_t)p * nd.C;
+      for (int c0 = 0; c0 < nd.Cp; c0 += V) {
+        T v[V];
+#pragma unroll
+        for (int i = 0; i < V; ++i) v[i] = (c0 + i < nd.C) ? ip[c0 + i] : (T)0;
+        *(u32x4_t*)(out + (size_t)p * nd.Cp + c0) = *(const u32x4_t*)v;
+      }
+    }
+  } else {
+    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += blockDim.x)
+      for (int c = 0; c < nd.Cp; ++c) out[(size_t)p * nd.Cp + c] = (c < nd.C) ? in[(size_t)p * nd.C + c] : (T)0;
+  }
+}
+
+// GAP + dense head (App. A2: fully connected edge after pooling), one item per (image, pixel slab):
+// the slab's channel sums go to `partial`; the item that finishes last for an image adds the slabs
+// in slab order, applies the dense map, bias and activation, stores the node's state and, if this
+// node is being recorded, the rollout output.  smem: Cin floats, one int, 4*64 floats.
+template <typename T>
+__device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, const SrHead& h, int b, int split,
+                                             float* smem) {
+  const int cur = ctx->frame & 1;
+  const T* src = (const T*)h.src[h.bridge ? (cur ^ 1) : cur] + (size_t)b * h.HW * h.Csp;
+  const int per = (h.HW + h.splits - 1) / h.splits;
+  const int p0 = split * per, p1 = min(h.HW, p0 + per);
+  const float inv = 1.0f / (float)h.HW;
+  int* flag = (int*)(smem + h.Cin);
+  float* red = smem + h.Cin + 4;
+  for (int c = threadIdx.x; c < h.Cin; c += blockDim.x) {
+    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+    int p = p0;
+    for (; p + 4 <= p1; p += 4) {
+      s0 += Store<T>::load(src + (size_t)p * h.Csp + c);
+      s1 += Store<T>::load(src + (size_t)(p + 1) * h.Csp + c);
+      s2 += Store<T>::load(src + (size_t)(p + 2) * h.Csp + c);
+      s3 += Store<T>::load(src + (size_t)(p + 3) * h.Csp + c);
+    }
+    for (; p < p1; ++p) s0 += Store<T>::load(src + (size_t)p * h.Csp + c);
+    const float sum = (s0 + s1) + (s2 + s3);
+    if (h.splits == 1) smem[c] = sum * inv;
+    else h.partial[((size_t)b * h.splits + split) * h.Cin + c] = sum;
+  }
+  if (h.splits > 1) {
+    __threadfence();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      const int old = atomicAdd(&h.counters[b], 1);
+      *flag = (old == h.splits - 1);
+      if (old == h.splits - 1) h.counters[b] = 0;
+    }
+    __syncthreads();
+    if (!*flag) return;
+    __threadfence();
+    for (int c = threadIdx.x; c < h.Cin; c += blockDim.x) {
+      float sum = 0.f;
+      for (int s = 0; s < h.splits; ++s)
+        sum += __hip_atomic_load(&h.partial[((size_t)b * h.splits + s) * h.Cin + c], __ATOMIC_RELAXED,
+                                 __HIP_MEMORY_SCOPE_AGENT);
+      smem[c] = sum * inv;
+    }
+  }
+  __syncthreads();
+  char* rec = h.record ? (char*)ctx->out_ptr : nullptr;
+  T* recp = rec ? (T*)(rec + (int64_t)(ctx->frame - ctx->out_base) * ctx->out_stride) : nullptr;
+  // dense map: 64 outputs at a time, the channel range split over the 4 waves and added in wave order
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  const int cper = (h.Cin + 3) / 4;
+  const int c_lo = part * cper, c_hi = min(h.Cin, c_lo + cper);
+  for (int co0 = 0; co0 < h.Cout; co0 += 64) {
+    const int co = co0 + lane;
+    float acc = 0.f;
+    if (co < h.Cout)
+      for (int ci = c_lo; ci < c_hi; ++ci) acc += smem[ci] * h.w[(size_t)ci * h.Cout + co];
+    red[part * 64 + lane] = acc;
+    __syncthreads();
+    if (part == 0 && co < h.Cout) {
+      float v = h.bias[co] + ((red[lane] + red[64 + lane]) + (red[128 + lane] + red[192 + lane]));
+      if (h.act == 1) v = fmaxf(v, 0.f);
+      Store<T>::store((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
+      if (recp) Store<T>::store(recp + (size_t)b * h.Cout + co, v);
+    }
+    __syncthreads();
+  }
+}
+
+template <typename T>
+__device__ __forceinline__ void sr_aux_item(const SrCtx* __restrict__ ctx, const SrAux& it,
+                                            const SrHead* __restrict__ heads,
+                                            const SrStageNode* __restrict__ stage_nodes, float* smem) {
+  if (it.kind == SR_AUX_HEAD) sr_head_item<T>(ctx, heads[it.a], it.b, it.c, smem);
+  else if (it.kind == SR_AUX_STAGE) sr_stage_item<T>(ctx, stage_nodes[it.a], it.b);
+}
+
+// ---------------------------------------------------------------------------
 // direct path
 // ---------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(256) void sr_direct_kernel(const SrCtx* __restrict__ ctx,
-                                                        const SrDirectNode* __restrict__ nodes,
-                                                        const SrDirectEdge* __restrict__ edges,
-                                                        const SrDirectBlock* __restrict__ blocks, int batch) {
-  const SrDirectBlock blk = blocks[blockIdx.x];
-  const SrDirectNode nd = nodes[blk.node];
+__device__ __forceinline__ void sr_direct_block(const SrCtx* __restrict__ ctx, const SrDirectNode& nd,
+                                                const SrDirectEdge* __restrict__ edges, int first, int batch) {
   const int cur = ctx->frame & 1;
-  const int idx = blk.first + threadIdx.x;
+  const int idx = first + threadIdx.x;
   const int HW = nd.H * nd.W;
   if (idx >= batch * HW * nd.C) return;
   const int m = idx / nd.C, co = idx - m * nd.C;
@@ -162,48 +267,21 @@ __global__ __launch_bounds__(256) void sr_direct_kernel(const SrCtx* __restrict_
   Store<T>::store((T*)nd.out[cur] + (size_t)m * nd.Cp + co, acc);
 }
 
-// ---------------------------------------------------------------------------
-// GAP + dense head
-// ---------------------------------------------------------------------------
-// partial[b][s][c] = sum over the s-th slab of pixels of src[b][p][c]
 template <typename T>
-__global__ __launch_bounds__(256) void sr_gap_partial_kernel(const SrCtx* __restrict__ ctx,
-                                                             const SrHead* __restrict__ heads) {
-  const SrHead h = heads[blockIdx.z];
-  const int b = blockIdx.y, s = blockIdx.x;
-  if (b >= h.B || s >= h.splits) return;
-  const int cur = ctx->frame & 1;
-  const T* src = (const T*)h.src[h.bridge ? (cur ^ 1) : cur] + (size_t)b * h.HW * h.Csp;
-  const int per = (h.HW + h.splits - 1) / h.splits;
-  const int p0 = s * per, p1 = min(h.HW, p0 + per);
-  for (int c = threadIdx.x; c < h.Cin; c += blockDim.x) {
-    float sum = 0.f;
-    for (int p = p0; p < p1; ++p) sum += Store<T>::load(src + (size_t)p * h.Csp + c);
-    h.partial[((size_t)b * h.splits + s) * h.Cin + c] = sum;
+__global__ __launch_bounds__(256) void sr_direct_kernel(SrCtx* __restrict__ ctx, const SrDirectNode* __restrict__ nodes,
+                                                        const SrDirectEdge* __restrict__ edges,
+                                                        const SrDirectBlock* __restrict__ blocks, int n_blocks,
+                                                        int batch, const SrAux* __restrict__ aux,
+                                                        const SrHead* __restrict__ heads,
+                                                        const SrStageNode* __restrict__ stage_nodes, int is_last) {
+  extern __shared__ float sr_aux_smem[];
+  if ((int)blockIdx.x < n_blocks) {
+    const SrDirectBlock blk = blocks[blockIdx.x];
+    sr_direct_block<T>(ctx, nodes[blk.node], edges, blk.first, batch);
+  } else {
+    sr_aux_item<T>(ctx, aux[blockIdx.x - n_blocks], heads, stage_nodes, sr_aux_smem);
   }
-}
-
-template <typename T>
-__global__ __launch_bounds__(256) void sr_head_dense_kernel(const SrCtx* __restrict__ ctx,
-                                                            const SrHead* __restrict__ heads) {
-  extern __shared__ float mean[];
-  const SrHead h = heads[blockIdx.y];
-  const int b = blockIdx.x;
-  if (b >= h.B) return;
-  const int cur = ctx->frame & 1;
-  const float inv = 1.0f / (float)h.HW;
-  for (int c = threadIdx.x; c < h.Cin; c += blockDim.x) {
-    float sum = 0.f;
-    for (int s = 0; s < h.splits; ++s) sum += h.partial[((size_t)b * h.splits + s) * h.Cin + c];
-    mean[c] = sum * inv;
-  }
-  __syncthreads();
-  for (int co = threadIdx.x; co < h.Cout; co += blockDim.x) {
-    float acc = h.bias[co];
-    for (int ci = 0; ci < h.Cin; ++ci) acc += mean[ci] * h.w[(size_t)ci * h.Cout + co];
-    if (h.act == 1) acc = fmaxf(acc, 0.f);
-    Store<T>::store((T*)h.out[cur] + (size_t)b * h.Cp + co, acc);
-  }
+  if (is_last) sr_block_done(ctx, gridDim.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -495,17 +573,28 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
   }
 }
 
-__global__ __launch_bounds__(256, 2) void sr_mfma_kernel(const SrCtx* __restrict__ ctx,
-                                                         const SrMfmaNode* __restrict__ nodes,
+__global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
                                                          const SrMfmaEdge* __restrict__ edges,
-                                                         const SrMfmaTile* __restrict__ tiles) {
+                                                         const SrMfmaTile* __restrict__ tiles, int n_tiles,
+                                                         const SrAux* __restrict__ aux, int n_aux, int aux_at,
+                                                         const SrHead* __restrict__ heads,
+                                                         const SrStageNode* __restrict__ stage_nodes, int is_last) {
   extern __shared__ __align__(16) unsigned char sr_lds[];
-  const SrMfmaTile t = tiles[blockIdx.x];
-  const int node_index = SR_UNIFORM(t.node);
-  if (nodes[node_index].wn_tiles == 2)
-    sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
-  else
-    sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
+  // work list: tiles in decreasing cost; the auxiliary items are spliced in at position aux_at so
+  // that neither the longest tiles start late nor the launch ends on an auxiliary item
+  const int item = blockIdx.x;
+  const bool is_aux = item >= aux_at && item < aux_at + n_aux;
+  if (!is_aux) {
+    const SrMfmaTile t = tiles[item < aux_at ? item : item - n_aux];
+    const int node_index = SR_UNIFORM(t.node);
+    if (nodes[node_index].wn_tiles == 2)
+      sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
+    else
+      sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
+  } else {
+    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, stage_nodes, (float*)sr_lds);
+  }
+  if (is_last) sr_block_done(ctx, gridDim.x);
 }
 
 // ---------------------------------------------------------------------------
@@ -538,13 +627,19 @@ hipError_t sr_launch_fill_zero(hipStream_t s, void* p, size_t bytes) {
   return hipGetLastError();
 }
 
-hipError_t sr_launch_stage_inputs(hipStream_t s, const SrCtx* ctx, const SrStageNode* nodes, int n_nodes,
-                                  int max_elems, int bf16) {
-  if (n_nodes == 0) return hipSuccess;
-  int nb = blocks_for(max_elems, 256 * 4);
-  if (nb > 2048) nb = 2048;
-  if (bf16) hipLaunchKernelGGL(sr_stage_inputs_kernel<uint16_t>, dim3(nb, n_nodes), dim3(256), 0, s, ctx, nodes);
-  else hipLaunchKernelGGL(sr_stage_inputs_kernel<float>, dim3(nb, n_nodes), dim3(256), 0, s, ctx, nodes);
+template <typename T>
+__global__ void sr_aux_kernel(SrCtx* __restrict__ ctx, const SrAux* __restrict__ aux, const SrHead* __restrict__ heads,
+                              const SrStageNode* __restrict__ stage_nodes, int is_last) {
+  extern __shared__ float sr_aux_smem2[];
+  sr_aux_item<T>(ctx, aux[blockIdx.x], heads, stage_nodes, sr_aux_smem2);
+  if (is_last) sr_block_done(ctx, gridDim.x);
+}
+
+hipError_t sr_launch_aux(hipStream_t s, SrCtx* ctx, const SrAux* aux, int n_aux, const SrHead* heads,
+                         const SrStageNode* stage_nodes, int smem_bytes, int bf16, int is_last) {
+  if (n_aux == 0) return hipSuccess;
+  if (bf16) hipLaunchKernelGGL(sr_aux_kernel<uint16_t>, dim3(n_aux), dim3(256), smem_bytes, s, ctx, aux, heads, stage_nodes, is_last);
+  else hipLaunchKernelGGL(sr_aux_kernel<float>, dim3(n_aux), dim3(256), smem_bytes, s, ctx, aux, heads, stage_nodes, is_last);
   return hipGetLastError();
 }
 
@@ -568,17 +663,19 @@ hipError_t sr_launch_record_output(hipStream_t s, const SrCtx* ctx, const void* 
   return hipGetLastError();
 }
 
-hipError_t sr_launch_direct(hipStream_t s, const SrCtx* ctx, const SrDirectNode* nodes, const SrDirectEdge* edges,
-                            const SrDirectBlock* blocks, int n_blocks, int bf16, int batch) {
-  if (n_blocks == 0) return hipSuccess;
-  if (bf16) hipLaunchKernelGGL(sr_direct_kernel<uint16_t>, dim3(n_blocks), dim3(256), 0, s, ctx, nodes, edges, blocks, batch);
-  else hipLaunchKernelGGL(sr_direct_kernel<float>, dim3(n_blocks), dim3(256), 0, s, ctx, nodes, edges, blocks, batch);
+hipError_t sr_launch_direct(hipStream_t s, SrCtx* ctx, const SrDirectNode* nodes, const SrDirectEdge* edges,
+                            const SrDirectBlock* blocks, int n_blocks, int bf16, int batch, const SrAux* aux, int n_aux,
+                            const SrHead* heads, const SrStageNode* stage_nodes, int smem_bytes, int is_last) {
+  if (n_blocks + n_aux == 0) return hipSuccess;
+  if (bf16) hipLaunchKernelGGL(sr_direct_kernel<uint16_t>, dim3(n_blocks + n_aux), dim3(256), smem_bytes, s, ctx, nodes, edges, blocks, n_blocks, batch, aux, heads, stage_nodes, is_last);
+  else hipLaunchKernelGGL(sr_direct_kernel<float>, dim3(n_blocks + n_aux), dim3(256), smem_bytes, s, ctx, nodes, edges, blocks, n_blocks, batch, aux, heads, stage_nodes, is_last);
   return hipGetLastError();
 }
 
-hipError_t sr_launch_mfma(hipStream_t s, const SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
-                          const SrMfmaTile* tiles, int n_tiles, int lds_bytes) {
-  if (n_tiles == 0) return hipSuccess;
+hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
+                          const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
+                          const SrHead* heads, const SrStageNode* stage_nodes, int is_last) {
+  if (n_tiles + n_aux == 0) return hipSuccess;
   static bool attr_set = false;
   if (!attr_set) {   // dynamic LDS above 64 KiB has to be requested once
     hipError_t e = hipFuncSetAttribute((const void*)sr_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -586,20 +683,8 @@ hipError_t sr_launch_mfma(hipStream_t s, const SrCtx* ctx, const SrMfmaNode* nod
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles), dim3(256), lds_bytes, s, ctx, nodes, edges, tiles);
-  return hipGetLastError();
-}
-
-hipError_t sr_launch_head(hipStream_t s, const SrCtx* ctx, const SrHead* heads, int n_heads, int max_B,
-                          int max_splits, int max_cin, int bf16) {
-  if (n_heads == 0) return hipSuccess;
-  if (bf16) {
-    hipLaunchKernelGGL(sr_gap_partial_kernel<uint16_t>, dim3(max_splits, max_B, n_heads), dim3(256), 0, s, ctx, heads);
-    hipLaunchKernelGGL(sr_head_dense_kernel<uint16_t>, dim3(max_B, n_heads), dim3(256), max_cin * sizeof(float), s, ctx, heads);
-  } else {
-    hipLaunchKernelGGL(sr_gap_partial_kernel<float>, dim3(max_splits, max_B, n_heads), dim3(256), 0, s, ctx, heads);
-    hipLaunchKernelGGL(sr_head_dense_kernel<float>, dim3(max_B, n_heads), dim3(256), max_cin * sizeof(float), s, ctx, heads);
-  }
+  hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles + n_aux), dim3(256), lds_bytes, s, ctx, nodes, edges, tiles, n_tiles,
+                     aux, n_aux, n_tiles / 2, heads, stage_nodes, is_last);
   return hipGetLastError();
 }
 

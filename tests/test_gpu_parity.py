@@ -90,6 +90,25 @@ def test_hires_reduced_bf16_mfma():
     check(g2, seed=4, label="hires_sr/64x64")
 
 
+def test_gap_head_with_several_pixel_slabs():
+    # 24x24 source -> 576 pixels per image: the head sums 9 slabs, the last one to finish combines them
+    nodes = [Node("in", 3, 24, 24, ACT_IDENTITY), Node("a", 32, 24, 24), Node("out", 7, 1, 1, ACT_IDENTITY)]
+    edges = [Edge(0, 1), Edge(1, 1), Edge(1, 2, "gap_dense", 1, 1, 1, 0)]
+    for dtype in ("bf16", "f32"):
+        g = Graph("gap", nodes, edges, batch=3, frames=4, dtype=dtype, out_node=2)
+        check(g, seed=8, label=f"gap_head/{dtype}")
+        check(g.with_pattern([0, 1, 0]), seed=8, label=f"gap_head/{dtype}/sequential")
+
+
+def test_recording_a_hidden_node():
+    g = W.cifar_sr(batch=2, frames=5)
+    w, b, x = W.make_case(g, seed=9)
+    got = gpu_rollout(g, w, b, x, 5, out_node=3)
+    ref = oracle_states(g, w, b, x, 5, "bf16", nodes=[3])[3]
+    for t in range(5):
+        assert max_abs_rel(got[t], ref[t]) <= 2e-2
+
+
 def test_rollout_equals_frame_steps_and_hipgraph_equals_eager():
     g = W.cifar_sr(batch=2, frames=11)       # 11 frames: one 8-frame graph + 3 single frames
     w, b, x = W.make_case(g, seed=5, bias_scale=0.1)
