@@ -430,15 +430,31 @@ sr_status finalize(sr_graph* g) {
       if (n.kind == 1) {
         // ---- MFMA node: tile shape, per-edge staging depth, tiles
         const int Cout = n.d.channels;
-        const int wn_tiles = (Cout % 64 == 0) ? 2 : 1;
-        const int cw = 32 * wn_tiles;
-        int waves_n = 1;
-        for (int cand : {4, 2, 1})
-          if (Cout % (cw * cand) == 0) { waves_n = cand; break; }
-        const int waves_m = 4 / waves_n;
         const int64_t M = (int64_t)B * n.d.height * n.d.width;
-        const int BM = 128 * waves_m, BN = cw * waves_n;
+        // tile shapes to try, preferred first: each wave owns 128 pixels x 32*wn_tiles channels, the 4
+        // waves are arranged waves_m x waves_n; a narrower wave tile gives a shorter pixel tile and so a
+        // smaller source patch when the preferred shape does not fit the LDS
+        struct Shape { int wn_tiles, waves_n; };
+        std::vector<Shape> shapes;
+        for (int wt : {2, 1})
+          for (int wn : {4, 2, 1})
+            if (Cout % (32 * wt * wn) == 0) {
+              bool dominated = false;   // same pixel tile, narrower channel tile: never better
+              for (const Shape& sh : shapes) dominated |= (sh.waves_n == wn);
+              if (!dominated) shapes.push_back(Shape{wt, wn});
+            }
+        int wn_tiles = 0, cw = 0, waves_n = 0, waves_m = 0, BM = 0, BN = 0;
         SrMfmaNode node{};
+        double ksum = 0;
+        bool ok = false;
+        for (const Shape& sh : shapes) {
+        wn_tiles = sh.wn_tiles;
+        cw = 32 * wn_tiles;
+        waves_n = sh.waves_n;
+        waves_m = 4 / waves_n;
+        BM = 128 * waves_m;
+        BN = cw * waves_n;
+        node = SrMfmaNode{};
         node.out[0] = n.state[0];
         node.out[1] = n.state[1];
         node.bias = n.bias_dev;
@@ -453,8 +469,8 @@ sr_status finalize(sr_graph* g) {
         node.waves_n = waves_n;
         node.wn_tiles = wn_tiles;
         node.zero_page = g->zero_page;
-        double ksum = 0;
-        bool ok = true;
+        ksum = 0;
+        ok = true;
         for (EdgeRt& e : g->edges) {
           if (e.d.dst != v) continue;
           const NodeRt& sn = g->nodes[e.d.src];
@@ -500,6 +516,9 @@ sr_status finalize(sr_graph* g) {
           g->lds_bytes = std::max<int>(g->lds_bytes, 4 * 64 * (32 * wn_tiles * 2 + 16));
           ksum += (double)sn.Cp * m.kh * m.kw;
           me.push_back(m);
+        }
+        if (ok) break;
+        me.resize(node.edge_begin);
         }
         if (!ok) {   // patch does not fit: this node goes the direct way
           me.resize(node.edge_begin);
