@@ -35,6 +35,9 @@ def main():
     ap.add_argument("--pattern", default="streaming")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hipgraph", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 512 MiB device copy (a kernel of known HBM traffic, for scaling "
+                         "FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -66,6 +69,12 @@ def main():
     info = dev.info()
     work = dev.work()
 
+    if args.copy_calibration:
+        a = torch.empty(128 * 1024 * 1024, dtype=torch.float32, device="cuda").normal_()
+        c = torch.empty_like(a)
+        c.copy_(a)            # reads 512 MiB, writes 512 MiB
+        torch.cuda.synchronize()
+        del a, c
     for _ in range(args.warmup):
         dev.rollout(xin, T, g.out_node, out)
     dev.synchronize()
@@ -122,12 +131,13 @@ def main():
         except Exception:
             cores = os.cpu_count()
         mode = "bf16" if g.dtype == "bf16" else "f64"
-        sample_frames = 2 if work["flops_per_frame"] > 5e10 else min(T, 8)
         r = orc.Rollout(g, w, b, mode)
         r.reset({v: x[v][0] for v in ins})
         c0 = time.perf_counter()
-        for t in range(1, sample_frames + 1):
-            r.step({v: x[v][t] for v in ins})
+        sample_frames = 0
+        while sample_frames < 2 or (time.perf_counter() - c0 < 10.0 and sample_frames < 64):
+            r.step({v: x[v][1 + sample_frames % T] for v in ins})   # bounded sample: about 10 s of CPU work
+            sample_frames += 1
         cdt = time.perf_counter() - c0
         cpu = {"value": round(B * sample_frames / cdt, 3), "unit": "frames/s", "cores": int(cores), "kind": "oracle",
                "sample": f"{sample_frames} frame updates of the full batch ({mode} mode), {cdt:.1f} s",

@@ -387,6 +387,7 @@ sr_status finalize(sr_graph* g) {
   const int lds_cap = sr_mfma_max_lds_bytes();
   g->lds_bytes = 0;
   g->flops = 0;
+  g->n_mfma_tiles = 0;
 
   for (const EdgeRt& e : g->edges) {
     const sr_node_desc& s = g->nodes[e.d.src].d;
@@ -531,12 +532,20 @@ sr_status finalize(sr_graph* g) {
           grp.node_index = node_index;
           grp.cost = ksum * BM * BN;
           const int n_mt = (int)((M + BM - 1) / BM), n_nt = Cout / BN;
-          // order: groups of 8 consecutive pixel tiles (one per XCD when workgroups are dealt
-          // round-robin), all channel tiles of a group back to back, so that the channel tiles of
-          // one pixel tile land on the same XCD and share its L2 copy of the source patch
-          for (int mg = 0; mg < n_mt; mg += 8)
-            for (int nt = 0; nt < n_nt; ++nt)
-              for (int mi = mg; mi < std::min(mg + 8, n_mt); ++mi) {
+          // estimated cycles of one tile: k-steps at the MFMA rate of two resident workgroups,
+          // plus the staging latency of every stage and a fixed prologue/epilogue
+          {
+            double cyc = 8000;
+            for (int ei = 0; ei < node.edge_count; ++ei) {
+              const SrMfmaEdge& m = me[node.edge_begin + ei];
+              const double steps = (double)m.kh * m.kw * (m.KC / 16);
+              cyc += m.nchunk * (4500.0 + steps * 512.0 * wn_tiles / 2);
+            }
+            grp.cost = cyc;
+          }
+          // channel tiles of one pixel tile are neighbours in the list (they share the source patch)
+          for (int mi = 0; mi < n_mt; ++mi)
+            for (int nt = 0; nt < n_nt; ++nt) {
                 SrMfmaTile t{};
                 t.node = node_index;
                 t.m0 = mi * BM;
@@ -645,10 +654,34 @@ sr_status finalize(sr_graph* g) {
         }
       }
     }
-    // longest tiles first, so that the tail of the launch is made of short ones
+    // Work list of the level.  Workgroups are dealt to the 8 XCDs round-robin (workgroup i runs on
+    // XCD i % 8) and every XCD has an L2 of its own, so the list is built per XCD: the tiles, longest
+    // first, are cut into 8 runs of equal estimated cost, run x goes to XCD x (positions x, x+8, ...).
+    // An XCD then works on one or two nodes at a time, whose packed weights and neighbouring source
+    // patches stay in its L2, instead of every L2 streaming every node's weights.  Shorter runs are
+    // padded with empty tiles (node -1).
     std::stable_sort(groups.begin(), groups.end(),
                      [](const TileGroup& a, const TileGroup& b) { return a.cost > b.cost; });
-    for (const TileGroup& grp : groups) mt.insert(mt.end(), grp.tiles.begin(), grp.tiles.end());
+    {
+      double total = 0;
+      for (const TileGroup& grp : groups) total += grp.cost * grp.tiles.size();
+      std::vector<std::vector<SrMfmaTile>> per_xcd(SR_XCDS);
+      double cum = 0;
+      for (const TileGroup& grp : groups)
+        for (const SrMfmaTile& t : grp.tiles) {
+          int x = total > 0 ? (int)((cum + 0.5 * grp.cost) / total * SR_XCDS) : 0;
+          x = std::min(std::max(x, 0), SR_XCDS - 1);
+          per_xcd[x].push_back(t);
+          cum += grp.cost;
+          g->n_mfma_tiles += 1;
+        }
+      size_t longest = 0;
+      for (const auto& v : per_xcd) longest = std::max(longest, v.size());
+      SrMfmaTile none{};
+      none.node = -1;
+      for (size_t pos = 0; pos < longest; ++pos)
+        for (int x = 0; x < SR_XCDS; ++x) mt.push_back(pos < per_xcd[x].size() ? per_xcd[x][pos] : none);
+    }
     lp.n_tiles = (int)mt.size() - lp.tile_begin;
     lp.n_blocks = (int)db.size() - lp.block_begin;
     lp.n_heads = (int)hd.size() - lp.head_begin;
@@ -656,7 +689,6 @@ sr_status finalize(sr_graph* g) {
     aux.insert(aux.end(), level_aux.begin(), level_aux.end());
     lp.n_aux = (int)level_aux.size();
   }
-  g->n_mfma_tiles = (int64_t)mt.size();
 
   sr_status st;
   if ((st = upload(g, &g->stage_nodes, stage)) != SR_OK) return st;

@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #define SR_MAX_INPUTS 16
+#define SR_XCDS 8          // accelerator complex dies of an MI355X; workgroup i of a launch runs on XCD i % 8
 
 // One per graph, in device memory.  Kernels read the frame counter from here, so
 // the same captured HIP graph serves every frame: the buffer written at frame t
@@ -85,7 +86,7 @@ struct SrMfmaNode {
 };
 
 struct SrMfmaTile {
-  int32_t node;
+  int32_t node;  // < 0: empty slot (pads an XCD's run)
   int32_t m0;    // first output pixel (linear over [B][Ho][Wo])
   int32_t n0;    // first output channel
   int32_t plan_begin;  // first entry of this tile in plan_index (one per incoming edge)

@@ -587,7 +587,9 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
   if (!is_aux) {
     const SrMfmaTile t = tiles[item < aux_at ? item : item - n_aux];
     const int node_index = SR_UNIFORM(t.node);
-    if (nodes[node_index].wn_tiles == 2)
+    if (node_index < 0) {
+      // empty slot
+    } else if (nodes[node_index].wn_tiles == 2)
       sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
     else
       sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);

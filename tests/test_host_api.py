@@ -1,0 +1,129 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every symbol the header declares, and its
+host-only logic (network / rollout validation, tableau levels, inference factor, pattern count)
+agrees with the oracle.  No compute call is made; nothing here needs a GPU."""
+import ctypes
+import os
+import random
+import re
+
+import pytest
+
+import paper_1806_04965_amd as sr
+from paper_1806_04965_amd import binding
+from oracle import theory as th
+import workloads as W
+from workloads.graphs import Edge
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def header_functions():
+    text = open(os.path.join(ROOT, "include", "sr.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(sr_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sr.load_library()
+    names = header_functions()
+    assert len(names) >= 18
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def edges_of(pairs, bits=None):
+    bits = bits or [1] * len(pairs)
+    return [Edge(s, t, "conv", 3, 3, 1, 1, 1, b) for (s, t), b in zip(pairs, bits)]
+
+
+def test_analyze_matches_printed_factors():
+    pairs = [(0, 1), (1, 2), (2, 3), (1, 3), (1, 1)]          # skip+recurrent example net
+    assert sr.analyze(4, edges_of(pairs, [0, 0, 0, 0, 1])) == ([0, 1, 2, 3], 3)
+    assert sr.analyze(4, edges_of(pairs))[1] == 1
+    assert sr.count_valid_patterns(4, edges_of(pairs)) == 16
+    assert sr.count_valid_patterns(4, edges_of([(0, 1), (1, 2), (2, 3), (3, 1)])) == 14
+
+
+def test_analyze_agrees_with_oracle_on_random_graphs():
+    rng = random.Random(5)
+    checked = 0
+    for _ in range(200):
+        n = rng.randint(2, 7)
+        pairs = list({(rng.randrange(n), rng.randrange(n)) for _ in range(rng.randint(1, 2 * n))})
+        R = [rng.randint(0, 1) for _ in pairs]
+        try:
+            th.check_network(n, pairs)
+            net_ok = True
+        except th.GraphError:
+            net_ok = False
+        if not net_ok:
+            with pytest.raises(sr.SrError) as ei:
+                sr.analyze(n, edges_of(pairs, R))
+            assert ei.value.name == "SR_ERR_GRAPH"
+            continue
+        if not th.is_valid(n, pairs, R):
+            with pytest.raises(sr.SrError) as ei:
+                sr.analyze(n, edges_of(pairs, R))
+            assert ei.value.name == "SR_ERR_ROLLOUT"
+            continue
+        lv, f = sr.analyze(n, edges_of(pairs, R))
+        assert lv == th.levels(n, pairs, R) and f == th.inference_factor(n, pairs, R)
+        if len(pairs) <= 8:
+            assert sr.count_valid_patterns(n, edges_of(pairs)) == len(th.all_valid_patterns(n, pairs))
+        checked += 1
+    assert checked > 30
+
+
+def test_benchmark_graph_levels():
+    for name, f in W.BENCH_CONFIGS.items():
+        g = f()
+        for bits in (W.streaming_pattern(g), W.sequential_pattern(g), W.hybrid_pattern(g)):
+            gg = g.with_pattern(bits)
+            pairs = [(e.src, e.dst) for e in gg.edges]
+            lv, fac = sr.analyze(len(gg.nodes), gg.edges)
+            assert lv == th.levels(len(gg.nodes), pairs, bits) and fac == th.inference_factor(len(gg.nodes), pairs, bits)
+
+
+def create(nodes, edges, batch=1, dtype=0):
+    lib = sr.load_library()
+    na = (binding.NodeDesc * len(nodes))(*[binding.NodeDesc(*n) for n in nodes])
+    h = ctypes.c_void_p()
+    st = lib.sr_graph_create(na, len(nodes), binding._edge_array(edges), len(edges), batch, dtype, None, ctypes.byref(h))
+    name = lib.sr_status_str(st).decode()
+    if st == 0:
+        lib.sr_graph_destroy(h)
+    return name
+
+
+def test_create_rejects_bad_graphs_before_touching_a_device():
+    n3 = [(4, 8, 8, 0), (4, 8, 8, 1), (4, 8, 8, 1)]
+    assert create(n3, []) == "SR_ERR_GRAPH"
+    assert create(n3, edges_of([(0, 1), (2, 2)])) == "SR_ERR_GRAPH"                    # node 2 only feeds itself
+    assert create([(4, 8, 8, 1)] * 4, edges_of([(0, 1), (1, 3), (3, 2), (2, 0)])) == "SR_ERR_GRAPH"   # cycle, no input
+    assert create(n3, edges_of([(0, 1), (1, 2), (1, 1)], [1, 1, 0])) == "SR_ERR_ROLLOUT"   # self-edge must bridge
+    assert create(n3, edges_of([(0, 1), (1, 2), (2, 1)], [0, 0, 0])) == "SR_ERR_ROLLOUT"
+    assert create(n3, [Edge(0, 1), Edge(1, 2, stride=2)]) == "SR_ERR_SHAPE"
+    assert create(n3, [Edge(0, 1), Edge(1, 2, bridge=2)]) == "SR_ERR_ARG"
+    assert create(n3, edges_of([(0, 1), (1, 2)]), batch=0) == "SR_ERR_ARG"
+    assert create([(4, 8, 8, 7)] * 3, edges_of([(0, 1), (1, 2)])) == "SR_ERR_ARG"
+    lib = sr.load_library()
+    assert lib.sr_graph_create(None, 0, None, 0, 1, 0, None, None) == 1
+    assert b"SR_ERR_SHAPE" == lib.sr_status_str(4)
+
+
+def test_null_handles_are_errors_not_crashes():
+    lib = sr.load_library()
+    assert lib.sr_reset(None, None) == 1
+    assert lib.sr_frame_step(None, None) == 1
+    assert lib.sr_rollout(None, None, 1, 0, None) == 1
+    assert lib.sr_get_state(None, 0, None, 0) == 1
+    assert lib.sr_graph_info(None, None, None, None) == 1
+    lib.sr_graph_destroy(None)
+
+
+def test_bench_rejects_more_than_one_gpu():
+    import subprocess
+    import sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True)
+    assert r.returncode != 0 and "ONE GPU" in r.stderr
