@@ -397,20 +397,28 @@ template <int WN>
 __device__ __forceinline__ void sr_step(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
                                         sr_gfrag_ptr wchunk, bf16x8_t (&a)[4], bf16x8_t (&b)[WN],
                                         f32x16_t (&acc)[4][WN], int st, int NS) {
-  const bool more_a = st + 1 < NS;
-  const SrStep nx = sr_step_decode(e, more_a ? st + 1 : st);
+  // the loads are unconditional (past the end of the stage they repeat its last step) so that the
+  // loop body is branch-free and the hardware wait counters can be tracked exactly
+  const SrStep nx = sr_step_decode(e, min(st + 1, NS - 1));
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
 #pragma unroll
     for (int nj = 0; nj < WN; ++nj)
       acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[nj], a[mi], acc[mi][nj], 0, 0, 0);
-    if (more_a) a[mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
+    a[mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
   }
-  if (st + SR_RING < NS) {
-    const SrStep nb = sr_step_decode(e, st + SR_RING);
+  const SrStep nb = sr_step_decode(e, min(st + SR_RING, NS - 1));
 #pragma unroll
-    for (int nj = 0; nj < WN; ++nj) b[nj] = wchunk[nb.boff + nj * 64];
+  for (int nj = 0; nj < WN; ++nj) b[nj] = wchunk[nb.boff + nj * 64];
+  // keep the issue order written above: WN MFMAs, then the address add and the LDS read of the row
+  // they have just released, four times; then the weight loads
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    __builtin_amdgcn_sched_group_barrier(0x008, WN, 0);   // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);    // VALU (address)
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // DS read
   }
+  __builtin_amdgcn_sched_group_barrier(0x020, WN, 0);     // VMEM read
 }
 
 // One stage of the contraction: NS = taps * KC/16 k-steps over the patch in LDS.
@@ -497,6 +505,7 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
     for (int mi = 0; mi < 4; ++mi) {
       const int ox = pix[mi] & 0xfff, oy = (pix[mi] >> 12) & 0xfff, db = pix[mi] >> 24;
       abase[mi] = (db * e.PH + ((oy >> e.lgup) << e.lgs) - row_first) * e.RPB + (ox >> e.lgup) * e.SP + (lane >> 5) * 16;
+      asm volatile("" : "+v"(abase[mi]));   // keep it in a register: one add per k-step, not a re-derivation
     }
     const sr_gfrag_ptr wlane = e.wpk + ntile0 * 64 + lane;
     const int NS = e.ntaps << e.lgK16;
@@ -507,11 +516,9 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       bf16x8_t bq[SR_RING][WN];
 #pragma unroll
       for (int d = 0; d < SR_RING; ++d) {
-        if (d < NS) {
-          const SrStep nb = sr_step_decode(e, d);
+        const SrStep nb = sr_step_decode(e, min(d, NS - 1));
 #pragma unroll
-          for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[nb.boff + nj * 64];
-        }
+        for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[nb.boff + nj * 64];
       }
       sr_stage_dma(dma_base + (size_t)chunk * e.KC * 2, zero_page, lds, n_pos, tid, dma_off);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
