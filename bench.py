@@ -22,6 +22,27 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+TRAFFIC_RECORD = os.path.join(ROOT, "profiles", "hbm_traffic_sr_mfma_kernel_gtsrb_sr.json")
+KERNEL_SOURCES = ["sr_kernels.hip", "sr_host.cpp", "sr_internal.h"]
+
+
+def recorded_traffic(workload, pattern):
+    """HBM bytes per launch of the dominant kernel from the committed counter record (FETCH_SIZE and
+    WRITE_SIZE, scaled by a plain copy of known size); None if the record is for another workload or
+    the kernel sources have changed since the counters were taken."""
+    import hashlib
+    try:
+        rec = json.load(open(TRAFFIC_RECORD))
+        h = hashlib.sha256()
+        for f in KERNEL_SOURCES:
+            h.update(open(os.path.join(ROOT, "paper_1806_04965_amd", "csrc", f), "rb").read())
+        if h.hexdigest() != rec["source_sha256"] or not rec["workload"].startswith(f"{workload} ({pattern}"):
+            return None
+        return rec["hbm_bytes_per_launch"]
+    except Exception:
+        return None
+
+
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_FP32_VALU_TFLOPS = 157.3  # fp32 vector peak (the fp32 graph runs on plain ALUs)
 
@@ -111,7 +132,8 @@ def main():
         frame_conv_ms = mfma_launch_ms * launches_per_frame
         achieved = conv_flops / (frame_conv_ms * 1e-3) / 1e12
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
-                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4), "traffic": None,
+                    "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
+                    "traffic": recorded_traffic(args.workload, args.pattern),
                     "kernel": "sr_mfma_kernel", "launch_ms": round(mfma_launch_ms, 4),
                     "launches_per_frame": launches_per_frame, "flop_per_frame": conv_flops}
         del per_frame
