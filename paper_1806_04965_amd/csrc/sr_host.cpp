@@ -7,6 +7,7 @@
 #include <cstdio>
 #include <cstdlib>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <string>
 #include <unordered_map>
@@ -189,6 +190,11 @@ struct sr_graph {
   SrMfmaTile* m_tiles = nullptr;
   int32_t* plan_index = nullptr;
   int32_t* plan_tables = nullptr;
+  float* split_scratch = nullptr;
+  size_t split_scratch_bytes = 0;
+  int32_t* split_counters = nullptr;
+  int n_split_slots = 0;
+  bool allow_split = true;
   SrHead* heads = nullptr;
   void* zero_page = nullptr;
   int lds_bytes = 0;
@@ -222,6 +228,29 @@ sr_status gfail(sr_graph* g, sr_status st, const std::string& msg) {
   } while (0)
 
 size_t elem_size(const sr_graph* g) { return g->dtype == SR_BF16 ? 2 : 4; }
+
+// Uncached device memory for data that workgroups on different XCDs hand to each other inside one
+// launch (K-split partial sums).  Blocks are never given back to the driver: a destroyed graph
+// returns its block to this process-wide free list and a later graph reuses it.
+struct UncachedBlock { void* ptr; size_t bytes; };
+std::vector<UncachedBlock> g_uncached_free;
+std::mutex g_uncached_mutex;
+
+hipError_t uncached_alloc(void** p, size_t bytes) {
+  std::lock_guard<std::mutex> lock(g_uncached_mutex);
+  for (size_t i = 0; i < g_uncached_free.size(); ++i)
+    if (g_uncached_free[i].bytes >= bytes) {
+      *p = g_uncached_free[i].ptr;
+      g_uncached_free.erase(g_uncached_free.begin() + i);
+      return hipSuccess;
+    }
+  return hipExtMallocWithFlags(p, bytes, hipDeviceMallocUncached);
+}
+
+void uncached_release(void* p, size_t bytes) {
+  std::lock_guard<std::mutex> lock(g_uncached_mutex);
+  g_uncached_free.push_back(UncachedBlock{p, bytes});
+}
 
 sr_status dev_alloc(sr_graph* g, void** p, size_t bytes) {
   *p = nullptr;
@@ -420,7 +449,7 @@ sr_status finalize(sr_graph* g) {
     lp.tile_begin = (int)mt.size();
     lp.block_begin = (int)db.size();
     lp.head_begin = (int)hd.size();
-    struct TileGroup { int node_index; double cost; std::vector<SrMfmaTile> tiles; };
+    struct TileGroup { int node_index; double cost; int n_stages; std::vector<SrMfmaTile> tiles; };
     std::vector<TileGroup> groups;
     std::vector<SrAux> level_aux;
     if (L == 1 && g->stage_folded) level_aux = stage_aux;
@@ -543,6 +572,9 @@ sr_status finalize(sr_graph* g) {
             }
             grp.cost = cyc;
           }
+          int n_stages = 0;
+          for (int ei = 0; ei < node.edge_count; ++ei) n_stages += me[node.edge_begin + ei].nchunk;
+          grp.n_stages = n_stages;
           // channel tiles of one pixel tile are neighbours in the list (they share the source patch)
           for (int mi = 0; mi < n_mt; ++mi)
             for (int nt = 0; nt < n_nt; ++nt) {
@@ -551,6 +583,10 @@ sr_status finalize(sr_graph* g) {
                 t.m0 = mi * BM;
                 t.n0 = nt * BN;
                 t.plan_begin = (int)plan_index.size();
+                t.stage_begin = 0;
+                t.stage_end = n_stages;
+                t.split_slot = -1;
+                t.part = 1 << 16;
                 for (int ei = 0; ei < node.edge_count; ++ei) {
                   const SrMfmaEdge& m = me[node.edge_begin + ei];
                   const PatchRows r = patch_rows(t.m0, std::min<int64_t>((int64_t)t.m0 + BM, M) - 1,
@@ -660,6 +696,40 @@ sr_status finalize(sr_graph* g) {
     // An XCD then works on one or two nodes at a time, whose packed weights and neighbouring source
     // patches stay in its L2, instead of every L2 streaming every node's weights.  Shorter runs are
     // padded with empty tiles (node -1).
+    // K-split: when a node's tiles are long compared with an even share of the level's work (few
+    // pixels, deep K) they are cut into parts by stage range, so that the launch does not end on a
+    // handful of long tiles while most of the chip idles.
+    {
+      double level_cost = 0;
+      for (const TileGroup& grp : groups) level_cost += grp.cost * grp.tiles.size();
+      const double slots = 2.0 * 256;                       // resident workgroups of the chip
+      const double share = level_cost / slots;
+      for (TileGroup& grp : groups) {
+        // only tiles longer than an even share of the level are cut, into parts of about half a
+        // share but not shorter than ~25 us (a part pays for its own staging and for the reduction)
+        // (a part leaves 128 KiB of partial sums in uncached memory and the last one reads them all:
+        // measured, parts shorter than this cost more than the better balance gains)
+        const double part_cost = std::max(0.5 * share, 60000.0);
+        int parts = (grp.cost > share) ? (int)std::ceil(grp.cost / part_cost) : 1;
+        parts = std::max(1, std::min(std::min(parts, 16), grp.n_stages));
+        if (parts <= 1 || !g->allow_split) continue;
+        std::vector<SrMfmaTile> cut;
+        for (const SrMfmaTile& t : grp.tiles) {
+          const int slot = g->n_split_slots;
+          g->n_split_slots += parts;
+          for (int p = 0; p < parts; ++p) {
+            SrMfmaTile tp = t;
+            tp.stage_begin = (int)((int64_t)grp.n_stages * p / parts);
+            tp.stage_end = (int)((int64_t)grp.n_stages * (p + 1) / parts);
+            tp.split_slot = slot;
+            tp.part = p | (parts << 16);
+            cut.push_back(tp);
+          }
+        }
+        grp.tiles.swap(cut);
+        grp.cost = grp.cost / parts + 4000.0;
+      }
+    }
     std::stable_sort(groups.begin(), groups.end(),
                      [](const TileGroup& a, const TileGroup& b) { return a.cost > b.cost; });
     {
@@ -697,7 +767,23 @@ sr_status finalize(sr_graph* g) {
   if ((st = upload(g, &g->d_blocks, db)) != SR_OK) return st;
   if ((st = upload(g, &g->plan_index, plan_index)) != SR_OK) return st;
   if ((st = upload(g, &g->plan_tables, plan_tables)) != SR_OK) return st;
-  for (SrMfmaNode& node : mn) { node.plan_index = g->plan_index; node.plan_tables = g->plan_tables; }
+  if (g->n_split_slots > 0) {
+    void* sp = nullptr;
+    g->split_scratch_bytes = (size_t)g->n_split_slots * SR_SPLIT_FLOATS * sizeof(float);
+    // a reused block may be larger; remember the size actually held
+    SR_HIP(g, uncached_alloc(&sp, g->split_scratch_bytes));
+    g->split_scratch = (float*)sp;
+    g->device_bytes += (int64_t)g->split_scratch_bytes;
+    if ((st = dev_alloc(g, &sp, (size_t)g->n_split_slots * sizeof(int32_t))) != SR_OK) return st;
+    g->split_counters = (int32_t*)sp;
+    SR_HIP(g, sr_launch_fill_zero(g->stream, sp, (size_t)g->n_split_slots * sizeof(int32_t)));
+  }
+  for (SrMfmaNode& node : mn) {
+    node.plan_index = g->plan_index;
+    node.plan_tables = g->plan_tables;
+    node.split_scratch = g->split_scratch;
+    node.split_counters = g->split_counters;
+  }
   if ((st = upload(g, &g->m_nodes, mn)) != SR_OK) return st;
   if ((st = upload(g, &g->m_edges, me)) != SR_OK) return st;
   if ((st = upload(g, &g->m_tiles, mt)) != SR_OK) return st;
@@ -1102,6 +1188,7 @@ sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value) {
   switch (option) {
     case SR_OPT_USE_HIPGRAPH: g->use_hipgraph = value != 0; return SR_OK;
     case SR_OPT_FORCE_DIRECT: g->force_direct = value != 0; return SR_OK;
+    case SR_OPT_K_SPLIT: g->allow_split = value != 0; return SR_OK;
     case SR_OPT_FRAMES_PER_GRAPH:
       if (value < 1 || value > 1024) return gfail(g, SR_ERR_ARG, "frames per graph must be in 1..1024");
       g->frames_per_graph = (int)value;
@@ -1245,6 +1332,7 @@ void sr_graph_destroy(sr_graph* g) {
   if (g->stream || !g->dev_allocs.empty()) hipStreamSynchronize(g->stream);
   drop_graphs(g);
   for (void* p : g->dev_allocs) hipFree(p);
+  if (g->split_scratch) uncached_release(g->split_scratch, g->split_scratch_bytes);
   delete g;
 }
 

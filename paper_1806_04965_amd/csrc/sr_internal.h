@@ -5,6 +5,7 @@
 #include <stdint.h>
 
 #define SR_MAX_INPUTS 16
+#define SR_SPLIT_FLOATS (128 * 256)   // accumulator floats one part leaves in scratch
 #define SR_XCDS 8          // accelerator complex dies of an MI355X; workgroup i of a launch runs on XCD i % 8
 
 // One per graph, in device memory.  Kernels read the frame counter from here, so
@@ -75,6 +76,8 @@ struct SrMfmaNode {
   const void* zero_page; // 256 zero bytes: source of padding pixels for the direct-to-LDS loads
   const int32_t* plan_index;   // [tile.plan_begin + edge]: offset of that (tile, edge) plan in plan_tables
   const int32_t* plan_tables;  // per LDS position: source byte offset, -1 zero page, -2 not written
+  float* split_scratch;        // [slot][16*4*2 registers][256 threads] accumulators of K-split parts
+  int32_t* split_counters;     // [slot] parts finished (returns to 0)
   int32_t M;             // B*Ho*Wo
   int32_t Ho, Wo;
   int32_t Cout, Cp;
@@ -90,6 +93,12 @@ struct SrMfmaTile {
   int32_t m0;    // first output pixel (linear over [B][Ho][Wo])
   int32_t n0;    // first output channel
   int32_t plan_begin;  // first entry of this tile in plan_index (one per incoming edge)
+  // K-split: a long tile is cut into parts that each walk a range of the node's stages (a stage =
+  // one channel chunk of one edge, counted over the node's edges in order) and leave their
+  // accumulators in scratch; the part that finishes last adds them up in part order and stores.
+  int32_t stage_begin, stage_end;
+  int32_t split_slot;  // index of part 0 of this tile in the scratch / counter arrays, -1: not split
+  int32_t part;        // part index | number of parts << 16
 };
 
 // ---------------------------------------------------------------------------

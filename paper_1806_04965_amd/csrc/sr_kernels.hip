@@ -168,19 +168,20 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
     for (; p < p1; ++p) s0 += Store<T>::load(src + (size_t)p * h.Csp + c);
     const float sum = (s0 + s1) + (s2 + s3);
     if (h.splits == 1) smem[c] = sum * inv;
-    else h.partial[((size_t)b * h.splits + split) * h.Cin + c] = sum;
+    else   // device-coherent (write-through) store, read back below by whichever slab finishes last
+      __hip_atomic_store(&h.partial[((size_t)b * h.splits + split) * h.Cin + c], sum, __ATOMIC_RELAXED,
+                         __HIP_MEMORY_SCOPE_AGENT);
   }
   if (h.splits > 1) {
-    __threadfence();
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
     if (threadIdx.x == 0) {
-      const int old = atomicAdd(&h.counters[b], 1);
+      const int old = __hip_atomic_fetch_add(&h.counters[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       *flag = (old == h.splits - 1);
       if (old == h.splits - 1) h.counters[b] = 0;
     }
     __syncthreads();
     if (!*flag) return;
-    __threadfence();
     for (int c = threadIdx.x; c < h.Cin; c += blockDim.x) {
       float sum = 0.f;
       for (int s = 0; s < h.splits; ++s)
@@ -443,7 +444,8 @@ __device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const unsigne
 template <int WN>
 __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
                                              const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
-                                             int tile_n0, int plan_begin, unsigned char* lds) {
+                                             int tile_n0, int plan_begin, int stage_begin, int stage_end,
+                                             int split_slot, int part_info, unsigned char* lds) {
   const __attribute__((address_space(4))) SrMfmaNode* nd =
       (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
   const int tid = threadIdx.x;
@@ -489,8 +491,12 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
 
+  int stage_base = 0;   // index of the current edge's first stage among the node's stages
   for (int ei = 0; ei < edge_count; ++ei) {
     const SrEdgeK e = sr_load_edge(edges, edge_begin + ei, cur);
+    const int chunk_lo = max(stage_begin - stage_base, 0), chunk_hi = min(stage_end - stage_base, e.nchunk);
+    stage_base += e.nchunk;
+    if (chunk_lo >= chunk_hi) continue;   // this part of a K-split tile has no stage on this edge
     const int row_first = (oy_first >> e.lgup) << e.lgs;          // first padded source row, in its image
     const int Q0 = b_first * e.PH + row_first;
     const int Q1 = b_last * e.PH + ((oy_last >> e.lgup) << e.lgs) + e.kh - 1;
@@ -509,7 +515,7 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
     }
     const sr_gfrag_ptr wlane = e.wpk + ntile0 * 64 + lane;
     const int NS = e.ntaps << e.lgK16;
-    for (int chunk = 0; chunk < e.nchunk; ++chunk) {
+    for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
       const sr_gfrag_ptr wchunk = wlane + (size_t)(chunk << e.lgK16) * e.wstride8;
       __syncthreads();   // everyone has finished reading the previous patch
       // the first weight fragments go out ahead of the patch so that both are in flight together
@@ -525,6 +531,49 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       __syncthreads();                                     // ... and everybody else's
       sr_stage_compute<WN>(e, lds, abase, wchunk, bq, acc, NS);
     }
+  }
+
+  // ---- K-split tiles: leave the accumulators in scratch; the part that arrives last adds all parts
+  // in part order (so the result does not depend on which part that is) and goes on to the epilogue.
+  // The scratch is uncached device memory, so plain 16-byte stores and loads are coherent across
+  // the chip's L2s once they have completed.
+  const int n_parts = part_info >> 16;
+  if (n_parts > 1) {
+    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+    f32x4_t* scratch = (f32x4_t*)((float*)nd->split_scratch + (size_t)(split_slot + (part_info & 0xffff)) * SR_SPLIT_FLOATS);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4_t v = {acc[mi][nj][4 * q], acc[mi][nj][4 * q + 1], acc[mi][nj][4 * q + 2], acc[mi][nj][4 * q + 3]};
+          scratch[((mi * WN + nj) * 4 + q) * 256 + tid] = v;
+        }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have reached memory
+    __syncthreads();
+    int* flag = (int*)lds;
+    if (tid == 0) {
+      int* counter = (int*)nd->split_counters + split_slot;
+      const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *flag = (old == n_parts - 1);
+      if (old == n_parts - 1) *counter = 0;
+    }
+    __syncthreads();
+    if (!*flag) return;
+    const f32x4_t* all = (const f32x4_t*)((const float*)nd->split_scratch + (size_t)split_slot * SR_SPLIT_FLOATS);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+          for (int p = 0; p < n_parts; ++p)
+            sum += all[(size_t)p * (SR_SPLIT_FLOATS / 4) + ((mi * WN + nj) * 4 + q) * 256 + tid];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] = sum[i];
+        }
   }
 
   // ---- epilogue: bias, activation, round to bf16, NHWC store.
@@ -597,9 +646,13 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
     if (node_index < 0) {
       // empty slot
     } else if (nodes[node_index].wn_tiles == 2)
-      sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
+      sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
+                      SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
+                      sr_lds);
     else
-      sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin), sr_lds);
+      sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
+                      SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
+                      sr_lds);
   } else {
     sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, stage_nodes, (float*)sr_lds);
   }

@@ -100,6 +100,14 @@ def test_gap_head_with_several_pixel_slabs():
         check(g.with_pattern([0, 1, 0]), seed=8, label=f"gap_head/{dtype}/sequential")
 
 
+def test_k_split_on_and_off_agree_with_the_oracle():
+    # deep nodes with few pixels are cut along the contraction; with the option off they are not
+    g = W.cifar_sr(batch=4, frames=5)
+    _, work_on = check(g, seed=11, label="cifar_sr/k-split on")
+    _, work_off = check(g, seed=11, options={3: 0}, label="cifar_sr/k-split off")
+    assert work_on["mfma_tiles"] > work_off["mfma_tiles"]
+
+
 def test_recording_a_hidden_node():
     g = W.cifar_sr(batch=2, frames=5)
     w, b, x = W.make_case(g, seed=9)
