@@ -306,7 +306,8 @@ __global__ __launch_bounds__(256) void sr_direct_kernel(SrCtx* __restrict__ ctx,
 // B operand (weights): pre-packed on the host in exactly the per-lane order of the instruction,
 // [tap][k16 block][32-channel tile][lane][8], so a wave's fragment is one coalesced 1 KiB load
 // straight into registers, prefetched a few k-steps ahead through a small ring.
-#define SR_RING 4   // depth of the weight-fragment ring; the step loop is unrolled by it
+#define SR_RING 3   // depth of the weight-fragment ring
+#define SR_UNROLL 6 // k-steps per loop body: a multiple of the ring depth and of the 2 A-fragment buffers
 
 typedef const __attribute__((address_space(1))) bf16x8_t* sr_gfrag_ptr;   // global memory
 #define SR_UNIFORM(x) __builtin_amdgcn_readfirstlane(x)
@@ -391,33 +392,33 @@ __device__ __forceinline__ SrStep sr_step_decode(const SrEdgeK& e, int st) {
   return r;
 }
 
-// One k-step: 4 x WN MFMAs.  Each A fragment is reloaded for the next step right after its last
-// use, which leaves the other rows' MFMAs to cover the LDS latency; the weight fragments of ring
-// slot u are replaced by those of step st + SR_RING once all rows have used them.
+// One k-step: 4 x WN MFMAs on the A fragments `a`, while the next step's A fragments are read
+// from LDS into `an` (double buffer: the reads have a whole step to complete) and the weight
+// fragments of ring slot `b` are replaced, once used, by those of step st + SR_RING.  The loads are
+// unconditional (past the end of the stage they repeat its last step) so that the loop body is
+// branch-free and the hardware wait counters can be tracked exactly.
 template <int WN>
 __device__ __forceinline__ void sr_step(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
-                                        sr_gfrag_ptr wchunk, bf16x8_t (&a)[4], bf16x8_t (&b)[WN],
-                                        f32x16_t (&acc)[4][WN], int st, int NS) {
-  // the loads are unconditional (past the end of the stage they repeat its last step) so that the
-  // loop body is branch-free and the hardware wait counters can be tracked exactly
+                                        sr_gfrag_ptr wchunk, const bf16x8_t (&a)[4], bf16x8_t (&an)[4],
+                                        bf16x8_t (&b)[WN], f32x16_t (&acc)[4][WN], int st, int NS) {
   const SrStep nx = sr_step_decode(e, min(st + 1, NS - 1));
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
+    an[mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
 #pragma unroll
     for (int nj = 0; nj < WN; ++nj)
       acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[nj], a[mi], acc[mi][nj], 0, 0, 0);
-    a[mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
   }
   const SrStep nb = sr_step_decode(e, min(st + SR_RING, NS - 1));
 #pragma unroll
   for (int nj = 0; nj < WN; ++nj) b[nj] = wchunk[nb.boff + nj * 64];
-  // keep the issue order written above: WN MFMAs, then the address add and the LDS read of the row
-  // they have just released, four times; then the weight loads
+  // keep the issue order written above: address add + LDS read, then WN MFMAs, four times; then the
+  // weight loads
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
-    __builtin_amdgcn_sched_group_barrier(0x008, WN, 0);   // MFMA
     __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);    // VALU (address)
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // DS read
+    __builtin_amdgcn_sched_group_barrier(0x008, WN, 0);   // MFMA
   }
   __builtin_amdgcn_sched_group_barrier(0x020, WN, 0);     // VMEM read
 }
@@ -427,18 +428,19 @@ template <int WN>
 __device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
                                                  sr_gfrag_ptr wchunk, bf16x8_t (&bq)[SR_RING][WN],
                                                  f32x16_t (&acc)[4][WN], int NS) {
-  bf16x8_t a[4];
+  bf16x8_t a[2][4];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi) a[mi] = *(const bf16x8_t*)(lds + abase[mi]);
+  for (int mi = 0; mi < 4; ++mi) a[0][mi] = *(const bf16x8_t*)(lds + abase[mi]);
   int st0 = 0;
-  for (; st0 + SR_RING <= NS; st0 += SR_RING) {
+  for (; st0 + SR_UNROLL <= NS; st0 += SR_UNROLL) {
 #pragma unroll
-    for (int u = 0; u < SR_RING; ++u) sr_step<WN>(e, lds, abase, wchunk, a, bq[u], acc, st0 + u, NS);
+    for (int u = 0; u < SR_UNROLL; ++u)
+      sr_step<WN>(e, lds, abase, wchunk, a[u & 1], a[(u + 1) & 1], bq[u % SR_RING], acc, st0 + u, NS);
   }
-  // remaining 0..SR_RING-1 steps (their weight fragments are already in ring slots 0, 1, ...)
+  // remaining 0..SR_UNROLL-1 steps (their fragments are already in buffer 0 / ring slots 0, 1, ...)
 #pragma unroll
-  for (int u = 0; u < SR_RING - 1; ++u)
-    if (st0 + u < NS) sr_step<WN>(e, lds, abase, wchunk, a, bq[u], acc, st0 + u, NS);
+  for (int u = 0; u < SR_UNROLL - 1; ++u)
+    if (st0 + u < NS) sr_step<WN>(e, lds, abase, wchunk, a[u & 1], a[(u + 1) & 1], bq[u % SR_RING], acc, st0 + u, NS);
 }
 
 template <int WN>
