@@ -196,6 +196,7 @@ struct sr_graph {
   int n_split_slots = 0;
   bool allow_split = true;
   SrHead* heads = nullptr;
+  SrHeadEdge* head_edges = nullptr;
   void* zero_page = nullptr;
   int lds_bytes = 0;
   int64_t n_mfma_tiles = 0;
@@ -382,11 +383,17 @@ sr_status finalize(sr_graph* g) {
   for (int v = 0; v < g->n_nodes; ++v) {
     NodeRt& n = g->nodes[v];
     if (g->an.is_input[v]) { n.kind = 0; continue; }
-    int n_in = 0, n_gap = 0;
-    for (const EdgeRt& e : g->edges)
-      if (e.d.dst == v) { ++n_in; n_gap += (e.d.kind == SR_EDGE_GAP_DENSE); }
+    // head: every incoming edge is dense or GAP+dense, with input vectors and outputs that fit the item
+    bool head_ok = !g->force_direct && n.d.channels <= SR_HEAD_MAX_COUT;
+    for (const EdgeRt& e : g->edges) {
+      if (e.d.dst != v) continue;
+      const sr_node_desc& sd = g->nodes[e.d.src].d;
+      if (e.d.kind == SR_EDGE_CONV) head_ok = false;
+      if (e.d.kind == SR_EDGE_DENSE && (int64_t)sd.height * sd.width * sd.channels > SR_HEAD_MAX_K) head_ok = false;
+      if (e.d.kind == SR_EDGE_GAP_DENSE && sd.channels > SR_HEAD_MAX_K) head_ok = false;
+    }
     if (mfma_eligible(g, v)) n.kind = 1;
-    else if (n_in == 1 && n_gap == 1 && !g->force_direct) n.kind = 3;
+    else if (head_ok) n.kind = 3;
     else n.kind = 2;
   }
 
@@ -410,6 +417,7 @@ sr_status finalize(sr_graph* g) {
   std::vector<SrMfmaEdge> me;
   std::vector<SrMfmaTile> mt;
   std::vector<SrHead> hd;
+  std::vector<SrHeadEdge> he;
   std::vector<int32_t> plan_index, plan_tables, plan_tmp;   // per (tile, edge): offset of its plan
   std::unordered_map<uint64_t, std::vector<int>> plan_seen;
   g->levels.assign(F + 1, LevelPlan());
@@ -612,17 +620,25 @@ sr_status finalize(sr_graph* g) {
       }
       if (n.kind == 3) {
         SrHead h{};
+        h.edge_begin = (int)he.size();
+        int max_vec = 0, pooled_hw = 0, pooled_cin = 0;
         for (const EdgeRt& e : g->edges) {
           if (e.d.dst != v) continue;
           const NodeRt& sn = g->nodes[e.d.src];
-          h.src[0] = sn.state[0];
-          h.src[1] = sn.state[1];
-          h.w = e.w_dev;
-          h.bridge = e.d.bridge;
-          h.HW = sn.d.height * sn.d.width;
-          h.Cin = sn.d.channels;
-          h.Csp = sn.Cp;
+          SrHeadEdge x{};
+          x.src[0] = sn.state[0];
+          x.src[1] = sn.state[1];
+          x.w = e.w_dev;
+          x.bridge = e.d.bridge;
+          x.pooled = (e.d.kind == SR_EDGE_GAP_DENSE) ? 1 : 0;
+          x.HW = sn.d.height * sn.d.width;
+          x.Cin = sn.d.channels;
+          x.Csp = sn.Cp;
+          max_vec = std::max(max_vec, x.pooled ? x.Cin : x.HW * x.Cin);
+          if (x.pooled) { pooled_hw = x.HW; pooled_cin = x.Cin; }
+          he.push_back(x);
         }
+        h.edge_count = (int)he.size() - h.edge_begin;
         h.out[0] = n.state[0];
         h.out[1] = n.state[1];
         h.bias = n.bias_dev;
@@ -630,7 +646,8 @@ sr_status finalize(sr_graph* g) {
         h.B = B;
         h.Cout = n.d.channels;
         h.Cp = n.Cp;
-        h.splits = std::max(1, std::min(64, (h.HW + 63) / 64));
+        // a single pooled edge over many pixels is cut into slabs of 64 pixels
+        h.splits = (h.edge_count == 1 && pooled_hw > 0) ? std::max(1, std::min(64, (pooled_hw + 63) / 64)) : 1;
         h.record = 0;
         void* cnt = nullptr;
         {
@@ -640,14 +657,14 @@ sr_status finalize(sr_graph* g) {
         }
         h.counters = (int32_t*)cnt;
         void* part = nullptr;
-        sr_status st = dev_alloc(g, &part, (size_t)B * h.splits * h.Cin * sizeof(float));
+        sr_status st = dev_alloc(g, &part, (size_t)B * h.splits * std::max(pooled_cin, 1) * sizeof(float));
         if (st != SR_OK) return st;
         h.partial = (float*)part;
         for (int b = 0; b < B; ++b)
           for (int sp = 0; sp < h.splits; ++sp) level_aux.push_back(SrAux{SR_AUX_HEAD, (int)hd.size(), b, sp});
         g->head_node.push_back(v);
         hd.push_back(h);
-        g->aux_smem_bytes = std::max(g->aux_smem_bytes, (int)(h.Cin * sizeof(float) + 16 + 256 * sizeof(float)));
+        g->aux_smem_bytes = std::max(g->aux_smem_bytes, (int)(max_vec * sizeof(float) + 16 + 4096));
       }
       if (n.kind == 2) {
         SrDirectNode node{};
@@ -788,6 +805,7 @@ sr_status finalize(sr_graph* g) {
   if ((st = upload(g, &g->m_edges, me)) != SR_OK) return st;
   if ((st = upload(g, &g->m_tiles, mt)) != SR_OK) return st;
   if ((st = upload(g, &g->heads, hd)) != SR_OK) return st;
+  if ((st = upload(g, &g->head_edges, he)) != SR_OK) return st;
   if ((st = upload(g, &g->aux, aux)) != SR_OK) return st;
   g->heads_host = hd;
   g->lds_bytes = std::max(g->lds_bytes, g->aux_smem_bytes);
@@ -856,7 +874,7 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
   }
   if (!g->stage_folded) {
     SR_HIP(g, mark(0));
-    SR_HIP(g, sr_launch_aux(s, g->ctx, g->aux + g->stage_aux_begin, g->n_stage_aux, g->heads, g->stage_nodes,
+    SR_HIP(g, sr_launch_aux(s, g->ctx, g->aux + g->stage_aux_begin, g->n_stage_aux, g->heads, g->head_edges, g->stage_nodes,
                             g->aux_smem_bytes, bf16, 0));
   }
   for (int L = 1; L <= g->an.factor; ++L) {
@@ -867,14 +885,15 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
       const int is_last = (!copy_out && L == last_level && !last_is_direct) ? 1 : 0;
       SR_HIP(g, mark(1));
       SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes,
-                               g->aux + lp.aux_begin, lp.n_aux, g->heads, g->stage_nodes, is_last));
+                               g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes, g->aux_smem_bytes,
+                               is_last));
     }
     if (direct_launch) {
       const int is_last = (!copy_out && L == last_level) ? 1 : 0;
       const int n_aux = has_tiles ? 0 : lp.n_aux;   // aux items already went with the tiles
       SR_HIP(g, mark(2));
       SR_HIP(g, sr_launch_direct(s, g->ctx, g->d_nodes, g->d_edges, g->d_blocks + lp.block_begin, lp.n_blocks, bf16,
-                                 g->batch, g->aux + lp.aux_begin, n_aux, g->heads, g->stage_nodes,
+                                 g->batch, g->aux + lp.aux_begin, n_aux, g->heads, g->head_edges, g->stage_nodes,
                                  g->aux_smem_bytes, is_last));
     }
   }

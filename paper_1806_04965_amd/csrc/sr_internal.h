@@ -102,19 +102,29 @@ struct SrMfmaTile {
 };
 
 // ---------------------------------------------------------------------------
-// GAP + dense head (node with a single GAP+dense incoming edge)
+// head nodes: 1x1 nodes all of whose incoming edges are dense or GAP+dense
 // ---------------------------------------------------------------------------
-struct SrHead {
+struct SrHeadEdge {
   const void* src[2];
+  const float* w;        // [K][Cout] float, K = Cin (pooled) or HW*Cin (flattened, (h,w,c) order)
+  int32_t bridge;
+  int32_t pooled;        // 1: mean over the HW pixels first; 0: the flattened source is the vector
+  int32_t HW, Cin, Csp;  // source pixels per image, channels, channel pitch
+  int32_t pad_;
+};
+
+struct SrHead {
   void* out[2];
-  const float* w;        // [Cin][Cout] float
   const float* bias;
-  float* partial;        // [B][splits][Cin] float scratch
+  float* partial;        // [B][splits][Cin] float scratch (pooled single-edge heads with several slabs)
   int32_t* counters;     // [B] slabs finished per image (return to 0)
-  int32_t bridge, act;
-  int32_t B, HW, Cin, Csp, Cout, Cp;
+  int32_t edge_begin, edge_count;
+  int32_t act, B, Cout, Cp;
   int32_t splits, record;   // record: also write the result to the rollout output
 };
+
+#define SR_HEAD_MAX_K 12288   // longest input vector of a head edge (floats held in LDS)
+#define SR_HEAD_MAX_COUT 256
 
 // input staging / state packing
 struct SrStageNode {
@@ -140,11 +150,14 @@ hipError_t sr_launch_pack(hipStream_t s, void* dst, const void* src, int px, int
 hipError_t sr_launch_record_output(hipStream_t s, const SrCtx* ctx, const void* state0, const void* state1,
                                    int px, int C, int Cp, int bf16);
 hipError_t sr_launch_aux(hipStream_t s, SrCtx* ctx, const SrAux* aux, int n_aux, const SrHead* heads,
-                         const SrStageNode* stage_nodes, int smem_bytes, int bf16, int is_last);
+                         const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int smem_bytes, int bf16,
+                         int is_last);
 hipError_t sr_launch_direct(hipStream_t s, SrCtx* ctx, const SrDirectNode* nodes, const SrDirectEdge* edges,
                             const SrDirectBlock* blocks, int n_blocks, int bf16, int batch, const SrAux* aux, int n_aux,
-                            const SrHead* heads, const SrStageNode* stage_nodes, int smem_bytes, int is_last);
+                            const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
+                            int smem_bytes, int is_last);
 hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
                           const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
-                          const SrHead* heads, const SrStageNode* stage_nodes, int is_last);
+                          const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
+                          int aux_smem_bytes, int is_last);
 int sr_mfma_max_lds_bytes();

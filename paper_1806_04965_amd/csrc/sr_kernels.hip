@@ -142,83 +142,104 @@ __device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, con
   }
 }
 
-// GAP + dense head (App. A2: fully connected edge after pooling), one item per (image, pixel slab):
-// the slab's channel sums go to `partial`; the item that finishes last for an image adds the slabs
-// in slab order, applies the dense map, bias and activation, stores the node's state and, if this
-// node is being recorded, the rollout output.  smem: Cin floats, one int, 4*64 floats.
+// Head node (App. A2: fully connected layers, optionally after global average pooling): a 1x1 node
+// whose incoming edges are all dense or GAP+dense.  One item per image (and, for a single pooled
+// edge over many pixels, per pixel slab: the slab sums go to `partial` and the item that finishes
+// last for an image adds them in slab order).  For every edge the input vector (pooled means or the
+// flattened source) is put into LDS, then each of the 4 waves multiplies a quarter of it into up to
+// 256 outputs; the quarters are added in wave order, then bias, activation, store and, if this node
+// is being recorded, the rollout output.  smem: SR_HEAD_MAX_K floats, one int, 4*64*4 floats.
 template <typename T>
-__device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, const SrHead& h, int b, int split,
-                                             float* smem) {
+__device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, const SrHead& h,
+                                             const SrHeadEdge* __restrict__ head_edges, int b, int split,
+                                             float* smem, int vec_floats) {
   const int cur = ctx->frame & 1;
-  const T* src = (const T*)h.src[h.bridge ? (cur ^ 1) : cur] + (size_t)b * h.HW * h.Csp;
-  const int per = (h.HW + h.splits - 1) / h.splits;
-  const int p0 = split * per, p1 = min(h.HW, p0 + per);
-  const float inv = 1.0f / (float)h.HW;
-  int* flag = (int*)(smem + h.Cin);
-  float* red = smem + h.Cin + 4;
-  for (int c = threadIdx.x; c < h.Cin; c += blockDim.x) {
-    float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
-    int p = p0;
-    for (; p + 4 <= p1; p += 4) {
-      s0 += Store<T>::load(src + (size_t)p * h.Csp + c);
-      s1 += Store<T>::load(src + (size_t)(p + 1) * h.Csp + c);
-      s2 += Store<T>::load(src + (size_t)(p + 2) * h.Csp + c);
-      s3 += Store<T>::load(src + (size_t)(p + 3) * h.Csp + c);
+  int* flag = (int*)(smem + vec_floats);
+  float* red = smem + vec_floats + 4;
+  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
+  float acc[4] = {0.f, 0.f, 0.f, 0.f};     // outputs lane, lane+64, lane+128, lane+192: this wave's share
+  for (int ei = 0; ei < h.edge_count; ++ei) {
+    const SrHeadEdge e = head_edges[h.edge_begin + ei];
+    const T* src = (const T*)e.src[e.bridge ? (cur ^ 1) : cur] + (size_t)b * e.HW * e.Csp;
+    int K;
+    __syncthreads();   // the previous edge's vector is no longer needed
+    if (e.pooled) {
+      K = e.Cin;
+      const int per = (e.HW + h.splits - 1) / h.splits;
+      const int p0 = split * per, p1 = min(e.HW, p0 + per);
+      const float inv = 1.0f / (float)e.HW;
+      for (int c = threadIdx.x; c < e.Cin; c += blockDim.x) {
+        float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
+        int p = p0;
+        for (; p + 4 <= p1; p += 4) {
+          s0 += Store<T>::load(src + (size_t)p * e.Csp + c);
+          s1 += Store<T>::load(src + (size_t)(p + 1) * e.Csp + c);
+          s2 += Store<T>::load(src + (size_t)(p + 2) * e.Csp + c);
+          s3 += Store<T>::load(src + (size_t)(p + 3) * e.Csp + c);
+        }
+        for (; p < p1; ++p) s0 += Store<T>::load(src + (size_t)p * e.Csp + c);
+        const float sum = (s0 + s1) + (s2 + s3);
+        if (h.splits == 1) smem[c] = sum * inv;
+        else   // device-coherent (write-through) store, read back below by whichever slab finishes last
+          __hip_atomic_store(&h.partial[((size_t)b * h.splits + split) * e.Cin + c], sum, __ATOMIC_RELAXED,
+                             __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (h.splits > 1) {   // only single-edge heads are cut into slabs
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        if (threadIdx.x == 0) {
+          const int old = __hip_atomic_fetch_add(&h.counters[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          *flag = (old == h.splits - 1);
+          if (old == h.splits - 1) h.counters[b] = 0;
+        }
+        __syncthreads();
+        if (!*flag) return;
+        for (int c = threadIdx.x; c < e.Cin; c += blockDim.x) {
+          float sum = 0.f;
+          for (int s = 0; s < h.splits; ++s)
+            sum += __hip_atomic_load(&h.partial[((size_t)b * h.splits + s) * e.Cin + c], __ATOMIC_RELAXED,
+                                     __HIP_MEMORY_SCOPE_AGENT);
+          smem[c] = sum * inv;
+        }
+      }
+    } else {
+      K = e.HW * e.Cin;
+      for (int k = threadIdx.x; k < K; k += blockDim.x) {
+        const int p = k / e.Cin, c = k - p * e.Cin;
+        smem[k] = Store<T>::load(src + (size_t)p * e.Csp + c);
+      }
     }
-    for (; p < p1; ++p) s0 += Store<T>::load(src + (size_t)p * h.Csp + c);
-    const float sum = (s0 + s1) + (s2 + s3);
-    if (h.splits == 1) smem[c] = sum * inv;
-    else   // device-coherent (write-through) store, read back below by whichever slab finishes last
-      __hip_atomic_store(&h.partial[((size_t)b * h.splits + split) * h.Cin + c], sum, __ATOMIC_RELAXED,
-                         __HIP_MEMORY_SCOPE_AGENT);
-  }
-  if (h.splits > 1) {
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
-    if (threadIdx.x == 0) {
-      const int old = __hip_atomic_fetch_add(&h.counters[b], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *flag = (old == h.splits - 1);
-      if (old == h.splits - 1) h.counters[b] = 0;
-    }
-    __syncthreads();
-    if (!*flag) return;
-    for (int c = threadIdx.x; c < h.Cin; c += blockDim.x) {
-      float sum = 0.f;
-      for (int s = 0; s < h.splits; ++s)
-        sum += __hip_atomic_load(&h.partial[((size_t)b * h.splits + s) * h.Cin + c], __ATOMIC_RELAXED,
-                                 __HIP_MEMORY_SCOPE_AGENT);
-      smem[c] = sum * inv;
+    const int kper = (K + 3) / 4;
+    const int k_lo = part * kper, k_hi = min(K, k_lo + kper);
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int co = lane + 64 * j;
+      if (co < h.Cout)
+        for (int k = k_lo; k < k_hi; ++k) acc[j] += smem[k] * e.w[(size_t)k * h.Cout + co];
     }
   }
+#pragma unroll
+  for (int j = 0; j < 4; ++j) red[(part * 4 + j) * 64 + lane] = acc[j];
   __syncthreads();
   char* rec = h.record ? (char*)ctx->out_ptr : nullptr;
   T* recp = rec ? (T*)(rec + (int64_t)(ctx->frame - ctx->out_base) * ctx->out_stride) : nullptr;
-  // dense map: 64 outputs at a time, the channel range split over the 4 waves and added in wave order
-  const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const int cper = (h.Cin + 3) / 4;
-  const int c_lo = part * cper, c_hi = min(h.Cin, c_lo + cper);
-  for (int co0 = 0; co0 < h.Cout; co0 += 64) {
-    const int co = co0 + lane;
-    float acc = 0.f;
-    if (co < h.Cout)
-      for (int ci = c_lo; ci < c_hi; ++ci) acc += smem[ci] * h.w[(size_t)ci * h.Cout + co];
-    red[part * 64 + lane] = acc;
-    __syncthreads();
-    if (part == 0 && co < h.Cout) {
-      float v = h.bias[co] + ((red[lane] + red[64 + lane]) + (red[128 + lane] + red[192 + lane]));
-      if (h.act == 1) v = fmaxf(v, 0.f);
-      Store<T>::store((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
-      if (recp) Store<T>::store(recp + (size_t)b * h.Cout + co, v);
-    }
-    __syncthreads();
+  for (int co = threadIdx.x; co < h.Cout; co += blockDim.x) {
+    const int j = co >> 6, l = co & 63;
+    float v = h.bias[co] + ((red[(0 * 4 + j) * 64 + l] + red[(1 * 4 + j) * 64 + l]) +
+                            (red[(2 * 4 + j) * 64 + l] + red[(3 * 4 + j) * 64 + l]));
+    if (h.act == 1) v = fmaxf(v, 0.f);
+    Store<T>::store((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
+    if (recp) Store<T>::store(recp + (size_t)b * h.Cout + co, v);
   }
 }
 
 template <typename T>
 __device__ __forceinline__ void sr_aux_item(const SrCtx* __restrict__ ctx, const SrAux& it,
                                             const SrHead* __restrict__ heads,
-                                            const SrStageNode* __restrict__ stage_nodes, float* smem) {
-  if (it.kind == SR_AUX_HEAD) sr_head_item<T>(ctx, heads[it.a], it.b, it.c, smem);
+                                            const SrHeadEdge* __restrict__ head_edges,
+                                            const SrStageNode* __restrict__ stage_nodes, float* smem, int vec_floats) {
+  if (it.kind == SR_AUX_HEAD) sr_head_item<T>(ctx, heads[it.a], head_edges, it.b, it.c, smem, vec_floats);
   else if (it.kind == SR_AUX_STAGE) sr_stage_item<T>(ctx, stage_nodes[it.a], it.b);
 }
 
@@ -274,13 +295,15 @@ __global__ __launch_bounds__(256) void sr_direct_kernel(SrCtx* __restrict__ ctx,
                                                         const SrDirectBlock* __restrict__ blocks, int n_blocks,
                                                         int batch, const SrAux* __restrict__ aux,
                                                         const SrHead* __restrict__ heads,
-                                                        const SrStageNode* __restrict__ stage_nodes, int is_last) {
+                                                        const SrHeadEdge* __restrict__ head_edges,
+                                                        const SrStageNode* __restrict__ stage_nodes, int vec_floats,
+                                                        int is_last) {
   extern __shared__ float sr_aux_smem[];
   if ((int)blockIdx.x < n_blocks) {
     const SrDirectBlock blk = blocks[blockIdx.x];
     sr_direct_block<T>(ctx, nodes[blk.node], edges, blk.first, batch);
   } else {
-    sr_aux_item<T>(ctx, aux[blockIdx.x - n_blocks], heads, stage_nodes, sr_aux_smem);
+    sr_aux_item<T>(ctx, aux[blockIdx.x - n_blocks], heads, head_edges, stage_nodes, sr_aux_smem, vec_floats);
   }
   if (is_last) sr_block_done(ctx, gridDim.x);
 }
@@ -636,7 +659,9 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
                                                          const SrMfmaTile* __restrict__ tiles, int n_tiles,
                                                          const SrAux* __restrict__ aux, int n_aux, int aux_at,
                                                          const SrHead* __restrict__ heads,
-                                                         const SrStageNode* __restrict__ stage_nodes, int is_last) {
+                                                         const SrHeadEdge* __restrict__ head_edges,
+                                                         const SrStageNode* __restrict__ stage_nodes, int vec_floats,
+                                                         int is_last) {
   extern __shared__ __align__(16) unsigned char sr_lds[];
   // work list: tiles in decreasing cost; the auxiliary items are spliced in at position aux_at so
   // that neither the longest tiles start late nor the launch ends on an auxiliary item
@@ -656,7 +681,7 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
                       SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
                       sr_lds);
   } else {
-    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, stage_nodes, (float*)sr_lds);
+    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds, vec_floats);
   }
   if (is_last) sr_block_done(ctx, gridDim.x);
 }
@@ -693,17 +718,23 @@ hipError_t sr_launch_fill_zero(hipStream_t s, void* p, size_t bytes) {
 
 template <typename T>
 __global__ void sr_aux_kernel(SrCtx* __restrict__ ctx, const SrAux* __restrict__ aux, const SrHead* __restrict__ heads,
-                              const SrStageNode* __restrict__ stage_nodes, int is_last) {
+                              const SrHeadEdge* __restrict__ head_edges, const SrStageNode* __restrict__ stage_nodes,
+                              int vec_floats, int is_last) {
   extern __shared__ float sr_aux_smem2[];
-  sr_aux_item<T>(ctx, aux[blockIdx.x], heads, stage_nodes, sr_aux_smem2);
+  sr_aux_item<T>(ctx, aux[blockIdx.x], heads, head_edges, stage_nodes, sr_aux_smem2, vec_floats);
   if (is_last) sr_block_done(ctx, gridDim.x);
 }
 
+// smem_bytes of the aux items: vector floats + 16 bytes + 4 KiB of partial outputs
+static inline int sr_vec_floats(int smem_bytes) { return (smem_bytes - 16 - 4096) / 4; }
+
 hipError_t sr_launch_aux(hipStream_t s, SrCtx* ctx, const SrAux* aux, int n_aux, const SrHead* heads,
-                         const SrStageNode* stage_nodes, int smem_bytes, int bf16, int is_last) {
+                         const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int smem_bytes, int bf16,
+                         int is_last) {
   if (n_aux == 0) return hipSuccess;
-  if (bf16) hipLaunchKernelGGL(sr_aux_kernel<uint16_t>, dim3(n_aux), dim3(256), smem_bytes, s, ctx, aux, heads, stage_nodes, is_last);
-  else hipLaunchKernelGGL(sr_aux_kernel<float>, dim3(n_aux), dim3(256), smem_bytes, s, ctx, aux, heads, stage_nodes, is_last);
+  const int vf = sr_vec_floats(smem_bytes);
+  if (bf16) hipLaunchKernelGGL(sr_aux_kernel<uint16_t>, dim3(n_aux), dim3(256), smem_bytes, s, ctx, aux, heads, head_edges, stage_nodes, vf, is_last);
+  else hipLaunchKernelGGL(sr_aux_kernel<float>, dim3(n_aux), dim3(256), smem_bytes, s, ctx, aux, heads, head_edges, stage_nodes, vf, is_last);
   return hipGetLastError();
 }
 
@@ -729,16 +760,19 @@ hipError_t sr_launch_record_output(hipStream_t s, const SrCtx* ctx, const void* 
 
 hipError_t sr_launch_direct(hipStream_t s, SrCtx* ctx, const SrDirectNode* nodes, const SrDirectEdge* edges,
                             const SrDirectBlock* blocks, int n_blocks, int bf16, int batch, const SrAux* aux, int n_aux,
-                            const SrHead* heads, const SrStageNode* stage_nodes, int smem_bytes, int is_last) {
+                            const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
+                            int smem_bytes, int is_last) {
   if (n_blocks + n_aux == 0) return hipSuccess;
-  if (bf16) hipLaunchKernelGGL(sr_direct_kernel<uint16_t>, dim3(n_blocks + n_aux), dim3(256), smem_bytes, s, ctx, nodes, edges, blocks, n_blocks, batch, aux, heads, stage_nodes, is_last);
-  else hipLaunchKernelGGL(sr_direct_kernel<float>, dim3(n_blocks + n_aux), dim3(256), smem_bytes, s, ctx, nodes, edges, blocks, n_blocks, batch, aux, heads, stage_nodes, is_last);
+  const int vf = sr_vec_floats(smem_bytes);
+  if (bf16) hipLaunchKernelGGL(sr_direct_kernel<uint16_t>, dim3(n_blocks + n_aux), dim3(256), smem_bytes, s, ctx, nodes, edges, blocks, n_blocks, batch, aux, heads, head_edges, stage_nodes, vf, is_last);
+  else hipLaunchKernelGGL(sr_direct_kernel<float>, dim3(n_blocks + n_aux), dim3(256), smem_bytes, s, ctx, nodes, edges, blocks, n_blocks, batch, aux, heads, head_edges, stage_nodes, vf, is_last);
   return hipGetLastError();
 }
 
 hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
                           const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
-                          const SrHead* heads, const SrStageNode* stage_nodes, int is_last) {
+                          const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
+                          int aux_smem_bytes, int is_last) {
   if (n_tiles + n_aux == 0) return hipSuccess;
   static bool attr_set = false;
   if (!attr_set) {   // dynamic LDS above 64 KiB has to be requested once
@@ -748,7 +782,7 @@ hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, co
     attr_set = true;
   }
   hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles + n_aux), dim3(256), lds_bytes, s, ctx, nodes, edges, tiles, n_tiles,
-                     aux, n_aux, n_tiles / 2, heads, stage_nodes, is_last);
+                     aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last);
   return hipGetLastError();
 }
 
