@@ -165,3 +165,58 @@ def test_first_response_frame_on_gpu():
     for t in range(1, 5):
         assert np.all(out[t - 1] == 0.0)
     assert np.any(out[4] != 0.0)
+
+
+def test_two_inputs_and_unordered_node_ids():
+    # node ids in no particular order: outputs first, two input nodes last
+    nodes = [Node("out", 5, 1, 1, ACT_IDENTITY), Node("b", 32, 8, 8), Node("a", 32, 16, 16),
+             Node("in2", 4, 16, 16, ACT_IDENTITY), Node("in1", 3, 16, 16, ACT_IDENTITY)]
+    edges = [Edge(4, 2), Edge(3, 2), Edge(2, 1, stride=2), Edge(1, 1), Edge(1, 0, "gap_dense", 1, 1, 1, 0),
+             Edge(3, 1, stride=2)]
+    for dtype in ("bf16", "f32"):
+        g = Graph("two_in", nodes, edges, batch=3, frames=4, dtype=dtype, out_node=0)
+        assert g.input_nodes() == [3, 4]
+        check(g, seed=12, label=f"two_in/{dtype}")
+        check(g.with_pattern([0, 1, 0, 1, 0, 1]), seed=12, label=f"two_in/{dtype}/hybrid")
+
+
+def test_zero_frames_and_single_sample():
+    import torch
+    import paper_1806_04965_amd as sr
+    from gpu_util import to_device
+    g = W.cifar_sr(batch=1, frames=3)
+    w, b, x = W.make_case(g, seed=13)
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    xd = to_device(x[0], "bf16")
+    dev.rollout([xd], 0, g.out_node, None)          # T = 0: only the initial state
+    dev.synchronize()
+    assert dev.frame_index() == 0
+    np.testing.assert_array_equal(dev.get_state(0).float().cpu().numpy(), xd[0].float().cpu().numpy())
+    for v in range(1, len(g.nodes)):
+        assert float(dev.get_state(v).float().abs().max()) == 0.0
+    dev.close()
+    check(g, seed=13, label="cifar_sr/B1")
+
+
+def test_errors_on_the_device_path():
+    import paper_1806_04965_amd as sr
+    from gpu_util import to_device
+    g = W.tiny_sr()
+    w, b, x = W.make_case(g, seed=14)
+    dev = sr.SrGraph(g)
+    xd = to_device(x[0], "f32")
+    with pytest.raises(sr.SrError) as ei:
+        dev.frame_step([xd[1]])
+    assert ei.value.name == "SR_ERR_STATE"          # no sr_reset yet
+    with pytest.raises(sr.SrError) as ei:
+        dev.reset([xd[0]])
+    assert ei.value.name == "SR_ERR_STATE"          # weights missing
+    dev.set_parameters(w, b)
+    dev.reset([xd[0]])
+    dev.frame_step([xd[1]])
+    dev.synchronize()
+    with pytest.raises(sr.SrError) as ei:
+        dev.set_weights(0, np.zeros(5, np.float32))
+    assert ei.value.name == "SR_ERR_ARG"
+    dev.close()
