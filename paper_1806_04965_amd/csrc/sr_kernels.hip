@@ -329,8 +329,8 @@ __global__ __launch_bounds__(256) void sr_direct_kernel(SrCtx* __restrict__ ctx,
 // B operand (weights): pre-packed on the host in exactly the per-lane order of the instruction,
 // [tap][k16 block][32-channel tile][lane][8], so a wave's fragment is one coalesced 1 KiB load
 // straight into registers, prefetched a few k-steps ahead through a small ring.
-#define SR_RING 3   // depth of the weight-fragment ring
-#define SR_UNROLL 6 // k-steps per loop body: a multiple of the ring depth and of the 2 A-fragment buffers
+#define SR_RING 5   // depth of the weight-fragment ring
+#define SR_UNROLL 5 // k-steps per loop body: a multiple of the ring depth
 
 typedef const __attribute__((address_space(1))) bf16x8_t* sr_gfrag_ptr;   // global memory
 #define SR_UNIFORM(x) __builtin_amdgcn_readfirstlane(x)
@@ -401,69 +401,83 @@ __device__ __forceinline__ void sr_stage_dma(const unsigned char* __restrict__ b
   }
 }
 
-// k-step st of a stage -> byte offset of its A fragments relative to tap (0,0), k = 0, and index
-// of its weight fragment relative to the chunk's first one.  All wave-uniform (scalar unit).
-struct SrStep { int aoff; int boff; };
-__device__ __forceinline__ SrStep sr_step_decode(const SrEdgeK& e, int st) {
-  const int tap = st >> e.lgK16;
-  const int k = st - (tap << e.lgK16);
+// k-step st of a stage = (tap, 16-channel block k inside the chunk).  The per-tap parts of the
+// offsets -- LDS byte offset of the tap's A fragments relative to tap (0,0), index of the tap's
+// first weight fragment -- are tabulated once per edge with one tap per lane (SrTaps); a step then
+// costs a shift, a mask and a lane read instead of a division and five multiplies.  This matters
+// when a wave has its SIMD to itself: a wave's own non-MFMA instructions do not overlap with its
+// MFMAs (only another wave's do), so every instruction of the step's bookkeeping costs MFMA time.
+struct SrTaps { int a; int b; };   // one tap per lane
+__device__ __forceinline__ SrTaps sr_tap_table(const SrEdgeK& e, int lane) {
+  const int tap = min(lane, e.ntaps - 1);
   const int ti = (tap * e.magicKW) >> 16;
   const int tj = tap - ti * e.kw;
-  SrStep r;
-  r.aoff = ti * e.RPB + ((tj & (e.stride - 1)) * e.PWs + (tj >> e.lgs)) * e.SP + k * 32;
-  r.boff = (tap * e.k16_total + k) * e.wstride8;
-  return r;
+  SrTaps t;
+  t.a = ti * e.RPB + ((tj & (e.stride - 1)) * e.PWs + (tj >> e.lgs)) * e.SP;
+  t.b = tap * e.k16_total * e.wstride8;
+  return t;
+}
+__device__ __forceinline__ int sr_step_aoff(const SrEdgeK& e, const SrTaps& t, int st) {
+  const int tap = st >> e.lgK16;
+  return __builtin_amdgcn_readlane(t.a, tap) + ((st - (tap << e.lgK16)) << 5);
+}
+__device__ __forceinline__ int sr_step_boff(const SrEdgeK& e, const SrTaps& t, int st) {
+  const int tap = st >> e.lgK16;
+  return __builtin_amdgcn_readlane(t.b, tap) + (st - (tap << e.lgK16)) * e.wstride8;
 }
 
-// One k-step: 4 x WN MFMAs on the A fragments `a`, while the next step's A fragments are read
-// from LDS into `an` (double buffer: the reads have a whole step to complete) and the weight
-// fragments of ring slot `b` are replaced, once used, by those of step st + SR_RING.  The loads are
+// One k-step: 4 x WN MFMAs.  Each A fragment is reloaded for the next step right after its last
+// use, which leaves the other rows' MFMAs to cover the LDS latency; the weight fragments of ring
+// slot `b` are replaced, once used, by those of step st + SR_RING (the ring is deep enough to cover
+// the L2 latency even when the workgroup has the compute unit to itself).  The loads are
 // unconditional (past the end of the stage they repeat its last step) so that the loop body is
 // branch-free and the hardware wait counters can be tracked exactly.
 template <int WN>
-__device__ __forceinline__ void sr_step(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
-                                        sr_gfrag_ptr wchunk, const bf16x8_t (&a)[4], bf16x8_t (&an)[4],
+__device__ __forceinline__ void sr_step(const SrEdgeK& e, const SrTaps& taps, const unsigned char* lds,
+                                        const int (&abase)[4], sr_gfrag_ptr wchunk, bf16x8_t (&a)[4],
                                         bf16x8_t (&b)[WN], f32x16_t (&acc)[4][WN], int st, int NS) {
-  const SrStep nx = sr_step_decode(e, min(st + 1, NS - 1));
+  const int aoff = sr_step_aoff(e, taps, min(st + 1, NS - 1));
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
-    an[mi] = *(const bf16x8_t*)(lds + abase[mi] + nx.aoff);
 #pragma unroll
     for (int nj = 0; nj < WN; ++nj)
       acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[nj], a[mi], acc[mi][nj], 0, 0, 0);
+    a[mi] = *(const bf16x8_t*)(lds + abase[mi] + aoff);
   }
-  const SrStep nb = sr_step_decode(e, min(st + SR_RING, NS - 1));
+  const int boff = sr_step_boff(e, taps, min(st + SR_RING, NS - 1));
 #pragma unroll
-  for (int nj = 0; nj < WN; ++nj) b[nj] = wchunk[nb.boff + nj * 64];
-  // keep the issue order written above: address add + LDS read, then WN MFMAs, four times; then the
-  // weight loads
+  for (int nj = 0; nj < WN; ++nj) b[nj] = wchunk[boff + nj * 64];
+  // issue order: lane read of the next A offset; then, four times, WN MFMAs followed by the address
+  // add and the LDS read of the row they have just released; then the lane read and address of the
+  // weight fragments and their loads
+  __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);      // VALU (lane read)
 #pragma unroll
   for (int mi = 0; mi < 4; ++mi) {
+    __builtin_amdgcn_sched_group_barrier(0x008, WN, 0);   // MFMA
     __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);    // VALU (address)
     __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // DS read
-    __builtin_amdgcn_sched_group_barrier(0x008, WN, 0);   // MFMA
   }
+  __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);      // VALU (lane read, pointer)
   __builtin_amdgcn_sched_group_barrier(0x020, WN, 0);     // VMEM read
 }
 
 // One stage of the contraction: NS = taps * KC/16 k-steps over the patch in LDS.
 template <int WN>
-__device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const unsigned char* lds, const int (&abase)[4],
-                                                 sr_gfrag_ptr wchunk, bf16x8_t (&bq)[SR_RING][WN],
+__device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const SrTaps& taps, const unsigned char* lds,
+                                                 const int (&abase)[4], sr_gfrag_ptr wchunk, bf16x8_t (&bq)[SR_RING][WN],
                                                  f32x16_t (&acc)[4][WN], int NS) {
-  bf16x8_t a[2][4];
+  bf16x8_t a[4];
 #pragma unroll
-  for (int mi = 0; mi < 4; ++mi) a[0][mi] = *(const bf16x8_t*)(lds + abase[mi]);
+  for (int mi = 0; mi < 4; ++mi) a[mi] = *(const bf16x8_t*)(lds + abase[mi]);
   int st0 = 0;
   for (; st0 + SR_UNROLL <= NS; st0 += SR_UNROLL) {
 #pragma unroll
-    for (int u = 0; u < SR_UNROLL; ++u)
-      sr_step<WN>(e, lds, abase, wchunk, a[u & 1], a[(u + 1) & 1], bq[u % SR_RING], acc, st0 + u, NS);
+    for (int u = 0; u < SR_UNROLL; ++u) sr_step<WN>(e, taps, lds, abase, wchunk, a, bq[u % SR_RING], acc, st0 + u, NS);
   }
-  // remaining 0..SR_UNROLL-1 steps (their fragments are already in buffer 0 / ring slots 0, 1, ...)
+  // remaining 0..SR_UNROLL-1 steps (their weight fragments are already in ring slots 0, 1, ...)
 #pragma unroll
   for (int u = 0; u < SR_UNROLL - 1; ++u)
-    if (st0 + u < NS) sr_step<WN>(e, lds, abase, wchunk, a[u & 1], a[(u + 1) & 1], bq[u % SR_RING], acc, st0 + u, NS);
+    if (st0 + u < NS) sr_step<WN>(e, taps, lds, abase, wchunk, a, bq[u % SR_RING], acc, st0 + u, NS);
 }
 
 template <int WN>
@@ -539,6 +553,7 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       asm volatile("" : "+v"(abase[mi]));   // keep it in a register: one add per k-step, not a re-derivation
     }
     const sr_gfrag_ptr wlane = e.wpk + ntile0 * 64 + lane;
+    const SrTaps taps = sr_tap_table(e, lane);
     const int NS = e.ntaps << e.lgK16;
     for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
       const sr_gfrag_ptr wchunk = wlane + (size_t)(chunk << e.lgK16) * e.wstride8;
@@ -547,14 +562,14 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       bf16x8_t bq[SR_RING][WN];
 #pragma unroll
       for (int d = 0; d < SR_RING; ++d) {
-        const SrStep nb = sr_step_decode(e, min(d, NS - 1));
+        const int boff = sr_step_boff(e, taps, min(d, NS - 1));
 #pragma unroll
-        for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[nb.boff + nj * 64];
+        for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[boff + nj * 64];
       }
       sr_stage_dma(dma_base + (size_t)chunk * e.KC * 2, zero_page, lds, n_pos, tid, dma_off);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
       __syncthreads();                                     // ... and everybody else's
-      sr_stage_compute<WN>(e, lds, abase, wchunk, bq, acc, NS);
+      sr_stage_compute<WN>(e, taps, lds, abase, wchunk, bq, acc, NS);
     }
   }
 
