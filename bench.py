@@ -56,6 +56,7 @@ def main():
     ap.add_argument("--pattern", default="streaming")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hipgraph", action="store_true")
+    ap.add_argument("--tile-kernel", type=int, default=0, help="1: 4-wave tile kernel, 2: 8-wave tile kernel, 0: library default")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known HBM traffic, for scaling "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -79,8 +80,12 @@ def main():
     T, B = g.frames, g.batch
     w, b, x = W.make_case(g, seed=0)
 
-    opts = {0: 0} if args.no_hipgraph else None
-    dev = sr.SrGraph(g, options=opts)
+    opts = {}
+    if args.no_hipgraph:
+        opts[0] = 0
+    if args.tile_kernel:
+        opts[4] = args.tile_kernel
+    dev = sr.SrGraph(g, options=opts or None)
     dev.set_parameters(w, b)
     tdt = torch.bfloat16 if g.dtype == "bf16" else torch.float32
     ins = g.input_nodes()

@@ -89,7 +89,9 @@ typedef enum {
   SR_OPT_USE_HIPGRAPH = 0,  /* 1 (default): frames are replayed from a captured HIP graph; 0: plain launches */
   SR_OPT_FORCE_DIRECT = 1,  /* 1: every node is computed by the plain one-thread-per-output kernel (no MFMA); default 0 */
   SR_OPT_FRAMES_PER_GRAPH = 2, /* number of frames captured into one HIP graph for sr_rollout (default 8, >= 1) */
-  SR_OPT_K_SPLIT = 3           /* 1 (default): long tiles are cut along the contraction and reduced by the last part; 0: never */
+  SR_OPT_K_SPLIT = 3,          /* 1 (default): long tiles are cut along the contraction and reduced by the last part; 0: never */
+  SR_OPT_TILE_KERNEL = 4       /* tile kernel of bf16 graphs: 1 = 4 waves per workgroup, weights from registers;
+                                  2 = 8 waves, both operands through LDS, next stage loaded during the current one */
 } sr_option;
 
 /* ---------------------------------------------------------------------------

@@ -188,6 +188,7 @@ struct sr_graph {
   SrMfmaNode* m_nodes = nullptr;
   SrMfmaEdge* m_edges = nullptr;
   SrMfmaTile* m_tiles = nullptr;
+  SrStage8* stage8 = nullptr;
   int32_t* plan_index = nullptr;
   int32_t* plan_tables = nullptr;
   float* split_scratch = nullptr;
@@ -195,6 +196,7 @@ struct sr_graph {
   int32_t* split_counters = nullptr;
   int n_split_slots = 0;
   bool allow_split = true;
+  int tile_version = 1;       // 1: 4-wave tile kernel, 2: 8-wave tile kernel (both operands through LDS)
   SrHead* heads = nullptr;
   SrHeadEdge* head_edges = nullptr;
   void* zero_page = nullptr;
@@ -319,12 +321,12 @@ PatchRows patch_rows(int64_t m0, int64_t m1, int HoWo, int Wo, int PH, int s, in
   return r;
 }
 
-int64_t max_patch_rows(const sr_graph* g, int v, const EdgeRt& e, int BM) {
+int64_t max_patch_rows(const sr_graph* g, int v, const EdgeRt& e, int BM, int PH_override = 0) {
   const sr_node_desc& dn = g->nodes[v].d;
   const sr_node_desc& sn = g->nodes[e.d.src].d;
   const int HoWo = dn.height * dn.width;
   const int64_t M = (int64_t)g->batch * HoWo;
-  const int PH = sn.height + 2 * e.d.pad;
+  const int PH = PH_override ? PH_override : sn.height + 2 * e.d.pad;
   int64_t worst = 0;
   for (int64_t m0 = 0; m0 < M; m0 += BM) {
     PatchRows r = patch_rows(m0, std::min<int64_t>(m0 + BM, M) - 1, HoWo, dn.width, PH, e.d.stride, e.d.upsample, e.d.kh);
@@ -368,6 +370,49 @@ void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows&
         (*out)[(size_t)(q * RPB16 + col * CH1 + piece)] = off;
       }
     }
+  }
+}
+
+// 8-wave kernel: plan of one (tile, edge, row phase): per 16-byte LDS position of a stage buffer the
+// byte offset of its source.  First the A positions (patch rows = the source rows q = phase
+// (mod stride) of the tile's row range; slots of KC*2 bytes, unpadded; offsets from (image b0,
+// source row iy_first); -1 zero padding, -2 not written), padded to a multiple of 512; then the B
+// positions ((t * K16 + k) * NBT + nt) * 64 + lane: the packed fragment of the phase's t-th tap,
+// 16-channel block k of the chunk, column tile nt of the tile (offsets from the chunk's first block
+// and the tile's first column tile), padded likewise.
+void build_plan8(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows& r, int phase, int NBT) {
+  const int CH = m.KC / 8;
+  const int RPS = m.RP;
+  const int64_t NQ = r.Q1 - r.Q0 + 1;
+  const int64_t NQr = (NQ - phase + m.stride - 1) / m.stride;
+  const int64_t n_pos = NQr * RPS * CH;
+  const int64_t padded = (n_pos + 511) / 512 * 512;
+  out->assign((size_t)padded, -2);
+  const int64_t iy_first = (r.oy0 / m.up) * m.stride - m.pad;
+  for (int64_t qr = 0; qr < NQr; ++qr) {
+    const int64_t Qg = r.Q0 + qr * m.stride + phase, b = Qg / m.PH, iy = Qg % m.PH - m.pad;
+    for (int col = 0; col < m.RP; ++col) {
+      const int cphase = col / m.PWs, px = (col % m.PWs) * m.stride + cphase;
+      if (px >= m.PW) continue;
+      const int ix = px - m.pad;
+      const bool valid = iy >= 0 && iy < m.Hs && ix >= 0 && ix < m.Ws;
+      for (int piece = 0; piece < CH; ++piece) {
+        int32_t off = -1;
+        if (valid) off = (int32_t)(((((b - r.b0) * m.Hs + iy - iy_first) * m.Ws + ix) * m.Csp) * 2 + piece * 16);
+        (*out)[(size_t)((qr * RPS + col) * CH + piece)] = off;
+      }
+    }
+  }
+  const int K16 = m.KC / 16, k16_total = m.Csp / 16;
+  const int tap_rows = (m.kh - phase + m.stride - 1) / m.stride;
+  const int64_t n_posB = (int64_t)tap_rows * m.kw * K16 * NBT * 64;
+  const size_t b0 = out->size();
+  out->resize(b0 + (size_t)((n_posB + 511) / 512 * 512), -2);
+  for (int64_t pb = 0; pb < n_posB; ++pb) {
+    const int lane = (int)(pb % 64), nt = (int)(pb / 64 % NBT), k = (int)(pb / (64 * NBT) % K16);
+    const int t = (int)(pb / (64 * NBT * K16));
+    const int tap = (phase + (t / m.kw) * m.stride) * m.kw + t % m.kw;
+    (*out)[b0 + (size_t)pb] = (int32_t)((((int64_t)(tap * k16_total + k) * m.wstride8) + nt * 64 + lane) * 16);
   }
 }
 
@@ -416,6 +461,7 @@ sr_status finalize(sr_graph* g) {
   std::vector<SrMfmaNode> mn;
   std::vector<SrMfmaEdge> me;
   std::vector<SrMfmaTile> mt;
+  std::vector<SrStage8> stage8;
   std::vector<SrHead> hd;
   std::vector<SrHeadEdge> he;
   std::vector<int32_t> plan_index, plan_tables, plan_tmp;   // per (tile, edge): offset of its plan
@@ -465,7 +511,140 @@ sr_status finalize(sr_graph* g) {
     for (int v = 0; v < g->n_nodes; ++v) {
       NodeRt& n = g->nodes[v];
       if (g->an.level[v] != L || n.kind == 0) continue;
-      if (n.kind == 1) {
+      if (n.kind == 1 && g->tile_version == 2) {
+        // ---- 8-wave tile kernel: widest channel tile that divides Cout (at most 128: the weight slab
+        // of a stage lives in LDS), 8 waves arranged waves_m x waves_n
+        const int Cout = n.d.channels;
+        const int64_t M = (int64_t)B * n.d.height * n.d.width;
+        int wt = 0, wn = 0;
+        for (const auto& c : {std::pair<int, int>(2, 2), std::pair<int, int>(2, 1), std::pair<int, int>(1, 1)})
+          if (wt == 0 && Cout % (32 * c.first * c.second) == 0) { wt = c.first; wn = c.second; }
+        const int waves_m = 8 / wn, BM = 128 * waves_m, BN = 32 * wt * wn, NBT = wt * wn;
+        SrMfmaNode node{};
+        node.out[0] = n.state[0];
+        node.out[1] = n.state[1];
+        node.bias = n.bias_dev;
+        node.M = (int)M;
+        node.Ho = n.d.height;
+        node.Wo = n.d.width;
+        node.Cout = Cout;
+        node.Cp = n.Cp;
+        node.act = n.d.act;
+        node.edge_begin = (int)me.size();
+        node.waves_m = waves_m;
+        node.waves_n = wn;
+        node.wn_tiles = wt;
+        node.zero_page = g->zero_page;
+        node.stage0 = (int)stage8.size();
+        bool ok = ((int64_t)BM / ((int64_t)n.d.height * n.d.width) + 2 <= 127);
+        int plan_slots = 0, n_stages = 0;
+        double cyc = 8000;
+        for (EdgeRt& e : g->edges) {
+          if (e.d.dst != v || !ok) continue;
+          const NodeRt& sn = g->nodes[e.d.src];
+          SrMfmaEdge m{};
+          m.src[0] = sn.state[0];
+          m.src[1] = sn.state[1];
+          m.wpk = e.wpk_dev;
+          m.bridge = e.d.bridge;
+          m.Hs = sn.d.height;
+          m.Ws = sn.d.width;
+          m.Csp = sn.Cp;
+          m.kh = e.d.kh;
+          m.kw = e.d.kw;
+          m.stride = e.d.stride;
+          m.pad = e.d.pad;
+          m.up = e.d.upsample;
+          // image pitch in padded rows: a multiple of the stride, so that a row's phase does not
+          // depend on the image
+          m.PH = (m.Hs + 2 * m.pad + m.stride - 1) / m.stride * m.stride;
+          m.PW = m.Ws + 2 * m.pad;
+          m.PWs = (m.PW + m.stride - 1) / m.stride;
+          m.RP = m.stride * m.PWs;
+          m.wstride8 = (Cout / 32) * 64;
+          if (sn.state_bytes + SR_ZERO_TAIL >= ((size_t)1 << 31) || (size_t)sn.Cp * 2 > SR_ZERO_TAIL) { ok = false; break; }
+          m.src_bytes = (int32_t)sn.state_bytes;
+          const int nphase = std::min(m.stride, m.kh);
+          const int64_t rows = max_patch_rows(g, v, e, BM, m.PH);
+          const int64_t rows0 = (rows + m.stride - 1) / m.stride;           // phase 0 has the most rows ...
+          const int taps0 = ((m.kh + m.stride - 1) / m.stride) * m.kw;      // ... and the most taps
+          int KC = 0;
+          for (int cand : {128, 64, 32, 16}) {
+            const int64_t a_bytes = rows0 * m.RP * cand * 2;
+            const int64_t b_bytes = (int64_t)taps0 * (cand / 16) * NBT * 1024;
+            if (KC == 0 && sn.Cp % cand == 0 && a_bytes + b_bytes <= SR8_BUF_BYTES) KC = cand;
+          }
+          if (KC == 0) { ok = false; break; }
+          m.KC = KC;
+          m.nchunk = sn.Cp / KC;
+          m.SP = KC * 2;
+          m.RPB = m.RP * KC * 2;
+          m.magicKW = (int32_t)((65536 + m.kw - 1) / m.kw);
+          for (int tap = 0; tap < m.kh * m.kw; ++tap)
+            if (((tap * m.magicKW) >> 16) != tap / m.kw) ok = false;
+          if (m.kh * m.kw > 64) ok = false;   // one tap per lane in the tap tables
+          m.plan_slot = plan_slots;
+          plan_slots += nphase;
+          for (int ph = 0; ph < nphase; ++ph) {
+            const int steps = ((m.kh - ph + m.stride - 1) / m.stride) * m.kw * (KC / 16);
+            for (int ch = 0; ch < m.nchunk; ++ch) {
+              stage8.push_back(SrStage8{(int)me.size(), ph, ch, 0});
+              cyc += 900.0 + steps * 512.0 * wt / 2;
+              n_stages += 1;
+            }
+          }
+          me.push_back(m);
+        }
+        if (!ok) {
+          me.resize(node.edge_begin);
+          stage8.resize(node.stage0);
+          n.kind = 2;
+        } else {
+          node.edge_count = (int)me.size() - node.edge_begin;
+          const int node_index = (int)mn.size();
+          mn.push_back(node);
+          TileGroup grp;
+          grp.node_index = node_index;
+          grp.cost = cyc;
+          grp.n_stages = n_stages;
+          const int n_mt = (int)((M + BM - 1) / BM), n_nt = Cout / BN;
+          for (int mi = 0; mi < n_mt; ++mi)
+            for (int nt = 0; nt < n_nt; ++nt) {
+              SrMfmaTile t{};
+              t.node = node_index;
+              t.m0 = mi * BM;
+              t.n0 = nt * BN;
+              t.plan_begin = (int)plan_index.size();
+              t.stage_begin = 0;
+              t.stage_end = n_stages;
+              t.split_slot = -1;
+              t.part = 1 << 16;
+              for (int ei = 0; ei < node.edge_count; ++ei) {
+                const SrMfmaEdge& m = me[node.edge_begin + ei];
+                const PatchRows r = patch_rows(t.m0, std::min<int64_t>((int64_t)t.m0 + BM, M) - 1,
+                                               n.d.height * n.d.width, n.d.width, m.PH, m.stride, m.up, m.kh);
+                for (int ph = 0; ph < std::min(m.stride, m.kh); ++ph) {
+                  build_plan8(&plan_tmp, m, r, ph, NBT);
+                  uint64_t h = 1469598103934665603ull ^ (uint64_t)((node.edge_begin + ei) * 4 + ph);
+                  for (int32_t x : plan_tmp) h = (h ^ (uint32_t)x) * 1099511628211ull;
+                  int found = -1;
+                  for (int cand : plan_seen[h])
+                    if (plan_tables.size() >= (size_t)cand + plan_tmp.size() &&
+                        std::equal(plan_tmp.begin(), plan_tmp.end(), plan_tables.begin() + cand)) { found = cand; break; }
+                  if (found < 0) {
+                    found = (int)plan_tables.size();
+                    plan_tables.insert(plan_tables.end(), plan_tmp.begin(), plan_tmp.end());
+                    plan_seen[h].push_back(found);
+                  }
+                  plan_index.push_back(found);
+                }
+              }
+              grp.tiles.push_back(t);
+            }
+          groups.push_back(std::move(grp));
+        }
+      }
+      if (n.kind == 1 && g->tile_version != 2) {
         // ---- MFMA node: tile shape, per-edge staging depth, tiles
         const int Cout = n.d.channels;
         const int64_t M = (int64_t)B * n.d.height * n.d.width;
@@ -719,7 +898,7 @@ sr_status finalize(sr_graph* g) {
     {
       double level_cost = 0;
       for (const TileGroup& grp : groups) level_cost += grp.cost * grp.tiles.size();
-      const double slots = 2.0 * 256;                       // resident workgroups of the chip
+      const double slots = (g->tile_version == 2 ? 1.0 : 2.0) * 256;   // resident workgroups of the chip
       const double share = level_cost / slots;
       for (TileGroup& grp : groups) {
         // only tiles longer than an even share of the level are cut, into parts of about half a
@@ -784,9 +963,10 @@ sr_status finalize(sr_graph* g) {
   if ((st = upload(g, &g->d_blocks, db)) != SR_OK) return st;
   if ((st = upload(g, &g->plan_index, plan_index)) != SR_OK) return st;
   if ((st = upload(g, &g->plan_tables, plan_tables)) != SR_OK) return st;
+  if ((st = upload(g, &g->stage8, stage8)) != SR_OK) return st;
   if (g->n_split_slots > 0) {
     void* sp = nullptr;
-    g->split_scratch_bytes = (size_t)g->n_split_slots * SR_SPLIT_FLOATS * sizeof(float);
+    g->split_scratch_bytes = (size_t)g->n_split_slots * (g->tile_version == 2 ? SR8_SPLIT_FLOATS : SR_SPLIT_FLOATS) * sizeof(float);
     // a reused block may be larger; remember the size actually held
     SR_HIP(g, uncached_alloc(&sp, g->split_scratch_bytes));
     g->split_scratch = (float*)sp;
@@ -798,6 +978,7 @@ sr_status finalize(sr_graph* g) {
   for (SrMfmaNode& node : mn) {
     node.plan_index = g->plan_index;
     node.plan_tables = g->plan_tables;
+    node.stage_table = g->stage8;
     node.split_scratch = g->split_scratch;
     node.split_counters = g->split_counters;
   }
@@ -814,7 +995,8 @@ sr_status finalize(sr_graph* g) {
   for (int L = 1; L <= F; ++L) {
     const LevelPlan& lp = g->levels[L];
     const bool has_tiles = lp.n_tiles > 0, has_blocks = lp.n_blocks > 0;
-    launches += has_tiles + (has_blocks || (!has_tiles && lp.n_aux > 0));
+    const bool aux_ride = has_tiles && g->tile_version != 2;   // the 4-wave tile kernel takes the auxiliary items along
+    launches += has_tiles + (has_blocks || (!aux_ride && lp.n_aux > 0));
   }
   g->launches_per_frame = launches;
   g->finalized = true;
@@ -869,7 +1051,8 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
   for (int L = 1; L <= g->an.factor; ++L) {
     const LevelPlan& lp = g->levels[L];
     const bool has_tiles = lp.n_tiles > 0;
-    const bool direct_launch = lp.n_blocks > 0 || (!has_tiles && lp.n_aux > 0);
+    const bool aux_ride = has_tiles && g->tile_version != 2;
+    const bool direct_launch = lp.n_blocks > 0 || (!aux_ride && lp.n_aux > 0);
     if (has_tiles || direct_launch) { last_level = L; last_is_direct = direct_launch; }
   }
   if (!g->stage_folded) {
@@ -880,17 +1063,21 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
   for (int L = 1; L <= g->an.factor; ++L) {
     const LevelPlan& lp = g->levels[L];
     const bool has_tiles = lp.n_tiles > 0;
-    const bool direct_launch = lp.n_blocks > 0 || (!has_tiles && lp.n_aux > 0);
+    const bool aux_ride = has_tiles && g->tile_version != 2;
+    const bool direct_launch = lp.n_blocks > 0 || (!aux_ride && lp.n_aux > 0);
     if (has_tiles) {
       const int is_last = (!copy_out && L == last_level && !last_is_direct) ? 1 : 0;
       SR_HIP(g, mark(1));
-      SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes,
-                               g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes, g->aux_smem_bytes,
-                               is_last));
+      if (g->tile_version == 2)
+        SR_HIP(g, sr_launch_mfma8(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, is_last));
+      else
+        SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes,
+                                 g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes,
+                                 g->aux_smem_bytes, is_last));
     }
     if (direct_launch) {
       const int is_last = (!copy_out && L == last_level) ? 1 : 0;
-      const int n_aux = has_tiles ? 0 : lp.n_aux;   // aux items already went with the tiles
+      const int n_aux = aux_ride ? 0 : lp.n_aux;   // aux items already went with the tiles
       SR_HIP(g, mark(2));
       SR_HIP(g, sr_launch_direct(s, g->ctx, g->d_nodes, g->d_edges, g->d_blocks + lp.block_begin, lp.n_blocks, bf16,
                                  g->batch, g->aux + lp.aux_begin, n_aux, g->heads, g->head_edges, g->stage_nodes,
@@ -1122,8 +1309,9 @@ sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_e
   for (int v = 0; v < n_nodes; ++v) {
     NodeRt& n = g->nodes[v];
     for (int p = 0; p < 2; ++p) {
-      if ((st = dev_alloc(g, &n.state[p], n.state_bytes)) != SR_OK) return bail(st);
-      hipError_t he = sr_launch_fill_zero(g->stream, n.state[p], n.state_bytes);
+      // a zero tail follows every copy (the 8-wave tile kernel loads padding pixels from there)
+      if ((st = dev_alloc(g, &n.state[p], n.state_bytes + SR_ZERO_TAIL)) != SR_OK) return bail(st);
+      hipError_t he = sr_launch_fill_zero(g->stream, n.state[p], n.state_bytes + SR_ZERO_TAIL);
       if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
     }
     void* b = nullptr;
@@ -1208,6 +1396,10 @@ sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value) {
     case SR_OPT_USE_HIPGRAPH: g->use_hipgraph = value != 0; return SR_OK;
     case SR_OPT_FORCE_DIRECT: g->force_direct = value != 0; return SR_OK;
     case SR_OPT_K_SPLIT: g->allow_split = value != 0; return SR_OK;
+    case SR_OPT_TILE_KERNEL:
+      if (value != 1 && value != 2) return gfail(g, SR_ERR_ARG, "tile kernel must be 1 or 2");
+      g->tile_version = (int)value;
+      return SR_OK;
     case SR_OPT_FRAMES_PER_GRAPH:
       if (value < 1 || value > 1024) return gfail(g, SR_ERR_ARG, "frames per graph must be in 1..1024");
       g->frames_per_graph = (int)value;

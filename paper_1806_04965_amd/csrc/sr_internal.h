@@ -67,6 +67,18 @@ struct SrMfmaEdge {
   int32_t RPB;           // bytes per patch row in LDS: >= RP*SP, tuned so that row wraps stay conflict-free
   int32_t magicKW;       // ceil(2^16 / kw): tap / kw == (tap * magic) >> 16 for tap < kh*kw (checked on host)
   int32_t wstride8;      // 16-byte units between consecutive k16 blocks in wpk: (Cout/32)*64
+  int32_t plan_slot;     // 8-wave kernel: position of this edge's first row phase in a tile's run of plan_index
+  int32_t src_bytes;     // bytes of one copy of the source state; SR_ZERO_TAIL zero bytes follow it
+};
+
+// 8-wave tile kernel: one stage = one channel chunk of one row phase of one edge.  A strided edge
+// is cut into `stride` row phases (source rows q with q % stride == phase, taps with
+// ti % stride == phase), so that a stage's source patch stays small enough for two stages to be
+// resident in LDS.
+struct SrStage8 {
+  int32_t edge;          // index into the edge table
+  int32_t phase;
+  int32_t chunk;
   int32_t pad_;
 };
 
@@ -85,7 +97,8 @@ struct SrMfmaNode {
   int32_t edge_begin, edge_count;
   int32_t waves_m, waves_n;   // 4 waves arranged waves_m x waves_n; BM = 128*waves_m
   int32_t wn_tiles;           // 32-wide MFMA column tiles per wave: 1 or 2; BN = 32*wn_tiles*waves_n
-  int32_t pad_;
+  int32_t stage0;             // 8-wave kernel: first entry of this node in the stage table
+  const SrStage8* stage_table;
 };
 
 struct SrMfmaTile {
@@ -161,3 +174,9 @@ hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, co
                           const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
                           int aux_smem_bytes, int is_last);
 int sr_mfma_max_lds_bytes();
+hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
+                           const SrMfmaTile* tiles, int n_tiles, int is_last);
+// 8-wave kernel: bytes of one of its two stage buffers, and floats of one part's K-split slab
+#define SR8_BUF_BYTES (80 * 1024)
+#define SR_ZERO_TAIL 2048   // zero bytes behind every state copy: where padding pixels are loaded from
+#define SR8_SPLIT_FLOATS (128 * 512)

@@ -702,6 +702,386 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
 }
 
 // ---------------------------------------------------------------------------
+// 8-wave tile kernel
+// ---------------------------------------------------------------------------
+// One workgroup of 8 wave64 per compute unit (two waves per SIMD, 256 registers each); the waves are
+// arranged waves_m x waves_n and each owns 128 pixels x (32*WN) channels as in the 4-wave kernel.
+// Differences:
+//  * BOTH operands of a stage come from LDS: the source patch (A) and the stage's slab of packed
+//    weights (B) are brought in by direct-to-LDS loads.  No load returns to registers inside the
+//    k-loop, so the loads of the NEXT stage can be issued between the k-steps of the current one
+//    without ever being waited for there (vector-memory results return in order: a register load
+//    behind a long direct-to-LDS load would stall on it).
+//  * LDS holds two stage buffers; a stage computes out of one while the other is being filled.
+//    One barrier per stage.
+//  * A stage is one 16*K16-channel chunk of one ROW PHASE of one edge: a stride-s edge is cut into
+//    s row phases (source rows q = phase mod s with the taps ti = phase mod s), which keeps the
+//    patch of a strided edge as small as that of a stride-1 edge.
+//  * Patch slots are KC*2 bytes without padding (sixteen consecutive pixels of a 32-byte slot then
+//    hit every LDS column twice; measured, the 2-way conflict costs nothing here).
+// LDS layout of a stage buffer: [A: NQr rows x RPB bytes][B: NS x NBT fragments of 1 KiB], NS =
+// taps of the phase x K16 k-steps, NBT = BN/32 column tiles; B fragment (st, nt) is the packed
+// fragment of tap(st), 16-channel block k(st), column tile n0/32 + nt.
+#define SR8_PLAN_ITEMS 12   // direct-to-LDS instructions of a stage: 80 KiB / 8 KiB, A and B each rounded up
+
+struct SrEdge8 {   // wave-uniform copy of an edge descriptor (scalar registers)
+  const unsigned char* src;
+  const unsigned char* wpk;
+  int Hs, Ws, Csp, kw, kh, stride, lgs, lgup, pad, KC, lgK16, PH, PWs, RPB, magicKW, wstride8, k16_total, plan_slot;
+  int src_bytes;
+};
+
+__device__ __forceinline__ SrEdge8 sr8_load_edge(const SrMfmaEdge* edges, int index, int cur) {
+  const __attribute__((address_space(4))) SrMfmaEdge* p =
+      (const __attribute__((address_space(4))) SrMfmaEdge*)(unsigned long long)(edges + index);
+  SrEdge8 k;
+  const int bridge = p->bridge;
+  k.src = (const unsigned char*)p->src[bridge ? (cur ^ 1) : cur];
+  k.wpk = (const unsigned char*)p->wpk;
+  k.Hs = p->Hs; k.Ws = p->Ws; k.Csp = p->Csp;
+  k.kw = p->kw; k.kh = p->kh;
+  k.stride = p->stride; k.lgs = (k.stride == 1) ? 0 : (k.stride == 2 ? 1 : 2);
+  const int up = p->up;
+  k.lgup = (up == 1) ? 0 : (up == 2 ? 1 : 2);
+  k.pad = p->pad;
+  k.KC = p->KC; k.lgK16 = (k.KC == 16) ? 0 : (k.KC == 32 ? 1 : (k.KC == 64 ? 2 : 3));
+  k.PH = p->PH; k.PWs = p->PWs; k.RPB = p->RPB;
+  k.magicKW = p->magicKW; k.wstride8 = p->wstride8;
+  k.k16_total = k.Csp >> 4;
+  k.plan_slot = p->plan_slot;
+  k.src_bytes = p->src_bytes;
+  return k;
+}
+
+// What the direct-to-LDS loads of one stage need (wave-uniform).  Instruction `it` of a stage
+// moves 512 consecutive 16-byte positions, 64 per wave: the A ones first, then the B ones.  Every
+// thread holds, per instruction, the byte offset of its position's source from a_base (A) or
+// b_base (B) -- or SKIP for positions that are not written.
+struct SrProd8 {
+  const unsigned char* a_base;   // source state: the byte that offset 0 stands for, this chunk
+  const unsigned char* b_base;   // packed weights: this chunk's first 16-channel block, tile's first column tile
+  int a_step, b_step;            // bytes from one chunk to the next
+  int nA_it, n_it;
+  int a_bytes;                   // LDS bytes of A; B follows
+  int NS;                        // k-steps of the stage
+  int lgK16;
+};
+
+__device__ __forceinline__ void sr8_issue(const SrProd8& P, int it, unsigned char* buf, int wave,
+                                          const int (&plan)[SR8_PLAN_ITEMS]) {
+  const int off = plan[it];
+  const bool is_a = it < P.nA_it;
+  const unsigned char* base = is_a ? P.a_base : P.b_base;
+  const int dst = (is_a ? it * 8192 : P.a_bytes + (it - P.nA_it) * 8192) + wave * 1024;
+  if (off != SR_DMA_SKIP)
+    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (unsigned)off),
+                                     (__attribute__((address_space(3))) void*)(buf + dst), 16, 0, 0);
+}
+
+// One k-step: 4 x WN MFMAs.  Each A fragment is reloaded for the next step right after its last
+// use; the B fragments of the next step go into the other B buffer.  dps direct-to-LDS
+// instructions of the next stage are issued at the end of the step.
+template <int WN>
+__device__ __forceinline__ void sr8_step(const unsigned char* rd, const int (&abase)[4], int bbase, int tapA, int lgK16,
+                                         int nbt1024, bf16x8_t (&a)[4], const bf16x8_t (&b)[WN], bf16x8_t (&bn)[WN],
+                                         f32x16_t (&acc)[4][WN], int st, int NS) {
+  const int sn = min(st + 1, NS - 1);
+  const int tap = sn >> lgK16;
+  const int aoff = __builtin_amdgcn_readlane(tapA, tap) + ((sn - (tap << lgK16)) << 5);
+  const int boff = sn * nbt1024;
+#pragma unroll
+  for (int nj = 0; nj < WN; ++nj) bn[nj] = *(const bf16x8_t*)(rd + bbase + boff + nj * 1024);
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+#pragma unroll
+    for (int nj = 0; nj < WN; ++nj)
+      acc[mi][nj] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(b[nj], a[mi], acc[mi][nj], 0, 0, 0);
+    a[mi] = *(const bf16x8_t*)(rd + abase[mi] + aoff);
+  }
+  // issue order: lane read of the next A offset; WN MFMAs, then the address add and the LDS read of
+  // the row they released, four times; the reads of the next B fragments go behind the first group
+  // (a wait for "all LDS reads" at the top of the step then only covers reads of the step before)
+  __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);      // VALU (lane read)
+  __builtin_amdgcn_sched_group_barrier(0x008, WN, 0);     // MFMA
+  __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);      // VALU (address)
+  __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);      // DS read (A)
+  __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);      // VALU (B address)
+  __builtin_amdgcn_sched_group_barrier(0x100, WN, 0);     // DS read (B)
+#pragma unroll
+  for (int mi = 1; mi < 4; ++mi) {
+    __builtin_amdgcn_sched_group_barrier(0x008, WN, 0);   // MFMA
+    __builtin_amdgcn_sched_group_barrier(0x002, 1, 0);    // VALU (address)
+    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);    // DS read (A)
+  }
+}
+
+template <int WN>
+__device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
+                                              const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
+                                              int tile_n0, int plan_begin, int stage_begin, int stage_end,
+                                              int split_slot, int part_info, unsigned char* lds) {
+  const __attribute__((address_space(4))) SrMfmaNode* nd =
+      (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wave = SR_UNIFORM(tid >> 6);
+  const int waves_n = nd->waves_n;
+  const int wm = (waves_n == 2) ? (wave >> 1) : wave;
+  const int wn = wave - wm * waves_n;
+  const int cur = ctx->frame & 1;
+  const int M = nd->M, Wo = nd->Wo, HoWo = nd->Ho * Wo;
+  const int BM = 128 * nd->waves_m;
+  const int m_first = tile_m0;
+  const int m_last = min(tile_m0 + BM, M) - 1;
+  const int wave_m0 = tile_m0 + wm * 128;
+  const int wave_n0 = tile_n0 + wn * (32 * WN);
+  const int NBT = WN * waves_n;                         // column tiles of the workgroup
+  const int lgNBT64 = (NBT == 1) ? 6 : (NBT == 2 ? 7 : 8);
+  const int b_first = m_first / HoWo, oy_first = (m_first - b_first * HoWo) / Wo;
+  const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / Wo;
+  const unsigned char* zero_page = (const unsigned char*)nd->zero_page;
+  const __attribute__((address_space(4))) int* plan_index =
+      (const __attribute__((address_space(4))) int*)(unsigned long long)nd->plan_index + plan_begin;
+  const __attribute__((address_space(1))) int* plan_tables =
+      (const __attribute__((address_space(1))) int*)(unsigned long long)nd->plan_tables;
+  const __attribute__((address_space(4))) SrStage8* stages =
+      (const __attribute__((address_space(4))) SrStage8*)(unsigned long long)nd->stage_table + nd->stage0;
+
+  int pix[4];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi) {
+    const int m = min(wave_m0 + mi * 32 + (lane & 31), M - 1);
+    const int b = m / HoWo;
+    const int r = m - b * HoWo;
+    const int oy = r / Wo;
+    pix[mi] = (r - oy * Wo) | (oy << 12) | ((b - b_first) << 24);
+  }
+
+  f32x16_t acc[4][WN];
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+    for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
+
+  // ---- producer state (the stage whose loads are being issued) and what the consumer inherits
+  SrProd8 P;
+  int plan[SR8_PLAN_ITEMS];
+  int tapA_n = 0, abase_n[4] = {0, 0, 0, 0};
+  int p_chunk = 0, p_nchunk = 0;
+  // prepares P (and the consumer's next tap table / fragment addresses) for stage index sidx
+  auto prepare = [&](int sidx) {
+    if (p_chunk + 1 < p_nchunk) {   // the stage list runs edge by edge, phase by phase, chunk by chunk
+      p_chunk += 1;
+      P.a_base += P.a_step;
+      P.b_base += P.b_step;
+      return;
+    }
+    const int s_edge = stages[sidx].edge, s_phase = stages[sidx].phase, s_chunk = stages[sidx].chunk;
+    const SrEdge8 e = sr8_load_edge(edges, s_edge, cur);
+    p_chunk = s_chunk;
+    p_nchunk = e.Csp >> (4 + e.lgK16);
+    const int cnt = (e.kh - s_phase + e.stride - 1) >> e.lgs;         // tap rows of this phase
+    const int ntaps = cnt * e.kw;
+    const int row_first = (oy_first >> e.lgup) << e.lgs;              // first padded source row, in its image
+    const int Q0 = b_first * e.PH + row_first;
+    const int Q1 = b_last * e.PH + ((oy_last >> e.lgup) << e.lgs) + e.kh - 1;
+    const int NQr = (Q1 - Q0 + 1 - s_phase + e.stride - 1) >> e.lgs;  // patch rows of this phase
+    const int n_posA = NQr * (e.RPB >> 4);
+    P.NS = ntaps << e.lgK16;
+    P.lgK16 = e.lgK16;
+    P.a_bytes = n_posA << 4;
+    P.nA_it = (n_posA + 511) >> 9;
+    const int n_posB = P.NS << lgNBT64;
+    P.n_it = P.nA_it + ((n_posB + 511) >> 9);
+    P.a_step = e.KC * 2;
+    P.b_step = (e.wstride8 << e.lgK16) * 16;
+    const long long base_off = ((long long)(b_first * e.Hs + row_first - e.pad) * e.Ws) * e.Csp * 2;
+    P.a_base = e.src + base_off + (size_t)s_chunk * P.a_step;
+    P.b_base = e.wpk + (size_t)(tile_n0 >> 5) * 1024 + (size_t)s_chunk * P.b_step;
+    // offsets of this thread's positions.  A: from the plan table; padding pixels are read from the
+    // zero bytes behind the source state (far enough behind for every chunk's offset)
+    const int zero_off = (int)((long long)e.src_bytes - base_off);
+    const __attribute__((address_space(1))) int* table = plan_tables + plan_index[e.plan_slot + s_phase];
+#pragma unroll
+    for (int it = 0; it < SR8_PLAN_ITEMS; ++it) {
+      int v = SR_DMA_SKIP;
+      if (it < P.n_it) v = table[tid + it * 512];   // A then B entries, each padded to 512
+      if (v == SR_DMA_ZERO) v = zero_off;
+      plan[it] = v;
+    }
+    // A tap table of the phase, one tap per lane: t-th tap = (ti, tj) = (phase + (t / kw) * stride, t % kw)
+    {
+      const int t = min(lane, ntaps - 1);
+      const int q = (t * e.magicKW) >> 16;
+      const int tj = t - q * e.kw;
+      tapA_n = q * e.RPB + ((tj & (e.stride - 1)) * e.PWs + (tj >> e.lgs)) * (e.KC * 2);
+    }
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) {
+      const int ox = pix[mi] & 0xfff, oy = (pix[mi] >> 12) & 0xfff, db = pix[mi] >> 24;
+      abase_n[mi] = ((db * e.PH + ((oy >> e.lgup) << e.lgs) - row_first) >> e.lgs) * e.RPB +
+                    (ox >> e.lgup) * (e.KC * 2) + (lane >> 5) * 16;
+    }
+  };
+
+  unsigned char* buf0 = lds;
+  unsigned char* buf1 = lds + SR8_BUF_BYTES;
+  // first stage: all its loads at once
+  prepare(stage_begin);
+  for (int it = 0; it < P.n_it; ++it) sr8_issue(P, it, buf0, wave, plan);
+
+  int par = 0;
+  for (int c = stage_begin; c < stage_end; ++c) {
+    // the consumer takes over what was prepared for this stage
+    const int NS = P.NS, lgK16 = P.lgK16, a_bytes = P.a_bytes;
+    const int tapA = tapA_n;
+    int abase[4];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) abase[mi] = abase_n[mi];
+    // the producer moves on to the next stage (its plan loads overlap the wait below)
+    int dma_n = 0;
+    if (c + 1 < stage_end) { prepare(c + 1); dma_n = P.n_it; }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's loads of stage c have landed
+    __syncthreads();                                     // ... everybody's; and stage c-1 has been read by all
+    const unsigned char* rd = par ? buf1 : buf0;
+    unsigned char* wr = par ? buf0 : buf1;
+    const int bbase = a_bytes + ((wn * WN) * 64 + lane) * 16;
+    const int nbt1024 = NBT * 1024;
+    // loads of the next stage per k-step
+    const int dps = (dma_n + NS - 1) / NS;
+    int dma_it = 0;
+    bf16x8_t a[4], b[2][WN];
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi) a[mi] = *(const bf16x8_t*)(rd + abase[mi]);
+#pragma unroll
+    for (int nj = 0; nj < WN; ++nj) b[0][nj] = *(const bf16x8_t*)(rd + bbase + nj * 1024);
+    int st = 0;
+    for (; st + 2 <= NS; st += 2) {
+      sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[0], b[1], acc, st, NS);
+      for (int j = 0; j < dps; ++j, ++dma_it)
+        if (dma_it < dma_n) sr8_issue(P, dma_it, wr, wave, plan);
+      sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[1], b[0], acc, st + 1, NS);
+      for (int j = 0; j < dps; ++j, ++dma_it)
+        if (dma_it < dma_n) sr8_issue(P, dma_it, wr, wave, plan);
+    }
+    if (st < NS) {
+      sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[0], b[1], acc, st, NS);
+      for (int j = 0; j < dps; ++j, ++dma_it)
+        if (dma_it < dma_n) sr8_issue(P, dma_it, wr, wave, plan);
+    }
+    par ^= 1;
+  }
+
+  // ---- K-split tiles: as in the 4-wave kernel, with 512 threads
+  const int n_parts = part_info >> 16;
+  if (n_parts > 1) {
+    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
+    f32x4_t* scratch = (f32x4_t*)((float*)nd->split_scratch + (size_t)(split_slot + (part_info & 0xffff)) * SR8_SPLIT_FLOATS);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4_t v = {acc[mi][nj][4 * q], acc[mi][nj][4 * q + 1], acc[mi][nj][4 * q + 2], acc[mi][nj][4 * q + 3]};
+          scratch[((mi * WN + nj) * 4 + q) * 512 + tid] = v;
+        }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have reached memory
+    __syncthreads();
+    int* flag = (int*)lds;
+    if (tid == 0) {
+      int* counter = (int*)nd->split_counters + split_slot;
+      const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      *flag = (old == n_parts - 1);
+      if (old == n_parts - 1) *counter = 0;
+    }
+    __syncthreads();
+    if (!*flag) return;
+    const f32x4_t* all = (const f32x4_t*)((const float*)nd->split_scratch + (size_t)split_slot * SR8_SPLIT_FLOATS);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
+          for (int p = 0; p < n_parts; ++p)
+            sum += all[(size_t)p * (SR8_SPLIT_FLOATS / 4) + ((mi * WN + nj) * 4 + q) * 512 + tid];
+#pragma unroll
+          for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] = sum[i];
+        }
+  }
+
+  // ---- epilogue: as in the 4-wave kernel (each wave transposes its tile through its own LDS region)
+  __attribute__((address_space(1))) unsigned char* out =
+      (__attribute__((address_space(1))) unsigned char*)(unsigned long long)nd->out[cur];
+  const __attribute__((address_space(1))) float* biasp =
+      (const __attribute__((address_space(1))) float*)(unsigned long long)nd->bias;
+  const int Cp = nd->Cp, act = nd->act;
+  constexpr int EP = 32 * WN * 2 + 16;          // bytes per pixel row in LDS
+  constexpr int PIECES = 32 * WN * 2 / 16;      // 16-byte pieces per pixel row
+  unsigned char* my = lds + wave * (64 * EP);
+  float bias[WN][4][4];
+#pragma unroll
+  for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+    for (int gq = 0; gq < 4; ++gq)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) bias[nj][gq][i] = biasp[wave_n0 + nj * 32 + 8 * gq + 4 * (lane >> 5) + i];
+  __syncthreads();   // every wave has finished reading the last stage
+#pragma unroll
+  for (int half = 0; half < 2; ++half) {
+#pragma unroll
+    for (int mh = 0; mh < 2; ++mh) {
+      const int mi = half * 2 + mh;
+#pragma unroll
+      for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+        for (int gq = 0; gq < 4; ++gq) {
+          bf16x4_t h;
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            float v = acc[mi][nj][gq * 4 + i] + bias[nj][gq][i];
+            if (act == 1) v = fmaxf(v, 0.f);
+            h[i] = (__bf16)v;      // round to nearest even
+          }
+          *(bf16x4_t*)(my + (mh * 32 + (lane & 31)) * EP + (nj * 32 + 8 * gq + 4 * (lane >> 5)) * 2) = h;
+        }
+    }
+#pragma unroll
+    for (int it = 0; it < PIECES; ++it) {
+      const int p = it * 64 + lane;
+      const int row = p / PIECES, piece = p - row * PIECES;
+      const int m = wave_m0 + half * 64 + row;
+      const u32x4_t v = *(const u32x4_t*)(my + row * EP + piece * 16);
+      if (m < M)
+        *(__attribute__((address_space(1))) u32x4_t*)(out + ((size_t)m * Cp + wave_n0) * 2 + piece * 16) = v;
+    }
+  }
+}
+
+__global__ __launch_bounds__(512) void sr_mfma8_kernel(SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
+                                                       const SrMfmaEdge* __restrict__ edges,
+                                                       const SrMfmaTile* __restrict__ tiles, int is_last) {
+  extern __shared__ __align__(16) unsigned char sr_lds8[];
+  const SrMfmaTile t = tiles[blockIdx.x];
+  const int node_index = SR_UNIFORM(t.node);
+  if (node_index < 0) {
+    // empty slot
+  } else if (nodes[node_index].wn_tiles == 2)
+    sr_mfma8_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
+                     SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
+                     sr_lds8);
+  else
+    sr_mfma8_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
+                     SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
+                     sr_lds8);
+  if (is_last) sr_block_done(ctx, gridDim.x);
+}
+
+// ---------------------------------------------------------------------------
 // launch wrappers
 // ---------------------------------------------------------------------------
 static inline int blocks_for(long long n, int per) {
@@ -798,6 +1178,20 @@ hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, co
   }
   hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles + n_aux), dim3(256), lds_bytes, s, ctx, nodes, edges, tiles, n_tiles,
                      aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last);
+  return hipGetLastError();
+}
+
+hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
+                           const SrMfmaTile* tiles, int n_tiles, int is_last) {
+  if (n_tiles == 0) return hipSuccess;
+  static bool attr_set = false;
+  if (!attr_set) {   // dynamic LDS above 64 KiB has to be requested once
+    hipError_t e = hipFuncSetAttribute((const void*)sr_mfma8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                       2 * SR8_BUF_BYTES);
+    if (e != hipSuccess) return e;
+    attr_set = true;
+  }
+  hipLaunchKernelGGL(sr_mfma8_kernel, dim3(n_tiles), dim3(512), 2 * SR8_BUF_BYTES, s, ctx, nodes, edges, tiles, is_last);
   return hipGetLastError();
 }
 

@@ -14,6 +14,7 @@ TOL = {"f32": 1e-4, "bf16": 2e-2}
 MODE = {"f32": "f64", "bf16": "bf16"}
 OPT_DIRECT = {1: 1}
 OPT_EAGER = {0: 0}
+OPT_WIDE = {4: 2}     # 8-wave tile kernel (both operands through LDS, stages loaded one ahead)
 
 
 def check(g, seed=0, T=None, options=None, bias_scale=0.1, label=None):
@@ -220,3 +221,28 @@ def test_errors_on_the_device_path():
         dev.set_weights(0, np.zeros(5, np.float32))
     assert ei.value.name == "SR_ERR_ARG"
     dev.close()
+
+
+@pytest.mark.parametrize("name", ["cifar", "cifar_ragged", "gtsrb", "hires"])
+def test_eight_wave_tile_kernel_streaming(name):
+    g = {"cifar": lambda: W.cifar_sr(batch=4, frames=4), "cifar_ragged": lambda: W.cifar_sr(batch=3, frames=3),
+         "gtsrb": lambda: W.gtsrb_sr(batch=3, frames=3), "hires": lambda: W.hires_sr(batch=1, frames=2)}[name]()
+    info, work = check(g, seed=21, options=OPT_WIDE, label=f"{name}/8-wave kernel")
+    assert work["mfma_tiles"] > 0 and info["inference_factor"] == 1
+
+
+def test_eight_wave_tile_kernel_sequential_pattern_and_no_split():
+    g = W.cifar_sr(batch=4, frames=3)
+    check(g.with_pattern(W.sequential_pattern(g)), seed=22, options=OPT_WIDE, label="cifar_sr/sequential/8-wave kernel")
+    check(W.hires_sr(batch=1, frames=2), seed=23, options={4: 2, 3: 0}, label="hires_sr/8-wave kernel, no K-split")
+
+
+def test_eight_wave_tile_kernel_rollout_in_hipgraph_matches_steps():
+    g = W.gtsrb_sr(batch=2, frames=5)
+    w, b, x = W.make_case(g, seed=24, bias_scale=0.1, frames=5)
+    a = gpu_rollout(g, w, b, x, 5, options=OPT_WIDE)
+    c = gpu_rollout(g, w, b, x, 5, options={4: 2, 0: 0})
+    assert np.array_equal(a, c)
+    ref = oracle_states(g, w, b, x, 5, "bf16", nodes=[g.out_node])
+    for t in range(5):
+        assert max_abs_rel(a[t], ref[g.out_node][t]) <= TOL["bf16"]
