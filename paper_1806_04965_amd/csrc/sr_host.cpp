@@ -516,11 +516,22 @@ sr_status finalize(sr_graph* g) {
         // of a stage lives in LDS), 8 waves arranged waves_m x waves_n
         const int Cout = n.d.channels;
         const int64_t M = (int64_t)B * n.d.height * n.d.width;
-        int wt = 0, wn = 0;
-        for (const auto& c : {std::pair<int, int>(2, 2), std::pair<int, int>(2, 1), std::pair<int, int>(1, 1)})
-          if (wt == 0 && Cout % (32 * c.first * c.second) == 0) { wt = c.first; wn = c.second; }
-        const int waves_m = 8 / wn, BM = 128 * waves_m, BN = 32 * wt * wn, NBT = wt * wn;
+        // shapes (wn_tiles, waves_n), preferred first: the widest channel tile up to 128 (the weight slab
+        // of a stage lives in LDS) on the longest pixel tile; then shorter pixel tiles, whose source
+        // patches are smaller
+        std::vector<std::pair<int, int>> shapes;
+        for (const auto& c : {std::pair<int, int>(2, 2), std::pair<int, int>(2, 1), std::pair<int, int>(1, 1),
+                              std::pair<int, int>(1, 2), std::pair<int, int>(1, 4)})
+          if (Cout % (32 * c.first * c.second) == 0) shapes.push_back(c);
+        int wt = 0, wn = 0, waves_m = 0, BM = 0, BN = 0, NBT = 0;
         SrMfmaNode node{};
+        bool ok = false;
+        int plan_slots = 0, n_stages = 0;
+        double cyc = 0;
+        for (const auto& shape : shapes) {
+        wt = shape.first; wn = shape.second;
+        waves_m = 8 / wn; BM = 128 * waves_m; BN = 32 * wt * wn; NBT = wt * wn;
+        node = SrMfmaNode{};
         node.out[0] = n.state[0];
         node.out[1] = n.state[1];
         node.bias = n.bias_dev;
@@ -536,9 +547,9 @@ sr_status finalize(sr_graph* g) {
         node.wn_tiles = wt;
         node.zero_page = g->zero_page;
         node.stage0 = (int)stage8.size();
-        bool ok = ((int64_t)BM / ((int64_t)n.d.height * n.d.width) + 2 <= 127);
-        int plan_slots = 0, n_stages = 0;
-        double cyc = 8000;
+        ok = ((int64_t)BM / ((int64_t)n.d.height * n.d.width) + 2 <= 127);
+        plan_slots = 0; n_stages = 0;
+        cyc = 8000;
         for (EdgeRt& e : g->edges) {
           if (e.d.dst != v || !ok) continue;
           const NodeRt& sn = g->nodes[e.d.src];
@@ -594,6 +605,10 @@ sr_status finalize(sr_graph* g) {
             }
           }
           me.push_back(m);
+        }
+        if (ok) break;
+        me.resize(node.edge_begin);
+        stage8.resize(node.stage0);
         }
         if (!ok) {
           me.resize(node.edge_begin);
@@ -1079,9 +1094,13 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
       const int is_last = (!copy_out && L == last_level) ? 1 : 0;
       const int n_aux = aux_ride ? 0 : lp.n_aux;   // aux items already went with the tiles
       SR_HIP(g, mark(2));
-      SR_HIP(g, sr_launch_direct(s, g->ctx, g->d_nodes, g->d_edges, g->d_blocks + lp.block_begin, lp.n_blocks, bf16,
-                                 g->batch, g->aux + lp.aux_begin, n_aux, g->heads, g->head_edges, g->stage_nodes,
-                                 g->aux_smem_bytes, is_last));
+      if (lp.n_blocks == 0)   // auxiliary items only
+        SR_HIP(g, sr_launch_aux(s, g->ctx, g->aux + lp.aux_begin, n_aux, g->heads, g->head_edges, g->stage_nodes,
+                                g->aux_smem_bytes, bf16, is_last));
+      else
+        SR_HIP(g, sr_launch_direct(s, g->ctx, g->d_nodes, g->d_edges, g->d_blocks + lp.block_begin, lp.n_blocks, bf16,
+                                   g->batch, g->aux + lp.aux_begin, n_aux, g->heads, g->head_edges, g->stage_nodes,
+                                   g->aux_smem_bytes, is_last));
     }
   }
   if (copy_out) {

@@ -826,7 +826,7 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
   const int lane = tid & 63;
   const int wave = SR_UNIFORM(tid >> 6);
   const int waves_n = nd->waves_n;
-  const int wm = (waves_n == 2) ? (wave >> 1) : wave;
+  const int wm = (waves_n == 4) ? (wave >> 2) : (waves_n == 2 ? (wave >> 1) : wave);
   const int wn = wave - wm * waves_n;
   const int cur = ctx->frame & 1;
   const int M = nd->M, Wo = nd->Wo, HoWo = nd->Ho * Wo;
