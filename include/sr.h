@@ -114,6 +114,31 @@ sr_status sr_analyze(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges
 sr_status sr_count_valid_patterns(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
                                   uint64_t* count);
 
+/* Inference tableau of the rollout window of size W (Eq. 5): tableau[i * n_nodes + v], frames
+ * i = 0..W, is the number of update steps (Eq. 3, 4) after which node v of frame i has been
+ * computed, starting from the initial state (frame 0 and all input nodes given): the length of
+ * the longest path of the window ending in (i, v) that does not start with an edge into frame 0.
+ * tableau: host, (W + 1) * n_nodes ints.  W >= 1.  The maximum over the window of size 1 is the
+ * inference factor (Eq. 6).  Errors: SR_ERR_ARG, SR_ERR_GRAPH, SR_ERR_ROLLOUT. */
+sr_status sr_tableau(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges, int32_t W, int32_t* tableau);
+
+/* Are two rollout patterns of one network equally model-parallel (Sec. 3), i.e. equal on every
+ * edge that does not leave an input node?  bridge_a, bridge_b: host, n_edges values in {0, 1}
+ * (the bridge fields of `edges` are ignored); neither needs to be valid.  equal (host) receives
+ * 1 or 0.  Errors: SR_ERR_ARG, SR_ERR_GRAPH. */
+sr_status sr_equally_model_parallel(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
+                                    const uint8_t* bridge_a, const uint8_t* bridge_b, int32_t* equal);
+
+/* Bounds of Lemma 1 on the number n of valid rollout patterns:
+ *   lower_forward = 2^|E_forward|         (edges on no cycle),
+ *   lower_cycles  = max over sets C of pairwise edge-disjoint minimal cycles of prod (2^|p| - 1),
+ *   upper         = 2^(|E| - |E_rec|)     (E_rec: self-connecting edges),
+ * lower_forward <= n, lower_cycles <= n <= upper.  Exhaustive over the minimal cycles: networks
+ * with more than 24 edges or more than 20 minimal cycles are refused.  Any output may be NULL.
+ * The bridge fields of `edges` are ignored.  Errors: SR_ERR_ARG, SR_ERR_GRAPH. */
+sr_status sr_pattern_count_bounds(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
+                                  uint64_t* lower_forward, uint64_t* lower_cycles, uint64_t* upper);
+
 /* ---------------------------------------------------------------------------
  * Create the device-side representation of a network and its rollout pattern
  * (Sec. 3: network, rollout pattern; App. A1.2: node and edge maps).

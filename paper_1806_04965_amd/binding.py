@@ -13,7 +13,8 @@ SR_F32, SR_BF16 = 0, 1
 _KIND = {"conv": 0, "dense": 1, "gap_dense": 2}
 SR_OPT_USE_HIPGRAPH, SR_OPT_FORCE_DIRECT, SR_OPT_FRAMES_PER_GRAPH = 0, 1, 2
 
-EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_graph_create", "sr_graph_set_weights",
+EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_model_parallel",
+           "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
            "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
            "sr_graph_work", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
@@ -112,6 +113,33 @@ def count_valid_patterns(n_nodes: int, edges) -> int:
     c = C.c_uint64(0)
     _check(lib, lib.sr_count_valid_patterns(n_nodes, _edge_array(edges), len(edges), C.byref(c)))
     return c.value
+
+
+def tableau(n_nodes: int, edges, W: int) -> list:
+    """sr_tableau: inference tableau of the window of size W as W + 1 rows of n_nodes values."""
+    lib = load_library()
+    t = (C.c_int32 * max(1, (W + 1) * n_nodes))()
+    _check(lib, lib.sr_tableau(n_nodes, _edge_array(edges), len(edges), W, t))
+    flat = list(t)
+    return [flat[i * n_nodes:(i + 1) * n_nodes] for i in range(W + 1)]
+
+
+def equally_model_parallel(n_nodes: int, edges, bridge_a, bridge_b) -> bool:
+    lib = load_library()
+    a = (C.c_uint8 * max(1, len(edges)))(*[int(x) for x in bridge_a])
+    b = (C.c_uint8 * max(1, len(edges)))(*[int(x) for x in bridge_b])
+    eq = C.c_int32(0)
+    _check(lib, lib.sr_equally_model_parallel(n_nodes, _edge_array(edges), len(edges), a, b, C.byref(eq)))
+    return bool(eq.value)
+
+
+def pattern_count_bounds(n_nodes: int, edges) -> tuple:
+    """sr_pattern_count_bounds: (lower_forward, lower_cycles, upper) of Lemma 1."""
+    lib = load_library()
+    lo_f, lo_c, up = C.c_uint64(0), C.c_uint64(0), C.c_uint64(0)
+    _check(lib, lib.sr_pattern_count_bounds(n_nodes, _edge_array(edges), len(edges), C.byref(lo_f), C.byref(lo_c),
+                                            C.byref(up)))
+    return lo_f.value, lo_c.value, up.value
 
 
 class SrGraph:

@@ -1246,6 +1246,107 @@ sr_status sr_count_valid_patterns(int32_t n_nodes, const sr_edge_desc* edges, in
   return SR_OK;
 }
 
+sr_status sr_tableau(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges, int32_t W, int32_t* tableau) {
+  if (!tableau || W < 1) return fail(nullptr, SR_ERR_ARG, "tableau is null or W < 1");
+  std::vector<int> is_input;
+  sr_status st = check_network(n_nodes, edges, n_edges, &is_input, nullptr);
+  if (st != SR_OK) return st;
+  std::vector<uint8_t> bits(n_edges);
+  for (int e = 0; e < n_edges; ++e) bits[e] = edges[e].bridge;
+  Analysis an;
+  st = analyse_pattern(n_nodes, edges, n_edges, bits.data(), is_input, &an, nullptr);
+  if (st != SR_OK) return st;
+  // nodes of one frame in an order in which every R = 0 edge points forward: by their level in the
+  // size-1 window (an R = 0 edge raises the level by at least one)
+  std::vector<int> order(n_nodes);
+  for (int v = 0; v < n_nodes; ++v) order[v] = v;
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return an.level[a] < an.level[b]; });
+  // frame 0 is given: no path may start with an edge into it, so its values are 0; in a later frame
+  // the longest path into (i, v) extends the longest path into the source of one of v's edges, in
+  // frame i (R = 0) or i - 1 (R = 1)
+  for (int v = 0; v < n_nodes; ++v) tableau[v] = 0;
+  for (int i = 1; i <= W; ++i) {
+    int32_t* row = tableau + (size_t)i * n_nodes;
+    const int32_t* prev = row - n_nodes;
+    for (int v = 0; v < n_nodes; ++v) row[v] = 0;
+    for (int v : order)
+      for (int e = 0; e < n_edges; ++e) {
+        if (edges[e].dst != v) continue;
+        const int32_t from = bits[e] ? prev[edges[e].src] : row[edges[e].src];
+        row[v] = std::max(row[v], from + 1);
+      }
+  }
+  return SR_OK;
+}
+
+sr_status sr_equally_model_parallel(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
+                                    const uint8_t* bridge_a, const uint8_t* bridge_b, int32_t* equal) {
+  if (!bridge_a || !bridge_b || !equal) return fail(nullptr, SR_ERR_ARG, "null argument");
+  std::vector<int> is_input;
+  sr_status st = check_network(n_nodes, edges, n_edges, &is_input, nullptr);
+  if (st != SR_OK) return st;
+  int same = 1;
+  for (int e = 0; e < n_edges; ++e) {
+    if (bridge_a[e] > 1 || bridge_b[e] > 1) return fail(nullptr, SR_ERR_ARG, "R(e) must be 0 or 1");
+    if (!is_input[edges[e].src] && bridge_a[e] != bridge_b[e]) same = 0;
+  }
+  *equal = same;
+  return SR_OK;
+}
+
+namespace {
+// minimal (simple) cycles as bit masks over the edges; a cycle is found from its smallest node
+void cycles_from(int start, int node, uint32_t path, uint32_t seen_nodes_lo, std::vector<char>& seen, int n_edges,
+                 const sr_edge_desc* edges, std::vector<uint32_t>* out) {
+  (void)seen_nodes_lo;
+  for (int e = 0; e < n_edges; ++e) {
+    if (edges[e].src != node) continue;
+    const int t = edges[e].dst;
+    if (t == start) {
+      out->push_back(path | (1u << e));
+    } else if (t > start && !seen[t]) {
+      seen[t] = 1;
+      cycles_from(start, t, path | (1u << e), 0, seen, n_edges, edges, out);
+      seen[t] = 0;
+    }
+  }
+}
+
+uint64_t best_disjoint_product(const std::vector<uint32_t>& cycles, size_t i, uint32_t used) {
+  if (i == cycles.size()) return 1;
+  uint64_t best = best_disjoint_product(cycles, i + 1, used);   // without cycle i
+  if ((cycles[i] & used) == 0) {
+    const int len = __builtin_popcount(cycles[i]);
+    best = std::max(best, (((uint64_t)1 << len) - 1) * best_disjoint_product(cycles, i + 1, used | cycles[i]));
+  }
+  return best;
+}
+}  // namespace
+
+sr_status sr_pattern_count_bounds(int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
+                                  uint64_t* lower_forward, uint64_t* lower_cycles, uint64_t* upper) {
+  std::vector<int> is_input;
+  sr_status st = check_network(n_nodes, edges, n_edges, &is_input, nullptr);
+  if (st != SR_OK) return st;
+  if (n_edges > 24) return fail(nullptr, SR_ERR_ARG, "the bounds are computed exhaustively: at most 24 edges");
+  std::vector<uint32_t> cycles;
+  std::vector<char> seen(n_nodes, 0);
+  for (int v = 0; v < n_nodes; ++v) {
+    seen[v] = 1;
+    cycles_from(v, v, 0, 0, seen, n_edges, edges, &cycles);
+    seen[v] = 0;
+    if (cycles.size() > 20) return fail(nullptr, SR_ERR_ARG, "more than 20 minimal cycles");
+  }
+  uint32_t on_cycle = 0;
+  for (uint32_t c : cycles) on_cycle |= c;
+  int n_rec = 0;
+  for (int e = 0; e < n_edges; ++e) n_rec += edges[e].src == edges[e].dst;
+  if (lower_forward) *lower_forward = (uint64_t)1 << (n_edges - __builtin_popcount(on_cycle));
+  if (lower_cycles) *lower_cycles = best_disjoint_product(cycles, 0, 0);
+  if (upper) *upper = (uint64_t)1 << (n_edges - n_rec);
+  return SR_OK;
+}
+
 sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_edge_desc* edges, int32_t n_edges,
                           int32_t batch, sr_dtype dtype, void* hip_stream, sr_graph** out) {
   if (!out || !nodes || n_nodes <= 0 || batch <= 0 || (dtype != SR_F32 && dtype != SR_BF16))

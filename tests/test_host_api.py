@@ -75,6 +75,42 @@ def test_analyze_agrees_with_oracle_on_random_graphs():
     assert checked > 30
 
 
+def test_tableau_bounds_and_model_parallel_classes_match_paper_and_oracle():
+    # skip+recurrent example net (Sec. 4): sequential tableau of the size-1 window is 0,1,2,3;
+    # Lemma 1: 16 = 2^4 = 2^(5-1) patterns.  3-cycle fed by an input: bounds 2, 7 and 16 around 14.
+    pairs = [(0, 1), (1, 2), (2, 3), (1, 3), (1, 1)]
+    assert sr.tableau(4, edges_of(pairs, [0, 0, 0, 0, 1]), 1) == [[0, 0, 0, 0], [0, 1, 2, 3]]
+    assert sr.tableau(4, edges_of(pairs), 3) == [[0, 0, 0, 0], [0, 1, 1, 1], [0, 2, 2, 2], [0, 3, 3, 3]]
+    assert sr.pattern_count_bounds(4, edges_of(pairs)) == (16, 1, 16)
+    assert sr.pattern_count_bounds(4, edges_of([(0, 1), (1, 2), (2, 3), (3, 1)])) == (2, 7, 16)
+    seq, stream = [0, 0, 0, 0, 1], [1, 1, 1, 1, 1]
+    assert not sr.equally_model_parallel(4, edges_of(pairs), seq, stream)
+    assert sr.equally_model_parallel(4, edges_of(pairs), [0, 1, 1, 1, 1], stream)   # differs on the input edge only
+    rng = random.Random(9)
+    checked = 0
+    for _ in range(150):
+        n = rng.randint(2, 6)
+        pairs = list({(rng.randrange(n), rng.randrange(n)) for _ in range(rng.randint(1, 2 * n))})
+        try:
+            th.check_network(n, pairs)
+        except th.GraphError:
+            continue
+        R = [rng.randint(0, 1) for _ in pairs]
+        R2 = [rng.randint(0, 1) for _ in pairs]
+        assert sr.equally_model_parallel(n, edges_of(pairs), R, R2) == th.equally_model_parallel(n, pairs, R, R2)
+        lo_f, lo_c, up = sr.pattern_count_bounds(n, edges_of(pairs))
+        assert (lo_f, lo_c, up) == th.lemma1_bounds(n, pairs)
+        if len(pairs) <= 8:
+            cnt = sr.count_valid_patterns(n, edges_of(pairs))
+            assert lo_f <= cnt <= up and lo_c <= cnt
+        if th.is_valid(n, pairs, R):
+            W_ = rng.randint(1, 4)
+            t = sr.tableau(n, edges_of(pairs, R), W_)
+            assert t == th.tableau_longest_path(n, pairs, R, W_) == th.tableau_update_steps(n, pairs, R, W_)
+            checked += 1
+    assert checked > 20
+
+
 def test_benchmark_graph_levels():
     for name, f in W.BENCH_CONFIGS.items():
         g = f()
