@@ -9,6 +9,13 @@ taken on the library's stream) and the CPU oracle timed on a bounded sample of t
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gtsrb_sr|cifar_sr|hires_sr|tiny_sr]
                     [--pattern streaming|sequential|hybrid] [--no-cpu-baseline]
+
+Further workloads: the paper's own network shapes (App. A2) mnist_ff, mnist_s, mnist_sr, dsr0 .. dsr6,
+gtsrb_dsr4.  Extra fields of the line: frame_latency_us (p50 / p99 over single sr_frame_step calls,
+HIP events), response_frames (frame updates between an input frame and the first output that depends
+on it: the smallest number of bridging edges on a path from an input to the output node, at least 1 --
+Sec. 4: the streaming rollout responds after the shortest path) and response_us = response_frames *
+us_per_frame.
 """
 from __future__ import annotations
 
@@ -43,6 +50,21 @@ def recorded_traffic(workload, pattern):
         return None
 
 
+def response_frames(g):
+    """Frame updates until the output node first depends on a new input frame: 0-1 shortest path over
+    the bridging bits from any input node to the output node, at least one update."""
+    n = len(g.nodes)
+    INF = 1 << 30
+    dist = [INF] * n
+    for v in g.input_nodes():
+        dist[v] = 0
+    for _ in range(n):
+        for e in g.edges:
+            if dist[e.src] + int(e.bridge) < dist[e.dst]:
+                dist[e.dst] = dist[e.src] + int(e.bridge)
+    return max(1, dist[g.out_node])
+
+
 PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_FP32_VALU_TFLOPS = 157.3  # fp32 vector peak (the fp32 graph runs on plain ALUs)
 
@@ -73,7 +95,7 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     torch.cuda.set_device(0)
-    g = W.BENCH_CONFIGS[args.workload]()
+    g = {**W.BENCH_CONFIGS, **W.PAPER_CONFIGS}[args.workload]()
     bits = {"streaming": W.streaming_pattern, "sequential": W.sequential_pattern,
             "hybrid": W.hybrid_pattern}[args.pattern](g)
     g = g.with_pattern(bits)
@@ -120,9 +142,12 @@ def main():
         dev.frame_step([xi[t] for xi in xin])
     dev.synchronize()
     kind_ms = {}
-    reps = min(T, 12)
+    frame_ms = []
+    reps = max(min(T, 12), 32)
     for r in range(reps):
-        for kind, ms in dev.frame_step_timed([xi[1 + (r % T)] for xi in xin]):
+        launches = dev.frame_step_timed([xi[1 + (r % T)] for xi in xin])
+        frame_ms.append(sum(ms for _, ms in launches))
+        for kind, ms in launches:
             kind_ms.setdefault(kind, []).append(ms)
     conv_flops = 0
     for e in g.edges:
@@ -187,6 +212,11 @@ def main():
                    "nodes": len(g.nodes), "edges": len(g.edges), "inference_factor": info["inference_factor"],
                    "launches_per_frame": info["launches_per_frame"], "hipgraph": not args.no_hipgraph},
         "us_per_frame": round(ms_per_step * 1e3 / T, 2),
+        "frame_latency_us": {"p50": round(float(np.percentile(frame_ms, 50)) * 1e3, 2),
+                             "p99": round(float(np.percentile(frame_ms, 99)) * 1e3, 2), "frames": len(frame_ms),
+                             "how": "single sr_frame_step calls, plain launches, HIP events around every launch"},
+        "response_frames": response_frames(g),
+        "response_us": round(response_frames(g) * ms_per_step * 1e3 / T, 2),
         "gflop_per_frame": round(work["flops_per_frame"] / 1e9, 3),
         "frame_tflops": round(work["flops_per_frame"] * T / (ms_per_step * 1e-3) / 1e12, 2),
         "roofline": roofline,

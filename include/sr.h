@@ -91,7 +91,8 @@ typedef enum {
   SR_OPT_FRAMES_PER_GRAPH = 2, /* number of frames captured into one HIP graph for sr_rollout (default 8, >= 1) */
   SR_OPT_K_SPLIT = 3,          /* 1 (default): long tiles are cut along the contraction and reduced by the last part; 0: never */
   SR_OPT_TILE_KERNEL = 4       /* tile kernel of bf16 graphs: 1 = 4 waves per workgroup, weights from registers;
-                                  2 = 8 waves, both operands through LDS, next stage loaded during the current one */
+                                  2 = 8 waves, both operands through LDS, next stage loaded during the current one;
+                                  0 (default) = 1 unless a node's source patches do not fit its LDS budget, then 2 */
 } sr_option;
 
 /* ---------------------------------------------------------------------------

@@ -196,7 +196,7 @@ struct sr_graph {
   int32_t* split_counters = nullptr;
   int n_split_slots = 0;
   bool allow_split = true;
-  int tile_version = 1;       // 1: 4-wave tile kernel, 2: 8-wave tile kernel (both operands through LDS)
+  int tile_version = 0;       // 1: 4-wave tile kernel, 2: 8-wave tile kernel (both operands through LDS); 0: choose
   SrHead* heads = nullptr;
   SrHeadEdge* head_edges = nullptr;
   void* zero_page = nullptr;
@@ -373,6 +373,32 @@ void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows&
   }
 }
 
+// Does the 4-wave tile kernel have a tile shape for node v whose source patches fit its LDS budget?
+bool four_wave_kernel_fits(const sr_graph* g, int v, int lds_cap) {
+  const NodeRt& n = g->nodes[v];
+  const int Cout = n.d.channels;
+  for (int wt : {2, 1})
+    for (int wn : {4, 2, 1}) {
+      if (Cout % (32 * wt * wn) != 0) continue;
+      const int BM = 128 * (4 / wn);
+      bool ok = true;
+      for (const EdgeRt& e : g->edges) {
+        if (e.d.dst != v) continue;
+        const NodeRt& sn = g->nodes[e.d.src];
+        const int PW = sn.d.width + 2 * e.d.pad, PWs = (PW + e.d.stride - 1) / e.d.stride, RP = e.d.stride * PWs;
+        const int64_t rows = max_patch_rows(g, v, e, BM);
+        bool fits = false;
+        for (int cand : {64, 32, 16})
+          if (sn.Cp % cand == 0 &&
+              rows * row_pitch16(RP, cand / 8 + 1, e.d.stride, e.d.upsample, n.d.width) * 16 <= lds_cap)
+            fits = true;
+        ok = ok && fits;
+      }
+      if (ok) return true;
+    }
+  return false;
+}
+
 // 8-wave kernel: plan of one (tile, edge, row phase): per 16-byte LDS position of a stage buffer the
 // byte offset of its source.  First the A positions (patch rows = the source rows q = phase
 // (mod stride) of the tile's row range; slots of KC*2 bytes, unpadded; offsets from (image b0,
@@ -440,6 +466,15 @@ sr_status finalize(sr_graph* g) {
     if (mfma_eligible(g, v)) n.kind = 1;
     else if (head_ok) n.kind = 3;
     else n.kind = 2;
+  }
+
+  // Tile kernel: the 4-wave kernel unless one of its nodes would not fit its LDS budget (patches of
+  // edges with a large stride on small images span many images) -- the 8-wave kernel cuts strided
+  // edges into row phases and takes those; a node it cannot take either goes the direct way.
+  if (g->tile_version == 0) {
+    g->tile_version = 1;
+    for (int v = 0; v < g->n_nodes; ++v)
+      if (g->nodes[v].kind == 1 && !four_wave_kernel_fits(g, v, sr_mfma_max_lds_bytes())) g->tile_version = 2;
   }
 
   std::vector<SrStageNode> stage;
@@ -1517,7 +1552,7 @@ sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value) {
     case SR_OPT_FORCE_DIRECT: g->force_direct = value != 0; return SR_OK;
     case SR_OPT_K_SPLIT: g->allow_split = value != 0; return SR_OK;
     case SR_OPT_TILE_KERNEL:
-      if (value != 1 && value != 2) return gfail(g, SR_ERR_ARG, "tile kernel must be 1 or 2");
+      if (value < 0 || value > 2) return gfail(g, SR_ERR_ARG, "tile kernel must be 0 (choose), 1 or 2");
       g->tile_version = (int)value;
       return SR_OK;
     case SR_OPT_FRAMES_PER_GRAPH:

@@ -147,8 +147,9 @@ __device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, con
 // edge over many pixels, per pixel slab: the slab sums go to `partial` and the item that finishes
 // last for an image adds them in slab order).  For every edge the input vector (pooled means or the
 // flattened source) is put into LDS, then each of the 4 waves multiplies a quarter of it into up to
-// 256 outputs; the quarters are added in wave order, then bias, activation, store and, if this node
-// is being recorded, the rollout output.  smem: SR_HEAD_MAX_K floats, one int, 4*64*4 floats.
+// 256 outputs (with at most 64 outputs: 256 / CO slices of it into CO = 16, 32 or 64 output columns);
+// the parts are added in a fixed order, then bias, activation, store and, if this node is being
+// recorded, the rollout output.  smem: SR_HEAD_MAX_K floats, one int, 4*64*4 floats.
 template <typename T>
 __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, const SrHead& h,
                                              const SrHeadEdge* __restrict__ head_edges, int b, int split,
@@ -158,6 +159,11 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
   float* red = smem + vec_floats + 4;
   const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
   float acc[4] = {0.f, 0.f, 0.f, 0.f};     // outputs lane, lane+64, lane+128, lane+192: this wave's share
+  // up to 64 outputs: CO = 16, 32 or 64 output columns, 256 / CO slices of the input vector
+  const bool narrow = h.Cout <= 64;
+  const int CO = h.Cout <= 16 ? 16 : (h.Cout <= 32 ? 32 : 64);
+  const int n_slices = 256 / CO;
+  const int co_n = threadIdx.x & (CO - 1), slice = threadIdx.x / CO;
   for (int ei = 0; ei < h.edge_count; ++ei) {
     const SrHeadEdge e = head_edges[h.edge_begin + ei];
     const T* src = (const T*)e.src[e.bridge ? (cur ^ 1) : cur] + (size_t)b * e.HW * e.Csp;
@@ -210,20 +216,51 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
       }
     }
     __syncthreads();
-    const int kper = (K + 3) / 4;
-    const int k_lo = part * kper, k_hi = min(K, k_lo + kper);
+    if (narrow) {
+      // few outputs: the threads are arranged (slice of the vector) x (output)
+      const int kper = (K + n_slices - 1) / n_slices;
+      const int k_lo = slice * kper, k_hi = min(K, k_lo + kper);
+      if (co_n < h.Cout) {
+        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;   // four chains keep several weight loads in flight
+        int k = k_lo;
+        for (; k + 4 <= k_hi; k += 4) {
+          a0 += smem[k] * e.w[(size_t)k * h.Cout + co_n];
+          a1 += smem[k + 1] * e.w[(size_t)(k + 1) * h.Cout + co_n];
+          a2 += smem[k + 2] * e.w[(size_t)(k + 2) * h.Cout + co_n];
+          a3 += smem[k + 3] * e.w[(size_t)(k + 3) * h.Cout + co_n];
+        }
+        for (; k < k_hi; ++k) a0 += smem[k] * e.w[(size_t)k * h.Cout + co_n];
+        acc[0] += (a0 + a1) + (a2 + a3);
+      }
+    } else {
+      const int kper = (K + 3) / 4;
+      const int k_lo = part * kper, k_hi = min(K, k_lo + kper);
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int co = lane + 64 * j;
-      if (co < h.Cout)
-        for (int k = k_lo; k < k_hi; ++k) acc[j] += smem[k] * e.w[(size_t)k * h.Cout + co];
+      for (int j = 0; j < 4; ++j) {
+        const int co = lane + 64 * j;
+        if (co < h.Cout)
+          for (int k = k_lo; k < k_hi; ++k) acc[j] += smem[k] * e.w[(size_t)k * h.Cout + co];
+      }
     }
+  }
+  char* rec = h.record ? (char*)ctx->out_ptr : nullptr;
+  T* recp = rec ? (T*)(rec + (int64_t)(ctx->frame - ctx->out_base) * ctx->out_stride) : nullptr;
+  if (narrow) {
+    red[slice * CO + co_n] = acc[0];
+    __syncthreads();
+    for (int co = threadIdx.x; co < h.Cout; co += blockDim.x) {
+      float v = 0.f;
+      for (int sl = 0; sl < n_slices; ++sl) v += red[sl * CO + co];   // slice order: deterministic
+      v += h.bias[co];
+      if (h.act == 1) v = fmaxf(v, 0.f);
+      Store<T>::store((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
+      if (recp) Store<T>::store(recp + (size_t)b * h.Cout + co, v);
+    }
+    return;
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) red[(part * 4 + j) * 64 + lane] = acc[j];
   __syncthreads();
-  char* rec = h.record ? (char*)ctx->out_ptr : nullptr;
-  T* recp = rec ? (T*)(rec + (int64_t)(ctx->frame - ctx->out_base) * ctx->out_stride) : nullptr;
   for (int co = threadIdx.x; co < h.Cout; co += blockDim.x) {
     const int j = co >> 6, l = co & 63;
     float v = h.bias[co] + ((red[(0 * 4 + j) * 64 + l] + red[(1 * 4 + j) * 64 + l]) +

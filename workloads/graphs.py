@@ -305,6 +305,15 @@ BENCH_CONFIGS = {
     "hires_sr": hires_sr,
 }
 
+# the paper's own network shapes (App. A2) with the batch sizes of Tab. A1, as further workloads
+PAPER_CONFIGS = {
+    "mnist_ff": lambda: mnist_net("FF", batch=128, frames=16),
+    "mnist_s": lambda: mnist_net("S", batch=128, frames=16),
+    "mnist_sr": lambda: mnist_net("SR", batch=128, frames=16),
+    **{f"dsr{k}": (lambda k=k: dsr_net(k, batch=64, frames=16)) for k in range(7)},
+    "gtsrb_dsr4": lambda: dsr_net(4, batch=16, frames=16, self_recurrence=False, n_classes=43),
+}
+
 
 def flops_per_frame(g: Graph) -> int:
     """Nominal direct-convolution work of one frame update of the whole batch:
