@@ -221,15 +221,21 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
       const int kper = (K + n_slices - 1) / n_slices;
       const int k_lo = slice * kper, k_hi = min(K, k_lo + kper);
       if (co_n < h.Cout) {
-        float a0 = 0.f, a1 = 0.f, a2 = 0.f, a3 = 0.f;   // four chains keep several weight loads in flight
+        // sixteen independent chains keep sixteen weight loads in flight
+        float a[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) a[u] = 0.f;
         int k = k_lo;
-        for (; k + 4 <= k_hi; k += 4) {
-          a0 += smem[k] * e.w[(size_t)k * h.Cout + co_n];
-          a1 += smem[k + 1] * e.w[(size_t)(k + 1) * h.Cout + co_n];
-          a2 += smem[k + 2] * e.w[(size_t)(k + 2) * h.Cout + co_n];
-          a3 += smem[k + 3] * e.w[(size_t)(k + 3) * h.Cout + co_n];
+        for (; k + 16 <= k_hi; k += 16) {
+          float wv[16];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) wv[u] = e.w[(size_t)(k + u) * h.Cout + co_n];
+#pragma unroll
+          for (int u = 0; u < 16; ++u) a[u] += smem[k + u] * wv[u];
         }
-        for (; k < k_hi; ++k) a0 += smem[k] * e.w[(size_t)k * h.Cout + co_n];
+        for (; k < k_hi; ++k) a[0] += smem[k] * e.w[(size_t)k * h.Cout + co_n];
+        const float a0 = (a[0] + a[1]) + (a[2] + a[3]), a1 = (a[4] + a[5]) + (a[6] + a[7]);
+        const float a2 = (a[8] + a[9]) + (a[10] + a[11]), a3 = (a[12] + a[13]) + (a[14] + a[15]);
         acc[0] += (a0 + a1) + (a2 + a3);
       }
     } else {
