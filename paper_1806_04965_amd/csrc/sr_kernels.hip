@@ -126,7 +126,27 @@ __device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, con
   T* out = (T*)nd.state[frame & 1];
   const int end = min(nd.elems_px, (chunk + 1) * SR_STAGE_CHUNK);
   constexpr int V = 16 / sizeof(T);
-  if ((nd.Cp % V) == 0) {
+  if ((nd.Cp == V || nd.Cp == 2 * V) && nd.C <= V && blockDim.x * 4 == SR_STAGE_CHUNK) {
+    // few channels (an image): one 16-byte piece of data per pixel (and one of zeros if the pitch is two),
+    // four pixels per thread, all loads first
+    const int p0 = chunk * SR_STAGE_CHUNK + threadIdx.x;
+    T v[4][V];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = min(p0 + j * (int)blockDim.x, nd.elems_px - 1);
+      const T* ip = in + (size_t)p * nd.C;
+#pragma unroll
+      for (int i = 0; i < V; ++i) v[j][i] = (i < nd.C) ? ip[i] : (T)0;
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int p = p0 + j * (int)blockDim.x;
+      if (p < end) {
+        *(u32x4_t*)(out + (size_t)p * nd.Cp) = *(const u32x4_t*)v[j];
+        if (nd.Cp == 2 * V) *(u32x4_t*)(out + (size_t)p * nd.Cp + V) = u32x4_t{0u, 0u, 0u, 0u};
+      }
+    }
+  } else if ((nd.Cp % V) == 0) {
     for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += blockDim.x) {
       const T* ip = in + (size_t)p * nd.C;
       for (int c0 = 0; c0 < nd.Cp; c0 += V) {
@@ -177,6 +197,15 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
       for (int c = threadIdx.x; c < e.Cin; c += blockDim.x) {
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
         int p = p0;
+        for (; p + 12 <= p1; p += 12) {   // twelve loads in flight
+          float v[12];
+#pragma unroll
+          for (int u = 0; u < 12; ++u) v[u] = Store<T>::load(src + (size_t)(p + u) * e.Csp + c);
+          s0 += (v[0] + v[4]) + v[8];
+          s1 += (v[1] + v[5]) + v[9];
+          s2 += (v[2] + v[6]) + v[10];
+          s3 += (v[3] + v[7]) + v[11];
+        }
         for (; p + 4 <= p1; p += 4) {
           s0 += Store<T>::load(src + (size_t)p * e.Csp + c);
           s1 += Store<T>::load(src + (size_t)(p + 1) * e.Csp + c);
