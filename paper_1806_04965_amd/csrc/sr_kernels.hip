@@ -393,10 +393,10 @@ __global__ __launch_bounds__(256) void sr_direct_kernel(SrCtx* __restrict__ ctx,
 // a second workgroup on the same CU computes meanwhile.  LDS slot of padded source pixel
 // (row q relative to the tile's first row, column px), column-phase major for strided edges so
 // that consecutive output pixels read consecutive slots:
-//     slot = q*RP + (px % stride)*PWs + px / stride            KC*2 bytes per slot
-// and inside a slot the 16-byte piece p sits at p ^ ((slot >> SH) & (CH-1)), CH = KC/8 pieces,
-// SH = log2(16/CH): sixteen consecutive slots then cover sixteen different 16-byte columns of
-// the 256-byte LDS row, which is what a conflict-free ds_read_b128 needs.
+//     byte = q*RPB + ((px % stride)*PWs + px / stride)*SP,   SP = KC*2 + 16 bytes per slot.
+// The spare 16-byte piece of every slot (and a row pitch RPB chosen to match) makes sixteen
+// consecutive pixels fall into sixteen different 16-byte columns of the 256-byte LDS row, which
+// is what a conflict-free ds_read_b128 needs.
 //
 // B operand (weights): pre-packed on the host in exactly the per-lane order of the instruction,
 // [tap][k16 block][32-channel tile][lane][8], so a wave's fragment is one coalesced 1 KiB load
