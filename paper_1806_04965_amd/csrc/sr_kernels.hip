@@ -674,18 +674,27 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
     __syncthreads();
     if (!*flag) return;
     const f32x4_t* all = (const f32x4_t*)((const float*)nd->split_scratch + (size_t)split_slot * SR_SPLIT_FLOATS);
+    // part by part (so that all of a part's loads are in flight together), every element summed in
+    // part order
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int nj = 0; nj < WN; ++nj)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
-          for (int p = 0; p < n_parts; ++p)
-            sum += all[(size_t)p * (SR_SPLIT_FLOATS / 4) + ((mi * WN + nj) * 4 + q) * 256 + tid];
+        for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
+    for (int p = 0; p < n_parts; ++p) {
+      const f32x4_t* part = all + (size_t)p * (SR_SPLIT_FLOATS / 4) + tid;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] = sum[i];
-        }
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4_t v = part[((mi * WN + nj) * 4 + q) * 256];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] += v[i];
+          }
+    }
   }
 
   // ---- epilogue: bias, activation, round to bf16, NHWC store.
@@ -1072,18 +1081,27 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
     __syncthreads();
     if (!*flag) return;
     const f32x4_t* all = (const f32x4_t*)((const float*)nd->split_scratch + (size_t)split_slot * SR8_SPLIT_FLOATS);
+    // part by part (so that all of a part's loads are in flight together), every element summed in
+    // part order
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi)
 #pragma unroll
       for (int nj = 0; nj < WN; ++nj)
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4_t sum = {0.f, 0.f, 0.f, 0.f};
-          for (int p = 0; p < n_parts; ++p)
-            sum += all[(size_t)p * (SR8_SPLIT_FLOATS / 4) + ((mi * WN + nj) * 4 + q) * 512 + tid];
+        for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
+    for (int p = 0; p < n_parts; ++p) {
+      const f32x4_t* part = all + (size_t)p * (SR8_SPLIT_FLOATS / 4) + tid;
 #pragma unroll
-          for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] = sum[i];
-        }
+      for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+        for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+          for (int q = 0; q < 4; ++q) {
+            const f32x4_t v = part[((mi * WN + nj) * 4 + q) * 512];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] += v[i];
+          }
+    }
   }
 
   // ---- epilogue: as in the 4-wave kernel (each wave transposes its tile through its own LDS region)
