@@ -111,6 +111,22 @@ def test_tableau_bounds_and_model_parallel_classes_match_paper_and_oracle():
     assert checked > 20
 
 
+def test_analysis_calls_report_errors_as_status_codes():
+    pairs = [(0, 1), (1, 2), (2, 1)]
+    ok = edges_of(pairs)
+    for bad, name in ((lambda: sr.tableau(3, ok, 0), "SR_ERR_ARG"),                       # W < 1
+                      (lambda: sr.tableau(3, edges_of(pairs, [1, 0, 0]), 2), "SR_ERR_ROLLOUT"),   # R=0 cycle
+                      (lambda: sr.tableau(3, edges_of([(1, 2), (2, 1)]), 1), "SR_ERR_GRAPH"),     # no input node
+                      (lambda: sr.equally_model_parallel(3, ok, [1, 1, 2], [1, 1, 1]), "SR_ERR_ARG"),
+                      (lambda: sr.pattern_count_bounds(3, edges_of([(0, 5)])), "SR_ERR_GRAPH"),
+                      (lambda: sr.pattern_count_bounds(26, edges_of([(i, i + 1) for i in range(25)])), "SR_ERR_ARG")):
+        with pytest.raises(sr.SrError) as ei:
+            bad()
+        assert ei.value.name == name
+    # invalid patterns may still be compared for model-parallel equality
+    assert sr.equally_model_parallel(3, ok, [1, 0, 0], [0, 0, 0])
+
+
 def test_benchmark_graph_levels():
     for name, f in W.BENCH_CONFIGS.items():
         g = f()
