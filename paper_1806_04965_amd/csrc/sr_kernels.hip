@@ -790,7 +790,7 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
 // Differences:
 //  * BOTH operands of a stage come from LDS: the source patch (A) and the stage's slab of packed
 //    weights (B) are brought in by direct-to-LDS loads.  No load returns to registers inside the
-//    k-loop, so the loads of the NEXT stage can be issued between the k-steps of the current one
+//    k-loop, so the loads of the NEXT stage can be issued ahead of the current one's k-steps
 //    without ever being waited for there (vector-memory results return in order: a register load
 //    behind a long direct-to-LDS load would stall on it).
 //  * LDS holds two stage buffers; a stage computes out of one while the other is being filled.
@@ -860,8 +860,7 @@ __device__ __forceinline__ void sr8_issue(const SrProd8& P, int it, unsigned cha
 }
 
 // One k-step: 4 x WN MFMAs.  Each A fragment is reloaded for the next step right after its last
-// use; the B fragments of the next step go into the other B buffer.  dps direct-to-LDS
-// instructions of the next stage are issued at the end of the step.
+// use; the B fragments of the next step go into the other B buffer.
 template <int WN>
 __device__ __forceinline__ void sr8_step(const unsigned char* rd, const int (&abase)[4], int bbase, int tapA, int lgK16,
                                          int nbt1024, bf16x8_t (&a)[4], const bf16x8_t (&b)[WN], bf16x8_t (&bn)[WN],
@@ -1030,28 +1029,20 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
     unsigned char* wr = par ? buf0 : buf1;
     const int bbase = a_bytes + ((wn * WN) * 64 + lane) * 16;
     const int nbt1024 = NBT * 1024;
-    // loads of the next stage per k-step
-    const int dps = (dma_n + NS - 1) / NS;
-    int dma_it = 0;
     bf16x8_t a[4], b[2][WN];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) a[mi] = *(const bf16x8_t*)(rd + abase[mi]);
 #pragma unroll
     for (int nj = 0; nj < WN; ++nj) b[0][nj] = *(const bf16x8_t*)(rd + bbase + nj * 1024);
+    // all loads of the next stage go out now, none is waited for before the stage ends (spreading them
+    // over the k-steps measured slightly slower)
+    for (int it = 0; it < dma_n; ++it) sr8_issue(P, it, wr, wave, plan);
     int st = 0;
     for (; st + 2 <= NS; st += 2) {
       sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[0], b[1], acc, st, NS);
-      for (int j = 0; j < dps; ++j, ++dma_it)
-        if (dma_it < dma_n) sr8_issue(P, dma_it, wr, wave, plan);
       sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[1], b[0], acc, st + 1, NS);
-      for (int j = 0; j < dps; ++j, ++dma_it)
-        if (dma_it < dma_n) sr8_issue(P, dma_it, wr, wave, plan);
     }
-    if (st < NS) {
-      sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[0], b[1], acc, st, NS);
-      for (int j = 0; j < dps; ++j, ++dma_it)
-        if (dma_it < dma_n) sr8_issue(P, dma_it, wr, wave, plan);
-    }
+    if (st < NS) sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[0], b[1], acc, st, NS);
     par ^= 1;
   }
 
