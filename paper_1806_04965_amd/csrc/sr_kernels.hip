@@ -273,8 +273,19 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
       for (int j = 0; j < 4; ++j) {
         const int co = lane + 64 * j;
-        if (co < h.Cout)
-          for (int k = k_lo; k < k_hi; ++k) acc[j] += smem[k] * e.w[(size_t)k * h.Cout + co];
+        if (co < h.Cout) {
+          float p8[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};   // eight weight loads in flight
+          int k = k_lo;
+          for (; k + 8 <= k_hi; k += 8) {
+            float wv[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) wv[u] = e.w[(size_t)(k + u) * h.Cout + co];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) p8[u] += smem[k + u] * wv[u];
+          }
+          for (; k < k_hi; ++k) p8[0] += smem[k] * e.w[(size_t)k * h.Cout + co];
+          acc[j] += ((p8[0] + p8[1]) + (p8[2] + p8[3])) + ((p8[4] + p8[5]) + (p8[6] + p8[7]));
+        }
       }
     }
   }
