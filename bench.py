@@ -29,7 +29,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-TRAFFIC_RECORD = os.path.join(ROOT, "profiles", "hbm_traffic_sr_mfma_kernel_gtsrb_sr.json")
 KERNEL_SOURCES = ["sr_kernels.hip", "sr_host.cpp", "sr_internal.h"]
 
 
@@ -39,7 +38,7 @@ def recorded_traffic(workload, pattern):
     the kernel sources have changed since the counters were taken."""
     import hashlib
     try:
-        rec = json.load(open(TRAFFIC_RECORD))
+        rec = json.load(open(os.path.join(ROOT, "profiles", f"hbm_traffic_sr_mfma_kernel_{workload}.json")))
         h = hashlib.sha256()
         for f in KERNEL_SOURCES:
             h.update(open(os.path.join(ROOT, "paper_1806_04965_amd", "csrc", f), "rb").read())
