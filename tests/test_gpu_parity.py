@@ -6,7 +6,8 @@ import pytest
 
 import workloads as W
 from workloads.graphs import Node, Edge, Graph, ACT_IDENTITY, ACT_RELU
-from gpu_util import (gpu_states_by_steps, gpu_rollout, oracle_states, compare_all, max_abs_rel)
+from gpu_util import (gpu_states_by_steps, gpu_rollout, oracle_states, compare_all, max_abs_rel,
+                      to_device as to_device_)
 
 pytestmark = pytest.mark.gpu
 
@@ -246,3 +247,36 @@ def test_eight_wave_tile_kernel_rollout_in_hipgraph_matches_steps():
     ref = oracle_states(g, w, b, x, 5, "bf16", nodes=[g.out_node])
     for t in range(5):
         assert max_abs_rel(a[t], ref[g.out_node][t]) <= TOL["bf16"]
+
+
+def test_two_graphs_alive_interleaved_and_recreated():
+    # Two graphs with K-split nodes live side by side, stepped alternately; then both are destroyed and
+    # created again (the partial-sum scratch of the first pair is handed to the second).  Every
+    # graph's output must match its own single-graph run bit for bit and the oracle within tolerance.
+    import paper_1806_04965_amd as sr
+    ga = W.cifar_sr(batch=4, frames=5)
+    gb = W.gtsrb_sr(batch=2, frames=5)
+    cases = []
+    for g, seed in ((ga, 21), (gb, 22)):
+        w, b, x = W.make_case(g, seed=seed)
+        alone, _, work = gpu_states_by_steps(g, w, b, x, g.frames, nodes=[g.out_node])
+        ref = oracle_states(g, w, b, x, g.frames, "bf16", nodes=[g.out_node])[g.out_node]
+        cases.append((g, w, b, x, alone[g.out_node], ref))
+    for round_ in range(2):
+        devs = []
+        for g, w, b, x, _, _ in cases:
+            d = sr.SrGraph(g)
+            d.set_parameters(w, b)
+            ins = g.input_nodes()
+            xd = {v: to_device_(x[v], g.dtype) for v in ins}
+            d.reset([xd[v][0] for v in ins])
+            devs.append((d, xd, ins))
+        for t in range(1, 6):
+            for (d, xd, ins), (g, _, _, _, alone, ref) in zip(devs, cases):
+                d.frame_step([xd[v][t] for v in ins])
+            for (d, xd, ins), (g, _, _, _, alone, ref) in zip(devs, cases):
+                got = d.get_state(g.out_node).float().cpu().numpy().astype(np.float64)
+                np.testing.assert_array_equal(got, alone[t - 1])
+                assert max_abs_rel(got, ref[t - 1]) <= 2e-2
+        for d, _, _ in devs:
+            d.close()
