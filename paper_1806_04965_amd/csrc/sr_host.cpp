@@ -347,8 +347,15 @@ int row_pitch16(int RP, int CH1, int s, int up, int Wo) {
   return base;
 }
 
+// Positions that nothing reads repeat their predecessor's entry (the first one: zero padding): every
+// lane of a direct-to-LDS instruction then loads something valid and no lane mask is needed.
+void fill_unread_positions(std::vector<int32_t>* out, size_t begin, size_t end) {
+  for (size_t i = begin; i < end; ++i)
+    if ((*out)[i] == -2) (*out)[i] = (i > begin) ? (*out)[i - 1] : -1;
+}
+
 // Direct-to-LDS plan of one (tile, edge): for every 16-byte LDS position the byte offset of its
-// source relative to (image b0, source row iy_first), or ZERO (padding) / SKIP (not written).
+// source relative to (image b0, source row iy_first), or -1 (zero padding).
 void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows& r) {
   const int CH1 = m.KC / 8 + 1, CH = CH1 - 1;
   const int RPB16 = m.RPB / 16;
@@ -371,6 +378,7 @@ void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows&
       }
     }
   }
+  fill_unread_positions(out, 0, out->size());
 }
 
 // Does the 4-wave tile kernel have a tile shape for node v whose source patches fit its LDS budget?
@@ -402,17 +410,17 @@ bool four_wave_kernel_fits(const sr_graph* g, int v, int lds_cap) {
 // 8-wave kernel: plan of one (tile, edge, row phase): per 16-byte LDS position of a stage buffer the
 // byte offset of its source.  First the A positions (patch rows = the source rows q = phase
 // (mod stride) of the tile's row range; slots of KC*2 bytes, unpadded; offsets from (image b0,
-// source row iy_first); -1 zero padding, -2 not written), padded to a multiple of 512; then the B
-// positions ((t * K16 + k) * NBT + nt) * 64 + lane: the packed fragment of the phase's t-th tap,
-// 16-channel block k of the chunk, column tile nt of the tile (offsets from the chunk's first block
-// and the tile's first column tile), padded likewise.
+// source row iy_first); -1 zero padding), rounded up to a multiple of 64; then the B positions
+// ((t * K16 + k) * NBT + nt) * 64 + lane: the packed fragment of the phase's t-th tap, 16-channel
+// block k of the chunk, column tile nt of the tile (offsets from the chunk's first block and the
+// tile's first column tile); the whole padded to a multiple of 512.
 void build_plan8(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows& r, int phase, int NBT) {
   const int CH = m.KC / 8;
   const int RPS = m.RP;
   const int64_t NQ = r.Q1 - r.Q0 + 1;
   const int64_t NQr = (NQ - phase + m.stride - 1) / m.stride;
   const int64_t n_pos = NQr * RPS * CH;
-  const int64_t padded = (n_pos + 511) / 512 * 512;
+  const int64_t padded = (n_pos + 63) / 64 * 64;
   out->assign((size_t)padded, -2);
   const int64_t iy_first = (r.oy0 / m.up) * m.stride - m.pad;
   for (int64_t qr = 0; qr < NQr; ++qr) {
@@ -432,8 +440,9 @@ void build_plan8(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows
   const int K16 = m.KC / 16, k16_total = m.Csp / 16;
   const int tap_rows = (m.kh - phase + m.stride - 1) / m.stride;
   const int64_t n_posB = (int64_t)tap_rows * m.kw * K16 * NBT * 64;
+  fill_unread_positions(out, 0, out->size());
   const size_t b0 = out->size();
-  out->resize(b0 + (size_t)((n_posB + 511) / 512 * 512), -2);
+  out->resize((b0 + (size_t)n_posB + 511) / 512 * 512, 0);
   for (int64_t pb = 0; pb < n_posB; ++pb) {
     const int lane = (int)(pb % 64), nt = (int)(pb / 64 % NBT), k = (int)(pb / (64 * NBT) % K16);
     const int t = (int)(pb / (64 * NBT * K16));
@@ -608,7 +617,8 @@ sr_status finalize(sr_graph* g) {
           m.PWs = (m.PW + m.stride - 1) / m.stride;
           m.RP = m.stride * m.PWs;
           m.wstride8 = (Cout / 32) * 64;
-          if (sn.state_bytes + SR_ZERO_TAIL >= ((size_t)1 << 31) || (size_t)sn.Cp * 2 > SR_ZERO_TAIL) { ok = false; break; }
+          if (sn.state_bytes + SR_ZERO_TAIL + (size_t)(e.d.pad + 1) * sn.d.width * sn.Cp * 2 >= ((size_t)1 << 31) ||
+              (size_t)sn.Cp * 2 > SR_ZERO_TAIL) { ok = false; break; }
           m.src_bytes = (int32_t)sn.state_bytes;
           const int nphase = std::min(m.stride, m.kh);
           const int64_t rows = max_patch_rows(g, v, e, BM, m.PH);
@@ -616,7 +626,7 @@ sr_status finalize(sr_graph* g) {
           const int taps0 = ((m.kh + m.stride - 1) / m.stride) * m.kw;      // ... and the most taps
           int KC = 0;
           for (int cand : {128, 64, 32, 16}) {
-            const int64_t a_bytes = rows0 * m.RP * cand * 2;
+            const int64_t a_bytes = (rows0 * m.RP * cand * 2 + 1023) / 1024 * 1024;
             const int64_t b_bytes = (int64_t)taps0 * (cand / 16) * NBT * 1024;
             if (KC == 0 && sn.Cp % cand == 0 && a_bytes + b_bytes <= SR8_BUF_BYTES) KC = cand;
           }
@@ -759,6 +769,10 @@ sr_status finalize(sr_graph* g) {
           m.PWs = (m.PW + m.stride - 1) / m.stride;
           m.RP = m.stride * m.PWs;
           m.wstride8 = (Cout / 32) * 64;
+          // padding positions read the zero bytes behind the source state, at 32-bit offsets
+          if (sn.state_bytes + SR_ZERO_TAIL + (size_t)(e.d.pad + 1) * sn.d.width * sn.Cp * 2 >= ((size_t)1 << 31) ||
+              (size_t)sn.Cp * 2 > SR_ZERO_TAIL) { ok = false; break; }
+          m.src_bytes = (int32_t)sn.state_bytes;
           const int64_t rows = max_patch_rows(g, v, e, BM);
           int KC = 0;
           for (int cand : {64, 32, 16}) {
@@ -779,7 +793,7 @@ sr_status finalize(sr_graph* g) {
           for (int tap = 0; tap < m.kh * m.kw; ++tap)
             if (((tap * m.magicKW) >> 16) != tap / m.kw) ok = false;
           if (!ok) break;
-          g->lds_bytes = std::max<int>(g->lds_bytes, (int)(rows * m.RPB));
+          g->lds_bytes = std::max<int>(g->lds_bytes, (int)((rows * m.RPB + 1023) / 1024 * 1024));   // whole 1 KiB instructions
           g->lds_bytes = std::max<int>(g->lds_bytes, 4 * 64 * (32 * wn_tiles * 2 + 16));
           ksum += (double)sn.Cp * m.kh * m.kw;
           me.push_back(m);

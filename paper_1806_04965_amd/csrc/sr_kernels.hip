@@ -424,7 +424,7 @@ struct SrEdgeK {
   const unsigned char* src;
   sr_gfrag_ptr wpk;
   int Hs, Ws, Csp, kw, kh, ntaps, stride, lgs, lgup, pad, KC, lgK16, nchunk, PH, PWs, SP, RPB;
-  int magicKW, wstride8, k16_total;
+  int magicKW, wstride8, k16_total, src_bytes;
 };
 
 __device__ __forceinline__ SrEdgeK sr_load_edge(const SrMfmaEdge* edges, int index, int cur) {
@@ -445,6 +445,7 @@ __device__ __forceinline__ SrEdgeK sr_load_edge(const SrMfmaEdge* edges, int ind
   k.PH = p->PH; k.PWs = p->PWs; k.SP = p->SP; k.RPB = p->RPB;
   k.magicKW = p->magicKW; k.wstride8 = p->wstride8;
   k.k16_total = k.Csp >> 4;
+  k.src_bytes = p->src_bytes;
   return k;
 }
 
@@ -453,33 +454,42 @@ __device__ __forceinline__ SrEdgeK sr_load_edge(const SrMfmaEdge* edges, int ind
 // slot at p*16; the last piece of a slot is the spare one.  Which source bytes a position holds
 // does not depend on the channel chunk, so the host tabulates it once per (tile, edge) --
 // identical tables are shared -- as a byte offset from the tile's first source row, or ZERO for
-// padding (read from a zero page) or SKIP for positions that are never written.  A thread keeps
-// its table entries in registers for the whole edge; a stage only adds the chunk's offset.
+// padding.  Positions that are never read (spare pieces, row pitch, the tail of the last
+// kilobyte) repeat their predecessor's entry, so that every lane of every instruction loads and a
+// stage's issue is four instructions per load: no lane masks, no address selects.  ZERO becomes
+// the offset of the zero bytes that follow every state (far enough behind it for any chunk's
+// offset to stay inside them).  A thread keeps its entries in registers for the whole edge; a
+// stage only adds the chunk's offset to the (scalar) base.
 #define SR_DMA_ITEMS 20        // positions per thread: 80 KiB of LDS / 16 bytes / 256 threads
 #define SR_DMA_ZERO (-1)
-#define SR_DMA_SKIP (-2)
+
+__device__ __forceinline__ const unsigned char* sr_uniform_ptr(const unsigned char* p) {
+  const unsigned long long v = (unsigned long long)p;
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return (const unsigned char*)(((unsigned long long)hi << 32) | lo);
+}
 
 __device__ __forceinline__ void sr_dma_plan(const __attribute__((address_space(1))) int* __restrict__ table,
-                                            int n_pos, int tid, int (&off)[SR_DMA_ITEMS]) {
+                                            int n_pos, int tid, int zero_off, int (&off)[SR_DMA_ITEMS]) {
 #pragma unroll
   for (int it = 0; it < SR_DMA_ITEMS; ++it) {
-    off[it] = SR_DMA_SKIP;
-    if (it * 256 < n_pos) off[it] = table[tid + it * 256];   // tables are padded to 256 entries
+    int v = 0;
+    if (it * 256 < n_pos) v = table[tid + it * 256];   // tables are padded to 256 entries
+    off[it] = (v == SR_DMA_ZERO) ? zero_off : v;
   }
 }
 
-__device__ __forceinline__ void sr_stage_dma(const unsigned char* __restrict__ base,
-                                             const unsigned char* __restrict__ zero_page, unsigned char* lds,
-                                             int n_pos, int tid, const int (&off)[SR_DMA_ITEMS]) {
+__device__ __forceinline__ void sr_stage_dma(const unsigned char* __restrict__ base, unsigned char* lds,
+                                             int n_pos, int tid, int (&off)[SR_DMA_ITEMS]) {
   const int wave_pos = SR_UNIFORM(tid & ~63);
+  base = sr_uniform_ptr(base);
 #pragma unroll
   for (int it = 0; it < SR_DMA_ITEMS; ++it) {
     const int P0 = wave_pos + it * 256;     // first position of this wave's 1 KiB piece
     if (P0 < n_pos) {
-      const unsigned char* g = (off[it] == SR_DMA_ZERO) ? zero_page : base + off[it];
-      if (off[it] != SR_DMA_SKIP)
-        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)g,
-                                         (__attribute__((address_space(3))) void*)(lds + (size_t)P0 * 16), 16, 0, 0);
+      asm volatile("" : "+v"(off[it]));   // keeps the offset 32-bit: scalar base + 32-bit lane offset addressing
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (unsigned)off[it]),
+                                       (__attribute__((address_space(3))) void*)(lds + (size_t)P0 * 16), 16, 0, 0);
     }
   }
 }
@@ -586,7 +596,6 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
   const int ntile0 = wave_n0 >> 5;
   const int b_first = m_first / HoWo, oy_first = (m_first - b_first * HoWo) / Wo;
   const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / Wo;
-  const unsigned char* zero_page = (const unsigned char*)nd->zero_page;
   const int edge_begin = nd->edge_begin, edge_count = nd->edge_count;
   const __attribute__((address_space(4))) int* plan_index =
       (const __attribute__((address_space(4))) int*)(unsigned long long)nd->plan_index + plan_begin;
@@ -624,9 +633,10 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
     const int Q1 = b_last * e.PH + ((oy_last >> e.lgup) << e.lgs) + e.kh - 1;
     const int n_pos = (Q1 - Q0 + 1) * (e.RPB >> 4);
     int dma_off[SR_DMA_ITEMS];
-    sr_dma_plan(plan_tables + plan_index[ei], n_pos, tid, dma_off);
     // plan offsets count from source row (row_first - pad) of image b_first
-    const unsigned char* dma_base = e.src + ((long long)(b_first * e.Hs + row_first - e.pad) * e.Ws) * e.Csp * 2;
+    const long long base_off = ((long long)(b_first * e.Hs + row_first - e.pad) * e.Ws) * e.Csp * 2;
+    const unsigned char* dma_base = e.src + base_off;
+    sr_dma_plan(plan_tables + plan_index[ei], n_pos, tid, (int)((long long)e.src_bytes - base_off), dma_off);
     // LDS byte address of the tap (0,0), k = 0 fragment of this lane's 4 rows
     int abase[4];
 #pragma unroll
@@ -649,7 +659,7 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
         for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[boff + nj * 64];
       }
-      sr_stage_dma(dma_base + (size_t)chunk * e.KC * 2, zero_page, lds, n_pos, tid, dma_off);
+      sr_stage_dma(dma_base + (size_t)chunk * e.KC * 2, lds, n_pos, tid, dma_off);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
       __syncthreads();                                     // ... and everybody else's
       sr_stage_compute<WN>(e, taps, lds, abase, wchunk, bq, acc, NS);
@@ -811,10 +821,10 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
 //    patch of a strided edge as small as that of a stride-1 edge.
 //  * Patch slots are KC*2 bytes without padding (sixteen consecutive pixels of a 32-byte slot then
 //    hit every LDS column twice; measured, the 2-way conflict costs nothing here).
-// LDS layout of a stage buffer: [A: NQr rows x RPB bytes][B: NS x NBT fragments of 1 KiB], NS =
-// taps of the phase x K16 k-steps, NBT = BN/32 column tiles; B fragment (st, nt) is the packed
-// fragment of tap(st), 16-channel block k(st), column tile n0/32 + nt.
-#define SR8_PLAN_ITEMS 12   // direct-to-LDS instructions of a stage: 80 KiB / 8 KiB, A and B each rounded up
+// LDS layout of a stage buffer: [A: NQr rows x RPB bytes, rounded up to 1 KiB][B: NS x NBT
+// fragments of 1 KiB], NS = taps of the phase x K16 k-steps, NBT = BN/32 column tiles; B fragment
+// (st, nt) is the packed fragment of tap(st), 16-channel block k(st), column tile n0/32 + nt.
+#define SR8_PLAN_ITEMS 10   // direct-to-LDS instructions of a stage: 80 KiB / 8 KiB
 
 struct SrEdge8 {   // wave-uniform copy of an edge descriptor (scalar registers)
   const unsigned char* src;
@@ -845,29 +855,35 @@ __device__ __forceinline__ SrEdge8 sr8_load_edge(const SrMfmaEdge* edges, int in
   return k;
 }
 
-// What the direct-to-LDS loads of one stage need (wave-uniform).  Instruction `it` of a stage
-// moves 512 consecutive 16-byte positions, 64 per wave: the A ones first, then the B ones.  Every
-// thread holds, per instruction, the byte offset of its position's source from a_base (A) or
-// b_base (B) -- or SKIP for positions that are not written.
+// What the direct-to-LDS loads of one stage need (wave-uniform).  The buffer is an array of 16-byte
+// positions, A's first (rounded up to a multiple of 64) and B's behind them; instruction `it` of a
+// stage moves 512 consecutive positions, 64 per wave, so one wave's instruction is all A or all B.
+// Every thread holds, per instruction, the byte offset of its position's source from a_base (A) or
+// b_base (B); positions that are never read repeat a neighbour's offset (no lane masks).
 struct SrProd8 {
   const unsigned char* a_base;   // source state: the byte that offset 0 stands for, this chunk
   const unsigned char* b_base;   // packed weights: this chunk's first 16-channel block, tile's first column tile
   int a_step, b_step;            // bytes from one chunk to the next
-  int nA_it, n_it;
+  int n_posA, n_pos;             // A positions (rounded); all positions
   int a_bytes;                   // LDS bytes of A; B follows
   int NS;                        // k-steps of the stage
   int lgK16;
 };
 
-__device__ __forceinline__ void sr8_issue(const SrProd8& P, int it, unsigned char* buf, int wave,
-                                          const int (&plan)[SR8_PLAN_ITEMS]) {
-  const int off = plan[it];
-  const bool is_a = it < P.nA_it;
-  const unsigned char* base = is_a ? P.a_base : P.b_base;
-  const int dst = (is_a ? it * 8192 : P.a_bytes + (it - P.nA_it) * 8192) + wave * 1024;
-  if (off != SR_DMA_SKIP)
-    __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (unsigned)off),
-                                     (__attribute__((address_space(3))) void*)(buf + dst), 16, 0, 0);
+// all of this wave's loads of a stage: per load a compare and branch, a base select, the LDS address, the load
+__device__ __forceinline__ void sr8_issue_stage(const SrProd8& P, unsigned char* buf, int wave,
+                                                const int (&plan)[SR8_PLAN_ITEMS]) {
+  const unsigned char* a_base = sr_uniform_ptr(P.a_base);
+  const unsigned char* b_base = sr_uniform_ptr(P.b_base);
+#pragma unroll
+  for (int it = 0; it < SR8_PLAN_ITEMS; ++it) {
+    const int pos = it * 512 + wave * 64;
+    if (pos < P.n_pos) {
+      const unsigned char* base = (pos < P.n_posA) ? a_base : b_base;
+      __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (unsigned)plan[it]),
+                                       (__attribute__((address_space(3))) void*)(buf + pos * 16), 16, 0, 0);
+    }
+  }
 }
 
 // One k-step: 4 x WN MFMAs.  Each A fragment is reloaded for the next step right after its last
@@ -930,7 +946,6 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
   const int lgNBT64 = (NBT == 1) ? 6 : (NBT == 2 ? 7 : 8);
   const int b_first = m_first / HoWo, oy_first = (m_first - b_first * HoWo) / Wo;
   const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / Wo;
-  const unsigned char* zero_page = (const unsigned char*)nd->zero_page;
   const __attribute__((address_space(4))) int* plan_index =
       (const __attribute__((address_space(4))) int*)(unsigned long long)nd->plan_index + plan_begin;
   const __attribute__((address_space(1))) int* plan_tables =
@@ -979,13 +994,11 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
     const int Q0 = b_first * e.PH + row_first;
     const int Q1 = b_last * e.PH + ((oy_last >> e.lgup) << e.lgs) + e.kh - 1;
     const int NQr = (Q1 - Q0 + 1 - s_phase + e.stride - 1) >> e.lgs;  // patch rows of this phase
-    const int n_posA = NQr * (e.RPB >> 4);
+    P.n_posA = (NQr * (e.RPB >> 4) + 63) & ~63;
     P.NS = ntaps << e.lgK16;
     P.lgK16 = e.lgK16;
-    P.a_bytes = n_posA << 4;
-    P.nA_it = (n_posA + 511) >> 9;
-    const int n_posB = P.NS << lgNBT64;
-    P.n_it = P.nA_it + ((n_posB + 511) >> 9);
+    P.a_bytes = P.n_posA << 4;
+    P.n_pos = P.n_posA + (P.NS << lgNBT64);
     P.a_step = e.KC * 2;
     P.b_step = (e.wstride8 << e.lgK16) * 16;
     const long long base_off = ((long long)(b_first * e.Hs + row_first - e.pad) * e.Ws) * e.Csp * 2;
@@ -997,10 +1010,9 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
     const __attribute__((address_space(1))) int* table = plan_tables + plan_index[e.plan_slot + s_phase];
 #pragma unroll
     for (int it = 0; it < SR8_PLAN_ITEMS; ++it) {
-      int v = SR_DMA_SKIP;
-      if (it < P.n_it) v = table[tid + it * 512];   // A then B entries, each padded to 512
-      if (v == SR_DMA_ZERO) v = zero_off;
-      plan[it] = v;
+      int v = 0;
+      if (it * 512 < P.n_pos) v = table[tid + it * 512];   // A then B entries, padded to 512 at the end
+      plan[it] = (v == SR_DMA_ZERO) ? zero_off : v;
     }
     // A tap table of the phase, one tap per lane: t-th tap = (ti, tj) = (phase + (t / kw) * stride, t % kw)
     {
@@ -1021,7 +1033,7 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
   unsigned char* buf1 = lds + SR8_BUF_BYTES;
   // first stage: all its loads at once
   prepare(stage_begin);
-  for (int it = 0; it < P.n_it; ++it) sr8_issue(P, it, buf0, wave, plan);
+  sr8_issue_stage(P, buf0, wave, plan);
 
   int par = 0;
   for (int c = stage_begin; c < stage_end; ++c) {
@@ -1032,8 +1044,8 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) abase[mi] = abase_n[mi];
     // the producer moves on to the next stage (its plan loads overlap the wait below)
-    int dma_n = 0;
-    if (c + 1 < stage_end) { prepare(c + 1); dma_n = P.n_it; }
+    const bool more = c + 1 < stage_end;
+    if (more) prepare(c + 1);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's loads of stage c have landed
     __syncthreads();                                     // ... everybody's; and stage c-1 has been read by all
     const unsigned char* rd = par ? buf1 : buf0;
@@ -1045,15 +1057,18 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
     for (int mi = 0; mi < 4; ++mi) a[mi] = *(const bf16x8_t*)(rd + abase[mi]);
 #pragma unroll
     for (int nj = 0; nj < WN; ++nj) b[0][nj] = *(const bf16x8_t*)(rd + bbase + nj * 1024);
-    // all loads of the next stage go out now, none is waited for before the stage ends (spreading them
-    // over the k-steps measured slightly slower)
-    for (int it = 0; it < dma_n; ++it) sr8_issue(P, it, wr, wave, plan);
-    int st = 0;
-    for (; st + 2 <= NS; st += 2) {
+    // The loads of the next stage are issued inside this stage's k-steps, one wave at a time: the
+    // vector-memory unit takes a direct-to-LDS instruction every ~30 cycles and a wave issuing into a
+    // full queue waits, which then costs the issuing wave only while the other wave of its SIMD
+    // keeps the matrix pipe busy.  Wave w takes its turn before k-step w*NSI/8 (rounded down to an
+    // even step), NSI = the stage's steps less the last three, which leave the loads time to land.
+    // (Preparing the next stage there as well, instead of ahead of the barrier, measured slower.)
+    const int my_step = more ? ((wave * max(NS - 3, 1)) >> 3) & ~1 : -1;
+    for (int st = 0; st < NS; st += 2) {
+      if (st == my_step) sr8_issue_stage(P, wr, wave, plan);
       sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[0], b[1], acc, st, NS);
-      sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[1], b[0], acc, st + 1, NS);
+      if (st + 1 < NS) sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[1], b[0], acc, st + 1, NS);
     }
-    if (st < NS) sr8_step<WN>(rd, abase, bbase, tapA, lgK16, nbt1024, a, b[0], b[1], acc, st, NS);
     par ^= 1;
   }
 
