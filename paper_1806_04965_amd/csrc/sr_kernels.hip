@@ -662,7 +662,9 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       sr_stage_dma(dma_base + (size_t)chunk * e.KC * 2, lds, n_pos, tid, dma_off);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
       __syncthreads();                                     // ... and everybody else's
+      __builtin_amdgcn_s_setprio(3);   // k-steps go ahead of the other workgroup's set-up and issue on this SIMD
       sr_stage_compute<WN>(e, taps, lds, abase, wchunk, bq, acc, NS);
+      __builtin_amdgcn_s_setprio(0);
     }
   }
 
