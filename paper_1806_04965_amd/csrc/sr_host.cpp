@@ -199,7 +199,6 @@ struct sr_graph {
   int tile_version = 0;       // 1: 4-wave tile kernel, 2: 8-wave tile kernel (both operands through LDS); 0: choose
   SrHead* heads = nullptr;
   SrHeadEdge* head_edges = nullptr;
-  void* zero_page = nullptr;
   int lds_bytes = 0;
   int64_t n_mfma_tiles = 0;
   double flops = 0;
@@ -589,7 +588,6 @@ sr_status finalize(sr_graph* g) {
         node.waves_m = waves_m;
         node.waves_n = wn;
         node.wn_tiles = wt;
-        node.zero_page = g->zero_page;
         node.stage0 = (int)stage8.size();
         ok = ((int64_t)BM / ((int64_t)n.d.height * n.d.width) + 2 <= 127);
         plan_slots = 0; n_stages = 0;
@@ -745,7 +743,6 @@ sr_status finalize(sr_graph* g) {
         node.waves_m = waves_m;
         node.waves_n = waves_n;
         node.wn_tiles = wn_tiles;
-        node.zero_page = g->zero_page;
         ksum = 0;
         ok = true;
         for (EdgeRt& e : g->edges) {
@@ -1483,7 +1480,7 @@ sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_e
   for (int v = 0; v < n_nodes; ++v) {
     NodeRt& n = g->nodes[v];
     for (int p = 0; p < 2; ++p) {
-      // a zero tail follows every copy (the 8-wave tile kernel loads padding pixels from there)
+      // a zero tail follows every copy (the tile kernels' direct-to-LDS loads read padding pixels from there)
       if ((st = dev_alloc(g, &n.state[p], n.state_bytes + SR_ZERO_TAIL)) != SR_OK) return bail(st);
       hipError_t he = sr_launch_fill_zero(g->stream, n.state[p], n.state_bytes + SR_ZERO_TAIL);
       if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
@@ -1492,11 +1489,6 @@ sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_e
     if ((st = dev_alloc(g, &b, n.Cp * sizeof(float))) != SR_OK) return bail(st);
     n.bias_dev = (float*)b;
     hipError_t he = sr_launch_fill_zero(g->stream, b, n.Cp * sizeof(float));
-    if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
-  }
-  if ((st = dev_alloc(g, &g->zero_page, 256)) != SR_OK) return bail(st);
-  {
-    hipError_t he = sr_launch_fill_zero(g->stream, g->zero_page, 256);
     if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
   }
   void* c = nullptr;

@@ -85,9 +85,8 @@ struct SrStage8 {
 struct SrMfmaNode {
   void* out[2];          // bf16 state [M][Cp]
   const float* bias;     // [Cout]
-  const void* zero_page; // 256 zero bytes: source of padding pixels for the direct-to-LDS loads
   const int32_t* plan_index;   // [tile.plan_begin + edge]: offset of that (tile, edge) plan in plan_tables
-  const int32_t* plan_tables;  // per LDS position: source byte offset, -1 zero page, -2 not written
+  const int32_t* plan_tables;  // per LDS position: source byte offset, or -1: padding (reads the zero tail of the state)
   float* split_scratch;        // [slot][16*4*2 registers][256 threads] accumulators of K-split parts
   int32_t* split_counters;     // [slot] parts finished (returns to 0)
   int32_t M;             // B*Ho*Wo
