@@ -1061,7 +1061,7 @@ sr_status finalize(sr_graph* g) {
   for (int L = 1; L <= F; ++L) {
     const LevelPlan& lp = g->levels[L];
     const bool has_tiles = lp.n_tiles > 0, has_blocks = lp.n_blocks > 0;
-    const bool aux_ride = has_tiles && g->tile_version != 2;   // the 4-wave tile kernel takes the auxiliary items along
+    const bool aux_ride = has_tiles;   // the tile kernels take the auxiliary items along
     launches += has_tiles + (has_blocks || (!aux_ride && lp.n_aux > 0));
   }
   g->launches_per_frame = launches;
@@ -1117,7 +1117,7 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
   for (int L = 1; L <= g->an.factor; ++L) {
     const LevelPlan& lp = g->levels[L];
     const bool has_tiles = lp.n_tiles > 0;
-    const bool aux_ride = has_tiles && g->tile_version != 2;
+    const bool aux_ride = has_tiles;
     const bool direct_launch = lp.n_blocks > 0 || (!aux_ride && lp.n_aux > 0);
     if (has_tiles || direct_launch) { last_level = L; last_is_direct = direct_launch; }
   }
@@ -1129,13 +1129,15 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
   for (int L = 1; L <= g->an.factor; ++L) {
     const LevelPlan& lp = g->levels[L];
     const bool has_tiles = lp.n_tiles > 0;
-    const bool aux_ride = has_tiles && g->tile_version != 2;
+    const bool aux_ride = has_tiles;
     const bool direct_launch = lp.n_blocks > 0 || (!aux_ride && lp.n_aux > 0);
     if (has_tiles) {
       const int is_last = (!copy_out && L == last_level && !last_is_direct) ? 1 : 0;
       SR_HIP(g, mark(1));
       if (g->tile_version == 2)
-        SR_HIP(g, sr_launch_mfma8(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, is_last));
+        SR_HIP(g, sr_launch_mfma8(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles,
+                                  g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes,
+                                  g->aux_smem_bytes, is_last));
       else
         SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes,
                                  g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes,

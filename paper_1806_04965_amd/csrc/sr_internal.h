@@ -150,6 +150,7 @@ struct SrStageNode {
 #define SR_AUX_HEAD 1        // a = head index, b = image, c = pixel slab
 #define SR_AUX_STAGE 2       // a = input node index (in stage order), b = chunk of SR_STAGE_CHUNK pixels
 #define SR_STAGE_CHUNK 1024
+#define SR_AUX_THREADS 256   // threads that work on an auxiliary item: a whole workgroup, or the first 256 of an 8-wave one
 struct SrAux {
   int32_t kind, a, b, c;
 };
@@ -174,7 +175,8 @@ hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, co
                           int aux_smem_bytes, int is_last);
 int sr_mfma_max_lds_bytes();
 hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
-                           const SrMfmaTile* tiles, int n_tiles, int is_last);
+                           const SrMfmaTile* tiles, int n_tiles, const SrAux* aux, int n_aux, const SrHead* heads,
+                           const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last);
 // 8-wave kernel: bytes of one of its two stage buffers, and floats of one part's K-split slab
 #define SR8_BUF_BYTES (80 * 1024)
 #define SR_ZERO_TAIL 2048   // zero bytes behind every state copy: where padding pixels are loaded from

@@ -126,28 +126,28 @@ __device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, con
   T* out = (T*)nd.state[frame & 1];
   const int end = min(nd.elems_px, (chunk + 1) * SR_STAGE_CHUNK);
   constexpr int V = 16 / sizeof(T);
-  if ((nd.Cp == V || nd.Cp == 2 * V) && nd.C <= V && blockDim.x * 4 == SR_STAGE_CHUNK) {
+  if ((nd.Cp == V || nd.Cp == 2 * V) && nd.C <= V && SR_AUX_THREADS * 4 == SR_STAGE_CHUNK) {
     // few channels (an image): one 16-byte piece of data per pixel (and one of zeros if the pitch is two),
     // four pixels per thread, all loads first
     const int p0 = chunk * SR_STAGE_CHUNK + threadIdx.x;
     T v[4][V];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int p = min(p0 + j * (int)blockDim.x, nd.elems_px - 1);
+      const int p = min(p0 + j * SR_AUX_THREADS, nd.elems_px - 1);
       const T* ip = in + (size_t)p * nd.C;
 #pragma unroll
       for (int i = 0; i < V; ++i) v[j][i] = (i < nd.C) ? ip[i] : (T)0;
     }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
-      const int p = p0 + j * (int)blockDim.x;
+      const int p = p0 + j * SR_AUX_THREADS;
       if (p < end) {
         *(u32x4_t*)(out + (size_t)p * nd.Cp) = *(const u32x4_t*)v[j];
         if (nd.Cp == 2 * V) *(u32x4_t*)(out + (size_t)p * nd.Cp + V) = u32x4_t{0u, 0u, 0u, 0u};
       }
     }
   } else if ((nd.Cp % V) == 0) {
-    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += blockDim.x) {
+    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += SR_AUX_THREADS) {
       const T* ip = in + (size_t)p * nd.C;
       for (int c0 = 0; c0 < nd.Cp; c0 += V) {
         T v[V];
@@ -157,7 +157,7 @@ __device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, con
       }
     }
   } else {
-    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += blockDim.x)
+    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += SR_AUX_THREADS)
       for (int c = 0; c < nd.Cp; ++c) out[(size_t)p * nd.Cp + c] = (c < nd.C) ? in[(size_t)p * nd.C + c] : (T)0;
   }
 }
@@ -194,7 +194,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
       const int per = (e.HW + h.splits - 1) / h.splits;
       const int p0 = split * per, p1 = min(e.HW, p0 + per);
       const float inv = 1.0f / (float)e.HW;
-      for (int c = threadIdx.x; c < e.Cin; c += blockDim.x) {
+      for (int c = threadIdx.x; c < e.Cin; c += SR_AUX_THREADS) {
         float s0 = 0.f, s1 = 0.f, s2 = 0.f, s3 = 0.f;
         int p = p0;
         for (; p + 12 <= p1; p += 12) {   // twelve loads in flight
@@ -229,7 +229,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
         }
         __syncthreads();
         if (!*flag) return;
-        for (int c = threadIdx.x; c < e.Cin; c += blockDim.x) {
+        for (int c = threadIdx.x; c < e.Cin; c += SR_AUX_THREADS) {
           float sum = 0.f;
           for (int s = 0; s < h.splits; ++s)
             sum += __hip_atomic_load(&h.partial[((size_t)b * h.splits + s) * e.Cin + c], __ATOMIC_RELAXED,
@@ -239,7 +239,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
       }
     } else {
       K = e.HW * e.Cin;
-      for (int k = threadIdx.x; k < K; k += blockDim.x) {
+      for (int k = threadIdx.x; k < K; k += SR_AUX_THREADS) {
         const int p = k / e.Cin, c = k - p * e.Cin;
         smem[k] = Store<T>::load(src + (size_t)p * e.Csp + c);
       }
@@ -294,7 +294,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
   if (narrow) {
     red[slice * CO + co_n] = acc[0];
     __syncthreads();
-    for (int co = threadIdx.x; co < h.Cout; co += blockDim.x) {
+    for (int co = threadIdx.x; co < h.Cout; co += SR_AUX_THREADS) {
       float v = 0.f;
       for (int sl = 0; sl < n_slices; ++sl) v += red[sl * CO + co];   // slice order: deterministic
       v += h.bias[co];
@@ -307,7 +307,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
   for (int j = 0; j < 4; ++j) red[(part * 4 + j) * 64 + lane] = acc[j];
   __syncthreads();
-  for (int co = threadIdx.x; co < h.Cout; co += blockDim.x) {
+  for (int co = threadIdx.x; co < h.Cout; co += SR_AUX_THREADS) {
     const int j = co >> 6, l = co & 63;
     float v = h.bias[co] + ((red[(0 * 4 + j) * 64 + l] + red[(1 * 4 + j) * 64 + l]) +
                             (red[(2 * 4 + j) * 64 + l] + red[(3 * 4 + j) * 64 + l]));
@@ -1173,9 +1173,24 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
 
 __global__ __launch_bounds__(512) void sr_mfma8_kernel(SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
                                                        const SrMfmaEdge* __restrict__ edges,
-                                                       const SrMfmaTile* __restrict__ tiles, int is_last) {
+                                                       const SrMfmaTile* __restrict__ tiles, int n_tiles,
+                                                       const SrAux* __restrict__ aux, int n_aux, int aux_at,
+                                                       const SrHead* __restrict__ heads,
+                                                       const SrHeadEdge* __restrict__ head_edges,
+                                                       const SrStageNode* __restrict__ stage_nodes, int vec_floats,
+                                                       int is_last) {
   extern __shared__ __align__(16) unsigned char sr_lds8[];
-  const SrMfmaTile t = tiles[blockIdx.x];
+  // work list as in the 4-wave kernel: the auxiliary items are spliced in at position aux_at.  An
+  // auxiliary item is written for 256 threads: the upper four waves of the workgroup leave (a
+  // barrier only waits for the waves that are still there).
+  const int item = blockIdx.x;
+  if (item >= aux_at && item < aux_at + n_aux) {
+    if (threadIdx.x >= SR_AUX_THREADS) return;
+    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds8, vec_floats);
+    if (is_last) sr_block_done(ctx, gridDim.x);
+    return;
+  }
+  const SrMfmaTile t = tiles[item < aux_at ? item : item - n_aux];
   const int node_index = SR_UNIFORM(t.node);
   if (node_index < 0) {
     // empty slot
@@ -1291,8 +1306,9 @@ hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, co
 }
 
 hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
-                           const SrMfmaTile* tiles, int n_tiles, int is_last) {
-  if (n_tiles == 0) return hipSuccess;
+                           const SrMfmaTile* tiles, int n_tiles, const SrAux* aux, int n_aux, const SrHead* heads,
+                           const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last) {
+  if (n_tiles + n_aux == 0) return hipSuccess;
   static bool attr_set = false;
   if (!attr_set) {   // dynamic LDS above 64 KiB has to be requested once
     hipError_t e = hipFuncSetAttribute((const void*)sr_mfma8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
@@ -1300,7 +1316,8 @@ hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, c
     if (e != hipSuccess) return e;
     attr_set = true;
   }
-  hipLaunchKernelGGL(sr_mfma8_kernel, dim3(n_tiles), dim3(512), 2 * SR8_BUF_BYTES, s, ctx, nodes, edges, tiles, is_last);
+  hipLaunchKernelGGL(sr_mfma8_kernel, dim3(n_tiles + n_aux), dim3(512), 2 * SR8_BUF_BYTES, s, ctx, nodes, edges, tiles, n_tiles,
+                     aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last);
   return hipGetLastError();
 }
 
