@@ -163,7 +163,8 @@ def main():
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
                     "traffic": recorded_traffic(args.workload, args.pattern),
-                    "kernel": "sr_mfma_kernel", "launch_ms": round(mfma_launch_ms, 4),
+                    "kernel": "sr_mfma8_kernel" if dev.tile_kernel() == 2 else "sr_mfma_kernel",
+                    "launch_ms": round(mfma_launch_ms, 4),
                     "launches_per_frame": launches_per_frame, "flop_per_frame": conv_flops}
         del per_frame
     else:

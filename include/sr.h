@@ -218,6 +218,11 @@ sr_status sr_frame_step_timed(sr_graph* g, const void* const* inputs_t, float* k
 sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfma_tiles,
                         int64_t* device_bytes);
 
+/* Which tile kernel the graph's MFMA nodes run on (what SR_OPT_TILE_KERNEL = 0 chose, Eq. 2 hot
+ * path): 1 = 4 waves per workgroup, 2 = 8 waves; 0 if the graph has no MFMA node (fp32 graphs,
+ * SR_OPT_FORCE_DIRECT).  Plans the graph if that has not happened yet, as sr_graph_work does. */
+sr_status sr_graph_tile_kernel(const sr_graph* g, int32_t* tile_kernel);
+
 void sr_graph_destroy(sr_graph* g);
 
 const char* sr_status_str(sr_status s);

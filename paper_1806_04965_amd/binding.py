@@ -17,7 +17,7 @@ EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_mo
            "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
            "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
-           "sr_graph_work", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
+           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
 
 
 class NodeDesc(C.Structure):
@@ -196,6 +196,11 @@ class SrGraph:
         fl, t, b = C.c_double(), C.c_int64(), C.c_int64()
         _check(self.lib, self.lib.sr_graph_work(self.h, C.byref(fl), C.byref(t), C.byref(b)), self.h)
         return {"flops_per_frame": fl.value, "mfma_tiles": t.value, "device_bytes": b.value}
+
+    def tile_kernel(self):
+        k = C.c_int32()
+        _check(self.lib, self.lib.sr_graph_tile_kernel(self.h, C.byref(k)), self.h)
+        return k.value
 
     # -- frames -----------------------------------------------------------
     def _ptrs(self, tensors):

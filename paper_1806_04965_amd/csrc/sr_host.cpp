@@ -1706,6 +1706,14 @@ sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfm
   return SR_OK;
 }
 
+sr_status sr_graph_tile_kernel(const sr_graph* g, int32_t* tile_kernel) {
+  if (!g || !tile_kernel) return fail(nullptr, SR_ERR_ARG, "null argument");
+  sr_status st = finalize(const_cast<sr_graph*>(g));
+  if (st != SR_OK) return st;
+  *tile_kernel = g->n_mfma_tiles > 0 ? g->tile_version : 0;
+  return SR_OK;
+}
+
 void sr_graph_destroy(sr_graph* g) {
   if (!g) return;
   if (g->stream || !g->dev_allocs.empty()) hipStreamSynchronize(g->stream);

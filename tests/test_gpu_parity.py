@@ -249,6 +249,19 @@ def test_eight_wave_tile_kernel_rollout_in_hipgraph_matches_steps():
         assert max_abs_rel(a[t], ref[g.out_node][t]) <= TOL["bf16"]
 
 
+def test_tile_kernel_choice_is_reported():
+    import paper_1806_04965_amd as sr
+    # CIFAR-shaped: every patch fits the 4-wave kernel; DSR0 at its batch of 64: the stride-4 edges into the 4x4 node do not;
+    # fp32 graphs have no MFMA node; an explicit choice is reported back
+    for g, options, want in ((W.cifar_sr(batch=2, frames=2), None, 1), (W.dsr_net(0, batch=64, frames=2), None, 2),
+                             (W.tiny_sr(), None, 0), (W.cifar_sr(batch=2, frames=2), OPT_WIDE, 2)):
+        dev = sr.SrGraph(g, options=options)
+        w, b, _ = W.make_case(g, seed=1)
+        dev.set_parameters(w, b)
+        assert dev.tile_kernel() == want, (g.name, options)
+        dev.close()
+
+
 def test_two_graphs_alive_interleaved_and_recreated():
     # Two graphs with K-split nodes live side by side, stepped alternately; then both are destroyed and
     # created again (the partial-sum scratch of the first pair is handed to the second).  Every

@@ -171,6 +171,7 @@ def test_null_handles_are_errors_not_crashes():
     assert lib.sr_rollout(None, None, 1, 0, None) == 1
     assert lib.sr_get_state(None, 0, None, 0) == 1
     assert lib.sr_graph_info(None, None, None, None) == 1
+    assert lib.sr_graph_tile_kernel(None, None) == 1
     lib.sr_graph_destroy(None)
 
 
