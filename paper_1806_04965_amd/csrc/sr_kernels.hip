@@ -36,12 +36,15 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
 }
 
 template <typename T> struct Store;
+#define SR_GLOBAL __attribute__((address_space(1)))
 template <> struct Store<float> {
   static __device__ __forceinline__ float load(const float* p) { return *p; }
+  static __device__ __forceinline__ float gload(const SR_GLOBAL float* p) { return *p; }
   static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
 };
 template <> struct Store<uint16_t> {
   static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
+  static __device__ __forceinline__ float gload(const SR_GLOBAL uint16_t* p) { return bf16_bits_to_float(*p); }
   static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = float_to_bf16_bits(v); }
 };
 
@@ -186,7 +189,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
   const int co_n = threadIdx.x & (CO - 1), slice = threadIdx.x / CO;
   for (int ei = 0; ei < h.edge_count; ++ei) {
     const SrHeadEdge e = head_edges[h.edge_begin + ei];
-    const T* src = (const T*)e.src[e.bridge ? (cur ^ 1) : cur] + (size_t)b * e.HW * e.Csp;
+    const T* src = (const T*)((e.bridge ? (cur ^ 1) : cur) ? e.src[1] : e.src[0]) + (size_t)b * e.HW * e.Csp;
     int K;
     __syncthreads();   // the previous edge's vector is no longer needed
     if (e.pooled) {
@@ -342,29 +345,42 @@ __device__ __forceinline__ void sr_direct_block(const SrCtx* __restrict__ ctx, c
   float acc = nd.bias[co];
   for (int ei = 0; ei < nd.edge_count; ++ei) {
     const SrDirectEdge e = edges[nd.edge_begin + ei];
-    const T* src = (const T*)e.src[e.bridge ? (cur ^ 1) : cur];
+    // global (not generic) pointers: plain global loads; the copy is picked by a select, not by a dynamic
+    // index into the by-value descriptor (which would put the whole descriptor into scratch memory)
+    const SR_GLOBAL T* src = (const SR_GLOBAL T*)(unsigned long long)((e.bridge ? (cur ^ 1) : cur) ? e.src[1] : e.src[0]);
+    const SR_GLOBAL float* wts = (const SR_GLOBAL float*)(unsigned long long)e.w;
     if (e.kind == 0) {
       const int sy = (oy / e.up) * e.stride - e.pad;
       const int sx = (ox / e.up) * e.stride - e.pad;
+      // branch-free: taps outside the source read a clamped (valid) pixel and are replaced by zero, so the
+      // loads of several taps and channels can be in flight together; the sum keeps the order
+      // (tap row, tap column, channel)
       for (int i = 0; i < e.kh; ++i) {
         const int iy = sy + i;
-        if (iy < 0 || iy >= e.Hs) continue;
+        const bool row_ok = iy >= 0 && iy < e.Hs;
+        const int iyc = min(max(iy, 0), e.Hs - 1);
+#pragma unroll 4
         for (int j = 0; j < e.kw; ++j) {
           const int ix = sx + j;
-          if (ix < 0 || ix >= e.Ws) continue;
-          const T* px = src + ((size_t)(b * e.Hs + iy) * e.Ws + ix) * e.Csp;
-          const float* w = e.w + (size_t)(i * e.kw + j) * e.Cin * nd.C + co;
-          for (int ci = 0; ci < e.Cin; ++ci) acc += Store<T>::load(px + ci) * w[(size_t)ci * nd.C];
+          const bool keep = row_ok && ix >= 0 && ix < e.Ws;
+          const int ixc = min(max(ix, 0), e.Ws - 1);
+          const SR_GLOBAL T* px = src + ((size_t)(b * e.Hs + iyc) * e.Ws + ixc) * e.Csp;
+          const SR_GLOBAL float* w = wts + (size_t)(i * e.kw + j) * e.Cin * nd.C + co;
+#pragma unroll 4
+          for (int ci = 0; ci < e.Cin; ++ci) {
+            const float v = Store<T>::gload(px + ci);
+            acc += (keep ? v : 0.f) * w[(size_t)ci * nd.C];
+          }
         }
       }
     } else {  // mean over (h,w), then dense
       const int n = e.Hs * e.Ws;
       const float inv = 1.0f / (float)n;
-      const T* img = src + (size_t)b * n * e.Csp;
+      const SR_GLOBAL T* img = src + (size_t)b * n * e.Csp;
       for (int ci = 0; ci < e.Cin; ++ci) {
         float s = 0.f;
-        for (int p = 0; p < n; ++p) s += Store<T>::load(img + (size_t)p * e.Csp + ci);
-        acc += (s * inv) * e.w[(size_t)ci * nd.C + co];
+        for (int p = 0; p < n; ++p) s += Store<T>::gload(img + (size_t)p * e.Csp + ci);
+        acc += (s * inv) * wts[(size_t)ci * nd.C + co];
       }
     }
   }
