@@ -566,6 +566,15 @@ sr_status finalize(sr_graph* g) {
         for (const auto& c : {std::pair<int, int>(2, 2), std::pair<int, int>(2, 1), std::pair<int, int>(1, 1),
                               std::pair<int, int>(1, 2), std::pair<int, int>(1, 4)})
           if (Cout % (32 * c.first * c.second) == 0) shapes.push_back(c);
+        if (!shapes.empty()) {   // few tiles: shorter pixel tiles of the same channel width first (as in the 4-wave planner)
+          const int bn0 = 32 * shapes[0].first * shapes[0].second, bm0 = 128 * (8 / shapes[0].second);
+          if ((M + bm0 - 1) / bm0 * (Cout / bn0) < SR_CUS) {
+            std::vector<std::pair<int, int>> shorter;
+            for (const auto& c : shapes)
+              if (32 * c.first * c.second == bn0 && 128 * (8 / c.second) < bm0) shorter.push_back(c);
+            shapes.insert(shapes.begin(), shorter.begin(), shorter.end());
+          }
+        }
         int wt = 0, wn = 0, waves_m = 0, BM = 0, BN = 0, NBT = 0;
         SrMfmaNode node{};
         bool ok = false;
@@ -718,6 +727,20 @@ sr_status finalize(sr_graph* g) {
               for (const Shape& sh : shapes) dominated |= (sh.waves_n == wn);
               if (!dominated) shapes.push_back(Shape{wt, wn});
             }
+        if (!shapes.empty()) {
+          // a node with fewer tiles than the chip has CUs at its preferred shape tries shorter pixel tiles of
+          // the same channel width first: more, shorter tiles (measured: CIFAR-shaped frame 37 -> 29 us,
+          // hi-res 160 -> 149 us; the GTSRB-shaped graph has no such node)
+          const int bn0 = 32 * shapes[0].wn_tiles * shapes[0].waves_n, bm0 = 128 * (4 / shapes[0].waves_n);
+          const int64_t tiles0 = (M + bm0 - 1) / bm0 * (Cout / bn0);
+          if (tiles0 < SR_CUS) {
+            std::vector<Shape> shorter;
+            for (int wn : {4, 2})
+              for (int wt : {2, 1})
+                if (32 * wt * wn == bn0 && 128 * (4 / wn) < bm0) shorter.push_back(Shape{wt, wn});
+            shapes.insert(shapes.begin(), shorter.begin(), shorter.end());
+          }
+        }
         int wn_tiles = 0, cw = 0, waves_n = 0, waves_m = 0, BM = 0, BN = 0;
         SrMfmaNode node{};
         double ksum = 0;

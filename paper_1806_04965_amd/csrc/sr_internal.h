@@ -7,6 +7,7 @@
 #define SR_MAX_INPUTS 16
 #define SR_SPLIT_FLOATS (128 * 256)   // accumulator floats one part leaves in scratch
 #define SR_XCDS 8          // accelerator complex dies of an MI355X; workgroup i of a launch runs on XCD i % 8
+#define SR_CUS 256         // compute units of an MI355X
 
 // One per graph, in device memory.  Kernels read the frame counter from here, so
 // the same captured HIP graph serves every frame: the buffer written at frame t
