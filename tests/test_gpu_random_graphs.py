@@ -73,6 +73,29 @@ def test_random_bf16_graph_both_tile_kernels(seed):
               f"launches/frame={info['launches_per_frame']}", flush=True)
 
 
+def scaled_up(g, seed):
+    """The same topology, strides and pattern with 2-4x larger images and a batch of 6..32: hundreds
+    of tiles, tiles that span several images, every XCD's share non-empty.  A dense head becomes
+    GAP + dense (its flattened input would no longer fit a head item)."""
+    rng = np.random.default_rng(seed + 7)
+    f = int(rng.choice([2, 2, 4]))
+    nodes = [Node(n.name, n.channels, n.height * f if n.height > 1 else 1, n.width * f if n.width > 1 else 1, n.act)
+             for n in g.nodes]
+    edges = [Edge(e.src, e.dst, "gap_dense", 1, 1, 1, 0, 1, e.bridge) if e.kind == "dense" else e for e in g.edges]
+    return Graph(g.name + "_big", nodes, edges, int(rng.integers(6, 33)), 3, g.dtype, out_node=g.out_node)
+
+
+@pytest.mark.parametrize("seed", [401, 405, 412, 429])
+def test_random_bf16_graph_scaled_up(seed):
+    g = scaled_up(random_graph(seed), seed)
+    w, b, x = W.make_case(g, seed=seed, bias_scale=0.1, frames=g.frames, recipe="uniform")
+    ref = oracle_states(g, w, b, x, g.frames, "bf16")
+    for label, opts in (("4-wave", {4: 1}), ("8-wave", {4: 2})):
+        got, info, work = gpu_states_by_steps(g, w, b, x, g.frames, opts)
+        worst = compare_all(got, ref, 2e-2, f"{g.name}/{label}")
+        print(f"[parity] {g.name}/{label}: worst {worst:.3e}, B={g.batch}, tiles={work['mfma_tiles']}", flush=True)
+
+
 @pytest.mark.parametrize("seed", range(4))
 def test_random_fp32_graph_direct_kernel(seed):
     g = random_graph(200 + seed, dtype="f32")
