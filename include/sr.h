@@ -223,6 +223,16 @@ sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfm
  * SR_OPT_FORCE_DIRECT).  Plans the graph if that has not happened yet, as sr_graph_work does. */
 sr_status sr_graph_tile_kernel(const sr_graph* g, int32_t* tile_kernel);
 
+/* Which kernel the planner gave each node of the frame update (App. A1.2 node map; plans the graph if
+ * that has not happened yet): kinds[v] (host, n_nodes ints) =
+ *   0 input node (its state is staged from the caller's frame),
+ *   1 matrix-core tile kernel with 4 waves per workgroup, 2 matrix-core tile kernel with 8 waves,
+ *   3 one-thread-per-output kernel (fp32 graphs; nodes neither tile kernel takes: an edge with stride
+ *     or upsampling outside {1,2,4}, a source patch larger than the LDS budget),
+ *   4 head item (1x1 node fed by dense / GAP+dense edges only).
+ * Errors: SR_ERR_ARG, and what planning can return (SR_ERR_STATE: weights missing, SR_ERR_OOM, SR_ERR_DEVICE). */
+sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
+
 void sr_graph_destroy(sr_graph* g);
 
 const char* sr_status_str(sr_status s);

@@ -17,7 +17,7 @@ EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_mo
            "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
            "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
-           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
+           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
 
 
 class NodeDesc(C.Structure):
@@ -71,6 +71,8 @@ def load_library():
     lib.sr_frame_index.argtypes = [vp, P(i64)]
     lib.sr_frame_step_timed.argtypes = [vp, P(vp), P(C.c_float), P(i32), i32, P(i32)]
     lib.sr_graph_work.argtypes = [vp, P(C.c_double), P(i64), P(i64)]
+    lib.sr_graph_tile_kernel.argtypes = [vp, P(i32)]
+    lib.sr_graph_node_kernels.argtypes = [vp, P(i32)]
     lib.sr_graph_destroy.argtypes = [vp]
     lib.sr_graph_destroy.restype = None
     lib.sr_status_str.argtypes = [i32]
@@ -202,7 +204,24 @@ class SrGraph:
         _check(self.lib, self.lib.sr_graph_tile_kernel(self.h, C.byref(k)), self.h)
         return k.value
 
+    def node_kernels(self):
+        """sr_graph_node_kernels: per node 0 input, 1 / 2 tile kernel (4 / 8 waves), 3 one thread per output, 4 head."""
+        k = (C.c_int32 * len(self.g.nodes))()
+        _check(self.lib, self.lib.sr_graph_node_kernels(self.h, k), self.h)
+        return list(k)
+
     # -- frames -----------------------------------------------------------
+    def _order(self, *tensors):
+        """Stream ordering between torch and the library's stream: work already enqueued on torch's
+        current stream (the producers of `tensors`) runs before what the library enqueues next, and
+        torch's allocator is told that the tensors are in use on the library's stream."""
+        cur = self.torch.cuda.current_stream()
+        if cur != self.stream:
+            self.stream.wait_stream(cur)
+            for t in tensors:
+                if t is not None:
+                    t.record_stream(self.stream)
+
     def _ptrs(self, tensors):
         arr = (C.c_void_p * max(1, len(self.inputs)))()
         for i, t in enumerate(tensors):
@@ -211,6 +230,7 @@ class SrGraph:
                 continue
             assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype, "inputs must be dense device tensors of the graph dtype"
             arr[i] = t.data_ptr()
+        self._order(*tensors)
         return arr
 
     def reset(self, inputs0=None):
@@ -233,17 +253,20 @@ class SrGraph:
         if outputs is not None:
             assert outputs.is_cuda and outputs.is_contiguous() and outputs.dtype == self.tdtype
             optr = C.c_void_p(outputs.data_ptr())
+            self._order(outputs)
         _check(self.lib, self.lib.sr_rollout(self.h, self._ptrs(inputs), T, out_node, optr), self.h)
 
     def get_state(self, node: int):
         n = self.g.nodes[node]
         t = self.torch.empty((self.g.batch, n.height, n.width, n.channels), dtype=self.tdtype, device="cuda")
+        self._order(t)
         _check(self.lib, self.lib.sr_get_state(self.h, node, C.c_void_p(t.data_ptr()), t.numel() * t.element_size()), self.h)
         self.stream.synchronize()
         return t
 
     def set_state(self, node: int, t):
         assert t.is_cuda and t.is_contiguous() and t.dtype == self.tdtype
+        self._order(t)
         _check(self.lib, self.lib.sr_set_state(self.h, node, C.c_void_p(t.data_ptr()), t.numel() * t.element_size()), self.h)
 
     def frame_index(self) -> int:

@@ -238,14 +238,18 @@ struct UncachedBlock { void* ptr; size_t bytes; };
 std::vector<UncachedBlock> g_uncached_free;
 std::mutex g_uncached_mutex;
 
-hipError_t uncached_alloc(void** p, size_t bytes) {
+// *held receives the size of the block handed out (a reused block may be larger than asked for);
+// that size goes back into the list with the block.
+hipError_t uncached_alloc(void** p, size_t bytes, size_t* held) {
   std::lock_guard<std::mutex> lock(g_uncached_mutex);
   for (size_t i = 0; i < g_uncached_free.size(); ++i)
     if (g_uncached_free[i].bytes >= bytes) {
       *p = g_uncached_free[i].ptr;
+      *held = g_uncached_free[i].bytes;
       g_uncached_free.erase(g_uncached_free.begin() + i);
       return hipSuccess;
     }
+  *held = bytes;
   return hipExtMallocWithFlags(p, bytes, hipDeviceMallocUncached);
 }
 
@@ -805,7 +809,8 @@ sr_status finalize(sr_graph* g) {
             }
           }
           const int64_t imgs_per_tile = BM / ((int64_t)n.d.height * n.d.width) + 2;
-          if (KC == 0 || imgs_per_tile > 255) { ok = false; break; }
+          // the kernel packs (image - first image of the tile) into the top byte of a signed int
+          if (KC == 0 || imgs_per_tile > 127) { ok = false; break; }
           m.KC = KC;
           m.nchunk = sn.Cp / KC;
           m.SP = KC * 2 + 16;
@@ -1054,12 +1059,9 @@ sr_status finalize(sr_graph* g) {
   if ((st = upload(g, &g->plan_tables, plan_tables)) != SR_OK) return st;
   if ((st = upload(g, &g->stage8, stage8)) != SR_OK) return st;
   if (g->n_split_slots > 0) {
+    // arrival counters of the K-split tiles; the slabs themselves are allocated by the first frame
+    // that runs on the graph's own scratch (ensure_split_scratch)
     void* sp = nullptr;
-    g->split_scratch_bytes = (size_t)g->n_split_slots * (g->tile_version == 2 ? SR8_SPLIT_FLOATS : SR_SPLIT_FLOATS) * sizeof(float);
-    // a reused block may be larger; remember the size actually held
-    SR_HIP(g, uncached_alloc(&sp, g->split_scratch_bytes));
-    g->split_scratch = (float*)sp;
-    g->device_bytes += (int64_t)g->split_scratch_bytes;
     if ((st = dev_alloc(g, &sp, (size_t)g->n_split_slots * sizeof(int32_t))) != SR_OK) return st;
     g->split_counters = (int32_t*)sp;
     SR_HIP(g, sr_launch_fill_zero(g->stream, sp, (size_t)g->n_split_slots * sizeof(int32_t)));
@@ -1068,8 +1070,6 @@ sr_status finalize(sr_graph* g) {
     node.plan_index = g->plan_index;
     node.plan_tables = g->plan_tables;
     node.stage_table = g->stage8;
-    node.split_scratch = g->split_scratch;
-    node.split_counters = g->split_counters;
   }
   if ((st = upload(g, &g->m_nodes, mn)) != SR_OK) return st;
   if ((st = upload(g, &g->m_edges, me)) != SR_OK) return st;
@@ -1121,7 +1121,22 @@ bool record_needs_copy(const sr_graph* g) {
   return true;
 }
 
-sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
+size_t split_slab_bytes(const sr_graph* g) {
+  return (size_t)g->n_split_slots * (g->tile_version == 2 ? SR8_SPLIT_FLOATS : SR_SPLIT_FLOATS) * sizeof(float);
+}
+
+// The graph's own K-split slabs: uncached device memory from the process-wide arena, taken by the
+// first frame that needs them (a graph that only ever steps on the static scratch never does).
+sr_status ensure_split_scratch(sr_graph* g) {
+  if (g->n_split_slots == 0 || g->split_scratch) return SR_OK;
+  void* sp = nullptr;
+  SR_HIP(g, uncached_alloc(&sp, split_slab_bytes(g), &g->split_scratch_bytes));   // split_scratch_bytes: the size held
+  g->split_scratch = (float*)sp;
+  g->device_bytes += (int64_t)split_slab_bytes(g);
+  return SR_OK;
+}
+
+sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft, SrSplitScratch split) {
   hipStream_t s = g->stream;
   const int bf16 = g->dtype == SR_BF16;
   auto mark = [&](int kind) -> hipError_t {
@@ -1160,11 +1175,11 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft) {
       if (g->tile_version == 2)
         SR_HIP(g, sr_launch_mfma8(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles,
                                   g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes,
-                                  g->aux_smem_bytes, is_last));
+                                  g->aux_smem_bytes, is_last, split));
       else
         SR_HIP(g, sr_launch_mfma(s, g->ctx, g->m_nodes, g->m_edges, g->m_tiles + lp.tile_begin, lp.n_tiles, g->lds_bytes,
                                  g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes,
-                                 g->aux_smem_bytes, is_last));
+                                 g->aux_smem_bytes, is_last, split));
     }
     if (direct_launch) {
       const int is_last = (!copy_out && L == last_level) ? 1 : 0;
@@ -1203,7 +1218,8 @@ void drop_graphs(sr_graph* g) {
 sr_status capture(sr_graph* g, int frames, hipGraph_t* graph, hipGraphExec_t* exec) {
   SR_HIP(g, hipStreamBeginCapture(g->stream, hipStreamCaptureModeThreadLocal));
   sr_status st = SR_OK;
-  for (int f = 0; f < frames && st == SR_OK; ++f) st = enqueue_frame(g, true, nullptr);
+  const SrSplitScratch own{g->split_scratch, g->split_counters};
+  for (int f = 0; f < frames && st == SR_OK; ++f) st = enqueue_frame(g, true, nullptr, own);
   hipError_t e = hipStreamEndCapture(g->stream, graph);
   if (st != SR_OK) return st;
   SR_HIP(g, e);
@@ -1225,9 +1241,14 @@ sr_status ensure_graphs(sr_graph* g) {
 }
 
 sr_status run_frames(sr_graph* g, int64_t frames) {
+  {
+    sr_status st = ensure_split_scratch(g);
+    if (st != SR_OK) return st;
+  }
   if (!g->use_hipgraph) {
+    const SrSplitScratch own{g->split_scratch, g->split_counters};
     for (int64_t f = 0; f < frames; ++f) {
-      sr_status st = enqueue_frame(g, true, nullptr);
+      sr_status st = enqueue_frame(g, true, nullptr, own);
       if (st != SR_OK) return st;
     }
   } else {
@@ -1543,6 +1564,8 @@ sr_status sr_graph_set_weights(sr_graph* g, int32_t edge, const float* host_w, s
     if (st != SR_OK) return st;
     e.w_dev = (float*)p;
   }
+  // frames still in flight on the graph's stream read the old weights: let them finish first
+  SR_HIP(g, hipStreamSynchronize(g->stream));
   SR_HIP(g, hipMemcpy(e.w_dev, e.w_host.data(), count * sizeof(float), hipMemcpyHostToDevice));
   if (bf16 && e.d.kind == SR_EDGE_CONV && g->nodes[e.d.dst].d.channels % 32 == 0) {
     // B operand of the tile kernel: [tap][Cin_p/16][Cout/32][lane 0..63][8]; lane l of a
@@ -1576,6 +1599,7 @@ sr_status sr_graph_set_bias(sr_graph* g, int32_t node, const float* host_b, size
   NodeRt& n = g->nodes[node];
   if (count != (size_t)n.d.channels) return gfail(g, SR_ERR_ARG, "bias length differs from the node's channels");
   std::copy(host_b, host_b + count, n.bias.begin());
+  SR_HIP(g, hipStreamSynchronize(g->stream));   // frames in flight read the old bias
   SR_HIP(g, hipMemcpy(n.bias_dev, n.bias.data(), n.Cp * sizeof(float), hipMemcpyHostToDevice));
   return SR_OK;
 }
@@ -1700,7 +1724,9 @@ sr_status sr_frame_step_timed(sr_graph* g, const void* const* inputs_t, float* k
   }
   SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
   FrameTimer ft;
-  sr_status st = enqueue_frame(g, false, &ft);
+  sr_status st = ensure_split_scratch(g);
+  if (st != SR_OK) return st;
+  st = enqueue_frame(g, false, &ft, SrSplitScratch{g->split_scratch, g->split_counters});
   hipError_t he = hipStreamSynchronize(g->stream);
   int n = 0;
   if (st == SR_OK && he == hipSuccess) {
@@ -1734,6 +1760,17 @@ sr_status sr_graph_tile_kernel(const sr_graph* g, int32_t* tile_kernel) {
   sr_status st = finalize(const_cast<sr_graph*>(g));
   if (st != SR_OK) return st;
   *tile_kernel = g->n_mfma_tiles > 0 ? g->tile_version : 0;
+  return SR_OK;
+}
+
+sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds) {
+  if (!g || !kinds) return fail(nullptr, SR_ERR_ARG, "null argument");
+  sr_status st = finalize(const_cast<sr_graph*>(g));
+  if (st != SR_OK) return st;
+  for (int v = 0; v < g->n_nodes; ++v) {
+    const int k = g->nodes[v].kind;   // 0 input, 1 tile kernel, 2 direct, 3 head
+    kinds[v] = (k == 0) ? 0 : (k == 1 ? (g->tile_version == 2 ? 2 : 1) : (k == 2 ? 3 : 4));
+  }
   return SR_OK;
 }
 

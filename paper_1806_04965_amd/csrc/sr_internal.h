@@ -88,8 +88,6 @@ struct SrMfmaNode {
   const float* bias;     // [Cout]
   const int32_t* plan_index;   // [tile.plan_begin + edge]: offset of that (tile, edge) plan in plan_tables
   const int32_t* plan_tables;  // per LDS position: source byte offset, or -1: padding (reads the zero tail of the state)
-  float* split_scratch;        // [slot][16*4*2 registers][256 threads] accumulators of K-split parts
-  int32_t* split_counters;     // [slot] parts finished (returns to 0)
   int32_t M;             // B*Ho*Wo
   int32_t Ho, Wo;
   int32_t Cout, Cp;
@@ -110,8 +108,15 @@ struct SrMfmaTile {
   // one channel chunk of one edge, counted over the node's edges in order) and leave their
   // accumulators in scratch; the part that finishes last adds them up in part order and stores.
   int32_t stage_begin, stage_end;
-  int32_t split_slot;  // index of part 0 of this tile in the scratch / counter arrays, -1: not split
+  int32_t split_slot;  // index of part 0 of this tile in the launch's scratch / counter arrays (SrSplitScratch), -1: not split
   int32_t part;        // part index | number of parts << 16
+};
+
+// Where the parts of K-split tiles leave their accumulators during a launch; a kernel argument, so
+// that the same tile lists run on the graph's own arena or on the library's static array.
+struct SrSplitScratch {
+  float* slabs;        // [slot][accumulator registers of a thread][threads of a workgroup] floats
+  int32_t* counters;   // [slot] parts finished (returns to 0 when the last part has arrived)
 };
 
 // ---------------------------------------------------------------------------
@@ -173,11 +178,12 @@ hipError_t sr_launch_direct(hipStream_t s, SrCtx* ctx, const SrDirectNode* nodes
 hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
                           const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
                           const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
-                          int aux_smem_bytes, int is_last);
+                          int aux_smem_bytes, int is_last, SrSplitScratch split);
 int sr_mfma_max_lds_bytes();
 hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
                            const SrMfmaTile* tiles, int n_tiles, const SrAux* aux, int n_aux, const SrHead* heads,
-                           const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last);
+                           const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last,
+                           SrSplitScratch split);
 // 8-wave kernel: bytes of one of its two stage buffers, and floats of one part's K-split slab
 #define SR8_BUF_BYTES (80 * 1024)
 #define SR_ZERO_TAIL 2048   // zero bytes behind every state copy: where padding pixels are loaded from

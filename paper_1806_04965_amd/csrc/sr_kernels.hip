@@ -15,6 +15,7 @@
 // Every kernel takes the frame counter from SrCtx: the copy written at frame t is t & 1.
 #include <hip/hip_runtime.h>
 #include <hip/hip_bf16.h>
+#include <atomic>
 #include "sr_internal.h"
 
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8_t;
@@ -589,11 +590,71 @@ __device__ __forceinline__ void sr_stage_compute(const SrEdgeK& e, const SrTaps&
     if (st0 + u < NS) sr_step<WN>(e, taps, lds, abase, wchunk, a, bq[u % SR_RING], acc, st0 + u, NS);
 }
 
+// K-split hand-off between the workgroups that share a tile.  Every part stores its accumulators to
+// its slab, [register pair][thread]; the part whose increment of the tile's counter finds all others
+// done adds the slabs up in part order and returns true (the others return false and leave).
+// The slabs are written and read with agent-scope accesses (write-through stores, loads that do not
+// take a stale line from this XCD's L2), so they may live in any device memory; a thread's stores
+// have completed when its wait for them ends, the barrier collects the workgroup's, and only then is
+// the counter raised.  The last part resets the counter for the next launch.
+template <int WN, int THREADS>
+__device__ __forceinline__ bool sr_split_reduce(f32x16_t (&acc)[4][WN], const SrSplitScratch& split, int split_slot,
+                                                int part_info, int slab_floats, int tid, int* flag) {
+  const int n_parts = part_info >> 16;
+  unsigned long long* mine =
+      (unsigned long long*)(split.slabs + (size_t)(split_slot + (part_info & 0xffff)) * slab_floats) + tid;
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+    for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        const unsigned long long v = (unsigned long long)__float_as_uint(acc[mi][nj][2 * q]) |
+                                     ((unsigned long long)__float_as_uint(acc[mi][nj][2 * q + 1]) << 32);
+        __hip_atomic_store(mine + ((mi * WN + nj) * 8 + q) * THREADS, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have reached memory
+  __syncthreads();
+  if (tid == 0) {
+    int* counter = split.counters + split_slot;
+    const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *flag = (old == n_parts - 1);
+    if (old == n_parts - 1) __hip_atomic_store(counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  __syncthreads();
+  if (!*flag) return false;
+  // part by part (so that all of a part's loads are in flight together), every element summed in
+  // part order
+#pragma unroll
+  for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+    for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+      for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
+  const unsigned long long* all = (const unsigned long long*)(split.slabs + (size_t)split_slot * slab_floats) + tid;
+  for (int p = 0; p < n_parts; ++p) {
+    const unsigned long long* part = all + (size_t)p * (slab_floats / 2);
+#pragma unroll
+    for (int mi = 0; mi < 4; ++mi)
+#pragma unroll
+      for (int nj = 0; nj < WN; ++nj)
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+          const unsigned long long v = __hip_atomic_load(part + ((mi * WN + nj) * 8 + q) * THREADS, __ATOMIC_RELAXED,
+                                                         __HIP_MEMORY_SCOPE_AGENT);
+          acc[mi][nj][2 * q] += __uint_as_float((unsigned)v);
+          acc[mi][nj][2 * q + 1] += __uint_as_float((unsigned)(v >> 32));
+        }
+  }
+  return true;
+}
+
 template <int WN>
 __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
                                              const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
                                              int tile_n0, int plan_begin, int stage_begin, int stage_end,
-                                             int split_slot, int part_info, unsigned char* lds) {
+                                             int split_slot, int part_info, unsigned char* lds,
+                                             const SrSplitScratch& split) {
   const __attribute__((address_space(4))) SrMfmaNode* nd =
       (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
   const int tid = threadIdx.x;
@@ -686,55 +747,9 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 
   // ---- K-split tiles: leave the accumulators in scratch; the part that arrives last adds all parts
   // in part order (so the result does not depend on which part that is) and goes on to the epilogue.
-  // The scratch is uncached device memory, so plain 16-byte stores and loads are coherent across
-  // the chip's L2s once they have completed.
-  const int n_parts = part_info >> 16;
-  if (n_parts > 1) {
-    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-    f32x4_t* scratch = (f32x4_t*)((float*)nd->split_scratch + (size_t)(split_slot + (part_info & 0xffff)) * SR_SPLIT_FLOATS);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4_t v = {acc[mi][nj][4 * q], acc[mi][nj][4 * q + 1], acc[mi][nj][4 * q + 2], acc[mi][nj][4 * q + 3]};
-          scratch[((mi * WN + nj) * 4 + q) * 256 + tid] = v;
-        }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have reached memory
-    __syncthreads();
-    int* flag = (int*)lds;
-    if (tid == 0) {
-      int* counter = (int*)nd->split_counters + split_slot;
-      const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *flag = (old == n_parts - 1);
-      if (old == n_parts - 1) *counter = 0;
-    }
-    __syncthreads();
-    if (!*flag) return;
-    const f32x4_t* all = (const f32x4_t*)((const float*)nd->split_scratch + (size_t)split_slot * SR_SPLIT_FLOATS);
-    // part by part (so that all of a part's loads are in flight together), every element summed in
-    // part order
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
-    for (int p = 0; p < n_parts; ++p) {
-      const f32x4_t* part = all + (size_t)p * (SR_SPLIT_FLOATS / 4) + tid;
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const f32x4_t v = part[((mi * WN + nj) * 4 + q) * 256];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] += v[i];
-          }
-    }
-  }
+  if ((part_info >> 16) > 1 &&
+      !sr_split_reduce<WN, 256>(acc, split, split_slot, part_info, SR_SPLIT_FLOATS, tid, (int*)lds))
+    return;
 
   // ---- epilogue: bias, activation, round to bf16, NHWC store.
   // The weights are the MFMA's row operand, so register r of lane l holds channel
@@ -796,7 +811,7 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
                                                          const SrHead* __restrict__ heads,
                                                          const SrHeadEdge* __restrict__ head_edges,
                                                          const SrStageNode* __restrict__ stage_nodes, int vec_floats,
-                                                         int is_last) {
+                                                         int is_last, SrSplitScratch split) {
   extern __shared__ __align__(16) unsigned char sr_lds[];
   // work list: tiles in decreasing cost; the auxiliary items are spliced in at position aux_at so
   // that neither the longest tiles start late nor the launch ends on an auxiliary item
@@ -810,11 +825,11 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
     } else if (nodes[node_index].wn_tiles == 2)
       sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
                       SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
-                      sr_lds);
+                      sr_lds, split);
     else
       sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
                       SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
-                      sr_lds);
+                      sr_lds, split);
   } else {
     sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds, vec_floats);
   }
@@ -944,7 +959,8 @@ template <int WN>
 __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
                                               const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
                                               int tile_n0, int plan_begin, int stage_begin, int stage_end,
-                                              int split_slot, int part_info, unsigned char* lds) {
+                                              int split_slot, int part_info, unsigned char* lds,
+                                              const SrSplitScratch& split) {
   const __attribute__((address_space(4))) SrMfmaNode* nd =
       (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
   const int tid = threadIdx.x;
@@ -1091,53 +1107,9 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
   }
 
   // ---- K-split tiles: as in the 4-wave kernel, with 512 threads
-  const int n_parts = part_info >> 16;
-  if (n_parts > 1) {
-    typedef __attribute__((__vector_size__(4 * sizeof(float)))) float f32x4_t;
-    f32x4_t* scratch = (f32x4_t*)((float*)nd->split_scratch + (size_t)(split_slot + (part_info & 0xffff)) * SR8_SPLIT_FLOATS);
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4_t v = {acc[mi][nj][4 * q], acc[mi][nj][4 * q + 1], acc[mi][nj][4 * q + 2], acc[mi][nj][4 * q + 3]};
-          scratch[((mi * WN + nj) * 4 + q) * 512 + tid] = v;
-        }
-    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's partial sums have reached memory
-    __syncthreads();
-    int* flag = (int*)lds;
-    if (tid == 0) {
-      int* counter = (int*)nd->split_counters + split_slot;
-      const int old = __hip_atomic_fetch_add(counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      *flag = (old == n_parts - 1);
-      if (old == n_parts - 1) *counter = 0;
-    }
-    __syncthreads();
-    if (!*flag) return;
-    const f32x4_t* all = (const f32x4_t*)((const float*)nd->split_scratch + (size_t)split_slot * SR8_SPLIT_FLOATS);
-    // part by part (so that all of a part's loads are in flight together), every element summed in
-    // part order
-#pragma unroll
-    for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-      for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-        for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
-    for (int p = 0; p < n_parts; ++p) {
-      const f32x4_t* part = all + (size_t)p * (SR8_SPLIT_FLOATS / 4) + tid;
-#pragma unroll
-      for (int mi = 0; mi < 4; ++mi)
-#pragma unroll
-        for (int nj = 0; nj < WN; ++nj)
-#pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            const f32x4_t v = part[((mi * WN + nj) * 4 + q) * 512];
-#pragma unroll
-            for (int i = 0; i < 4; ++i) acc[mi][nj][4 * q + i] += v[i];
-          }
-    }
-  }
+  if ((part_info >> 16) > 1 &&
+      !sr_split_reduce<WN, 512>(acc, split, split_slot, part_info, SR8_SPLIT_FLOATS, tid, (int*)lds))
+    return;
 
   // ---- epilogue: as in the 4-wave kernel (each wave transposes its tile through its own LDS region)
   __attribute__((address_space(1))) unsigned char* out =
@@ -1194,7 +1166,7 @@ __global__ __launch_bounds__(512) void sr_mfma8_kernel(SrCtx* __restrict__ ctx, 
                                                        const SrHead* __restrict__ heads,
                                                        const SrHeadEdge* __restrict__ head_edges,
                                                        const SrStageNode* __restrict__ stage_nodes, int vec_floats,
-                                                       int is_last) {
+                                                       int is_last, SrSplitScratch split) {
   extern __shared__ __align__(16) unsigned char sr_lds8[];
   // work list as in the 4-wave kernel: the auxiliary items are spliced in at position aux_at.  An
   // auxiliary item is written for 256 threads: the upper four waves of the workgroup leave (a
@@ -1213,11 +1185,11 @@ __global__ __launch_bounds__(512) void sr_mfma8_kernel(SrCtx* __restrict__ ctx, 
   } else if (nodes[node_index].wn_tiles == 2)
     sr_mfma8_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
                      SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
-                     sr_lds8);
+                     sr_lds8, split);
   else
     sr_mfma8_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
                      SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
-                     sr_lds8);
+                     sr_lds8, split);
   if (is_last) sr_block_done(ctx, gridDim.x);
 }
 
@@ -1304,36 +1276,45 @@ hipError_t sr_launch_direct(hipStream_t s, SrCtx* ctx, const SrDirectNode* nodes
   return hipGetLastError();
 }
 
+// hipFuncAttributeMaxDynamicSharedMemorySize of tile kernel `which`, set once on every device that
+// launches it (thread-safe; a failed attempt is tried again by the next launch)
+static hipError_t sr_request_lds(const void* kernel, int bytes, int which) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<int> done[2][kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev >= 0 && dev < kMaxDevices && done[which][dev].load(std::memory_order_acquire)) return hipSuccess;
+  e = hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  if (e == hipSuccess && dev >= 0 && dev < kMaxDevices) done[which][dev].store(1, std::memory_order_release);
+  return e;
+}
+
 hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
                           const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
                           const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
-                          int aux_smem_bytes, int is_last) {
+                          int aux_smem_bytes, int is_last, SrSplitScratch split) {
   if (n_tiles + n_aux == 0) return hipSuccess;
-  static bool attr_set = false;
-  if (!attr_set) {   // dynamic LDS above 64 KiB has to be requested once
-    hipError_t e = hipFuncSetAttribute((const void*)sr_mfma_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       sr_mfma_max_lds_bytes());
+  {   // dynamic LDS above 64 KiB has to be requested once per device
+    hipError_t e = sr_request_lds((const void*)sr_mfma_kernel, sr_mfma_max_lds_bytes(), 0);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles + n_aux), dim3(256), lds_bytes, s, ctx, nodes, edges, tiles, n_tiles,
-                     aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last);
+                     aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last, split);
   return hipGetLastError();
 }
 
 hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
                            const SrMfmaTile* tiles, int n_tiles, const SrAux* aux, int n_aux, const SrHead* heads,
-                           const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last) {
+                           const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last,
+                           SrSplitScratch split) {
   if (n_tiles + n_aux == 0) return hipSuccess;
-  static bool attr_set = false;
-  if (!attr_set) {   // dynamic LDS above 64 KiB has to be requested once
-    hipError_t e = hipFuncSetAttribute((const void*)sr_mfma8_kernel, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                       2 * SR8_BUF_BYTES);
+  {
+    hipError_t e = sr_request_lds((const void*)sr_mfma8_kernel, 2 * SR8_BUF_BYTES, 1);
     if (e != hipSuccess) return e;
-    attr_set = true;
   }
   hipLaunchKernelGGL(sr_mfma8_kernel, dim3(n_tiles + n_aux), dim3(512), 2 * SR8_BUF_BYTES, s, ctx, nodes, edges, tiles, n_tiles,
-                     aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last);
+                     aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last, split);
   return hipGetLastError();
 }
 

@@ -262,6 +262,32 @@ def test_tile_kernel_choice_is_reported():
         dev.close()
 
 
+def test_tile_spanning_more_than_127_images():
+    # a 1x3 node at batch 160: one 512-pixel tile would span 170 images, more than the tile kernels'
+    # packed image offset holds; the planner has to choose a shape (or kernel) that stays within it
+    nodes = [Node("in", 16, 1, 3, ACT_IDENTITY), Node("a", 32, 1, 3), Node("out", 5, 1, 1, ACT_IDENTITY)]
+    edges = [Edge(0, 1, "conv", 3, 3, 1, 1), Edge(1, 1, "conv", 3, 3, 1, 1), Edge(1, 2, "gap_dense", 1, 1, 1, 0)]
+    g = Graph("thin", nodes, edges, batch=160, frames=3, dtype="bf16", out_node=2)
+    for options in (None, OPT_WIDE):
+        check(g, seed=17, options=options, label=f"thin/B160/{options}")
+
+
+def test_mfma_nodes_of_the_benchmark_configurations():
+    # which kernel the planner gives every node: all convolution nodes of the three bf16 benchmark
+    # configurations run on matrix-core tiles (4-wave kernel), their heads as head items
+    import paper_1806_04965_amd as sr
+    for g in (W.cifar_sr(), W.gtsrb_sr(), W.hires_sr()):
+        dev = sr.SrGraph(g)
+        w, b, _ = W.make_case(g, seed=1, frames=0)
+        dev.set_parameters(w, b)
+        kinds = dev.node_kernels()
+        assert dev.tile_kernel() == 1
+        dev.close()
+        for v, n in enumerate(g.nodes):
+            want = 0 if v in g.input_nodes() else (4 if v == g.out_node else 1)
+            assert kinds[v] == want, (g.name, n.name, kinds)
+
+
 def test_two_graphs_alive_interleaved_and_recreated():
     # Two graphs with K-split nodes live side by side, stepped alternately; then both are destroyed and
     # created again (the partial-sum scratch of the first pair is handed to the second).  Every
