@@ -186,6 +186,27 @@ sr_status sr_reset(sr_graph* g, const void* const* input_frame0);
  * Errors: SR_ERR_ARG, SR_ERR_STATE (no sr_reset yet, weights missing), SR_ERR_DEVICE. */
 sr_status sr_frame_step(sr_graph* g, const void* const* inputs_t);
 
+/* sr_frame_step for callers that cannot allocate device memory: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  Same arguments, same result (bit for bit)
+ * as sr_frame_step, but
+ *  - it calls no hipMalloc / hipFree and no allocating library routine; every kernel of the frame is
+ *    a plain launch on the graph's stream (nothing is captured or instantiated, no memset node), so
+ *    the call may itself be captured by the caller;
+ *  - the partial sums and arrival counters of tiles that are cut along their contraction (the only
+ *    device memory a frame needs beyond the graph's states and tables) live in a static device
+ *    array of the library, 64 MiB on every GPU the library is loaded on, instead of the graph's own
+ *    arena: room for 1024 parts' counters and 64 MiB - 4 KiB of partial sums (128 KiB per part with
+ *    the 4-wave tile kernel, 256 KiB with the 8-wave one; the 256x256 high-resolution benchmark graph
+ *    needs about 38 MiB).  A graph that needs more is refused
+ *    with SR_ERR_ARG and sr_last_error names both sizes; sr_frame_step still serves it.
+ *  - the graph must have been planned and reset before (sr_reset does both and is where the graph's
+ *    tables are allocated): otherwise SR_ERR_STATE.
+ * All graphs on one GPU share the array, which keeps what the last call left (the counters are
+ * cleared by the call): calls that overlap in time on one GPU -- two graphs on two streams -- race
+ * on it and must be serialised by the caller.  Asynchronous.
+ * Errors: SR_ERR_ARG, SR_ERR_STATE, SR_ERR_DEVICE. */
+sr_status sr_frame_step_static(sr_graph* g, const void* const* inputs_t);
+
 /* sr_reset(frame 0) followed by T calls of sr_frame_step(frame t), t = 1..T, without returning to
  * the host in between.
  *   inputs[i]   device pointer to [T+1][B][H][W][C] of the i-th input node, frame 0 first

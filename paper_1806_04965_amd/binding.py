@@ -16,7 +16,7 @@ SR_OPT_USE_HIPGRAPH, SR_OPT_FORCE_DIRECT, SR_OPT_FRAMES_PER_GRAPH = 0, 1, 2
 EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_model_parallel",
            "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
-           "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
+           "sr_frame_step_static", "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
            "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
 
 
@@ -65,6 +65,7 @@ def load_library():
     lib.sr_graph_info.argtypes = [vp, P(i32), P(i32), P(i32)]
     lib.sr_reset.argtypes = [vp, P(vp)]
     lib.sr_frame_step.argtypes = [vp, P(vp)]
+    lib.sr_frame_step_static.argtypes = [vp, P(vp)]
     lib.sr_rollout.argtypes = [vp, P(vp), i32, i32, vp]
     lib.sr_get_state.argtypes = [vp, i32, vp, C.c_size_t]
     lib.sr_set_state.argtypes = [vp, i32, vp, C.c_size_t]
@@ -239,6 +240,9 @@ class SrGraph:
 
     def frame_step(self, inputs_t):
         _check(self.lib, self.lib.sr_frame_step(self.h, self._ptrs(inputs_t)), self.h)
+
+    def frame_step_static(self, inputs_t):
+        _check(self.lib, self.lib.sr_frame_step_static(self.h, self._ptrs(inputs_t)), self.h)
 
     def frame_step_timed(self, inputs_t, cap=64):
         ms = (C.c_float * cap)()

@@ -1655,6 +1655,41 @@ sr_status sr_frame_step(sr_graph* g, const void* const* inputs_t) {
   return run_frames(g, 1);
 }
 
+sr_status sr_frame_step_static(sr_graph* g, const void* const* inputs_t) {
+  if (!g || !inputs_t) return gfail(g, SR_ERR_ARG, "bad argument to sr_frame_step_static");
+  if (!g->finalized || !g->was_reset)
+    return gfail(g, SR_ERR_STATE, "sr_frame_step_static before sr_reset (which plans the graph and allocates its tables)");
+  const size_t slabs = split_slab_bytes(g);
+  const size_t counters = (size_t)SR_STATIC_MAX_SLOTS * sizeof(int32_t);
+  if (g->n_split_slots > SR_STATIC_MAX_SLOTS || counters + slabs > SR_STATIC_SCRATCH_BYTES)
+    return gfail(g, SR_ERR_ARG, "sr_frame_step_static: this graph's K-split tiles need " + std::to_string(g->n_split_slots) +
+                                    " slots and " + std::to_string(slabs) + " bytes of partial sums; the static scratch holds " +
+                                    std::to_string(SR_STATIC_MAX_SLOTS) + " slots and " +
+                                    std::to_string(SR_STATIC_SCRATCH_BYTES - counters) + " bytes");
+  SrCtx c{};
+  for (size_t i = 0; i < g->inputs.size(); ++i) {
+    if (!inputs_t[i]) return gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
+    c.in_ptr[i] = inputs_t[i];
+    c.in_stride[i] = 0;
+  }
+  c.out_ptr = nullptr;
+  SrSplitScratch split{nullptr, nullptr};
+  if (g->n_split_slots > 0) {
+    void* base = nullptr;
+    SR_HIP(g, sr_static_scratch(&base));
+    split.counters = (int32_t*)base;
+    split.slabs = (float*)((unsigned char*)base + counters);
+    // the array keeps what the last call (of any graph) left: the counters must start at zero
+    // (a fill kernel, not a memset: the caller may be capturing the stream)
+    SR_HIP(g, sr_launch_fill_zero(g->stream, split.counters, (size_t)g->n_split_slots * sizeof(int32_t)));
+  }
+  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  sr_status st = enqueue_frame(g, true, nullptr, split);   // plain launches: nothing is captured or instantiated
+  if (st != SR_OK) return st;
+  g->host_frame += 1;
+  return SR_OK;
+}
+
 sr_status sr_rollout(sr_graph* g, const void* const* inputs, int32_t T, int32_t out_node, void* outputs) {
   if (!g || !inputs || T < 0) return gfail(g, SR_ERR_ARG, "bad argument to sr_rollout");
   if (outputs && (out_node < 0 || out_node >= g->n_nodes)) return gfail(g, SR_ERR_ARG, "bad out_node");

@@ -184,6 +184,12 @@ hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, c
                            const SrMfmaTile* tiles, int n_tiles, const SrAux* aux, int n_aux, const SrHead* heads,
                            const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last,
                            SrSplitScratch split);
+// The library's static scratch: a file-scope device array of SR_STATIC_SCRATCH_BYTES on every GPU the
+// library runs on, for the entry point that allocates nothing.  Returns its device address on the
+// current device (looked up once per device).  Counters come first, slabs behind them.
+#define SR_STATIC_SCRATCH_BYTES (64u << 20)
+#define SR_STATIC_MAX_SLOTS 1024            // counters: 4 KiB at the start of the array
+hipError_t sr_static_scratch(void** ptr);
 // 8-wave kernel: bytes of one of its two stage buffers, and floats of one part's K-split slab
 #define SR8_BUF_BYTES (80 * 1024)
 #define SR_ZERO_TAIL 2048   // zero bytes behind every state copy: where padding pixels are loaded from

@@ -1318,4 +1318,27 @@ hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, c
   return hipGetLastError();
 }
 
+// Scratch for callers that may not allocate: one array per GPU, held from the moment the library is
+// loaded there until the process ends.  In host code the array's name is only a handle; its device
+// address on the current device comes from hipGetSymbolAddress, once per device.
+static __device__ __align__(256) unsigned char sr_static_scratch_array[SR_STATIC_SCRATCH_BYTES];
+
+hipError_t sr_static_scratch(void** ptr) {
+  constexpr int kMaxDevices = 64;
+  static std::atomic<void*> addr[kMaxDevices];
+  int dev = 0;
+  hipError_t e = hipGetDevice(&dev);
+  if (e != hipSuccess) return e;
+  if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+  void* p = addr[dev].load(std::memory_order_acquire);
+  if (!p) {
+    e = hipGetSymbolAddress(&p, HIP_SYMBOL(sr_static_scratch_array));
+    if (e != hipSuccess) return e;
+    if (!p) return hipErrorInvalidSymbol;
+    addr[dev].store(p, std::memory_order_release);
+  }
+  *ptr = p;
+  return hipSuccess;
+}
+
 int sr_mfma_max_lds_bytes() { return 80 * 1024; }   // two workgroups per CU share 160 KiB
