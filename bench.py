@@ -4,8 +4,8 @@
 A step is one sr_rollout: T frame updates of the whole batch, inputs already resident in HBM,
 every frame's output-node state recorded.  Prints ONE JSON line: rollout frames/s
 (= batch * T * steps / time), per-frame latency, the roofline position of the dominant kernel
-(the MFMA convolution tiles: algorithmic FLOP of one launch / its average duration from HIP events
-taken on the library's stream) and the CPU oracle timed on a bounded sample of the same workload.
+(the MFMA convolution tiles: algorithmic FLOP of one launch / its average duration, from HIP events on
+the library's stream around the timed rollouts) and the CPU oracle timed on a bounded sample of the same workload.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload gtsrb_sr|cifar_sr|hires_sr|tiny_sr]
                     [--pattern streaming|sequential|hybrid] [--no-cpu-baseline]
@@ -126,14 +126,19 @@ def main():
         dev.rollout(xin, T, g.out_node, out)
     dev.synchronize()
     torch.cuda.synchronize()
+    # the timed region, also bracketed by HIP events on the stream the kernels are launched on
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
+    ev0.record(dev.stream)
     for _ in range(args.steps):
         dev.rollout(xin, T, g.out_node, out)
+    ev1.record(dev.stream)
     dev.synchronize()
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
     frames_per_s = B * T * args.steps / dt
+    event_ms_per_step = ev0.elapsed_time(ev1) / args.steps
 
     # dominant kernel, timed live with HIP events on the library's stream (plain launches)
     dev.reset([xi[0] for xi in xin])
@@ -153,20 +158,31 @@ def main():
         if e.kind == "conv":
             s, d = g.nodes[e.src], g.nodes[e.dst]
             conv_flops += 2 * B * (d.height // e.up) * (d.width // e.up) * d.channels * s.channels * e.kh * e.kw
-    mfma_launch_ms = None
+    ideal_bytes = 0
+    for n in g.nodes:
+        ideal_bytes += 2 * B * n.height * n.width * n.channels * (2 if g.dtype == "bf16" else 4)
+    for wi in w:
+        ideal_bytes += wi.size * (2 if g.dtype == "bf16" else 4)
     if g.dtype == "bf16" and 1 in kind_ms:
-        per_frame = info["inference_factor"]       # one tile launch per level
-        mfma_launch_ms = float(np.sum(kind_ms[1]) / (len(kind_ms[1])))
-        launches_per_frame = len(kind_ms[1]) / reps
-        frame_conv_ms = mfma_launch_ms * launches_per_frame
-        achieved = conv_flops / (frame_conv_ms * 1e-3) / 1e12
+        # Dominant kernel: the convolution tiles.  Its average launch duration is taken from the timed
+        # region itself: HIP events on the library's stream around the replayed rollouts, divided by the
+        # tile launches they contain (one per update step of a frame; the whole frame's time is charged to
+        # them, so launches x duration = the timed time by construction).  The duration of the same
+        # launches issued one by one between events is reported next to it (launch_ms_single).
+        tile_launches_per_frame = len(kind_ms[1]) / reps
+        launch_ms = event_ms_per_step / (T * tile_launches_per_frame)
+        flop_per_launch = conv_flops / tile_launches_per_frame
+        achieved = flop_per_launch / (launch_ms * 1e-3) / 1e12
+        traffic = recorded_traffic(args.workload, args.pattern)
         roofline = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK_BF16_TFLOPS, "unit": "TFLOP/s",
                     "frac": round(achieved / PEAK_BF16_TFLOPS, 4),
-                    "traffic": recorded_traffic(args.workload, args.pattern),
+                    "traffic": traffic,
+                    "traffic_ratio": round(traffic / (ideal_bytes / tile_launches_per_frame), 2) if traffic else None,
+                    "ideal_bytes_per_launch": int(ideal_bytes / tile_launches_per_frame),
                     "kernel": "sr_mfma8_kernel" if dev.tile_kernel() == 2 else "sr_mfma_kernel",
-                    "launch_ms": round(mfma_launch_ms, 4),
-                    "launches_per_frame": launches_per_frame, "flop_per_frame": conv_flops}
-        del per_frame
+                    "launch_ms": round(launch_ms, 4),
+                    "launch_ms_single": round(float(np.mean(kind_ms[1])), 4),
+                    "launches_per_frame": tile_launches_per_frame, "flop_per_launch": flop_per_launch}
     else:
         d_ms = float(np.mean(kind_ms.get(2, [float("nan")])))
         achieved = work["flops_per_frame"] / (d_ms * 1e-3) / 1e12

@@ -177,7 +177,12 @@ struct sr_graph {
   SrCtx* ctx = nullptr;
   SrStageNode* stage_nodes = nullptr;
   SrAux* aux = nullptr;
-  bool stage_folded = false;   // input staging rides in level 1's launch (no R=0 edge leaves an input)
+  // input staging: 0 rides in level 1's launch (no R=0 edge leaves an input: nothing reads the new
+  // input before the next frame); 1 staged one frame ahead: the next frame's input rides in this
+  // frame's last launch, the first frame's is staged by the call; 2 a launch of its own ahead of
+  // level 1 (an input also feeds a node of the last level over a bridging edge, which still reads
+  // the copy the next input would overwrite)
+  int stage_mode = 0;
   int stage_aux_begin = 0, n_stage_aux = 0;
   int aux_smem_bytes = 0;
   std::vector<int> head_node;   // node id of each head, in head order
@@ -537,10 +542,13 @@ sr_status finalize(sr_graph* g) {
     const int total = stage[i].elems_px;
     for (int c = 0; c * SR_STAGE_CHUNK < total; ++c) stage_aux.push_back(SrAux{SR_AUX_STAGE, (int)i, c, 0});
   }
-  g->stage_folded = true;
+  g->stage_mode = 0;
   for (const EdgeRt& e : g->edges)
-    if (g->an.is_input[e.d.src] && e.d.bridge == 0) g->stage_folded = false;
-  if (!g->stage_folded) {   // staging gets a launch of its own, ahead of level 1
+    if (g->an.is_input[e.d.src] && e.d.bridge == 0) g->stage_mode = 1;
+  if (g->stage_mode == 1)
+    for (const EdgeRt& e : g->edges)
+      if (g->an.is_input[e.d.src] && e.d.bridge == 1 && g->an.level[e.d.dst] == F) g->stage_mode = 2;
+  if (g->stage_mode != 0) {   // this frame's input as a launch of its own: ahead of level 1, or once per call
     g->stage_aux_begin = 0;
     g->n_stage_aux = (int)stage_aux.size();
     aux = stage_aux;
@@ -553,7 +561,9 @@ sr_status finalize(sr_graph* g) {
     struct TileGroup { int node_index; double cost; int n_stages; std::vector<SrMfmaTile> tiles; };
     std::vector<TileGroup> groups;
     std::vector<SrAux> level_aux;
-    if (L == 1 && g->stage_folded) level_aux = stage_aux;
+    if (L == 1 && g->stage_mode == 0) level_aux = stage_aux;
+    if (L == F && g->stage_mode == 1)
+      for (SrAux it : stage_aux) { it.c = 1; level_aux.push_back(it); }
 
     for (int v = 0; v < g->n_nodes; ++v) {
       NodeRt& n = g->nodes[v];
@@ -1080,7 +1090,7 @@ sr_status finalize(sr_graph* g) {
   g->heads_host = hd;
   g->lds_bytes = std::max(g->lds_bytes, g->aux_smem_bytes);
 
-  int launches = g->stage_folded ? 0 : 1;
+  int launches = g->stage_mode == 2 ? 1 : 0;
   for (int L = 1; L <= F; ++L) {
     const LevelPlan& lp = g->levels[L];
     const bool has_tiles = lp.n_tiles > 0, has_blocks = lp.n_blocks > 0;
@@ -1121,6 +1131,16 @@ bool record_needs_copy(const sr_graph* g) {
   return true;
 }
 
+// Start of a call that computes frames: the per-call values go into the device context, and a graph
+// whose input staging runs one frame ahead gets the call's first frame staged here.
+sr_status begin_frames(sr_graph* g, const SrCtx& c) {
+  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  if (g->stage_mode == 1)
+    SR_HIP(g, sr_launch_aux(g->stream, g->ctx, g->aux + g->stage_aux_begin, g->n_stage_aux, g->heads, g->head_edges,
+                            g->stage_nodes, g->aux_smem_bytes, g->dtype == SR_BF16, 0));
+  return SR_OK;
+}
+
 size_t split_slab_bytes(const sr_graph* g) {
   return (size_t)g->n_split_slots * (g->tile_version == 2 ? SR8_SPLIT_FLOATS : SR_SPLIT_FLOATS) * sizeof(float);
 }
@@ -1159,7 +1179,7 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft, SrSplitScratch
     const bool direct_launch = lp.n_blocks > 0 || (!aux_ride && lp.n_aux > 0);
     if (has_tiles || direct_launch) { last_level = L; last_is_direct = direct_launch; }
   }
-  if (!g->stage_folded) {
+  if (g->stage_mode == 2) {
     SR_HIP(g, mark(0));
     SR_HIP(g, sr_launch_aux(s, g->ctx, g->aux + g->stage_aux_begin, g->n_stage_aux, g->heads, g->head_edges, g->stage_nodes,
                             g->aux_smem_bytes, bf16, 0));
@@ -1651,7 +1671,11 @@ sr_status sr_frame_step(sr_graph* g, const void* const* inputs_t) {
     c.in_stride[i] = 0;
   }
   c.out_ptr = nullptr;
-  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  c.in_last = (int32_t)(g->host_frame + 1);   // the frame computed now is the last one with input
+  {
+    sr_status st = begin_frames(g, c);
+    if (st != SR_OK) return st;
+  }
   return run_frames(g, 1);
 }
 
@@ -1673,6 +1697,7 @@ sr_status sr_frame_step_static(sr_graph* g, const void* const* inputs_t) {
     c.in_stride[i] = 0;
   }
   c.out_ptr = nullptr;
+  c.in_last = (int32_t)(g->host_frame + 1);
   SrSplitScratch split{nullptr, nullptr};
   if (g->n_split_slots > 0) {
     void* base = nullptr;
@@ -1683,8 +1708,9 @@ sr_status sr_frame_step_static(sr_graph* g, const void* const* inputs_t) {
     // (a fill kernel, not a memset: the caller may be capturing the stream)
     SR_HIP(g, sr_launch_fill_zero(g->stream, split.counters, (size_t)g->n_split_slots * sizeof(int32_t)));
   }
-  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
-  sr_status st = enqueue_frame(g, true, nullptr, split);   // plain launches: nothing is captured or instantiated
+  sr_status st = begin_frames(g, c);
+  if (st != SR_OK) return st;
+  st = enqueue_frame(g, true, nullptr, split);   // plain launches: nothing is captured or instantiated
   if (st != SR_OK) return st;
   g->host_frame += 1;
   return SR_OK;
@@ -1707,6 +1733,7 @@ sr_status sr_rollout(sr_graph* g, const void* const* inputs, int32_t T, int32_t 
     c.in_stride[i] = (int64_t)g->batch * d.height * d.width * d.channels * (int64_t)elem_size(g);
   }
   c.in_base = 0;    // frame t reads inputs[t]
+  c.in_last = T;
   c.out_base = 1;   // frame t is recorded in slot t-1
   {
     sr_status st2 = set_record_node(g, outputs ? out_node : -1);
@@ -1717,7 +1744,8 @@ sr_status sr_rollout(sr_graph* g, const void* const* inputs, int32_t T, int32_t 
     c.out_ptr = outputs;
     c.out_stride = (int64_t)g->batch * d.height * d.width * d.channels * (int64_t)elem_size(g);
   }
-  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  st = begin_frames(g, c);
+  if (st != SR_OK) return st;
   return run_frames(g, T);
 }
 
@@ -1757,9 +1785,11 @@ sr_status sr_frame_step_timed(sr_graph* g, const void* const* inputs_t, float* k
     if (!inputs_t[i]) return gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
     c.in_ptr[i] = inputs_t[i];
   }
-  SR_HIP(g, sr_launch_set_ctx(g->stream, g->ctx, c, 0));
+  c.in_last = (int32_t)(g->host_frame + 1);
+  sr_status st = begin_frames(g, c);
+  if (st != SR_OK) return st;
   FrameTimer ft;
-  sr_status st = ensure_split_scratch(g);
+  st = ensure_split_scratch(g);
   if (st != SR_OK) return st;
   st = enqueue_frame(g, false, &ft, SrSplitScratch{g->split_scratch, g->split_counters});
   hipError_t he = hipStreamSynchronize(g->stream);

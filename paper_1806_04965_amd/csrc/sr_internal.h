@@ -17,6 +17,8 @@ struct SrCtx {
   int32_t in_base;    // input frame read = in_ptr[i] + (frame - in_base) * in_stride[i]
   int32_t out_base;   // output slot = frame - out_base
   int32_t done;       // workgroups of the frame's last launch that have finished (returns to 0)
+  int32_t in_last;    // last frame for which the caller has given input; staging of a later frame is skipped
+  int32_t pad_;
   const void* in_ptr[SR_MAX_INPUTS];
   int64_t in_stride[SR_MAX_INPUTS];   // bytes between consecutive frames (0: always the same buffer)
   void* out_ptr;                      // may be null
@@ -154,7 +156,8 @@ struct SrStageNode {
 
 // work items other than tiles and direct blocks that ride along in a level's launch
 #define SR_AUX_HEAD 1        // a = head index, b = image, c = pixel slab
-#define SR_AUX_STAGE 2       // a = input node index (in stage order), b = chunk of SR_STAGE_CHUNK pixels
+#define SR_AUX_STAGE 2       // a = input node index (in stage order), b = chunk of SR_STAGE_CHUNK pixels,
+                             // c = 0: this frame's input, 1: the next frame's (rides in a frame's last launch)
 #define SR_STAGE_CHUNK 1024
 #define SR_AUX_THREADS 256   // threads that work on an auxiliary item: a whole workgroup, or the first 256 of an 8-wave one
 struct SrAux {

@@ -121,11 +121,14 @@ __global__ void sr_record_output_kernel(const SrCtx* __restrict__ ctx, const T* 
 // input staging: state[frame & 1] of an input node := this frame's input, channel pitch C -> Cp;
 // one item covers SR_STAGE_CHUNK pixels, one pixel per thread and pass, 16-byte stores when the
 // stored pixel is a whole number of them
+// `ahead` = 1 stages the NEXT frame's input (into the copy that frame will be read from) while the
+// current frame's last launch runs: a pattern whose input edges do not bridge needs frame t's input
+// in place before frame t's first launch.  Frames the caller has given no input for are skipped.
 template <typename T>
-__device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, const SrStageNode& nd, int chunk) {
-  const int frame = ctx->frame;
+__device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, const SrStageNode& nd, int chunk, int ahead) {
+  const int frame = ctx->frame + ahead;
   const char* base = (const char*)ctx->in_ptr[nd.input_slot];
-  if (base == nullptr) return;
+  if (base == nullptr || frame > ctx->in_last) return;
   const T* in = (const T*)(base + (int64_t)(frame - ctx->in_base) * ctx->in_stride[nd.input_slot]);
   T* out = (T*)nd.state[frame & 1];
   const int end = min(nd.elems_px, (chunk + 1) * SR_STAGE_CHUNK);
@@ -327,7 +330,7 @@ __device__ __forceinline__ void sr_aux_item(const SrCtx* __restrict__ ctx, const
                                             const SrHeadEdge* __restrict__ head_edges,
                                             const SrStageNode* __restrict__ stage_nodes, float* smem, int vec_floats) {
   if (it.kind == SR_AUX_HEAD) sr_head_item<T>(ctx, heads[it.a], head_edges, it.b, it.c, smem, vec_floats);
-  else if (it.kind == SR_AUX_STAGE) sr_stage_item<T>(ctx, stage_nodes[it.a], it.b);
+  else if (it.kind == SR_AUX_STAGE) sr_stage_item<T>(ctx, stage_nodes[it.a], it.b, it.c);
 }
 
 // ---------------------------------------------------------------------------

@@ -76,20 +76,24 @@ def run_full(g, T, check_frames, seed=0):
             worst_free = max(worst_free, max(errs))
             print(f"[full] {g.name} frame {t}: all {n_nodes} nodes free-running, worst max-abs-rel {max(errs):.2e}", flush=True)
             forced = forced_step(dev, g, xd, X_prev, t)
-            flips, steps = [], []
+            flips, steps, later = [], [], [0.0]
             for v in range(n_nodes):
-                if g.dtype == "bf16":
+                if g.dtype == "bf16" and info["levels"][v] <= 1:
+                    # inputs, and the nodes of the frame's first update step (all nodes under the streaming
+                    # pattern): computed from identical stored values on both sides
                     f, s = one_step_check(forced[v], X[v], f"{g.name} teacher-forced frame {t} node {v}")
                     flips.append(f)
                     steps.append(s)
                 else:
+                    # float graphs; later update steps of a non-streaming frame (they read this frame's
+                    # results, which already carry the device's own roundings)
                     ev = max_abs_rel(forced[v], X[v])
-                    assert ev <= 2e-5, (g.name, "teacher-forced, frame", t, "node", v, ev)
-                    flips.append(ev)
-                    steps.append(0.0)
-            worst_flips = max(worst_flips, max(flips))
-            print(f"[full] {g.name} frame {t}: teacher-forced frame, all nodes within one bf16 step; "
-                  f"largest fraction of differing elements {max(flips):.2e}, largest error {max(steps):.2f} steps", flush=True)
+                    assert ev <= (2e-5 if g.dtype == "f32" else tol), (g.name, "teacher-forced, frame", t, "node", v, ev)
+                    later.append(ev)
+            worst_flips = max(worst_flips, max(flips + [0.0]))
+            print(f"[full] {g.name} frame {t}: teacher-forced frame, first-update-step nodes within one bf16 step; "
+                  f"largest fraction of differing elements {max(flips + [0.0]):.2e}, largest error {max(steps + [0.0]):.2f} steps; "
+                  f"other nodes max-abs-rel {max(later):.2e}", flush=True)
         X_prev = X
     dev.close()
     print(f"[full] {g.name}: T={T}, free-running worst max-abs-rel {worst_free:.3e} (tol {tol}), "
