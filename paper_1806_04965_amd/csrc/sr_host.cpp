@@ -196,6 +196,8 @@ struct sr_graph {
   SrStage8* stage8 = nullptr;
   int32_t* plan_index = nullptr;
   int32_t* plan_tables = nullptr;
+  SrTap* tap_table = nullptr;
+  SrPlane4* planes4 = nullptr;
   float* split_scratch = nullptr;
   size_t split_scratch_bytes = 0;
   int32_t* split_counters = nullptr;
@@ -362,8 +364,11 @@ void fill_unread_positions(std::vector<int32_t>* out, size_t begin, size_t end) 
     if ((*out)[i] == -2) (*out)[i] = (i > begin) ? (*out)[i - 1] : -1;
 }
 
-// Direct-to-LDS plan of one (tile, edge): for every 16-byte LDS position the byte offset of its
-// source relative to (image b0, source row iy_first), or -1 (zero padding).
+// Direct-to-LDS plan of one (tile, plane): for every 16-byte LDS position the byte offset of its
+// source relative to (image b0, the source row that the tile's first patch row stands for), or -1
+// (zero padding).  A plane holds the padded source rows q = pr (mod PR) as patch rows (q - pr) / PR
+// and, if its columns are split as well, the padded columns px = pc (mod stride) as slots
+// (px - pc) / stride; an unsplit row keeps all columns, column-phase major.
 void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows& r) {
   const int CH1 = m.KC / 8 + 1, CH = CH1 - 1;
   const int RPB16 = m.RPB / 16;
@@ -371,11 +376,18 @@ void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows&
   const int64_t n_pos = NQ * RPB16;
   const int64_t padded = (n_pos + 255) / 256 * 256;
   out->assign((size_t)padded, -2);
-  const int64_t iy_first = (r.oy0 / m.up) * m.stride - m.pad;
+  const int64_t row_first = r.Q0 - r.b0 * m.PHr;                 // patch row of the tile's first row, in its image
+  const int64_t iy_first = row_first * m.PRmul + m.r0;
   for (int64_t q = 0; q < NQ; ++q) {
-    const int64_t Qg = r.Q0 + q, b = Qg / m.PH, iy = Qg % m.PH - m.pad;
+    const int64_t Qg = r.Q0 + q, b = Qg / m.PHr, iy = (Qg % m.PHr) * m.PRmul + m.r0;
     for (int col = 0; col < m.RP; ++col) {
-      const int phase = col / m.PWs, px = (col % m.PWs) * m.stride + phase;
+      int px;
+      if (m.PC == 1) {
+        const int phase = col / m.PWs;
+        px = (col % m.PWs) * m.stride + phase;
+      } else {
+        px = col * m.stride + m.pc;
+      }
       if (px >= m.PW) continue;
       const int ix = px - m.pad;
       const bool valid = iy >= 0 && iy < m.Hs && ix >= 0 && ix < m.Ws;
@@ -389,7 +401,101 @@ void build_plan(std::vector<int32_t>* out, const SrMfmaEdge& m, const PatchRows&
   fill_unread_positions(out, 0, out->size());
 }
 
-// Does the 4-wave tile kernel have a tile shape for node v whose source patches fit its LDS budget?
+// The planes an edge is cut into for a row split PR and column split PC (each 1 or the stride), and
+// what the tile kernel needs to know of each; KC, RPB and the tap table are filled in by the caller.
+struct PlaneGeom {
+  int pr, pc, PHr, lgRS, ta_max, RP, ntaps;
+  std::vector<SrTap> taps;   // here a = tap row offset in patch rows, b = tap slot offset (bytes are formed once RPB and SP are known)
+  std::vector<int> tap_id;   // ti * kw + tj of every tap, in the plane's tap order
+};
+std::vector<PlaneGeom> edge_planes(int kh, int kw, int s, int PH, int PW, int PR, int PC) {
+  std::vector<PlaneGeom> planes;
+  const int PWs = (PW + s - 1) / s;
+  const int lgs = (s == 1) ? 0 : (s == 2 ? 1 : 2);
+  for (int pr = 0; pr < PR; ++pr)
+    for (int pc = 0; pc < PC; ++pc) {
+      PlaneGeom pg;
+      pg.pr = pr; pg.pc = pc;
+      pg.PHr = (PR == 1) ? PH : (PH - pr + s - 1) / s;
+      pg.lgRS = (PR == 1) ? lgs : 0;
+      pg.RP = (PC == 1) ? s * PWs : (PW - pc + s - 1) / s;
+      pg.ta_max = 0;
+      for (int ti = 0; ti < kh; ++ti) {
+        if (ti % PR != pr) continue;
+        const int ta = (PR == 1) ? ti : (ti - pr) / s;
+        for (int tj = 0; tj < kw; ++tj) {
+          if (tj % PC != pc) continue;
+          const int tb = (PC == 1) ? (tj % s) * PWs + tj / s : (tj - pc) / s;
+          pg.taps.push_back(SrTap{ta, tb});
+          pg.tap_id.push_back(ti * kw + tj);
+          pg.ta_max = std::max(pg.ta_max, ta);
+        }
+      }
+      pg.ntaps = (int)pg.taps.size();
+      if (pg.ntaps > 0 && pg.PHr > 0 && pg.RP > 0) planes.push_back(pg);
+    }
+  return planes;
+}
+
+int64_t max_plane_rows(const sr_graph* g, int v, const EdgeRt& e, int BM, const PlaneGeom& pg) {
+  const sr_node_desc& dn = g->nodes[v].d;
+  const int HoWo = dn.height * dn.width;
+  const int64_t M = (int64_t)g->batch * HoWo;
+  int64_t worst = 0;
+  for (int64_t m0 = 0; m0 < M; m0 += BM) {
+    PatchRows r = patch_rows(m0, std::min<int64_t>(m0 + BM, M) - 1, HoWo, dn.width, pg.PHr, 1 << pg.lgRS, e.d.upsample, pg.ta_max + 1);
+    worst = std::max(worst, r.Q1 - r.Q0 + 1);
+  }
+  return worst;
+}
+
+// How an edge is staged by the 4-wave kernel: the split (PR, PC) and the channels per stage KC.
+// Every stage costs a fixed latency (its loads are issued and waited for in one burst) plus the time
+// its patch takes through the compute unit's vector memory path, which moves whole 128-byte lines:
+// a stage that takes KC * 2 bytes of a pixel's min(128, Csp * 2) pays for the whole line.  The
+// cheapest combination wins (GTSRB-shaped graph: the stride-2 edges from 64-channel 48x48 states go
+// from four 16-channel stages that each touch every line to four phase planes of whole lines, 424 ->
+// 406 us per frame; the hi-res graph keeps unsplit 32-channel stages, fewer of them).  KC = 0: no
+// combination fits the LDS budget.
+struct EdgeStaging { int PR = 1, PC = 1, KC = 0; };
+EdgeStaging choose_staging(const sr_graph* g, int v, const EdgeRt& e, int BM, int lds_cap) {
+  const NodeRt& n = g->nodes[v];
+  const NodeRt& sn = g->nodes[e.d.src];
+  const int s = e.d.stride, PH = sn.d.height + 2 * e.d.pad, PW = sn.d.width + 2 * e.d.pad;
+  constexpr double kStageCycles = 2500.0, kLineBytesPerCycle = 64.0;
+  EdgeStaging best;
+  double best_cost = 0;
+  std::vector<std::pair<int, int>> splits = {{1, 1}};
+  if (s > 1) { splits.push_back({s, 1}); splits.push_back({s, s}); }
+  for (const auto& sp : splits) {
+    const std::vector<PlaneGeom> planes = edge_planes(e.d.kh, e.d.kw, s, PH, PW, sp.first, sp.second);
+    for (int cand : {64, 32, 16}) {
+      if (sn.Cp % cand != 0) continue;
+      bool fits = true;
+      double bytes = 0;
+      for (const PlaneGeom& pg : planes) {
+        const int pitch = row_pitch16(pg.RP, cand / 8 + 1, 1 << pg.lgRS, e.d.upsample, n.d.width);
+        const int64_t b = max_plane_rows(g, v, e, BM, pg) * pitch * 16;
+        if (b > lds_cap) fits = false;
+        bytes += (double)b;
+      }
+      if (!fits) continue;
+      const double eff = std::min(1.0, cand * 2.0 / std::min(128, sn.Cp * 2));
+      const int chunks = sn.Cp / cand;
+      const double cost = chunks * ((double)planes.size() * kStageCycles + bytes / eff / kLineBytesPerCycle);
+      if (best.KC == 0 || cost < best_cost) {
+        best_cost = cost;
+        best.PR = sp.first; best.PC = sp.second; best.KC = cand;
+      }
+      break;   // smaller KC of the same split: never better
+    }
+  }
+  return best;
+}
+
+// Does the 4-wave tile kernel have a tile shape for node v whose UNSPLIT source patches fit its LDS
+// budget?  (Decides the default tile kernel: graphs with edges of a large stride onto small images
+// go to the 8-wave kernel, whose stages are cut by row phase throughout.)
 bool four_wave_kernel_fits(const sr_graph* g, int v, int lds_cap) {
   const NodeRt& n = g->nodes[v];
   const int Cout = n.d.channels;
@@ -517,6 +623,8 @@ sr_status finalize(sr_graph* g) {
   std::vector<SrHead> hd;
   std::vector<SrHeadEdge> he;
   std::vector<int32_t> plan_index, plan_tables, plan_tmp;   // per (tile, edge): offset of its plan
+  std::vector<SrTap> tap_table;                             // 4-wave kernel: taps of every plane
+  size_t tap_mark = 0;
   std::unordered_map<uint64_t, std::vector<int>> plan_seen;
   g->levels.assign(F + 1, LevelPlan());
   const int lds_cap = sr_mfma_max_lds_bytes();
@@ -558,7 +666,10 @@ sr_status finalize(sr_graph* g) {
     lp.tile_begin = (int)mt.size();
     lp.block_begin = (int)db.size();
     lp.head_begin = (int)hd.size();
-    struct TileGroup { int node_index; double cost; int n_stages; std::vector<SrMfmaTile> tiles; };
+    struct TileGroup {
+      int node_index; double cost; int n_stages; std::vector<SrMfmaTile> tiles;
+      std::vector<int> nchunks;   // 4-wave kernel: stages (channel chunks) of every plane of the node, in order
+    };
     std::vector<TileGroup> groups;
     std::vector<SrAux> level_aux;
     if (L == 1 && g->stage_mode == 0) level_aux = stage_aux;
@@ -782,6 +893,7 @@ sr_status finalize(sr_graph* g) {
         node.wn_tiles = wn_tiles;
         ksum = 0;
         ok = true;
+        tap_mark = tap_table.size();
         for (EdgeRt& e : g->edges) {
           if (e.d.dst != v) continue;
           const NodeRt& sn = g->nodes[e.d.src];
@@ -801,43 +913,53 @@ sr_status finalize(sr_graph* g) {
           m.PH = m.Hs + 2 * m.pad;
           m.PW = m.Ws + 2 * m.pad;
           m.PWs = (m.PW + m.stride - 1) / m.stride;
-          m.RP = m.stride * m.PWs;
           m.wstride8 = (Cout / 32) * 64;
           // padding positions read the zero bytes behind the source state, at 32-bit offsets
           if (sn.state_bytes + SR_ZERO_TAIL + (size_t)(e.d.pad + 1) * sn.d.width * sn.Cp * 2 >= ((size_t)1 << 31) ||
               (size_t)sn.Cp * 2 > SR_ZERO_TAIL) { ok = false; break; }
           m.src_bytes = (int32_t)sn.state_bytes;
-          const int64_t rows = max_patch_rows(g, v, e, BM);
-          int KC = 0;
-          for (int cand : {64, 32, 16}) {
-            const int pitch = row_pitch16(m.RP, cand / 8 + 1, m.stride, m.up, n.d.width);
-            // a patch must fit the LDS budget (= 20 plan positions for each of the 256 threads)
-            if (sn.Cp % cand == 0 && rows * pitch * 16 <= lds_cap) {
-              KC = cand;
-              m.RPB = pitch * 16;
-              break;
-            }
-          }
-          const int64_t imgs_per_tile = BM / ((int64_t)n.d.height * n.d.width) + 2;
           // the kernel packs (image - first image of the tile) into the top byte of a signed int
-          if (KC == 0 || imgs_per_tile > 127) { ok = false; break; }
-          m.KC = KC;
-          m.nchunk = sn.Cp / KC;
-          m.SP = KC * 2 + 16;
-          m.magicKW = (int32_t)((65536 + m.kw - 1) / m.kw);
-          for (int tap = 0; tap < m.kh * m.kw; ++tap)
-            if (((tap * m.magicKW) >> 16) != tap / m.kw) ok = false;
-          if (!ok) break;
-          g->lds_bytes = std::max<int>(g->lds_bytes, (int)((rows * m.RPB + 1023) / 1024 * 1024));   // whole 1 KiB instructions
+          const int64_t imgs_per_tile = BM / ((int64_t)n.d.height * n.d.width) + 2;
+          if (imgs_per_tile > 127 || m.kh * m.kw > 64) { ok = false; break; }
+          // how the edge is staged: unsplit, or cut into row planes, or into row x column planes
+          const EdgeStaging st = choose_staging(g, v, e, BM, lds_cap);
+          if (st.KC == 0) { ok = false; break; }
+          m.KC = st.KC;
+          m.nchunk = sn.Cp / st.KC;
+          m.SP = st.KC * 2 + 16;
+          m.PC = st.PC;
+          m.PRmul = st.PR;
+          const int k16_total = sn.Cp / 16;
+          for (const PlaneGeom& pg : edge_planes(m.kh, m.kw, m.stride, m.PH, m.PW, st.PR, st.PC)) {
+            SrMfmaEdge pm = m;
+            pm.pc = pg.pc;
+            pm.r0 = pg.pr - m.pad;
+            pm.PHr = pg.PHr;
+            pm.lgRS = pg.lgRS;
+            pm.ta_max = pg.ta_max;
+            pm.RP = pg.RP;
+            pm.ntaps = pg.ntaps;
+            pm.RPB = row_pitch16(pg.RP, st.KC / 8 + 1, 1 << pg.lgRS, m.up, n.d.width) * 16;
+            pm.imgB = (int32_t)((int64_t)m.Hs * m.Ws * m.Csp * 2);
+            pm.rowB = (int32_t)((int64_t)st.PR * m.Ws * m.Csp * 2);
+            pm.r0B = (int32_t)((int64_t)pm.r0 * m.Ws * m.Csp * 2);
+            pm.tap_begin = (int32_t)tap_table.size();
+            for (int t = 0; t < pg.ntaps; ++t)
+              tap_table.push_back(SrTap{pg.taps[t].a * pm.RPB + pg.taps[t].b * pm.SP, pg.tap_id[t] * k16_total * pm.wstride8});
+            const int64_t rows = max_plane_rows(g, v, e, BM, pg);
+            g->lds_bytes = std::max<int>(g->lds_bytes, (int)((rows * pm.RPB + 1023) / 1024 * 1024));   // whole 1 KiB instructions
+            me.push_back(pm);
+          }
           g->lds_bytes = std::max<int>(g->lds_bytes, 4 * 64 * (32 * wn_tiles * 2 + 16));
           ksum += (double)sn.Cp * m.kh * m.kw;
-          me.push_back(m);
         }
         if (ok) break;
         me.resize(node.edge_begin);
+        tap_table.resize(tap_mark);
         }
         if (!ok) {   // patch does not fit: this node goes the direct way
           me.resize(node.edge_begin);
+          tap_table.resize(tap_mark);
           n.kind = 2;
         } else {
           node.edge_count = (int)me.size() - node.edge_begin;
@@ -852,14 +974,17 @@ sr_status finalize(sr_graph* g) {
           {
             double cyc = 8000;
             for (int ei = 0; ei < node.edge_count; ++ei) {
-              const SrMfmaEdge& m = me[node.edge_begin + ei];
-              const double steps = (double)m.kh * m.kw * (m.KC / 16);
+              const SrMfmaEdge& m = me[node.edge_begin + ei];   // one plane of an edge
+              const double steps = (double)m.ntaps * (m.KC / 16);
               cyc += m.nchunk * (4500.0 + steps * 512.0 * wn_tiles / 2);
             }
             grp.cost = cyc;
           }
           int n_stages = 0;
-          for (int ei = 0; ei < node.edge_count; ++ei) n_stages += me[node.edge_begin + ei].nchunk;
+          for (int ei = 0; ei < node.edge_count; ++ei) {
+            n_stages += me[node.edge_begin + ei].nchunk;
+            grp.nchunks.push_back(me[node.edge_begin + ei].nchunk);
+          }
           grp.n_stages = n_stages;
           // channel tiles of one pixel tile are neighbours in the list (they share the source patch)
           for (int mi = 0; mi < n_mt; ++mi)
@@ -868,15 +993,19 @@ sr_status finalize(sr_graph* g) {
                 t.node = node_index;
                 t.m0 = mi * BM;
                 t.n0 = nt * BN;
-                t.plan_begin = (int)plan_index.size();
+                t.plan_begin = (int)plan_index.size() / 4;   // in SrPlanRef records
                 t.stage_begin = 0;
                 t.stage_end = n_stages;
                 t.split_slot = -1;
                 t.part = 1 << 16;
+                t.e_first = 0;
+                t.c_first = 0;
+                t.e_last = node.edge_count - 1;
+                t.c_end = me[node.edge_begin + node.edge_count - 1].nchunk;
                 for (int ei = 0; ei < node.edge_count; ++ei) {
                   const SrMfmaEdge& m = me[node.edge_begin + ei];
                   const PatchRows r = patch_rows(t.m0, std::min<int64_t>((int64_t)t.m0 + BM, M) - 1,
-                                                 n.d.height * n.d.width, n.d.width, m.PH, m.stride, m.up, m.kh);
+                                                 n.d.height * n.d.width, n.d.width, m.PHr, 1 << m.lgRS, m.up, m.ta_max + 1);
                   build_plan(&plan_tmp, m, r);
                   uint64_t h = 1469598103934665603ull ^ (uint64_t)(node.edge_begin + ei);
                   for (int32_t x : plan_tmp) h = (h ^ (uint32_t)x) * 1099511628211ull;
@@ -889,7 +1018,11 @@ sr_status finalize(sr_graph* g) {
                     plan_tables.insert(plan_tables.end(), plan_tmp.begin(), plan_tmp.end());
                     plan_seen[h].push_back(found);
                   }
+                  // SrPlanRef of this (tile, plane)
                   plan_index.push_back(found);
+                  plan_index.push_back((int32_t)((r.Q1 - r.Q0 + 1) * (m.RPB / 16)));
+                  plan_index.push_back(m.tap_begin);
+                  plan_index.push_back(m.ntaps);
                 }
                 grp.tiles.push_back(t);
               }
@@ -1020,6 +1153,19 @@ sr_status finalize(sr_graph* g) {
             tp.stage_end = (int)((int64_t)grp.n_stages * (p + 1) / parts);
             tp.split_slot = slot;
             tp.part = p | (parts << 16);
+            if (!grp.nchunks.empty()) {   // the same range as (plane, chunk) positions
+              int base = 0;
+              bool first_set = false;
+              for (int ei = 0; ei < (int)grp.nchunks.size(); ++ei) {
+                const int lo = std::max(tp.stage_begin - base, 0), hi = std::min(tp.stage_end - base, grp.nchunks[ei]);
+                if (lo < hi) {
+                  if (!first_set) { tp.e_first = ei; tp.c_first = lo; first_set = true; }
+                  tp.e_last = ei;
+                  tp.c_end = hi;
+                }
+                base += grp.nchunks[ei];
+              }
+            }
             cut.push_back(tp);
           }
         }
@@ -1067,6 +1213,29 @@ sr_status finalize(sr_graph* g) {
   if ((st = upload(g, &g->d_blocks, db)) != SR_OK) return st;
   if ((st = upload(g, &g->plan_index, plan_index)) != SR_OK) return st;
   if ((st = upload(g, &g->plan_tables, plan_tables)) != SR_OK) return st;
+  if ((st = upload(g, &g->tap_table, tap_table)) != SR_OK) return st;
+  if (g->tile_version != 2) {
+    std::vector<SrPlane4> p4(me.size());
+    auto lg2 = [](int v) { int l = 0; while ((1 << l) < v) ++l; return l; };
+    for (size_t i = 0; i < me.size(); ++i) {
+      const SrMfmaEdge& m = me[i];
+      SrPlane4& q = p4[i];
+      q.src[0] = m.src[0];
+      q.src[1] = m.src[1];
+      q.wpk = m.wpk;
+      q.flags = (m.bridge ? 1 : 0) | (m.lgRS << 8) | (lg2(m.up) << 16) | (lg2(m.KC / 16) << 24);
+      q.nchunk = m.nchunk;
+      q.PHr = m.PHr;
+      q.RPB = m.RPB;
+      q.imgB = m.imgB;
+      q.rowB = m.rowB;
+      q.r0B = m.r0B;
+      q.wstride8 = m.wstride8;
+      q.src_bytes = m.src_bytes;
+      q.pad_ = 0;
+    }
+    if ((st = upload(g, &g->planes4, p4)) != SR_OK) return st;
+  }
   if ((st = upload(g, &g->stage8, stage8)) != SR_OK) return st;
   if (g->n_split_slots > 0) {
     // arrival counters of the K-split tiles; the slabs themselves are allocated by the first frame
@@ -1079,6 +1248,8 @@ sr_status finalize(sr_graph* g) {
   for (SrMfmaNode& node : mn) {
     node.plan_index = g->plan_index;
     node.plan_tables = g->plan_tables;
+    node.tap_table = g->tap_table;
+    node.planes4 = g->planes4;
     node.stage_table = g->stage8;
   }
   if ((st = upload(g, &g->m_nodes, mn)) != SR_OK) return st;

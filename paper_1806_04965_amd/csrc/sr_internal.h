@@ -72,6 +72,49 @@ struct SrMfmaEdge {
   int32_t wstride8;      // 16-byte units between consecutive k16 blocks in wpk: (Cout/32)*64
   int32_t plan_slot;     // 8-wave kernel: position of this edge's first row phase in a tile's run of plan_index
   int32_t src_bytes;     // bytes of one copy of the source state; SR_ZERO_TAIL zero bytes follow it
+  // 4-wave kernel: a strided edge may be cut into phase planes -- the padded source rows q with
+  // q % PR == pr and columns px with px % PC == pc, together with the taps (ti, tj) of the same
+  // residues -- so that a stage's patch holds whole 128-byte lines of fewer pixels instead of a slice
+  // of every pixel.  Every plane is an entry of its own in the edge table, described in patch
+  // coordinates (an unsplit edge is the plane PR = PC = 1):
+  int32_t lgRS;          // log2 of patch rows per output row: log2(stride) if the rows are not split, else 0
+  int32_t PHr;           // patch rows per image
+  int32_t ta_max;        // largest tap row offset, in patch rows
+  int32_t PRmul, r0;     // source row of patch row r of an image: r * PRmul + r0 (negative or >= Hs: padding)
+  int32_t PC, pc;        // column split (1: all columns, column-phase major as described above) and residue
+  int32_t ntaps;         // taps of this plane
+  int32_t tap_begin;     // first entry of this plane in the node's tap table
+  int32_t imgB;          // bytes of one image of the source state: Hs * Ws * Csp * 2
+  int32_t rowB;          // source bytes from one patch row to the next: PRmul * Ws * Csp * 2
+  int32_t r0B;           // r0 * Ws * Csp * 2 (negative when the first patch row is padding)
+  int32_t pad2_;
+};
+
+// 4-wave kernel, per (tile, plane): what is needed to fetch the plane's plan and taps ahead of its descriptor
+struct SrPlanRef {
+  int32_t plan_at;     // offset of the plan in plan_tables
+  int32_t n_pos;       // 16-byte LDS positions of the patch
+  int32_t tap_begin;   // the plane's taps in the tap table
+  int32_t ntaps;
+};
+
+// 4-wave kernel: what the kernel reads of a plane, 16 dwords fetched by one scalar load
+struct SrPlane4 {
+  const void* src[2];    // source state, both copies
+  const void* wpk;       // packed weights of the edge
+  int32_t flags;         // bridge | lgRS << 8 | log2(upsample) << 16 | log2(KC / 16) << 24
+  int32_t nchunk;
+  int32_t PHr, RPB;
+  int32_t imgB, rowB, r0B;
+  int32_t wstride8;
+  int32_t src_bytes;
+  int32_t pad_;
+};
+
+// per tap of a plane: LDS byte offset of the tap's fragments relative to tap (0, 0) of the plane, and
+// the index (in 16-byte units) of the tap's first weight fragment in the packed weights
+struct SrTap {
+  int32_t a, b;
 };
 
 // 8-wave tile kernel: one stage = one channel chunk of one row phase of one edge.  A strided edge
@@ -89,7 +132,10 @@ struct SrMfmaNode {
   void* out[2];          // bf16 state [M][Cp]
   const float* bias;     // [Cout]
   const int32_t* plan_index;   // [tile.plan_begin + edge]: offset of that (tile, edge) plan in plan_tables
+                               // (4-wave kernel: SrPlanRef records, [tile.plan_begin + plane])
   const int32_t* plan_tables;  // per LDS position: source byte offset, or -1: padding (reads the zero tail of the state)
+  const SrTap* tap_table;      // 4-wave kernel: taps of every plane of every edge
+  const SrPlane4* planes4;     // 4-wave kernel: the edge table in the form the kernel loads (same indices)
   int32_t M;             // B*Ho*Wo
   int32_t Ho, Wo;
   int32_t Cout, Cp;
@@ -112,6 +158,9 @@ struct SrMfmaTile {
   int32_t stage_begin, stage_end;
   int32_t split_slot;  // index of part 0 of this tile in the launch's scratch / counter arrays (SrSplitScratch), -1: not split
   int32_t part;        // part index | number of parts << 16
+  // 4-wave kernel: the same stage range as (plane, chunk) positions in the node's edge table: the
+  // tile walks planes e_first..e_last, from chunk c_first of the first one to chunk c_end - 1 of the last
+  int32_t e_first, c_first, e_last, c_end;
 };
 
 // Where the parts of K-split tiles leave their accumulators during a launch; a kernel argument, so

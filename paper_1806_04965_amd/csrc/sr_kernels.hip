@@ -443,30 +443,40 @@ typedef const __attribute__((address_space(1))) bf16x8_t* sr_gfrag_ptr;   // glo
 struct SrEdgeK {
   const unsigned char* src;
   sr_gfrag_ptr wpk;
-  int Hs, Ws, Csp, kw, kh, ntaps, stride, lgs, lgup, pad, KC, lgK16, nchunk, PH, PWs, SP, RPB;
-  int magicKW, wstride8, k16_total, src_bytes;
+  int lgRS, lgup, lgK16, nchunk, PHr, RPB, imgB, rowB, r0B, wstride8, src_bytes;
 };
 
-__device__ __forceinline__ SrEdgeK sr_load_edge(const SrMfmaEdge* edges, int index, int cur) {
-  const __attribute__((address_space(4))) SrMfmaEdge* p =
-      (const __attribute__((address_space(4))) SrMfmaEdge*)(unsigned long long)(edges + index);
+typedef int sr_i32x16 __attribute__((ext_vector_type(16)));
+__device__ __forceinline__ SrEdgeK sr_load_edge(const __attribute__((address_space(4))) SrPlane4* planes, int index, int cur) {
+  // one 64-byte scalar load; everything the kernel derives from it is register arithmetic
+  const sr_i32x16 v = *(const __attribute__((address_space(4))) sr_i32x16*)(planes + index);
   SrEdgeK k;
-  const int bridge = p->bridge;
-  k.src = (const unsigned char*)p->src[bridge ? (cur ^ 1) : cur];
-  k.wpk = (sr_gfrag_ptr)(unsigned long long)p->wpk;
-  k.Hs = p->Hs; k.Ws = p->Ws; k.Csp = p->Csp;
-  k.kw = p->kw; k.kh = p->kh; k.ntaps = k.kh * k.kw;
-  k.stride = p->stride; k.lgs = (k.stride == 1) ? 0 : (k.stride == 2 ? 1 : 2);
-  const int up = p->up;
-  k.lgup = (up == 1) ? 0 : (up == 2 ? 1 : 2);
-  k.pad = p->pad;
-  k.KC = p->KC; k.lgK16 = (k.KC == 16) ? 0 : (k.KC == 32 ? 1 : 2);
-  k.nchunk = p->nchunk;
-  k.PH = p->PH; k.PWs = p->PWs; k.SP = p->SP; k.RPB = p->RPB;
-  k.magicKW = p->magicKW; k.wstride8 = p->wstride8;
-  k.k16_total = k.Csp >> 4;
-  k.src_bytes = p->src_bytes;
+  const int flags = v[6];
+  const int pick = (flags & 1) ? (cur ^ 1) : cur;
+  const unsigned lo = pick ? (unsigned)v[2] : (unsigned)v[0], hi = pick ? (unsigned)v[3] : (unsigned)v[1];
+  k.src = (const unsigned char*)(((unsigned long long)hi << 32) | lo);
+  k.wpk = (sr_gfrag_ptr)(((unsigned long long)(unsigned)v[5] << 32) | (unsigned)v[4]);
+  k.lgRS = (flags >> 8) & 0xff;
+  k.lgup = (flags >> 16) & 0xff;
+  k.lgK16 = (flags >> 24) & 0xff;
+  k.nchunk = v[7];
+  k.PHr = v[8];
+  k.RPB = v[9];
+  k.imgB = v[10]; k.rowB = v[11]; k.r0B = v[12];
+  k.wstride8 = v[13];
+  k.src_bytes = v[14];
   return k;
+}
+
+// what the tile needs of a plane ahead of its descriptor (SrPlanRef, scalar registers)
+struct SrRefK { int plan_at, n_pos, tap_begin, ntaps; };
+__device__ __forceinline__ SrRefK sr_load_ref(const __attribute__((address_space(4))) int* refs, int index) {
+  SrRefK r;
+  r.plan_at = refs[index * 4];
+  r.n_pos = refs[index * 4 + 1];
+  r.tap_begin = refs[index * 4 + 2];
+  r.ntaps = refs[index * 4 + 3];
+  return r;
 }
 
 // Direct-to-LDS staging.  The LDS patch is an array of 16-byte positions: row q (padded source
@@ -490,12 +500,12 @@ __device__ __forceinline__ const unsigned char* sr_uniform_ptr(const unsigned ch
 }
 
 __device__ __forceinline__ void sr_dma_plan(const __attribute__((address_space(1))) int* __restrict__ table,
-                                            int n_pos, int tid, int zero_off, int (&off)[SR_DMA_ITEMS]) {
+                                            int n_pos, int tid, int (&off)[SR_DMA_ITEMS]) {
 #pragma unroll
   for (int it = 0; it < SR_DMA_ITEMS; ++it) {
     int v = 0;
     if (it * 256 < n_pos) v = table[tid + it * 256];   // tables are padded to 256 entries
-    off[it] = (v == SR_DMA_ZERO) ? zero_off : v;
+    off[it] = v;                                        // SR_DMA_ZERO entries are resolved by the plane's set-up
   }
 }
 
@@ -516,18 +526,17 @@ __device__ __forceinline__ void sr_stage_dma(const unsigned char* __restrict__ b
 
 // k-step st of a stage = (tap, 16-channel block k inside the chunk).  The per-tap parts of the
 // offsets -- LDS byte offset of the tap's A fragments relative to tap (0,0), index of the tap's
-// first weight fragment -- are tabulated once per edge with one tap per lane (SrTaps); a step then
-// costs a shift, a mask and a lane read instead of a division and five multiplies.  This matters
+// first weight fragment -- are tabulated on the host per plane and held with one tap per lane
+// (SrTaps); a step then costs a shift, a mask and a lane read instead of a division and five multiplies.  This matters
 // when a wave has its SIMD to itself: a wave's own non-MFMA instructions do not overlap with its
 // MFMAs (only another wave's do), so every instruction of the step's bookkeeping costs MFMA time.
 struct SrTaps { int a; int b; };   // one tap per lane
-__device__ __forceinline__ SrTaps sr_tap_table(const SrEdgeK& e, int lane) {
-  const int tap = min(lane, e.ntaps - 1);
-  const int ti = (tap * e.magicKW) >> 16;
-  const int tj = tap - ti * e.kw;
+__device__ __forceinline__ SrTaps sr_tap_table(const SrRefK& r, const __attribute__((address_space(1))) SrTap* table,
+                                               int lane) {
+  const __attribute__((address_space(1))) SrTap* p = table + r.tap_begin + min(lane, r.ntaps - 1);
   SrTaps t;
-  t.a = ti * e.RPB + ((tj & (e.stride - 1)) * e.PWs + (tj >> e.lgs)) * e.SP;
-  t.b = tap * e.k16_total * e.wstride8;
+  t.a = p->a;
+  t.b = p->b;
   return t;
 }
 __device__ __forceinline__ int sr_step_aoff(const SrEdgeK& e, const SrTaps& t, int st) {
@@ -655,8 +664,8 @@ __device__ __forceinline__ bool sr_split_reduce(f32x16_t (&acc)[4][WN], const Sr
 template <int WN>
 __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
                                              const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
-                                             int tile_n0, int plan_begin, int stage_begin, int stage_end,
-                                             int split_slot, int part_info, unsigned char* lds,
+                                             int tile_n0, int plan_begin, int e_first, int c_first, int e_last,
+                                             int c_end, int split_slot, int part_info, unsigned char* lds,
                                              const SrSplitScratch& split) {
   const __attribute__((address_space(4))) SrMfmaNode* nd =
       (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
@@ -677,10 +686,12 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
   const int b_first = m_first / HoWo, oy_first = (m_first - b_first * HoWo) / Wo;
   const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / Wo;
   const int edge_begin = nd->edge_begin, edge_count = nd->edge_count;
-  const __attribute__((address_space(4))) int* plan_index =
-      (const __attribute__((address_space(4))) int*)(unsigned long long)nd->plan_index + plan_begin;
+  const __attribute__((address_space(4))) int* plan_index =      // SrPlanRef records of this tile's planes
+      (const __attribute__((address_space(4))) int*)(unsigned long long)nd->plan_index + plan_begin * 4;
   const __attribute__((address_space(1))) int* plan_tables =
       (const __attribute__((address_space(1))) int*)(unsigned long long)nd->plan_tables;
+  const __attribute__((address_space(1))) SrTap* tap_table =
+      (const __attribute__((address_space(1))) SrTap*)(unsigned long long)nd->tap_table;
 
   // pixel coordinates of this lane's 4 rows, packed: ox | oy << 12 | (image - first image) << 24;
   // rows past the end repeat the last pixel
@@ -702,32 +713,49 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
 
-  int stage_base = 0;   // index of the current edge's first stage among the node's stages
-  for (int ei = 0; ei < edge_count; ++ei) {
-    const SrEdgeK e = sr_load_edge(edges, edge_begin + ei, cur);
-    const int chunk_lo = max(stage_begin - stage_base, 0), chunk_hi = min(stage_end - stage_base, e.nchunk);
-    stage_base += e.nchunk;
-    if (chunk_lo >= chunk_hi) continue;   // this part of a K-split tile has no stage on this edge
-    const int row_first = (oy_first >> e.lgup) << e.lgs;          // first padded source row, in its image
-    const int Q0 = b_first * e.PH + row_first;
-    const int Q1 = b_last * e.PH + ((oy_last >> e.lgup) << e.lgs) + e.kh - 1;
-    const int n_pos = (Q1 - Q0 + 1) * (e.RPB >> 4);
+  // The tile walks the planes e_first..e_last of its node's edge table.  What a plane needs before its
+  // first stage can be issued -- its descriptor, its direct-to-LDS plan, its tap table -- is fetched
+  // while the previous plane's last stage computes: the descriptor (scalar loads) at the start of
+  // the previous plane, plan and taps (vector loads) behind the previous plane's last fill, into the
+  // registers that fill has just released.
+  const __attribute__((address_space(4))) SrPlane4* planes =
+      (const __attribute__((address_space(4))) SrPlane4*)(unsigned long long)nd->planes4 + edge_begin;
+  int ei = e_first;
+  SrRefK ref = sr_load_ref(plan_index, ei);
+  for (;;) {
+    // everything the plane's first stage needs goes out at once: plan and taps (vector loads, located by
+    // the plan reference fetched during the previous plane) and the descriptor (one scalar load)
     int dma_off[SR_DMA_ITEMS];
-    // plan offsets count from source row (row_first - pad) of image b_first
-    const long long base_off = ((long long)(b_first * e.Hs + row_first - e.pad) * e.Ws) * e.Csp * 2;
+    sr_dma_plan(plan_tables + ref.plan_at, ref.n_pos, tid, dma_off);
+    const SrTaps taps = sr_tap_table(ref, tap_table, lane);
+    const SrEdgeK e = sr_load_edge(planes, ei, cur);
+    const bool more = ei < e_last;
+    SrRefK ref_n = ref;
+    if (more) ref_n = sr_load_ref(plan_index, ei + 1);   // in flight during this plane's stages
+    const int chunk_lo = (ei == e_first) ? c_first : 0;
+    const int chunk_hi = (ei == e_last) ? c_end : e.nchunk;
+    const int row_first = (oy_first >> e.lgup) << e.lgRS;         // first patch row of the tile, in its image
+    const int n_pos = ref.n_pos;
+    const int NS = ref.ntaps << e.lgK16;
+    // plan offsets count from the source row that patch row row_first stands for, in image b_first;
+    // padding positions read the zero bytes behind the state
+    const long long base_off = (long long)b_first * e.imgB + (long long)row_first * e.rowB + e.r0B;
     const unsigned char* dma_base = e.src + base_off;
-    sr_dma_plan(plan_tables + plan_index[ei], n_pos, tid, (int)((long long)e.src_bytes - base_off), dma_off);
     // LDS byte address of the tap (0,0), k = 0 fragment of this lane's 4 rows
+    const int SP = (32 << e.lgK16) + 16;
     int abase[4];
 #pragma unroll
     for (int mi = 0; mi < 4; ++mi) {
       const int ox = pix[mi] & 0xfff, oy = (pix[mi] >> 12) & 0xfff, db = pix[mi] >> 24;
-      abase[mi] = (db * e.PH + ((oy >> e.lgup) << e.lgs) - row_first) * e.RPB + (ox >> e.lgup) * e.SP + (lane >> 5) * 16;
+      abase[mi] = (db * e.PHr + ((oy >> e.lgup) << e.lgRS) - row_first) * e.RPB + (ox >> e.lgup) * SP + (lane >> 5) * 16;
       asm volatile("" : "+v"(abase[mi]));   // keep it in a register: one add per k-step, not a re-derivation
     }
+    {
+      const int zero_off = (int)((long long)e.src_bytes - base_off);
+#pragma unroll
+      for (int it = 0; it < SR_DMA_ITEMS; ++it) dma_off[it] = (dma_off[it] == SR_DMA_ZERO) ? zero_off : dma_off[it];
+    }
     const sr_gfrag_ptr wlane = e.wpk + ntile0 * 64 + lane;
-    const SrTaps taps = sr_tap_table(e, lane);
-    const int NS = e.ntaps << e.lgK16;
     for (int chunk = chunk_lo; chunk < chunk_hi; ++chunk) {
       const sr_gfrag_ptr wchunk = wlane + (size_t)(chunk << e.lgK16) * e.wstride8;
       __syncthreads();   // everyone has finished reading the previous patch
@@ -739,13 +767,16 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
         for (int nj = 0; nj < WN; ++nj) bq[d][nj] = wchunk[boff + nj * 64];
       }
-      sr_stage_dma(dma_base + (size_t)chunk * e.KC * 2, lds, n_pos, tid, dma_off);
+      sr_stage_dma(dma_base + (size_t)(chunk << e.lgK16) * 32, lds, n_pos, tid, dma_off);
       asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // this thread's direct-to-LDS loads have landed
       __syncthreads();                                     // ... and everybody else's
       __builtin_amdgcn_s_setprio(3);   // k-steps go ahead of the other workgroup's set-up and issue on this SIMD
       sr_stage_compute<WN>(e, taps, lds, abase, wchunk, bq, acc, NS);
       __builtin_amdgcn_s_setprio(0);
     }
+    if (!more) break;
+    ref = ref_n;
+    ++ei;
   }
 
   // ---- K-split tiles: leave the accumulators in scratch; the part that arrives last adds all parts
@@ -827,12 +858,12 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
       // empty slot
     } else if (nodes[node_index].wn_tiles == 2)
       sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
-                      SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
-                      sr_lds, split);
+                      SR_UNIFORM(t.e_first), SR_UNIFORM(t.c_first), SR_UNIFORM(t.e_last), SR_UNIFORM(t.c_end),
+                      SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part), sr_lds, split);
     else
       sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
-                      SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
-                      sr_lds, split);
+                      SR_UNIFORM(t.e_first), SR_UNIFORM(t.c_first), SR_UNIFORM(t.e_last), SR_UNIFORM(t.c_end),
+                      SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part), sr_lds, split);
   } else {
     sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds, vec_floats);
   }
