@@ -78,6 +78,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-hipgraph", action="store_true")
     ap.add_argument("--tile-kernel", type=int, default=0, help="1: 4-wave tile kernel, 2: 8-wave tile kernel, 0: library default")
+    ap.add_argument("--option", action="append", default=[], metavar="KEY=VALUE",
+                    help="sr_graph_configure option by number, e.g. 5=0 (dependency-driven execution off)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known HBM traffic, for scaling "
                          "FETCH_SIZE / WRITE_SIZE counters)")
@@ -106,6 +108,9 @@ def main():
         opts[0] = 0
     if args.tile_kernel:
         opts[4] = args.tile_kernel
+    for kv in args.option:
+        k, v = kv.split("=")
+        opts[int(k)] = int(v)
     dev = sr.SrGraph(g, options=opts or None)
     dev.set_parameters(w, b)
     tdt = torch.bfloat16 if g.dtype == "bf16" else torch.float32

@@ -90,9 +90,17 @@ typedef enum {
   SR_OPT_FORCE_DIRECT = 1,  /* 1: every node is computed by the plain one-thread-per-output kernel (no MFMA); default 0 */
   SR_OPT_FRAMES_PER_GRAPH = 2, /* number of frames captured into one HIP graph for sr_rollout (default 8, >= 1) */
   SR_OPT_K_SPLIT = 3,          /* 1 (default): long tiles are cut along the contraction and reduced by the last part; 0: never */
-  SR_OPT_TILE_KERNEL = 4       /* tile kernel of bf16 graphs: 1 = 4 waves per workgroup, weights from registers;
+  SR_OPT_TILE_KERNEL = 4,      /* tile kernel of bf16 graphs: 1 = 4 waves per workgroup, weights from registers;
                                   2 = 8 waves, both operands through LDS, next stage loaded during the current one;
                                   0 (default) = 1 unless a node's source patches do not fit its LDS budget, then 2 */
+  SR_OPT_DATAFLOW = 5          /* dependency-driven execution of graphs whose nodes all run on the 4-wave tile kernel or as
+                                  head items: one launch covers every update step of a frame, and of several frames in
+                                  sr_rollout; a work item starts when the nodes it reads have completed the frame it
+                                  reads (Eq. 2: frame t - R(e) of the edge's source), not when a whole update step or
+                                  frame has -- consecutive frames overlap like the stages of a pipeline.
+                                  2 (default): for patterns with more than one update step per frame (F(R) > 1, Eq. 6);
+                                  1: whenever possible, also for the streaming pattern; 0: never (one launch per
+                                  update step) */
 } sr_option;
 
 /* ---------------------------------------------------------------------------
@@ -170,7 +178,9 @@ sr_status sr_graph_set_bias(sr_graph* g, int32_t node, const float* host_b, size
 sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value);
 
 /* Inference factor and tableau of the graph's pattern (as sr_analyze), plus the number of
- * kernel launches one frame takes (launches_per_frame, may be NULL). */
+ * kernel launches one frame takes (launches_per_frame, may be NULL): F(R) launches, one per update
+ * step, or 1 for a dependency-driven graph (SR_OPT_DATAFLOW), whose update steps are ordered by
+ * per-node completion counters inside the launch; sr_rollout then covers several frames per launch. */
 sr_status sr_graph_info(const sr_graph* g, int32_t* inference_factor, int32_t* levels,
                         int32_t* launches_per_frame);
 
@@ -243,6 +253,13 @@ sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfm
  * path): 1 = 4 waves per workgroup, 2 = 8 waves; 0 if the graph has no MFMA node (fp32 graphs,
  * SR_OPT_FORCE_DIRECT).  Plans the graph if that has not happened yet, as sr_graph_work does. */
 sr_status sr_graph_tile_kernel(const sr_graph* g, int32_t* tile_kernel);
+
+/* Health of a graph's device side.  dependency_driven (host, may be NULL): 1 if the graph runs
+ * dependency-driven (plans the graph if needed).  dependency_timeouts (host, may be NULL): waits
+ * for a node's completion counter that gave up at their spin limit since the last sr_reset; 0
+ * unless something is broken (results are undefined otherwise); synchronises with the stream.
+ * The waits implement the time index of Eq. 2 inside a launch. */
+sr_status sr_graph_health(sr_graph* g, int64_t* dependency_timeouts, int32_t* dependency_driven);
 
 /* Which kernel the planner gave each node of the frame update (App. A1.2 node map; plans the graph if
  * that has not happened yet): kinds[v] (host, n_nodes ints) =

@@ -17,7 +17,7 @@ EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_mo
            "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
            "sr_frame_step_static", "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
-           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
+           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_health", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
 
 
 class NodeDesc(C.Structure):
@@ -74,6 +74,7 @@ def load_library():
     lib.sr_graph_work.argtypes = [vp, P(C.c_double), P(i64), P(i64)]
     lib.sr_graph_tile_kernel.argtypes = [vp, P(i32)]
     lib.sr_graph_node_kernels.argtypes = [vp, P(i32)]
+    lib.sr_graph_health.argtypes = [vp, P(i64), P(i32)]
     lib.sr_graph_destroy.argtypes = [vp]
     lib.sr_graph_destroy.restype = None
     lib.sr_status_str.argtypes = [i32]
@@ -204,6 +205,12 @@ class SrGraph:
         k = C.c_int32()
         _check(self.lib, self.lib.sr_graph_tile_kernel(self.h, C.byref(k)), self.h)
         return k.value
+
+    def health(self):
+        """sr_graph_health: {'dependency_timeouts', 'dependency_driven'} (synchronises)."""
+        t, d = C.c_int64(), C.c_int32()
+        _check(self.lib, self.lib.sr_graph_health(self.h, C.byref(t), C.byref(d)), self.h)
+        return {"dependency_timeouts": t.value, "dependency_driven": bool(d.value)}
 
     def node_kernels(self):
         """sr_graph_node_kernels: per node 0 input, 1 / 2 tile kernel (4 / 8 waves), 3 one thread per output, 4 head."""

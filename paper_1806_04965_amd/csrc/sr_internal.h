@@ -18,11 +18,36 @@ struct SrCtx {
   int32_t out_base;   // output slot = frame - out_base
   int32_t done;       // workgroups of the frame's last launch that have finished (returns to 0)
   int32_t in_last;    // last frame for which the caller has given input; staging of a later frame is skipped
-  int32_t pad_;
+  int32_t dep_timeouts;   // dependency waits that gave up at their spin limit (stays 0 unless something is broken)
   const void* in_ptr[SR_MAX_INPUTS];
   int64_t in_stride[SR_MAX_INPUTS];   // bytes between consecutive frames (0: always the same buffer)
   void* out_ptr;                      // may be null
   int64_t out_stride;                 // bytes per recorded frame
+};
+
+// ---------------------------------------------------------------------------
+// Dependency-driven execution.  In a streaming rollout a node's update at frame t needs nothing but
+// its source nodes' states of frame t-1 (an edge with R(e) = 0: of frame t, computed at an earlier
+// update step).  A launch in this mode covers several frames and all update steps of each: every
+// work item (tile, head item, input-staging item) first waits until the nodes it depends on have
+// completed the frames it needs, and adds one to its own node's counter when its results are in
+// memory.  Work items are ordered so that every wait refers to items with a smaller workgroup index
+// (earlier frame, or earlier update step of the same frame), which the hardware has dispatched
+// before; waits are bounded by a spin limit all the same.
+struct SrDep {
+  int32_t node;    // graph node whose counter is read
+  int32_t units;   // work items of that node per frame
+  int32_t lag;     // the item at frame t needs units * (t - lag) completions (all of frame t - lag)
+  int32_t pad_;
+};
+
+#define SR_DONE_STRIDE 64
+struct SrFlow {
+  const SrDep* deps;   // null: no dependency tracking (one launch per update step, ordered by the stream)
+  int32_t* done;       // per graph node, SR_DONE_STRIDE ints apart (a memory line each: they are polled):
+                       // work items completed since the last reset (wraps; compared by difference)
+  int32_t spin_limit;  // polls before a wait gives up (and counts itself in SrCtx::dep_timeouts)
+  int32_t pad_;
 };
 
 // ---------------------------------------------------------------------------
@@ -90,14 +115,6 @@ struct SrMfmaEdge {
   int32_t pad2_;
 };
 
-// 4-wave kernel, per (tile, plane): what is needed to fetch the plane's plan and taps ahead of its descriptor
-struct SrPlanRef {
-  int32_t plan_at;     // offset of the plan in plan_tables
-  int32_t n_pos;       // 16-byte LDS positions of the patch
-  int32_t tap_begin;   // the plane's taps in the tap table
-  int32_t ntaps;
-};
-
 // 4-wave kernel: what the kernel reads of a plane, 16 dwords fetched by one scalar load
 struct SrPlane4 {
   const void* src[2];    // source state, both copies
@@ -109,6 +126,38 @@ struct SrPlane4 {
   int32_t wstride8;
   int32_t src_bytes;
   int32_t pad_;
+};
+
+// 4-wave kernel, per (tile, plane): what is needed to fetch the plane's plan and taps ahead of its descriptor
+struct SrPlanRef {
+  int32_t plan_at;     // offset of the plan in plan_tables
+  int32_t n_pos;       // 16-byte LDS positions of the patch
+  int32_t tap_begin;   // the plane's taps in the tap table
+  int32_t ntaps;
+};
+
+// 4-wave kernel: node and tile records in the form the kernel loads, 16 dwords each (one scalar load)
+struct SrNode4 {
+  void* out[2];          // bf16 state [M][Cp], both copies
+  const float* bias;     // [Cout rounded up to the tile width]
+  int32_t M, Ho, Wo, Cp, act;
+  int32_t waves_m, waves_n;
+  int32_t dep_begin, dep_count;   // what a tile of this node waits for (SrDep table)
+  int32_t gnode;                  // graph node id: index of this node's completion counter
+};
+
+struct SrTile4 {
+  int32_t node;          // < 0: empty slot (pads an XCD's run)
+  int32_t m0, n0;        // first output pixel and channel
+  int32_t ref_base;      // SrPlanRef of plane p of this tile: refs[ref_base + p]
+  int32_t p_first, p_last;   // planes walked (indices into the plane table)
+  int32_t chunks;        // first chunk of the first plane | (one past the last chunk of the last plane) << 16
+  int32_t split_slot;    // K-split: slot of part 0 in the launch's scratch, -1: not split
+  int32_t part;          // part index | number of parts << 16
+  int32_t shape;         // 32-channel tiles per wave (1 or 2) | (last image - first image) << 8
+  int32_t b_first;       // image of the first pixel
+  int32_t rows;          // output row of the first pixel | output row of the last pixel << 16
+  SrPlanRef ref0;        // plan reference of plane p_first
 };
 
 // per tap of a plane: LDS byte offset of the tap's fragments relative to tap (0, 0) of the plane, and
@@ -190,6 +239,7 @@ struct SrHead {
   int32_t edge_begin, edge_count;
   int32_t act, B, Cout, Cp;
   int32_t splits, record;   // record: also write the result to the rollout output
+  int32_t dep_begin, dep_count, gnode, pad_;   // dependency-driven launches: see SrDep
 };
 
 #define SR_HEAD_MAX_K 12288   // longest input vector of a head edge (floats held in LDS)
@@ -201,6 +251,7 @@ struct SrStageNode {
   int32_t elems_px;   // B*H*W
   int32_t C, Cp;
   int32_t input_slot; // index into SrCtx::in_ptr
+  int32_t dep_begin, dep_count, gnode, pad_;   // dependency-driven launches: see SrDep
 };
 
 // work items other than tiles and direct blocks that ride along in a level's launch
@@ -227,8 +278,16 @@ hipError_t sr_launch_direct(hipStream_t s, SrCtx* ctx, const SrDirectNode* nodes
                             const SrDirectBlock* blocks, int n_blocks, int bf16, int batch, const SrAux* aux, int n_aux,
                             const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
                             int smem_bytes, int is_last);
-hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
-                          const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
+struct SrTables4 {   // 4-wave kernel: the graph's device tables
+  const SrNode4* nodes;
+  const SrPlane4* planes;
+  const SrPlanRef* refs;
+  const int32_t* plan_tables;
+  const SrTap* tap_table;
+};
+// frames > 1 or flow.deps != null: dependency-driven launch covering `frames` frames (grid y)
+hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, SrTables4 tables, SrFlow flow, int frames,
+                          const SrTile4* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
                           const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
                           int aux_smem_bytes, int is_last, SrSplitScratch split);
 int sr_mfma_max_lds_bytes();

@@ -38,12 +38,27 @@ __device__ __forceinline__ uint16_t float_to_bf16_bits(float f) {
 
 template <typename T> struct Store;
 #define SR_GLOBAL __attribute__((address_space(1)))
+// load / store: ordinary accesses.  aload / astore: agent-scope accesses (a store goes through to
+// memory, a load does not take a stale line from this XCD's L2) for node states, which in a
+// dependency-driven launch are produced and consumed by workgroups on different XCDs.
 template <> struct Store<float> {
+  static __device__ __forceinline__ float aload(const float* p) {
+    return __uint_as_float(__hip_atomic_load((const unsigned*)p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  }
+  static __device__ __forceinline__ void astore(float* p, float v) {
+    __hip_atomic_store((unsigned*)p, __float_as_uint(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   static __device__ __forceinline__ float load(const float* p) { return *p; }
   static __device__ __forceinline__ float gload(const SR_GLOBAL float* p) { return *p; }
   static __device__ __forceinline__ void store(float* p, float v) { *p = v; }
 };
 template <> struct Store<uint16_t> {
+  static __device__ __forceinline__ float aload(const uint16_t* p) {
+    return bf16_bits_to_float(__hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+  }
+  static __device__ __forceinline__ void astore(uint16_t* p, float v) {
+    __hip_atomic_store(p, float_to_bf16_bits(v), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
   static __device__ __forceinline__ float load(const uint16_t* p) { return bf16_bits_to_float(*p); }
   static __device__ __forceinline__ float gload(const SR_GLOBAL uint16_t* p) { return bf16_bits_to_float(*p); }
   static __device__ __forceinline__ void store(uint16_t* p, float v) { *p = float_to_bf16_bits(v); }
@@ -54,9 +69,12 @@ template <> struct Store<uint16_t> {
 // ---------------------------------------------------------------------------
 __global__ void sr_set_ctx_kernel(SrCtx* ctx, SrCtx v, int set_frame) {
   if (threadIdx.x == 0 && blockIdx.x == 0) {
-    int frame = ctx->frame;
+    const int frame = ctx->frame, timeouts = ctx->dep_timeouts;
     *ctx = v;
-    if (!set_frame) ctx->frame = frame;
+    if (!set_frame) {   // a reset clears both; any other call keeps them
+      ctx->frame = frame;
+      ctx->dep_timeouts = timeouts;
+    }
   }
 }
 
@@ -65,8 +83,9 @@ __global__ void sr_tick_kernel(SrCtx* ctx) {
 }
 
 // Called by every workgroup of the last launch of a frame once its work is stored: the workgroup
-// that arrives last advances the frame counter (all others have read it long before).
-__device__ __forceinline__ void sr_block_done(SrCtx* ctx, int n_blocks) {
+// that arrives last advances the frame counter by the frames the launch covers (all others have
+// read it long before).
+__device__ __forceinline__ void sr_block_done(SrCtx* ctx, int n_blocks, int frames) {
   // no fence: the counter only orders "everyone has read the frame counter" (done at kernel start)
   // before its update, and the next launch sees the update through the kernel boundary
   __syncthreads();
@@ -74,9 +93,78 @@ __device__ __forceinline__ void sr_block_done(SrCtx* ctx, int n_blocks) {
     const int old = __hip_atomic_fetch_add(&ctx->done, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     if (old == n_blocks - 1) {
       ctx->done = 0;
-      ctx->frame = ctx->frame + 1;
+      ctx->frame = ctx->frame + frames;
     }
   }
+}
+
+// Dependency-driven launches: wait until every node this work item depends on has completed the
+// frames it needs.  The first wave polls, one dependency per lane, sleeping between polls; the other
+// waves wait at the barrier.  Counters wrap, so they are compared by signed difference.  The wait is
+// bounded: past the spin limit it gives up and reports itself (results are then undefined, the
+// launch still ends).
+struct SrDepPoll {   // a dependency wait whose first poll is in flight
+  const int* counter;
+  int need, first, count;
+};
+
+// first poll goes out (the caller has other things to do before it needs the answer)
+__device__ __forceinline__ SrDepPoll sr_deps_begin(const SrFlow& flow, int begin, int count, int frame) {
+  SrDepPoll w;
+  w.counter = flow.done;
+  w.need = 0;
+  w.first = 0;
+  w.count = (flow.deps == nullptr) ? 0 : count;
+  if (w.count > 0 && threadIdx.x < (unsigned)w.count) {
+    const SrDep d = flow.deps[begin + threadIdx.x];
+    w.counter = flow.done + d.node * SR_DONE_STRIDE;
+    w.need = d.units * (frame - d.lag);
+    w.first = __hip_atomic_load(w.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  return w;
+}
+
+// ... and the wait itself
+__device__ __forceinline__ void sr_deps_finish(const SrFlow& flow, const SrDepPoll& w, SrCtx* ctx) {
+  if (w.count == 0) return;
+  if (threadIdx.x < 64) {
+    const int lane = threadIdx.x;
+    int seen = w.first;
+    int spins = 0;
+    for (;;) {
+      const int ok = (lane >= w.count) || (seen - w.need) >= 0;
+      if (__builtin_amdgcn_ballot_w64(!ok) == 0) break;
+      // give up at the spin limit -- or at once if any wait of this graph has given up before, so that
+      // a broken dependency costs one limit, not one per work item
+      int failed = 0;
+      if ((spins & 63) == 63) failed = __hip_atomic_load(&ctx->dep_timeouts, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (++spins > flow.spin_limit || failed > 0) {
+        if (lane == 0) __hip_atomic_fetch_add(&ctx->dep_timeouts, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        break;
+      }
+      // back off: the counters are shared by every waiting workgroup of the chip
+      if (spins < 16) __builtin_amdgcn_s_sleep(8);
+      else if (spins < 64) __builtin_amdgcn_s_sleep(32);
+      else __builtin_amdgcn_s_sleep(127);
+      if (lane < w.count) seen = __hip_atomic_load(w.counter, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+  }
+  __syncthreads();
+}
+
+__device__ __forceinline__ void sr_wait_deps(const SrFlow& flow, int begin, int count, int frame, SrCtx* ctx) {
+  const SrDepPoll w = sr_deps_begin(flow, begin, count, frame);
+  sr_deps_finish(flow, w, ctx);
+}
+
+// ... and tell the dependants: this work item's results are in memory (its stores were agent-scope
+// and have completed when each thread's wait for them ends; the barrier collects the workgroup's).
+__device__ __forceinline__ void sr_signal_done(const SrFlow& flow, int gnode) {
+  if (flow.deps == nullptr) return;
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+  __syncthreads();
+  if (threadIdx.x == 0)
+    __hip_atomic_fetch_add(flow.done + gnode * SR_DONE_STRIDE, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
 __global__ void sr_fill_zero_kernel(uint4* p, size_t n16, unsigned char* tail, size_t ntail) {
@@ -115,6 +203,11 @@ __global__ void sr_record_output_kernel(const SrCtx* __restrict__ ctx, const T* 
   }
 }
 
+// 16-byte agent-scope store of node-state data (see Store<T>::astore)
+__device__ __forceinline__ void sr_store16_agent(void* p, u32x4_t v) {
+  asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"((__attribute__((address_space(1))) u32x4_t*)(unsigned long long)p), "v"(v) : "memory");
+}
+
 // ---------------------------------------------------------------------------
 // auxiliary work items that ride along in a level's launch
 // ---------------------------------------------------------------------------
@@ -123,50 +216,57 @@ __global__ void sr_record_output_kernel(const SrCtx* __restrict__ ctx, const T* 
 // stored pixel is a whole number of them
 // `ahead` = 1 stages the NEXT frame's input (into the copy that frame will be read from) while the
 // current frame's last launch runs: a pattern whose input edges do not bridge needs frame t's input
-// in place before frame t's first launch.  Frames the caller has given no input for are skipped.
+// in place before frame t's first launch.  Frames the caller has given no input for are skipped
+// (the item still counts as completed for its dependants).
 template <typename T>
-__device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, const SrStageNode& nd, int chunk, int ahead) {
-  const int frame = ctx->frame + ahead;
+__device__ __forceinline__ void sr_stage_item(SrCtx* __restrict__ ctx, const SrStageNode& nd, int chunk, int ahead,
+                                              int frame_now, const SrFlow& flow) {
+  const int frame = frame_now + ahead;
   const char* base = (const char*)ctx->in_ptr[nd.input_slot];
-  if (base == nullptr || frame > ctx->in_last) return;
-  const T* in = (const T*)(base + (int64_t)(frame - ctx->in_base) * ctx->in_stride[nd.input_slot]);
-  T* out = (T*)nd.state[frame & 1];
-  const int end = min(nd.elems_px, (chunk + 1) * SR_STAGE_CHUNK);
-  constexpr int V = 16 / sizeof(T);
-  if ((nd.Cp == V || nd.Cp == 2 * V) && nd.C <= V && SR_AUX_THREADS * 4 == SR_STAGE_CHUNK) {
-    // few channels (an image): one 16-byte piece of data per pixel (and one of zeros if the pitch is two),
-    // four pixels per thread, all loads first
-    const int p0 = chunk * SR_STAGE_CHUNK + threadIdx.x;
-    T v[4][V];
+  // the copy written was last read two frames ago (one frame ago, by bridging edges): wait for those readers
+  sr_wait_deps(flow, nd.dep_begin, nd.dep_count, frame, ctx);
+  if (base != nullptr && frame <= ctx->in_last) {
+    const T* in = (const T*)(base + (int64_t)(frame - ctx->in_base) * ctx->in_stride[nd.input_slot]);
+    T* out = (T*)nd.state[frame & 1];
+    const int end = min(nd.elems_px, (chunk + 1) * SR_STAGE_CHUNK);
+    constexpr int V = 16 / sizeof(T);
+    if ((nd.Cp == V || nd.Cp == 2 * V) && nd.C <= V && SR_AUX_THREADS * 4 == SR_STAGE_CHUNK) {
+      // few channels (an image): one 16-byte piece of data per pixel (and one of zeros if the pitch is two),
+      // four pixels per thread, all loads first
+      const int p0 = chunk * SR_STAGE_CHUNK + threadIdx.x;
+      T v[4][V];
 #pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int p = min(p0 + j * SR_AUX_THREADS, nd.elems_px - 1);
-      const T* ip = in + (size_t)p * nd.C;
+      for (int j = 0; j < 4; ++j) {
+        const int p = min(p0 + j * SR_AUX_THREADS, nd.elems_px - 1);
+        const T* ip = in + (size_t)p * nd.C;
 #pragma unroll
-      for (int i = 0; i < V; ++i) v[j][i] = (i < nd.C) ? ip[i] : (T)0;
-    }
-#pragma unroll
-    for (int j = 0; j < 4; ++j) {
-      const int p = p0 + j * SR_AUX_THREADS;
-      if (p < end) {
-        *(u32x4_t*)(out + (size_t)p * nd.Cp) = *(const u32x4_t*)v[j];
-        if (nd.Cp == 2 * V) *(u32x4_t*)(out + (size_t)p * nd.Cp + V) = u32x4_t{0u, 0u, 0u, 0u};
+        for (int i = 0; i < V; ++i) v[j][i] = (i < nd.C) ? ip[i] : (T)0;
       }
-    }
-  } else if ((nd.Cp % V) == 0) {
-    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += SR_AUX_THREADS) {
-      const T* ip = in + (size_t)p * nd.C;
-      for (int c0 = 0; c0 < nd.Cp; c0 += V) {
-        T v[V];
 #pragma unroll
-        for (int i = 0; i < V; ++i) v[i] = (c0 + i < nd.C) ? ip[c0 + i] : (T)0;
-        *(u32x4_t*)(out + (size_t)p * nd.Cp + c0) = *(const u32x4_t*)v;
+      for (int j = 0; j < 4; ++j) {
+        const int p = p0 + j * SR_AUX_THREADS;
+        if (p < end) {
+          sr_store16_agent(out + (size_t)p * nd.Cp, *(const u32x4_t*)v[j]);
+          if (nd.Cp == 2 * V) sr_store16_agent(out + (size_t)p * nd.Cp + V, u32x4_t{0u, 0u, 0u, 0u});
+        }
       }
+    } else if ((nd.Cp % V) == 0) {
+      for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += SR_AUX_THREADS) {
+        const T* ip = in + (size_t)p * nd.C;
+        for (int c0 = 0; c0 < nd.Cp; c0 += V) {
+          T v[V];
+#pragma unroll
+          for (int i = 0; i < V; ++i) v[i] = (c0 + i < nd.C) ? ip[c0 + i] : (T)0;
+          sr_store16_agent(out + (size_t)p * nd.Cp + c0, *(const u32x4_t*)v);
+        }
+      }
+    } else {
+      for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += SR_AUX_THREADS)
+        for (int c = 0; c < nd.Cp; ++c)
+          Store<T>::astore(out + (size_t)p * nd.Cp + c, (c < nd.C) ? Store<T>::load(in + (size_t)p * nd.C + c) : 0.f);
     }
-  } else {
-    for (int p = chunk * SR_STAGE_CHUNK + threadIdx.x; p < end; p += SR_AUX_THREADS)
-      for (int c = 0; c < nd.Cp; ++c) out[(size_t)p * nd.Cp + c] = (c < nd.C) ? in[(size_t)p * nd.C + c] : (T)0;
   }
+  sr_signal_done(flow, nd.gnode);
 }
 
 // Head node (App. A2: fully connected layers, optionally after global average pooling): a 1x1 node
@@ -178,10 +278,10 @@ __device__ __forceinline__ void sr_stage_item(const SrCtx* __restrict__ ctx, con
 // the parts are added in a fixed order, then bias, activation, store and, if this node is being
 // recorded, the rollout output.  smem: SR_HEAD_MAX_K floats, one int, 4*64*4 floats.
 template <typename T>
-__device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, const SrHead& h,
+__device__ __forceinline__ bool sr_head_body(const SrCtx* __restrict__ ctx, const SrHead& h,
                                              const SrHeadEdge* __restrict__ head_edges, int b, int split,
-                                             float* smem, int vec_floats) {
-  const int cur = ctx->frame & 1;
+                                             float* smem, int vec_floats, int frame) {
+  const int cur = frame & 1;
   int* flag = (int*)(smem + vec_floats);
   float* red = smem + vec_floats + 4;
   const int lane = threadIdx.x & 63, part = threadIdx.x >> 6;
@@ -207,19 +307,19 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
         for (; p + 12 <= p1; p += 12) {   // twelve loads in flight
           float v[12];
 #pragma unroll
-          for (int u = 0; u < 12; ++u) v[u] = Store<T>::load(src + (size_t)(p + u) * e.Csp + c);
+          for (int u = 0; u < 12; ++u) v[u] = Store<T>::aload(src + (size_t)(p + u) * e.Csp + c);
           s0 += (v[0] + v[4]) + v[8];
           s1 += (v[1] + v[5]) + v[9];
           s2 += (v[2] + v[6]) + v[10];
           s3 += (v[3] + v[7]) + v[11];
         }
         for (; p + 4 <= p1; p += 4) {
-          s0 += Store<T>::load(src + (size_t)p * e.Csp + c);
-          s1 += Store<T>::load(src + (size_t)(p + 1) * e.Csp + c);
-          s2 += Store<T>::load(src + (size_t)(p + 2) * e.Csp + c);
-          s3 += Store<T>::load(src + (size_t)(p + 3) * e.Csp + c);
+          s0 += Store<T>::aload(src + (size_t)p * e.Csp + c);
+          s1 += Store<T>::aload(src + (size_t)(p + 1) * e.Csp + c);
+          s2 += Store<T>::aload(src + (size_t)(p + 2) * e.Csp + c);
+          s3 += Store<T>::aload(src + (size_t)(p + 3) * e.Csp + c);
         }
-        for (; p < p1; ++p) s0 += Store<T>::load(src + (size_t)p * e.Csp + c);
+        for (; p < p1; ++p) s0 += Store<T>::aload(src + (size_t)p * e.Csp + c);
         const float sum = (s0 + s1) + (s2 + s3);
         if (h.splits == 1) smem[c] = sum * inv;
         else   // device-coherent (write-through) store, read back below by whichever slab finishes last
@@ -235,7 +335,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
           if (old == h.splits - 1) h.counters[b] = 0;
         }
         __syncthreads();
-        if (!*flag) return;
+        if (!*flag) return false;
         for (int c = threadIdx.x; c < e.Cin; c += SR_AUX_THREADS) {
           float sum = 0.f;
           for (int s = 0; s < h.splits; ++s)
@@ -248,7 +348,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
       K = e.HW * e.Cin;
       for (int k = threadIdx.x; k < K; k += SR_AUX_THREADS) {
         const int p = k / e.Cin, c = k - p * e.Cin;
-        smem[k] = Store<T>::load(src + (size_t)p * e.Csp + c);
+        smem[k] = Store<T>::aload(src + (size_t)p * e.Csp + c);
       }
     }
     __syncthreads();
@@ -297,7 +397,7 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
     }
   }
   char* rec = h.record ? (char*)ctx->out_ptr : nullptr;
-  T* recp = rec ? (T*)(rec + (int64_t)(ctx->frame - ctx->out_base) * ctx->out_stride) : nullptr;
+  T* recp = rec ? (T*)(rec + (int64_t)(frame - ctx->out_base) * ctx->out_stride) : nullptr;
   if (narrow) {
     red[slice * CO + co_n] = acc[0];
     __syncthreads();
@@ -306,10 +406,10 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
       for (int sl = 0; sl < n_slices; ++sl) v += red[sl * CO + co];   // slice order: deterministic
       v += h.bias[co];
       if (h.act == 1) v = fmaxf(v, 0.f);
-      Store<T>::store((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
+      Store<T>::astore((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
       if (recp) Store<T>::store(recp + (size_t)b * h.Cout + co, v);
     }
-    return;
+    return true;
   }
 #pragma unroll
   for (int j = 0; j < 4; ++j) red[(part * 4 + j) * 64 + lane] = acc[j];
@@ -319,18 +419,32 @@ __device__ __forceinline__ void sr_head_item(const SrCtx* __restrict__ ctx, cons
     float v = h.bias[co] + ((red[(0 * 4 + j) * 64 + l] + red[(1 * 4 + j) * 64 + l]) +
                             (red[(2 * 4 + j) * 64 + l] + red[(3 * 4 + j) * 64 + l]));
     if (h.act == 1) v = fmaxf(v, 0.f);
-    Store<T>::store((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
+    Store<T>::astore((T*)h.out[cur] + (size_t)b * h.Cp + co, v);
     if (recp) Store<T>::store(recp + (size_t)b * h.Cout + co, v);
   }
+  return true;
 }
 
+// ... as a work item: wait for the source nodes (and for the readers of the copy about to be
+// overwritten), compute, and count the image as done once its outputs are in memory
 template <typename T>
-__device__ __forceinline__ void sr_aux_item(const SrCtx* __restrict__ ctx, const SrAux& it,
+__device__ __forceinline__ void sr_head_item(SrCtx* __restrict__ ctx, const SrHead& h,
+                                             const SrHeadEdge* __restrict__ head_edges, int b, int split,
+                                             float* smem, int vec_floats, int frame, const SrFlow& flow) {
+  sr_wait_deps(flow, h.dep_begin, h.dep_count, frame, ctx);
+  const bool wrote = sr_head_body<T>(ctx, h, head_edges, b, split, smem, vec_floats, frame);
+  if (wrote) sr_signal_done(flow, h.gnode);
+}
+
+
+template <typename T>
+__device__ __forceinline__ void sr_aux_item(SrCtx* __restrict__ ctx, const SrAux& it,
                                             const SrHead* __restrict__ heads,
                                             const SrHeadEdge* __restrict__ head_edges,
-                                            const SrStageNode* __restrict__ stage_nodes, float* smem, int vec_floats) {
-  if (it.kind == SR_AUX_HEAD) sr_head_item<T>(ctx, heads[it.a], head_edges, it.b, it.c, smem, vec_floats);
-  else if (it.kind == SR_AUX_STAGE) sr_stage_item<T>(ctx, stage_nodes[it.a], it.b, it.c);
+                                            const SrStageNode* __restrict__ stage_nodes, float* smem, int vec_floats,
+                                            int frame, const SrFlow& flow) {
+  if (it.kind == SR_AUX_HEAD) sr_head_item<T>(ctx, heads[it.a], head_edges, it.b, it.c, smem, vec_floats, frame, flow);
+  else if (it.kind == SR_AUX_STAGE) sr_stage_item<T>(ctx, stage_nodes[it.a], it.b, it.c, frame, flow);
 }
 
 // ---------------------------------------------------------------------------
@@ -406,9 +520,10 @@ __global__ __launch_bounds__(256) void sr_direct_kernel(SrCtx* __restrict__ ctx,
     const SrDirectBlock blk = blocks[blockIdx.x];
     sr_direct_block<T>(ctx, nodes[blk.node], edges, blk.first, batch);
   } else {
-    sr_aux_item<T>(ctx, aux[blockIdx.x - n_blocks], heads, head_edges, stage_nodes, sr_aux_smem, vec_floats);
+    sr_aux_item<T>(ctx, aux[blockIdx.x - n_blocks], heads, head_edges, stage_nodes, sr_aux_smem, vec_floats, ctx->frame,
+                   SrFlow{nullptr, nullptr, 0, 0});
   }
-  if (is_last) sr_block_done(ctx, gridDim.x);
+  if (is_last) sr_block_done(ctx, gridDim.x, 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -519,7 +634,8 @@ __device__ __forceinline__ void sr_stage_dma(const unsigned char* __restrict__ b
     if (P0 < n_pos) {
       asm volatile("" : "+v"(off[it]));   // keeps the offset 32-bit: scalar base + 32-bit lane offset addressing
       __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(base + (unsigned)off[it]),
-                                       (__attribute__((address_space(3))) void*)(lds + (size_t)P0 * 16), 16, 0, 0);
+                                       (__attribute__((address_space(3))) void*)(lds + (size_t)P0 * 16), 16, 0,
+                                       16 /* sc1: agent scope, the state may have been written on another XCD */);
     }
   }
 }
@@ -661,37 +777,70 @@ __device__ __forceinline__ bool sr_split_reduce(f32x16_t (&acc)[4][WN], const Sr
   return true;
 }
 
+// A tile record as the kernel holds it (scalar registers)
+struct SrTileK {
+  int node, m0, n0, ref_base, p_first, p_last, c_first, c_end, split_slot, part, wn_tiles, b_first, b_last, oy_first, oy_last;
+  SrRefK ref0;
+};
+
+__device__ __forceinline__ SrTileK sr_load_tile(const SrTile4* tiles, int index) {
+  const sr_i32x16 v = *(const __attribute__((address_space(4))) sr_i32x16*)(unsigned long long)(tiles + index);
+  SrTileK t;
+  t.node = v[0]; t.m0 = v[1]; t.n0 = v[2]; t.ref_base = v[3];
+  t.p_first = v[4]; t.p_last = v[5];
+  t.c_first = v[6] & 0xffff; t.c_end = (unsigned)v[6] >> 16;
+  t.split_slot = v[7]; t.part = v[8];
+  t.wn_tiles = v[9] & 0xff;
+  t.b_first = v[10]; t.b_last = v[10] + ((unsigned)v[9] >> 8);
+  t.oy_first = v[11] & 0xffff; t.oy_last = (unsigned)v[11] >> 16;
+  t.ref0.plan_at = v[12]; t.ref0.n_pos = v[13]; t.ref0.tap_begin = v[14]; t.ref0.ntaps = v[15];
+  return t;
+}
+
 template <int WN>
-__device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
-                                             const SrMfmaEdge* __restrict__ edges, int node_index, int tile_m0,
-                                             int tile_n0, int plan_begin, int e_first, int c_first, int e_last,
-                                             int c_end, int split_slot, int part_info, unsigned char* lds,
-                                             const SrSplitScratch& split) {
-  const __attribute__((address_space(4))) SrMfmaNode* nd =
-      (const __attribute__((address_space(4))) SrMfmaNode*)(unsigned long long)(nodes + node_index);
+__device__ __forceinline__ void sr_mfma_tile(SrCtx* __restrict__ ctx, const SrTables4& tb, const SrTileK& t,
+                                             unsigned char* lds, const SrSplitScratch& split, int frame,
+                                             const SrFlow& flow) {
+  // the node's record: one scalar load, in flight together with the frame counter and the first plane's
+  // plan, taps and descriptor (the tile record names them all)
+  const sr_i32x16 nv = *(const __attribute__((address_space(4))) sr_i32x16*)(unsigned long long)(tb.nodes + t.node);
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wave = SR_UNIFORM(tid >> 6);
-  const int waves_n = nd->waves_n;
+  const int cur = frame & 1;
+  const int M = nv[6], Wo = nv[8], HoWo = nv[7] * nv[8];
+  const int Cp = nv[9], act = nv[10];
+  const int waves_n = nv[12];
   const int wm = (waves_n == 4) ? 0 : (waves_n == 2 ? (wave >> 1) : wave);
   const int wn = wave - wm * waves_n;
-  const int cur = ctx->frame & 1;
-  const int M = nd->M, Wo = nd->Wo, HoWo = nd->Ho * Wo;
-  const int BM = 128 * nd->waves_m;
-  const int m_first = tile_m0;
-  const int m_last = min(tile_m0 + BM, M) - 1;
+  const int tile_m0 = t.m0, tile_n0 = t.n0;
   const int wave_m0 = tile_m0 + wm * 128;
   const int wave_n0 = tile_n0 + wn * (32 * WN);
   const int ntile0 = wave_n0 >> 5;
-  const int b_first = m_first / HoWo, oy_first = (m_first - b_first * HoWo) / Wo;
-  const int b_last = m_last / HoWo, oy_last = (m_last - b_last * HoWo) / Wo;
-  const int edge_begin = nd->edge_begin, edge_count = nd->edge_count;
-  const __attribute__((address_space(4))) int* plan_index =      // SrPlanRef records of this tile's planes
-      (const __attribute__((address_space(4))) int*)(unsigned long long)nd->plan_index + plan_begin * 4;
+  const int b_first = t.b_first, oy_first = t.oy_first, b_last = t.b_last, oy_last = t.oy_last;
+  const int split_slot = t.split_slot, part_info = t.part;
+  const __attribute__((address_space(4))) int* refs =
+      (const __attribute__((address_space(4))) int*)(unsigned long long)tb.refs + (long long)t.ref_base * 4;
   const __attribute__((address_space(1))) int* plan_tables =
-      (const __attribute__((address_space(1))) int*)(unsigned long long)nd->plan_tables;
+      (const __attribute__((address_space(1))) int*)(unsigned long long)tb.plan_tables;
   const __attribute__((address_space(1))) SrTap* tap_table =
-      (const __attribute__((address_space(1))) SrTap*)(unsigned long long)nd->tap_table;
+      (const __attribute__((address_space(1))) SrTap*)(unsigned long long)tb.tap_table;
+  const __attribute__((address_space(4))) SrPlane4* planes =
+      (const __attribute__((address_space(4))) SrPlane4*)(unsigned long long)tb.planes;
+  // dependency-driven launch: what the tile reads (first nv[14] & 0xff entries of its node's list) is
+  // polled now and waited for before the first patch load; what it overwrites (the next nv[14] >> 8
+  // entries: the readers of the copy this frame replaces) before the epilogue's stores
+  const SrDepPoll dep_read = sr_deps_begin(flow, nv[13], nv[14] & 0xff, frame);
+
+  // Everything a plane's first stage needs goes out at once: plan and taps (vector loads, located by the
+  // plan reference that the tile record, or the previous plane, has fetched) and the descriptor (one
+  // scalar load).  For the first plane that is here, ahead of the tile's own set-up.
+  int p = t.p_first;
+  SrRefK ref = t.ref0;
+  int dma_off[SR_DMA_ITEMS];
+  sr_dma_plan(plan_tables + ref.plan_at, ref.n_pos, tid, dma_off);
+  SrTaps taps = sr_tap_table(ref, tap_table, lane);
+  SrEdgeK e = sr_load_edge(planes, p, cur);
 
   // pixel coordinates of this lane's 4 rows, packed: ox | oy << 12 | (image - first image) << 24;
   // rows past the end repeat the last pixel
@@ -713,27 +862,19 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
 #pragma unroll
       for (int r = 0; r < 16; ++r) acc[mi][nj][r] = 0.f;
 
-  // The tile walks the planes e_first..e_last of its node's edge table.  What a plane needs before its
-  // first stage can be issued -- its descriptor, its direct-to-LDS plan, its tap table -- is fetched
-  // while the previous plane's last stage computes: the descriptor (scalar loads) at the start of
-  // the previous plane, plan and taps (vector loads) behind the previous plane's last fill, into the
-  // registers that fill has just released.
-  const __attribute__((address_space(4))) SrPlane4* planes =
-      (const __attribute__((address_space(4))) SrPlane4*)(unsigned long long)nd->planes4 + edge_begin;
-  int ei = e_first;
-  SrRefK ref = sr_load_ref(plan_index, ei);
+  // dependency-driven launch: before the first patch is read the node's sources must have completed
+  // the frames this tile reads, and the node itself its previous frame (its K-split scratch is free then)
+  sr_deps_finish(flow, dep_read, ctx);
+
+  // The tile walks the planes p_first..p_last of the plane table; a plane's plan reference (where its
+  // plan and taps are) is fetched during the previous plane, so that at the top of a plane its plan,
+  // taps and descriptor all go out together.
   for (;;) {
-    // everything the plane's first stage needs goes out at once: plan and taps (vector loads, located by
-    // the plan reference fetched during the previous plane) and the descriptor (one scalar load)
-    int dma_off[SR_DMA_ITEMS];
-    sr_dma_plan(plan_tables + ref.plan_at, ref.n_pos, tid, dma_off);
-    const SrTaps taps = sr_tap_table(ref, tap_table, lane);
-    const SrEdgeK e = sr_load_edge(planes, ei, cur);
-    const bool more = ei < e_last;
+    const bool more = p < t.p_last;
     SrRefK ref_n = ref;
-    if (more) ref_n = sr_load_ref(plan_index, ei + 1);   // in flight during this plane's stages
-    const int chunk_lo = (ei == e_first) ? c_first : 0;
-    const int chunk_hi = (ei == e_last) ? c_end : e.nchunk;
+    if (more) ref_n = sr_load_ref(refs, p + 1);   // in flight during this plane's stages
+    const int chunk_lo = (p == t.p_first) ? t.c_first : 0;
+    const int chunk_hi = (p == t.p_last) ? t.c_end : e.nchunk;
     const int row_first = (oy_first >> e.lgup) << e.lgRS;         // first patch row of the tile, in its image
     const int n_pos = ref.n_pos;
     const int NS = ref.ntaps << e.lgK16;
@@ -776,7 +917,10 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
     }
     if (!more) break;
     ref = ref_n;
-    ++ei;
+    ++p;
+    sr_dma_plan(plan_tables + ref.plan_at, ref.n_pos, tid, dma_off);
+    taps = sr_tap_table(ref, tap_table, lane);
+    e = sr_load_edge(planes, p, cur);
   }
 
   // ---- K-split tiles: leave the accumulators in scratch; the part that arrives last adds all parts
@@ -785,16 +929,17 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       !sr_split_reduce<WN, 256>(acc, split, split_slot, part_info, SR_SPLIT_FLOATS, tid, (int*)lds))
     return;
 
+  sr_wait_deps(flow, nv[13] + (nv[14] & 0xff), nv[14] >> 8, frame, ctx);
+
   // ---- epilogue: bias, activation, round to bf16, NHWC store.
   // The weights are the MFMA's row operand, so register r of lane l holds channel
   // 8*(r/4) + 4*(l/32) + r%4 of pixel l%32: four consecutive channels per register quad.  Each
   // wave transposes its tile through its own LDS region (64 pixels at a time, rows of 32*WN
   // channels + 16 spare bytes) so that global stores are 16 bytes per lane and whole pixel rows.
-  __attribute__((address_space(1))) unsigned char* out =
-      (__attribute__((address_space(1))) unsigned char*)(unsigned long long)nd->out[cur];
-  const __attribute__((address_space(1))) float* biasp =
-      (const __attribute__((address_space(1))) float*)(unsigned long long)nd->bias;
-  const int Cp = nd->Cp, act = nd->act;
+  __attribute__((address_space(1))) unsigned char* out = (__attribute__((address_space(1))) unsigned char*)(
+      ((unsigned long long)(unsigned)(cur ? nv[3] : nv[1]) << 32) | (unsigned)(cur ? nv[2] : nv[0]));
+  const __attribute__((address_space(1))) float* biasp = (const __attribute__((address_space(1))) float*)(
+      ((unsigned long long)(unsigned)nv[5] << 32) | (unsigned)nv[4]);
   constexpr int EP = 32 * WN * 2 + 16;          // bytes per pixel row in LDS
   constexpr int PIECES = 32 * WN * 2 / 16;      // 16-byte pieces per pixel row
   unsigned char* my = lds + wave * (64 * EP);
@@ -832,15 +977,16 @@ __device__ __forceinline__ void sr_mfma_tile(const SrCtx* __restrict__ ctx, cons
       const int row = p / PIECES, piece = p - row * PIECES;
       const int m = wave_m0 + half * 64 + row;
       const u32x4_t v = *(const u32x4_t*)(my + row * EP + piece * 16);
-      if (m < M)
-        *(__attribute__((address_space(1))) u32x4_t*)(out + ((size_t)m * Cp + wave_n0) * 2 + piece * 16) = v;
+      if (m < M)   // agent-scope store: the consumers may run on other XCDs, within this launch
+        asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"((__attribute__((address_space(1))) u32x4_t*)(
+                         out + ((size_t)m * Cp + wave_n0) * 2 + piece * 16)), "v"(v) : "memory");
     }
   }
+  sr_signal_done(flow, nv[15]);
 }
 
-__global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx, const SrMfmaNode* __restrict__ nodes,
-                                                         const SrMfmaEdge* __restrict__ edges,
-                                                         const SrMfmaTile* __restrict__ tiles, int n_tiles,
+__global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx, SrTables4 tb, SrFlow flow,
+                                                         const SrTile4* __restrict__ tiles, int n_tiles,
                                                          const SrAux* __restrict__ aux, int n_aux, int aux_at,
                                                          const SrHead* __restrict__ heads,
                                                          const SrHeadEdge* __restrict__ head_edges,
@@ -849,25 +995,26 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
   extern __shared__ __align__(16) unsigned char sr_lds[];
   // work list: tiles in decreasing cost; the auxiliary items are spliced in at position aux_at so
   // that neither the longest tiles start late nor the launch ends on an auxiliary item
+  // A launch covers gridDim.y frames (more than one only when dependency-driven); the hardware hands
+  // workgroups out in the order x, then y: frame by frame.
   const int item = blockIdx.x;
+  const int frame = ctx->frame + (int)blockIdx.y;
   const bool is_aux = item >= aux_at && item < aux_at + n_aux;
   if (!is_aux) {
-    const SrMfmaTile t = tiles[item < aux_at ? item : item - n_aux];
-    const int node_index = SR_UNIFORM(t.node);
-    if (node_index < 0) {
+    const SrTileK t = sr_load_tile(tiles, item < aux_at ? item : item - n_aux);
+    if (t.node <= -2) {
+      // an auxiliary item placed in the list itself (dependency-driven launches order all items of a frame)
+      sr_aux_item<uint16_t>(ctx, aux[-2 - t.node], heads, head_edges, stage_nodes, (float*)sr_lds, vec_floats, frame, flow);
+    } else if (t.node < 0) {
       // empty slot
-    } else if (nodes[node_index].wn_tiles == 2)
-      sr_mfma_tile<2>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
-                      SR_UNIFORM(t.e_first), SR_UNIFORM(t.c_first), SR_UNIFORM(t.e_last), SR_UNIFORM(t.c_end),
-                      SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part), sr_lds, split);
+    } else if (t.wn_tiles == 2)
+      sr_mfma_tile<2>(ctx, tb, t, sr_lds, split, frame, flow);
     else
-      sr_mfma_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
-                      SR_UNIFORM(t.e_first), SR_UNIFORM(t.c_first), SR_UNIFORM(t.e_last), SR_UNIFORM(t.c_end),
-                      SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part), sr_lds, split);
+      sr_mfma_tile<1>(ctx, tb, t, sr_lds, split, frame, flow);
   } else {
-    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds, vec_floats);
+    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds, vec_floats, frame, flow);
   }
-  if (is_last) sr_block_done(ctx, gridDim.x);
+  if (is_last) sr_block_done(ctx, gridDim.x * gridDim.y, gridDim.y);
 }
 
 // ---------------------------------------------------------------------------
@@ -1208,8 +1355,9 @@ __global__ __launch_bounds__(512) void sr_mfma8_kernel(SrCtx* __restrict__ ctx, 
   const int item = blockIdx.x;
   if (item >= aux_at && item < aux_at + n_aux) {
     if (threadIdx.x >= SR_AUX_THREADS) return;
-    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds8, vec_floats);
-    if (is_last) sr_block_done(ctx, gridDim.x);
+    sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds8, vec_floats, ctx->frame,
+                          SrFlow{nullptr, nullptr, 0, 0});
+    if (is_last) sr_block_done(ctx, gridDim.x, 1);
     return;
   }
   const SrMfmaTile t = tiles[item < aux_at ? item : item - n_aux];
@@ -1224,7 +1372,7 @@ __global__ __launch_bounds__(512) void sr_mfma8_kernel(SrCtx* __restrict__ ctx, 
     sr_mfma8_tile<1>(ctx, nodes, edges, node_index, SR_UNIFORM(t.m0), SR_UNIFORM(t.n0), SR_UNIFORM(t.plan_begin),
                      SR_UNIFORM(t.stage_begin), SR_UNIFORM(t.stage_end), SR_UNIFORM(t.split_slot), SR_UNIFORM(t.part),
                      sr_lds8, split);
-  if (is_last) sr_block_done(ctx, gridDim.x);
+  if (is_last) sr_block_done(ctx, gridDim.x, 1);
 }
 
 // ---------------------------------------------------------------------------
@@ -1262,8 +1410,9 @@ __global__ void sr_aux_kernel(SrCtx* __restrict__ ctx, const SrAux* __restrict__
                               const SrHeadEdge* __restrict__ head_edges, const SrStageNode* __restrict__ stage_nodes,
                               int vec_floats, int is_last) {
   extern __shared__ float sr_aux_smem2[];
-  sr_aux_item<T>(ctx, aux[blockIdx.x], heads, head_edges, stage_nodes, sr_aux_smem2, vec_floats);
-  if (is_last) sr_block_done(ctx, gridDim.x);
+  sr_aux_item<T>(ctx, aux[blockIdx.x], heads, head_edges, stage_nodes, sr_aux_smem2, vec_floats, ctx->frame,
+                 SrFlow{nullptr, nullptr, 0, 0});
+  if (is_last) sr_block_done(ctx, gridDim.x, 1);
 }
 
 // smem_bytes of the aux items: vector floats + 16 bytes + 4 KiB of partial outputs
@@ -1324,17 +1473,18 @@ static hipError_t sr_request_lds(const void* kernel, int bytes, int which) {
   return e;
 }
 
-hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, const SrMfmaEdge* edges,
-                          const SrMfmaTile* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
-                          const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
-                          int aux_smem_bytes, int is_last, SrSplitScratch split) {
+hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, SrTables4 tables, SrFlow flow, int frames, const SrTile4* tiles,
+                          int n_tiles, int lds_bytes, const SrAux* aux, int n_aux, const SrHead* heads,
+                          const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last,
+                          SrSplitScratch split) {
   if (n_tiles + n_aux == 0) return hipSuccess;
   {   // dynamic LDS above 64 KiB has to be requested once per device
     hipError_t e = sr_request_lds((const void*)sr_mfma_kernel, sr_mfma_max_lds_bytes(), 0);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles + n_aux), dim3(256), lds_bytes, s, ctx, nodes, edges, tiles, n_tiles,
-                     aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last, split);
+  hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles + n_aux, frames), dim3(256), lds_bytes, s, ctx, tables, flow, tiles,
+                     n_tiles, aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last,
+                     split);
   return hipGetLastError();
 }
 

@@ -117,7 +117,8 @@ def test_cifar_sr_full_streaming():
 def test_cifar_sr_full_patterns(pattern):
     g = W.cifar_patterns()[pattern]
     info = run_full(g, g.frames, [1, g.frames])
-    assert info["launches_per_frame"] == info["inference_factor"]
+    # more than one update step per frame: dependency-driven, all update steps in one launch
+    assert info["inference_factor"] > 1 and info["launches_per_frame"] == 1
 
 
 @pytest.mark.timeout(900)

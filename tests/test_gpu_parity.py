@@ -262,6 +262,59 @@ def test_tile_kernel_choice_is_reported():
         dev.close()
 
 
+OPT_FLOW_ON, OPT_FLOW_OFF = {5: 1}, {5: 0}
+
+
+@pytest.mark.parametrize("pattern", ["streaming", "hybrid", "sequential"])
+def test_dependency_driven_execution_equals_one_launch_per_update_step(pattern):
+    # The same rollout dependency-driven (one launch for every update step of up to 8 frames; a work item
+    # waits for the nodes it reads) and with one launch per update step: bit-identical outputs over
+    # 19 frames (two 8-frame launches + 3 single frames), every node's final state too, and no
+    # dependency wait may have given up.  K-split tiles, head and input-staging items all take part.
+    import paper_1806_04965_amd as sr
+    g0 = W.cifar_sr(batch=6, frames=19)
+    g = g0.with_pattern({"streaming": W.streaming_pattern, "hybrid": W.hybrid_pattern,
+                         "sequential": W.sequential_pattern}[pattern](g0))
+    w, b, x = W.make_case(g, seed=41, bias_scale=0.1)
+    outs, finals = {}, {}
+    for name, opt in (("flow", OPT_FLOW_ON), ("steps", OPT_FLOW_OFF)):
+        res, dev = gpu_rollout(g, w, b, x, g.frames, options=opt, return_dev=True)
+        health, info = dev.health(), dev.info()
+        assert health["dependency_driven"] == (name == "flow")
+        assert health["dependency_timeouts"] == 0
+        assert info["launches_per_frame"] == (1 if name == "flow" else max(1, info["inference_factor"]))
+        outs[name] = res
+        finals[name] = [dev.get_state(v).float().cpu().numpy() for v in range(len(g.nodes))]
+        dev.close()
+    np.testing.assert_array_equal(outs["flow"], outs["steps"])
+    for a, c in zip(finals["flow"], finals["steps"]):
+        np.testing.assert_array_equal(a, c)
+    ref = oracle_states(g, w, b, x, g.frames, "bf16", nodes=[g.out_node])[g.out_node]
+    for t in range(g.frames):
+        assert np.abs(ref[t]).max() > 0
+        assert max_abs_rel(outs["flow"][t], ref[t]) <= TOL["bf16"]
+
+
+def test_dependency_driven_default_and_larger_graphs():
+    # default: dependency-driven exactly when a frame has more than one update step
+    import paper_1806_04965_amd as sr
+    for g, want in ((W.cifar_sr(batch=2, frames=2), False),
+                    (W.cifar_patterns(batch=2, frames=2)["sequential"], True), (W.tiny_sr(), False)):
+        dev = sr.SrGraph(g)
+        w, b, _ = W.make_case(g, seed=1)
+        dev.set_parameters(w, b)
+        assert dev.health()["dependency_driven"] == want, g.name
+        dev.close()
+    # forced on for streaming graphs with feedback, long skips and K-split tiles: against the oracle
+    for g, seed in ((W.gtsrb_sr(batch=3, frames=10), 43), (W.hires_sr(batch=1, frames=3), 44)):
+        if g.name == "hires_sr":
+            g = Graph("hires_sr", [n if n.name == "out" else Node(n.name, n.channels, n.height // 4, n.width // 4, n.act)
+                                   for n in g.nodes], g.edges, 1, 3, "bf16", g.out_node)
+        check(g, seed=seed, options=OPT_FLOW_ON, label=f"{g.name}/dependency-driven")
+        hy = g.with_pattern(W.hybrid_pattern(g))
+        check(hy, seed=seed, label=f"{g.name}/hybrid (dependency-driven by default)")
+
+
 def test_tile_spanning_more_than_127_images():
     # a 1x3 node at batch 160: one 512-pixel tile would span 170 images, more than the tile kernels'
     # packed image offset holds; the planner has to choose a shape (or kernel) that stays within it
