@@ -316,7 +316,6 @@ struct MfmaChoice {
 bool mfma_eligible(const sr_graph* g, int v) {
   if (g->dtype != SR_BF16 || g->force_direct) return false;
   const NodeRt& n = g->nodes[v];
-  if (n.d.channels % 32 != 0) return false;
   bool any = false;
   for (const EdgeRt& e : g->edges) {
     if (e.d.dst != v) continue;
@@ -508,7 +507,7 @@ EdgeStaging choose_staging(const sr_graph* g, int v, const EdgeRt& e, int BM, in
 // go to the 8-wave kernel, whose stages are cut by row phase throughout.)
 bool four_wave_kernel_fits(const sr_graph* g, int v, int lds_cap) {
   const NodeRt& n = g->nodes[v];
-  const int Cout = n.d.channels;
+  const int Cout = (n.d.channels + 31) / 32 * 32;   // channel tiles are 32 wide; the rest of the last one is padding
   for (int wt : {2, 1})
     for (int wn : {4, 2, 1}) {
       if (Cout % (32 * wt * wn) != 0) continue;
@@ -694,7 +693,9 @@ sr_status finalize(sr_graph* g) {
       if (n.kind == 1 && g->tile_version == 2) {
         // ---- 8-wave tile kernel: widest channel tile that divides Cout (at most 128: the weight slab
         // of a stage lives in LDS), 8 waves arranged waves_m x waves_n
-        const int Cout = n.d.channels;
+        // channel tiles are 32 wide: a node whose channel count is no multiple of 32 gets zero weights and
+        // zero bias for the rest of its last tile, and the epilogue stores only the pixel's Cp channels
+        const int Cout = (n.d.channels + 31) / 32 * 32;
         const int64_t M = (int64_t)B * n.d.height * n.d.width;
         // shapes (wn_tiles, waves_n), preferred first: the widest channel tile up to 128 (the weight slab
         // of a stage lives in LDS) on the longest pixel tile; then shorter pixel tiles, whose source
@@ -850,7 +851,9 @@ sr_status finalize(sr_graph* g) {
       }
       if (n.kind == 1 && g->tile_version != 2) {
         // ---- MFMA node: tile shape, per-edge staging depth, tiles
-        const int Cout = n.d.channels;
+        // channel tiles are 32 wide: a node whose channel count is no multiple of 32 gets zero weights and
+        // zero bias for the rest of its last tile, and the epilogue stores only the pixel's Cp channels
+        const int Cout = (n.d.channels + 31) / 32 * 32;
         const int64_t M = (int64_t)B * n.d.height * n.d.width;
         // tile shapes to try, preferred first: each wave owns 128 pixels x 32*wn_tiles channels, the 4
         // waves are arranged waves_m x waves_n; a narrower wave tile gives a shorter pixel tile and so a
@@ -1859,7 +1862,7 @@ sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_e
     n.d = nodes[v];
     n.Cp = (dtype == SR_BF16) ? ((n.d.channels + 15) / 16) * 16 : n.d.channels;
     n.state_bytes = (size_t)batch * n.d.height * n.d.width * n.Cp * elem_size(g);
-    n.bias.assign(n.Cp, 0.f);
+    n.bias.assign((n.d.channels + 31) / 32 * 32, 0.f);   // as long as whole 32-channel tiles
     if (is_input[v]) {
       n.input_slot = (int)g->inputs.size();
       g->inputs.push_back(v);
@@ -1905,9 +1908,9 @@ sr_status sr_graph_create(const sr_node_desc* nodes, int32_t n_nodes, const sr_e
       if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
     }
     void* b = nullptr;
-    if ((st = dev_alloc(g, &b, n.Cp * sizeof(float))) != SR_OK) return bail(st);
+    if ((st = dev_alloc(g, &b, n.bias.size() * sizeof(float))) != SR_OK) return bail(st);
     n.bias_dev = (float*)b;
-    hipError_t he = sr_launch_fill_zero(g->stream, b, n.Cp * sizeof(float));
+    hipError_t he = sr_launch_fill_zero(g->stream, b, n.bias.size() * sizeof(float));
     if (he != hipSuccess) { g->err = hipGetErrorString(he); return bail(SR_ERR_DEVICE); }
   }
   void* c = nullptr;
@@ -1940,13 +1943,13 @@ sr_status sr_graph_set_weights(sr_graph* g, int32_t edge, const float* host_w, s
   // frames still in flight on the graph's stream read the old weights: let them finish first
   SR_HIP(g, hipStreamSynchronize(g->stream));
   SR_HIP(g, hipMemcpy(e.w_dev, e.w_host.data(), count * sizeof(float), hipMemcpyHostToDevice));
-  if (bf16 && e.d.kind == SR_EDGE_CONV && g->nodes[e.d.dst].d.channels % 32 == 0) {
+  if (bf16 && e.d.kind == SR_EDGE_CONV) {
     // B operand of the tile kernel: [tap][Cin_p/16][Cout/32][lane 0..63][8]; lane l of a
     // (tap, k16 block, channel tile) holds channel tile*32 + l%32 and input channels
     // block*16 + (l/32)*8 + 0..7
     const int Cin = g->nodes[e.d.src].d.channels, Cinp = g->nodes[e.d.src].Cp;
     const int Cout = g->nodes[e.d.dst].d.channels;
-    const int taps = e.kh * e.kw, kb = Cinp / 16, nt = Cout / 32;
+    const int taps = e.kh * e.kw, kb = Cinp / 16, nt = (Cout + 31) / 32;   // the last tile's spare columns stay zero
     std::vector<uint16_t> pk((size_t)taps * kb * nt * 512, 0);
     for (int t = 0; t < taps; ++t)
       for (int k = 0; k < kb; ++k)
@@ -1954,7 +1957,7 @@ sr_status sr_graph_set_weights(sr_graph* g, int32_t edge, const float* host_w, s
           for (int l = 0; l < 64; ++l)
             for (int i = 0; i < 8; ++i) {
               const int ci = k * 16 + (l / 32) * 8 + i, co = n * 32 + (l % 32);
-              if (ci < Cin)
+              if (ci < Cin && co < Cout)
                 pk[((((size_t)t * kb + k) * nt + n) * 64 + l) * 8 + i] = f2bf(host_w[((size_t)t * Cin + ci) * Cout + co]);
             }
     if (!e.wpk_dev) {
@@ -1973,7 +1976,7 @@ sr_status sr_graph_set_bias(sr_graph* g, int32_t node, const float* host_b, size
   if (count != (size_t)n.d.channels) return gfail(g, SR_ERR_ARG, "bias length differs from the node's channels");
   std::copy(host_b, host_b + count, n.bias.begin());
   SR_HIP(g, hipStreamSynchronize(g->stream));   // frames in flight read the old bias
-  SR_HIP(g, hipMemcpy(n.bias_dev, n.bias.data(), n.Cp * sizeof(float), hipMemcpyHostToDevice));
+  SR_HIP(g, hipMemcpy(n.bias_dev, n.bias.data(), n.bias.size() * sizeof(float), hipMemcpyHostToDevice));
   return SR_OK;
 }
 

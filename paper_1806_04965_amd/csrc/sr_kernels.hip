@@ -977,7 +977,9 @@ __device__ __forceinline__ void sr_mfma_tile(SrCtx* __restrict__ ctx, const SrTa
       const int row = p / PIECES, piece = p - row * PIECES;
       const int m = wave_m0 + half * 64 + row;
       const u32x4_t v = *(const u32x4_t*)(my + row * EP + piece * 16);
-      if (m < M)   // agent-scope store: the consumers may run on other XCDs, within this launch
+      // agent-scope store (the consumers may run on other XCDs, within this launch) of the pieces that
+      // exist: a node whose channel count is no multiple of 32 has fewer than the tile's
+      if (m < M && wave_n0 + piece * 8 < Cp)
         asm volatile("global_store_dwordx4 %0, %1, off sc1" ::"v"((__attribute__((address_space(1))) u32x4_t*)(
                          out + ((size_t)m * Cp + wave_n0) * 2 + piece * 16)), "v"(v) : "memory");
     }
@@ -1334,7 +1336,7 @@ __device__ __forceinline__ void sr_mfma8_tile(const SrCtx* __restrict__ ctx, con
       const int row = p / PIECES, piece = p - row * PIECES;
       const int m = wave_m0 + half * 64 + row;
       const u32x4_t v = *(const u32x4_t*)(my + row * EP + piece * 16);
-      if (m < M)
+      if (m < M && wave_n0 + piece * 8 < Cp)
         *(__attribute__((address_space(1))) u32x4_t*)(out + ((size_t)m * Cp + wave_n0) * 2 + piece * 16) = v;
     }
   }

@@ -12,11 +12,11 @@ from gpu_util import gpu_states_by_steps, oracle_states, compare_all
 pytestmark = pytest.mark.gpu
 
 
-def random_graph(seed, dtype="bf16"):
+def random_graph(seed, dtype="bf16", cmul=None):
     rng = np.random.default_rng(seed)
     n_conv = int(rng.integers(3, 7))
     size = int(rng.choice([6, 8, 12, 16, 20, 24]))
-    cmul = 32 if dtype == "bf16" else 4
+    cmul = cmul or (32 if dtype == "bf16" else 4)
     nodes = [Node("in", int(rng.choice([1, 3, 4])), size, size, ACT_IDENTITY)]
     sizes = [size]
     for i in range(n_conv):
@@ -71,6 +71,35 @@ def test_random_bf16_graph_both_tile_kernels(seed):
         worst = compare_all(got, ref, 2e-2, f"{g.name}/{label}")
         print(f"[parity] {g.name}/{label}: worst {worst:.3e}, F(R)={info['inference_factor']}, tiles={work['mfma_tiles']}, "
               f"launches/frame={info['launches_per_frame']}", flush=True)
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_random_bf16_graph_channel_counts_off_the_tile_width(seed):
+    # channel counts 8..72 in steps of 8: not multiples of the 32-channel tile (nor, half of them, of the
+    # 16-channel pitch); the tile kernels pad their weights and bias and store only the channels that exist
+    import paper_1806_04965_amd as sr
+    g = random_graph(300 + seed, cmul=8)
+    g = Graph(g.name + "_c8", [Node(n.name, n.channels * (1 + (i + seed) % 3) if 0 < i < len(g.nodes) - 1 else n.channels,
+                                    n.height, n.width, n.act) for i, n in enumerate(g.nodes)],
+              g.edges, g.batch, g.frames, g.dtype, g.out_node)
+    w, b, x = W.make_case(g, seed=seed, bias_scale=0.1, frames=g.frames, recipe="uniform")
+    ref = oracle_states(g, w, b, x, g.frames, "bf16")
+    for label, opts in (("4-wave", {4: 1}), ("8-wave", {4: 2})):
+        got, info, work = gpu_states_by_steps(g, w, b, x, g.frames, opts)
+        worst = compare_all(got, ref, 2e-2, f"{g.name}/{label}")
+        # the planner treats the node as it would with its channel count rounded up to whole tiles
+        g32 = Graph(g.name + "_c32", [Node(n.name, (n.channels + 31) // 32 * 32 if 0 < i < len(g.nodes) - 1 else n.channels,
+                                           n.height, n.width, n.act) for i, n in enumerate(g.nodes)],
+                    g.edges, g.batch, g.frames, g.dtype, g.out_node)
+        kinds = []
+        for gg in (g, g32):
+            wg, bg, _ = W.make_case(gg, seed=seed, frames=1)
+            dev = sr.SrGraph(gg, options=opts)
+            dev.set_parameters(wg, bg)
+            kinds.append(dev.node_kernels())
+            dev.close()
+        print(f"[parity] {g.name}/{label}: worst {worst:.3e}, channels {[n.channels for n in g.nodes]}, kernels {kinds[0]}", flush=True)
+        assert kinds[0] == kinds[1] and work["mfma_tiles"] > 0
 
 
 def scaled_up(g, seed):
