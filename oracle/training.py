@@ -21,9 +21,11 @@ before it is processed.  Weights are shared by the W copies of an edge: their gr
 Pins (tests/test_oracle_training.py): central finite differences of the loss for every weight and
 bias of tiny graphs under the streaming, hybrid and sequential patterns; the same windows rebuilt
 from torch's CPU operators and differentiated by torch.autograd; softmax cross-entropy against its
-closed-form gradient; the adjoint identity <f_e(x), y> = <x, f_e^T(y)> of every edge kind; and what
+closed-form gradient; the adjoint identity <f_e(x), y> = <x, f_e^T(y)> of every edge kind; what
 Sec. 4 fixes: a window shorter than the shortest input-to-output path gives the weights of edges
-that leave an input no gradient at all under the streaming pattern.
+that leave an input no gradient at all under the streaming pattern; and the gradient with the
+rectifier's derivative toggled at chosen elements (see Window.near_kink) against torch.autograd on a
+window whose rectifiers carry that derivative.
 """
 from __future__ import annotations
 
@@ -139,9 +141,11 @@ class Window:
 
     def forward(self, inputs, W, init=None):
         """inputs[v]: (W+1,B,H,W,C) for every input node.  Returns X with X[i][v] the state of node v at
-        frame i = 0..W (frame 0: `init[v]` or zeros for nodes with incoming edges)."""
+        frame i = 0..W (frame 0: `init[v]` or zeros for nodes with incoming edges).  The pre-activations
+        a_v(i) are kept in self.A."""
         g = self.g
         X = [[None] * len(g.nodes) for _ in range(W + 1)]
+        A = [[None] * len(g.nodes) for _ in range(W + 1)]
         for v, n in enumerate(g.nodes):
             if v in self.inputs:
                 for i in range(W + 1):
@@ -157,19 +161,40 @@ class Window:
                     for ei in self.src_edges[v]:
                         e = g.edges[ei]
                         a = a + ro.edge_transform(e, self.theta[ei], X[i - e.bridge][e.src])
+                    A[i][v] = a
                     X[i][v] = ro.activation(n.act, a)
-        self.X, self.W = X, W
+        self.X, self.A, self.W = X, A, W
         return X
+
+    def near_kink(self, tau_rel):
+        """Elements of rectifier nodes whose pre-activation lies within tau_rel * max|x_v| of zero, as
+        (frame, node, flat index) triples.  There the rectifier's derivative is not defined by the
+        arithmetic of a finite-precision forward pass: a pre-activation that is +1e-8 in one summation
+        order is -1e-8 in another, and either decision is a correct one."""
+        out = []
+        for v, n in enumerate(self.g.nodes):
+            if v in self.inputs or n.act != ACT_RELU:
+                continue
+            scale = max(float(np.abs(self.X[i][v]).max()) for i in range(1, self.W + 1))
+            for i in range(1, self.W + 1):
+                for k in np.flatnonzero(np.abs(self.A[i][v]).ravel() <= tau_rel * scale):
+                    out.append((i, v, int(k)))
+        return out
 
     def loss(self, labels, out_node=None):
         """Mean over the frames 1..W of the batch-mean cross-entropy at the output node (App. A2)."""
         out = self.g.out_node if out_node is None else out_node
         return float(np.mean([softmax_cross_entropy(self.X[i][out], labels)[0] for i in range(1, self.W + 1)]))
 
-    def backward(self, labels, out_node=None):
+    def backward(self, labels, out_node=None, flips=()):
         """Gradients of `loss` with respect to every weight and bias (and, as a by-product, to the input
-        frames 1..W): returns (dtheta list, dbias list, dinputs {v: (W+1,B,H,W,C)})."""
+        frames 1..W): returns (dtheta list, dbias list, dinputs {v: (W+1,B,H,W,C)}).
+        flips: (frame, node, flat index) triples at which the rectifier's derivative is taken as the
+        other one of {0, 1} (see near_kink); the forward values stay as they are."""
         g, X, W = self.g, self.X, self.W
+        toggled = {}
+        for (fi, fv, fk) in set(flips):
+            toggled.setdefault((fi, fv), []).append(fk)
         out = g.out_node if out_node is None else out_node
         dtheta = [np.zeros_like(t) for t in self.theta]
         dbias = [np.zeros_like(b) for b in self.bias]
@@ -181,7 +206,15 @@ class Window:
                 for v in level:
                     n = g.nodes[v]
                     # x = sigma(a): for the rectifier a > 0 exactly where x > 0
-                    da = dX[i][v] * (X[i][v] > 0) if n.act == ACT_RELU else dX[i][v]
+                    if n.act == ACT_RELU:
+                        mask = X[i][v] > 0
+                        if (i, v) in toggled:
+                            mask = mask.copy()
+                            flat = mask.reshape(-1)
+                            flat[toggled[(i, v)]] = ~flat[toggled[(i, v)]]
+                        da = dX[i][v] * mask
+                    else:
+                        da = dX[i][v]
                     dbias[v] += da.sum(axis=(0, 1, 2))
                     for ei in self.src_edges[v]:
                         e = g.edges[ei]

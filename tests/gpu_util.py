@@ -122,3 +122,50 @@ def compare_all(got, ref, tol, label=""):
             worst = max(worst, e)
             assert e <= tol, f"{label} node {v} frame {t + 1}: max-abs-rel {e:.3e} > {tol}"
     return worst
+
+
+# ---------------------------------------------------------------------------
+# training windows: the rectifier's kink
+# ---------------------------------------------------------------------------
+# A pre-activation that the float64 oracle computes as -1e-8 may come out of a float32 forward pass as
+# +1e-8: the value of the rectifier is the same to rounding, its derivative is 0 on one side and 1 on
+# the other, and the gradient of the window changes by a finite amount.  Both decisions are correct
+# ones for a forward pass of finite precision; which elements are that close to zero is decided on the
+# oracle's side alone (Window.near_kink with KINK_TAU, a few times the float32 forward error measured
+# by the frame-update parity tests, <= 1.5e-6 of a tensor's largest element).  The library's gradients
+# then have to equal the oracle's for ONE assignment of derivatives to those elements, to the same
+# tolerance as everywhere else; the assignment is found by least squares on the bias gradients and
+# then checked exactly on every tensor.
+KINK_TAU = 4e-6
+KINK_MAX = 32
+
+
+def match_kinks(win, labels, got, base, verbose=None):
+    """Which near-kink elements of the oracle's window carry the other derivative in the gradients
+    `got` = (dtheta list, dbias list with None for input nodes)?  `base` = the oracle's (dtheta, dbias)
+    without toggles.  Returns the (frame, node, flat index) list to pass to Window.backward(flips=...)."""
+    cand = win.near_kink(KINK_TAU)
+    assert len(cand) <= KINK_MAX, f"{len(cand)} elements within {KINK_TAU} of the rectifier's kink: case too large"
+    if not cand:
+        return []
+    nodes = [v for v in range(len(base[1])) if got[1][v] is not None]
+
+    def flat(dth, db):
+        return np.concatenate([np.asarray(t, dtype=np.float64).ravel() for t in dth] +
+                              [np.asarray(db[v], dtype=np.float64).ravel() for v in nodes])
+
+    f0 = flat(*base)
+    cols = []
+    for c in cand:
+        dth, db, _ = win.backward(labels, flips=[c])
+        cols.append(flat(dth, db) - f0)
+    A = np.stack(cols, axis=1)
+    live = np.abs(A).max(axis=0) > 0          # a toggle where no gradient arrives changes nothing
+    sol = np.zeros(len(cand))
+    if live.any():
+        sol[live] = np.linalg.lstsq(A[:, live], flat(got[0], got[1]) - f0, rcond=None)[0]
+    chosen = [c for c, s in zip(cand, sol) if s > 0.5]
+    if verbose is not None:
+        print(f"[kink] {verbose}: {len(cand)} elements within {KINK_TAU:g} of the kink, {len(chosen)} taken on the other "
+              f"side: {chosen}", flush=True)
+    return chosen

@@ -67,8 +67,9 @@ def test_gradients_match_central_finite_differences(pattern):
             assert abs(fd - db[v][c]) <= 1e-6 + 1e-5 * abs(fd), (pattern, "bias", v, c, fd, db[v][c])
 
 
-def torch_window_loss(g, w, b, x, labels, Wn):
-    """The same window built from torch's CPU operators (float64); returns loss and autograd gradients."""
+def torch_window_loss(g, w, b, x, labels, Wn, flips=()):
+    """The same window built from torch's CPU operators (float64); returns loss and autograd gradients.
+    flips: (frame, node, flat index) at which the rectifier keeps its value but passes the other derivative."""
     import torch
     import torch.nn.functional as F
     tw = [torch.tensor(wi, dtype=torch.float64, requires_grad=True) for wi in w]
@@ -104,7 +105,14 @@ def torch_window_loss(g, w, b, x, labels, Wn):
                 else:
                     y = (src.mean(dim=(1, 2)) @ tw[ei].reshape(tw[ei].shape[2], -1)).reshape(g.batch, 1, 1, -1)
                 a = a + y
-            X[i][v] = torch.relu(a) if g.nodes[v].act == ACT_RELU else a
+            if g.nodes[v].act == ACT_RELU:
+                mask = (a.detach() > 0).to(torch.float64)
+                for (fi, fv, fk) in flips:
+                    if (fi, fv) == (i, v):
+                        mask.view(-1)[fk] = 1.0 - mask.view(-1)[fk]
+                X[i][v] = torch.relu(a).detach() + (a - a.detach()) * mask    # value of the rectifier, derivative = mask
+            else:
+                X[i][v] = a
     lab = torch.tensor(labels, dtype=torch.long)
     loss = sum(F.cross_entropy(X[i][g.out_node].reshape(g.batch, -1), lab) for i in range(1, Wn + 1)) / Wn
     loss.backward()
@@ -215,3 +223,74 @@ def test_gradient_is_the_mean_of_the_single_frame_gradients():
         acc = [a + (k * p - (k - 1) * q) / Wn for a, p, q in zip(acc, gk, gkm)]
     for a, c in zip(acc, dth):
         np.testing.assert_allclose(a, c, rtol=1e-9, atol=1e-12)
+
+
+def test_toggled_rectifier_derivatives_against_torch():
+    g = patterns(small_sr_graph(batch=2))["hybrid"]
+    Wn = 4
+    w, b, x, labels = case(g, 17, Wn)
+    win = tr.Window(g, w, b)
+    win.forward(x, Wn)
+    base = win.backward(labels)
+    rng = np.random.default_rng(3)
+    flips = [(int(rng.integers(1, Wn + 1)), v, int(rng.integers(0, win.X[1][v].size))) for v in (1, 2) for _ in range(4)]
+    dth, db, _ = win.backward(labels, flips=flips)
+    _, tdw, tdb = torch_window_loss(g, w, b, x, labels, Wn, flips=flips)
+    for a, c in zip(dth + db, tdw + tdb):
+        np.testing.assert_allclose(a, c, rtol=1e-9, atol=1e-12)
+    assert any(np.abs(a - c).max() > 1e-9 for a, c in zip(dth, base[0]))     # the toggles do change the gradient
+    none = win.backward(labels, flips=[])
+    for a, c in zip(none[0], base[0]):
+        assert np.array_equal(a, c)
+
+
+def test_near_kink_lists_exactly_the_small_preactivations():
+    g = patterns(small_sr_graph(batch=2))["streaming"]
+    w, b, x, labels = case(g, 19, 3)
+    win = tr.Window(g, w, b)
+    win.forward(x, 3)
+    got = set(win.near_kink(1e-2))
+    assert got
+    for v in (1, 2):
+        scale = max(np.abs(win.X[i][v]).max() for i in range(1, 4))
+        for i in range(1, 4):
+            a = win.A[i][v].ravel()
+            for k in range(a.size):
+                assert ((i, v, k) in got) == (abs(a[k]) <= 1e-2 * scale)
+    assert all(v in (1, 2) for (_, v, _) in got)          # the output node has no rectifier
+    assert win.near_kink(0.0) == [] or all(win.A[i][v].ravel()[k] == 0 for (i, v, k) in win.near_kink(0.0))
+
+
+def test_kink_matching_recovers_planted_toggles():
+    # the helper the GPU tests use to decide which near-kink elements carry the other derivative:
+    # plant toggles on the oracle's side, add float32-sized noise, and ask for them back
+    import gpu_util
+    g = patterns(small_sr_graph(batch=2))["sequential"]
+    Wn = 4
+    w, b, x, labels = case(g, 23, Wn)
+    win = tr.Window(g, w, b)
+    win.forward(x, Wn)
+    _, base_db, _ = win.backward(labels)
+    old = gpu_util.KINK_TAU
+    gpu_util.KINK_TAU = 1e-2              # wide enough to have candidates on this tiny window
+    try:
+        cand = win.near_kink(gpu_util.KINK_TAU)
+        assert 3 <= len(cand) <= gpu_util.KINK_MAX
+        planted = [cand[0], cand[-1]]
+        dth, db, _ = win.backward(labels, flips=planted)
+        base = win.backward(labels)[:2]
+        rng = np.random.default_rng(0)
+        noise = lambda t: t * (1 + 1e-6 * rng.standard_normal(t.shape))
+        noisy = ([noise(t) for t in dth], [None if v in g.input_nodes() else noise(t) for v, t in enumerate(db)])
+        found = gpu_util.match_kinks(win, labels, noisy, base)
+        assert found and set(found) <= set(cand)
+        # the same gradient as with the planted toggles (a toggle where no gradient arrives is not found
+        # and does not matter)
+        dth2, db2, _ = win.backward(labels, flips=found)
+        for t, u in zip(dth + db, dth2 + db2):
+            np.testing.assert_allclose(t, u, rtol=0, atol=1e-12)
+        assert any(np.abs(t - u).max() > 1e-6 for t, u in zip(db, base_db))
+        clean = (base[0], [None if v in g.input_nodes() else t for v, t in enumerate(base[1])])
+        assert gpu_util.match_kinks(win, labels, clean, base) == []
+    finally:
+        gpu_util.KINK_TAU = old
