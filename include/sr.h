@@ -271,6 +271,35 @@ sr_status sr_graph_health(sr_graph* g, int64_t* dependency_timeouts, int32_t* de
  * Errors: SR_ERR_ARG, and what planning can return (SR_ERR_STATE: weights missing, SR_ERR_OOM, SR_ERR_DEVICE). */
 sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
 
+/* ---------------------------------------------------------------------------
+ * One training window (Sec. 3: rollout window of size W >= 1 of the graph's pattern; Sec. 2: trained
+ * by backpropagation through the rolled-out network; App. A2, training details: zero initial state,
+ * loss = mean over the window's frames of the single-frame prediction losses, cross-entropy).
+ * Runs frames 1..W from the zero state (as sr_reset + W x sr_frame_step, keeping every frame's
+ * states), then the reverse sweep over the window: frames W..1, inside a frame the update steps of
+ * the inference tableau in reverse (Eq. 5).  With z(i) = state of out_node at frame i,
+ *     loss = 1/(W*B) * sum_{i=1..W} sum_b -log softmax(z_b(i))[labels[b]]
+ * and the gradients of that loss with respect to every theta_e and b_v are returned; the W copies
+ * of an edge share their weights, so their gradients are summed.
+ *   g         an SR_F32 graph with all weights set (SR_BF16 graphs: SR_ERR_ARG)
+ *   inputs    host array, one device pointer per input node: float [W+1][B][H][W][C], frame 0 first
+ *             (frame 0 is read by the bridging edges that leave an input node)
+ *   labels    device, B int32 class indices in [0, channels of out_node); values outside are clamped
+ *   out_node  a 1x1 node with incoming edges whose channels are the class scores
+ *   loss      device, 1 float
+ *   dtheta    host array of n_edges device pointers; dtheta[e]: floats laid out like the weights given
+ *             to sr_graph_set_weights for edge e ([kh][kw][Cin][Cout]); overwritten
+ *   dbias     host array of n_nodes device pointers or NULL; dbias[v]: [C] floats, overwritten; entries
+ *             of input nodes are ignored, a NULL entry skips that node
+ * fp32 arithmetic; every sum is taken in a fixed order (no floating-point atomics): the same call
+ * gives the same bits.  The graph is left at frame W.  Device memory for the window's states and
+ * gradients (about (W + 3) x the graph's node states) is allocated by the call, kept by the graph and
+ * reused by later calls.  Asynchronous on the graph's stream; the host arrays are consumed before
+ * the call returns.  No optimiser step is taken.
+ * Errors: SR_ERR_ARG, SR_ERR_STATE (weights missing), SR_ERR_OOM, SR_ERR_DEVICE. */
+sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const int32_t* labels,
+                              int32_t out_node, float* loss, float* const* dtheta, float* const* dbias);
+
 void sr_graph_destroy(sr_graph* g);
 
 const char* sr_status_str(sr_status s);

@@ -17,7 +17,7 @@ EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_mo
            "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
            "sr_frame_step_static", "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
-           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_health", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
+           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_health", "sr_window_gradients", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
 
 
 class NodeDesc(C.Structure):
@@ -75,6 +75,7 @@ def load_library():
     lib.sr_graph_tile_kernel.argtypes = [vp, P(i32)]
     lib.sr_graph_node_kernels.argtypes = [vp, P(i32)]
     lib.sr_graph_health.argtypes = [vp, P(i64), P(i32)]
+    lib.sr_window_gradients.argtypes = [vp, i32, P(vp), vp, i32, vp, P(vp), P(vp)]
     lib.sr_graph_destroy.argtypes = [vp]
     lib.sr_graph_destroy.restype = None
     lib.sr_status_str.argtypes = [i32]
@@ -266,6 +267,37 @@ class SrGraph:
             optr = C.c_void_p(outputs.data_ptr())
             self._order(outputs)
         _check(self.lib, self.lib.sr_rollout(self.h, self._ptrs(inputs), T, out_node, optr), self.h)
+
+    def window_gradients(self, inputs, labels, W: int, out_node: Optional[int] = None):
+        """inputs: one float tensor [W+1,B,H,W,C] per input node; labels: int32 tensor [B] on the device.
+        Returns (loss tensor [1], dtheta list, dbias list) as device tensors (dbias of input nodes: None)."""
+        torch = self.torch
+        g = self.g
+        out = g.out_node if out_node is None else out_node
+        assert labels.is_cuda and labels.dtype == torch.int32 and labels.is_contiguous()
+        loss = torch.empty(1, dtype=torch.float32, device="cuda")
+        dth, dbs = [], []
+        tarr = (C.c_void_p * len(g.edges))()
+        for ei, e in enumerate(g.edges):
+            s, d = g.nodes[e.src], g.nodes[e.dst]
+            shape = {"conv": (e.kh, e.kw, s.channels, d.channels), "dense": (s.height, s.width, s.channels, d.channels),
+                     "gap_dense": (1, 1, s.channels, d.channels)}[e.kind]
+            t = torch.empty(shape, dtype=torch.float32, device="cuda")
+            dth.append(t)
+            tarr[ei] = t.data_ptr()
+        barr = (C.c_void_p * len(g.nodes))()
+        for v, n in enumerate(g.nodes):
+            if v in self.inputs:
+                dbs.append(None)
+                barr[v] = None
+                continue
+            t = torch.empty(n.channels, dtype=torch.float32, device="cuda")
+            dbs.append(t)
+            barr[v] = t.data_ptr()
+        self._order(labels, loss, *dth, *dbs)
+        _check(self.lib, self.lib.sr_window_gradients(self.h, W, self._ptrs(inputs), C.c_void_p(labels.data_ptr()), out,
+                                                       C.c_void_p(loss.data_ptr()), tarr, barr), self.h)
+        return loss, dth, dbs
 
     def get_state(self, node: int):
         n = self.g.nodes[node]

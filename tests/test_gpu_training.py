@@ -1,0 +1,174 @@
+"""GPU parity of one training window (Sec. 3 rollout window of size W, Sec. 2 backpropagation through
+it, loss of App. A2): loss and every weight and bias gradient from the C-ABI library against the
+float64 oracle on the same seeded arrays, under the streaming, hybrid and sequential patterns.
+
+Tolerance.  Both sides compute the same sums, the library in float32: a gradient element is a sum of
+n = W * B * Ho * Wo (weights) or taps * Cout (states) products, each term already carrying the
+float32 error of the forward pass and of the gradient it was built from.  With sequential float32
+summation the error is about sqrt(n) * 2^-24 of the sum of magnitudes, n <= 3e5 here: up to a few
+1e-6 of the tensor's largest element (measured: 1e-7 .. 6e-7).  GRAD_TOL = 2e-5 of max|reference| per
+tensor leaves a factor of about 30 and is printed next to what was measured.  Rectifier elements whose
+pre-activation is zero to float32 accuracy may carry either derivative: see gpu_util.match_kinks.
+"""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+import workloads as W
+from oracle import training as tr
+from gpu_util import to_device, max_abs_rel, match_kinks
+from test_oracle_training import small_sr_graph
+
+pytestmark = pytest.mark.gpu
+
+GRAD_TOL = 2e-5
+LOSS_TOL = 1e-5
+PATTERNS = {"streaming": W.streaming_pattern, "hybrid": W.hybrid_pattern, "sequential": W.sequential_pattern}
+
+
+def cases():
+    return {
+        # every edge kind: strided and plain convolutions, skip, self-recurrence, 1x1 + up-sampling, dense, GAP+dense
+        "small_sr": (lambda: small_sr_graph(batch=3), 4),
+        "tiny_sr": (lambda: W.tiny_sr(batch=2, frames=5), 5),
+        # App. A2: MNIST net with skip and self-recurrence, 7x7 stride-4 convolution and dense edges
+        "mnist_sr": (lambda: W.mnist_net("SR", batch=16, frames=4), 4),
+        # App. A2: CIFAR10 family member (10 nodes, 64-channel 3x3 convolutions at 32x32 and 16x16)
+        "dsr2": (lambda: replace(W.dsr_net(2, batch=2, frames=6), dtype="f32"), 6),
+    }
+
+
+def run_case(g, Wn, seed, dev=None):
+    import torch
+    import paper_1806_04965_amd as sr
+    w, b, x = W.make_case(g, seed=seed, bias_scale=0.1, frames=Wn, recipe="uniform")
+    labels = np.random.default_rng(seed + 1).integers(0, g.nodes[g.out_node].channels, g.batch).astype(np.int32)
+    own = dev is None
+    if own:
+        dev = sr.SrGraph(g)
+        dev.set_parameters(w, b)
+    ins = g.input_nodes()
+    xd = [to_device(x[v][:Wn + 1], "f32") for v in ins]
+    loss, dth, dbs = dev.window_gradients(xd, torch.from_numpy(labels).to("cuda"), Wn)
+    dev.synchronize()
+    got = (float(loss.cpu()[0]), [t.cpu().numpy() for t in dth], [None if t is None else t.cpu().numpy() for t in dbs])
+    if own:
+        dev.close()
+    return got, (w, b, x, labels)
+
+
+def check_against_oracle(g, Wn, got, data, label, may_be_zero=False):
+    w, b, x, labels = data
+    loss, dth, dbs = got
+    win = tr.Window(g, w, b)
+    win.forward({v: x[v][:Wn + 1] for v in x}, Wn)
+    ref_loss = win.loss(labels)
+    ref_dth, ref_db, _ = win.backward(labels)
+    assert ref_loss > 0
+    assert abs(loss - ref_loss) <= LOSS_TOL * max(1.0, abs(ref_loss)), (label, loss, ref_loss)
+
+    def errors(rd, rb):
+        out = {}
+        for ei in range(len(g.edges)):
+            assert dth[ei].shape == rd[ei].shape
+            if may_be_zero and np.abs(rd[ei]).max() == 0:       # a window too short to inform this edge (Sec. 4)
+                assert np.abs(dth[ei]).max() == 0, (label, "edge", ei)
+                continue
+            assert np.abs(rd[ei]).max() > 0, (label, "edge", ei, "reference gradient is all zero")
+            out[f"dtheta[{ei}]"] = max_abs_rel(dth[ei], rd[ei])
+        for v in range(len(g.nodes)):
+            if dbs[v] is not None:
+                if may_be_zero and np.abs(rb[v]).max() == 0:
+                    assert np.abs(dbs[v]).max() == 0, (label, "bias", v)
+                    continue
+                assert np.abs(rb[v]).max() > 0, (label, "bias", v)
+                out[f"dbias[{v}]"] = max_abs_rel(dbs[v], rb[v])
+        return out
+
+    err = errors(ref_dth, ref_db)
+    flips = []
+    if max(err.values()) > GRAD_TOL:
+        # elements at the rectifier's kink may carry either derivative (see gpu_util.match_kinks)
+        flips = match_kinks(win, labels, (dth, dbs), (ref_dth, ref_db), verbose=label)
+        assert flips, f"{label}: {max(err, key=err.get)} max-abs-rel {max(err.values()):.3e} > {GRAD_TOL}, no element at the kink"
+        ref_dth, ref_db, _ = win.backward(labels, flips=flips)
+        err = errors(ref_dth, ref_db)
+    worst = max(err, key=err.get)
+    assert err[worst] <= GRAD_TOL, f"{label} {worst}: max-abs-rel {err[worst]:.3e} > {GRAD_TOL} (kink elements taken: {flips})"
+    print(f"[train] {label}: W={Wn}, loss {loss:.6f} (oracle {ref_loss:.6f}), worst gradient max-abs-rel {err[worst]:.2e} "
+          f"(tol {GRAD_TOL}), rectifier elements taken on the other side of the kink: {len(flips)}", flush=True)
+    return err[worst]
+
+
+@pytest.mark.parametrize("pattern", list(PATTERNS))
+@pytest.mark.parametrize("name", list(cases()))
+def test_window_gradients_match_the_oracle(name, pattern):
+    mk, Wn = cases()[name]
+    g0 = mk()
+    g = g0.with_pattern(PATTERNS[pattern](g0))
+    got, data = run_case(g, Wn, seed=41)
+    check_against_oracle(g, Wn, got, data, f"{name}/{pattern}")
+
+
+def test_window_sizes_on_one_graph_and_reproducible_bits():
+    # one graph object, windows of size 3, then 1, then 6 (its arena grows), then 3 again: every call
+    # stands alone (zero initial state) and the same call gives the same bits
+    import paper_1806_04965_amd as sr
+    g0 = small_sr_graph(batch=4)
+    g = g0.with_pattern(W.streaming_pattern(g0))
+    w, b, _ = W.make_case(g, seed=41, bias_scale=0.1, frames=6, recipe="uniform")
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    first = None
+    for Wn in (3, 1, 6, 3):
+        got, data = run_case(g, Wn, seed=41, dev=dev)
+        check_against_oracle(g, Wn, got, data, f"small_sr W={Wn}", may_be_zero=Wn < 3)
+        if Wn == 3:
+            if first is None:
+                first = got
+            else:
+                assert got[0] == first[0]
+                for a, c in zip(got[1] + [t for t in got[2] if t is not None],
+                                first[1] + [t for t in first[2] if t is not None]):
+                    assert np.array_equal(a, c)
+    assert dev.frame_index() == 3
+    dev.close()
+
+
+def test_window_shorter_than_the_shortest_path_gives_the_first_edge_no_gradient():
+    # Sec. 4 on the device: chain of 4 edges under the streaming pattern, W = 3 < shortest path
+    from workloads.graphs import Node, Graph, ACT_IDENTITY
+    g0 = W.chain(3, batch=2, frames=4, hw=4, c=2)
+    nodes = g0.nodes + [Node("out", 5, 1, 1, ACT_IDENTITY)]
+    edges = g0.edges + [W.Edge(3, 4, "dense", 4, 4, 1, 0)]
+    g0 = Graph("chain_head", nodes, edges, 2, 4, "f32", out_node=4)
+    g = g0.with_pattern(W.streaming_pattern(g0))
+    for Wn, informed in ((3, False), (4, True)):
+        got, _ = run_case(g, Wn, seed=5)
+        assert (np.abs(got[1][0]).max() > 0) == informed, Wn
+        assert np.abs(got[1][3]).max() > 0
+
+
+def test_refusals():
+    import torch
+    import paper_1806_04965_amd as sr
+    g = W.tiny_sr(batch=2, frames=2)
+    w, b, x = W.make_case(g, seed=1, frames=2)
+    labels = torch.zeros(2, dtype=torch.int32, device="cuda")
+    dev = sr.SrGraph(g, dtype="bf16")
+    dev.set_parameters(w, b)
+    xd = [to_device(x[v], "bf16") for v in g.input_nodes()]
+    with pytest.raises(sr.SrError) as ei:
+        dev.window_gradients(xd, labels, 2)
+    assert "SR_F32" in str(ei.value)
+    dev.close()
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    xd = [to_device(x[v], "f32") for v in g.input_nodes()]
+    for bad in (0, 1):      # an input node; a node that is not 1x1
+        with pytest.raises(sr.SrError):
+            dev.window_gradients(xd, labels, 2, out_node=bad)
+    with pytest.raises(sr.SrError):
+        dev.window_gradients(xd, labels, 0)
+    dev.close()
