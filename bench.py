@@ -29,7 +29,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-KERNEL_SOURCES = ["sr_kernels.hip", "sr_host.cpp", "sr_internal.h"]
+KERNEL_SOURCES = ["sr_kernels.hip", "sr_host.cpp", "sr_internal.h", "sr_graph.h"]
 
 
 def recorded_traffic(workload, pattern):

@@ -8,7 +8,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libsr.so")
-SOURCES = ["sr_kernels.hip", "sr_train.hip", "sr_host.cpp"]
+SOURCES = ["sr_kernels.hip", "sr_train.hip", "sr_host.cpp", "sr_train_host.cpp"]
 
 
 def build(verbose: bool = False) -> str:

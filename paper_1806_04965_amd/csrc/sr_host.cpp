@@ -15,6 +15,7 @@
 
 #include "../../include/sr.h"
 #include "sr_internal.h"
+#include "sr_graph.h"
 
 namespace {
 
@@ -23,11 +24,6 @@ thread_local std::string g_last_error;
 // ---------------------------------------------------------------------------
 // rollout analysis (host only)
 // ---------------------------------------------------------------------------
-struct Analysis {
-  std::vector<int> is_input;   // node has no incoming edge (Eq. 1)
-  std::vector<int> level;      // tableau value of (1, v) in the size-1 window (Eq. 5)
-  int factor = 0;              // F(R), Eq. 6
-};
 
 sr_status fail(std::string* err, sr_status st, const std::string& msg) {
   if (err) *err = msg;
@@ -124,132 +120,17 @@ inline uint64_t magic_range(uint32_t d) {
 
 }  // namespace
 
-// ---------------------------------------------------------------------------
-// the graph object
-// ---------------------------------------------------------------------------
-struct NodeRt {
-  sr_node_desc d{};
-  int Cp = 0;                 // channel pitch of the stored state
-  size_t state_bytes = 0;
-  void* state[2] = {nullptr, nullptr};
-  float* bias_dev = nullptr;  // [Cp] float
-  std::vector<float> bias;
-  int kind = 0;               // 0 input, 1 mfma, 2 direct, 3 head
-  int input_slot = -1;
-};
 
-struct EdgeRt {
-  sr_edge_desc d{};
-  int kh = 0, kw = 0;              // effective kernel (dense: source H, W; GAP: 1)
-  size_t w_count = 0;
-  bool has_w = false;
-  std::vector<float> w_host;       // rounded to the graph dtype, [kh][kw][Cin][Cout]
-  float* w_dev = nullptr;          // same, float, for the direct and head kernels
-  void* wpk_dev = nullptr;         // packed bf16 for the MFMA kernel
-};
-
-struct LevelPlan {
-  int tile_begin = 0, n_tiles = 0;
-  int block_begin = 0, n_blocks = 0;
-  int head_begin = 0, n_heads = 0;
-  int aux_begin = 0, n_aux = 0;     // head and input-staging items that ride along in this level's launch
-};
-
-struct sr_graph {
-  int n_nodes = 0, n_edges = 0, batch = 0;
-  sr_dtype dtype = SR_F32;
-  hipStream_t stream = nullptr;
-  std::vector<NodeRt> nodes;
-  std::vector<EdgeRt> edges;
-  Analysis an;
-  std::vector<int> inputs;    // node ids of the input set, in node order
-  std::string err;
-
-  // options
-  bool use_hipgraph = true, force_direct = false;
-  int frames_per_graph = 8;
-
-  // plan
-  bool finalized = false, was_reset = false;
-  int64_t host_frame = 0;
-  std::vector<LevelPlan> levels;
-  std::vector<void*> dev_allocs;     // everything to free
-  SrCtx* ctx = nullptr;
-  SrStageNode* stage_nodes = nullptr;
-  SrAux* aux = nullptr;
-  // input staging: 0 rides in level 1's launch (no R=0 edge leaves an input: nothing reads the new
-  // input before the next frame); 1 staged one frame ahead: the next frame's input rides in this
-  // frame's last launch, the first frame's is staged by the call; 2 a launch of its own ahead of
-  // level 1 (an input also feeds a node of the last level over a bridging edge, which still reads
-  // the copy the next input would overwrite)
-  int stage_mode = 0;
-  int stage_aux_begin = 0, n_stage_aux = 0;
-  int aux_smem_bytes = 0;
-  std::vector<int> head_node;   // node id of each head, in head order
-  std::vector<SrHead> heads_host;
-  SrDirectNode* d_nodes = nullptr;
-  SrDirectEdge* d_edges = nullptr;
-  SrDirectBlock* d_blocks = nullptr;
-  SrMfmaNode* m_nodes = nullptr;
-  SrMfmaEdge* m_edges = nullptr;
-  SrMfmaTile* m_tiles = nullptr;
-  SrStage8* stage8 = nullptr;
-  int32_t* plan_index = nullptr;
-  int32_t* plan_tables = nullptr;
-  SrTap* tap_table = nullptr;
-  SrPlane4* planes4 = nullptr;
-  SrNode4* nodes4 = nullptr;
-  SrTile4* tiles4 = nullptr;
-  // dependency-driven execution (see SrDep): one launch covers all update steps of several frames
-  int dataflow_option = 2;   // 0 never, 1 whenever possible, 2 (default) when a frame has more than one update step
-  bool dataflow = false;
-  SrDep* deps = nullptr;
-  int32_t* done_counters = nullptr;   // one per graph node
-  SrTile4* flow_items = nullptr;      // a frame's work items in dependency order: tiles, and aux items as node = -2 - index
-  int n_flow_items = 0;
-  std::vector<int> flow_dep_begin, flow_dep_count;
-  float* split_scratch = nullptr;
-  size_t split_scratch_bytes = 0;
-  int32_t* split_counters = nullptr;
-  int n_split_slots = 0;
-  bool allow_split = true;
-  int tile_version = 0;       // 1: 4-wave tile kernel, 2: 8-wave tile kernel (both operands through LDS); 0: choose
-  SrHead* heads = nullptr;
-  SrHeadEdge* head_edges = nullptr;
-  int lds_bytes = 0;
-  int64_t n_mfma_tiles = 0;
-  double flops = 0;
-  int64_t device_bytes = 0;
-  int launches_per_frame = 0;
-
-  // rollout output recording (set per call)
-  int rec_node = -1;
-
-  // training window: one arena holding every node's states of the frames 0..W, two gradient copies per
-  // node (frames i and i-1 of the reverse sweep) and the scratch of the gradient kernels
-  float* train_arena = nullptr;
-  size_t train_arena_floats = 0;
-
-  hipGraph_t graph1 = nullptr, graphN = nullptr;
-  hipGraphExec_t exec1 = nullptr, execN = nullptr;
-  int graph_rec_node = -2;   // out_node the captured graphs record
-};
-
-namespace {
-
-sr_status gfail(sr_graph* g, sr_status st, const std::string& msg) {
+sr_status sr_gfail(sr_graph* g, sr_status st, const std::string& msg) {
   if (g) g->err = msg;
   g_last_error = msg;
   return st;
 }
 
-#define SR_HIP(g, call)                                                                              \
-  do {                                                                                               \
-    hipError_t e_ = (call);                                                                          \
-    if (e_ != hipSuccess)                                                                            \
-      return gfail((g), e_ == hipErrorOutOfMemory ? SR_ERR_OOM : SR_ERR_DEVICE,                      \
-                   std::string(#call) + ": " + hipGetErrorString(e_));                               \
-  } while (0)
+namespace {
+
+sr_status gfail(sr_graph* g, sr_status st, const std::string& msg) { return sr_gfail(g, st, msg); }
+
 
 size_t elem_size(const sr_graph* g) { return g->dtype == SR_BF16 ? 2 : 4; }
 
@@ -1319,9 +1200,10 @@ sr_status finalize(sr_graph* g) {
       q.bias = a.bias;
       q.M = a.M; q.Ho = a.Ho; q.Wo = a.Wo; q.Cp = a.Cp; q.act = a.act;
       q.waves_m = a.waves_m; q.waves_n = a.waves_n;
+      q.gnode = mfma_graph_node[i];
       if (g->dataflow) {
         const int v = mfma_graph_node[i];
-        q.dep_begin = g->flow_dep_begin[v]; q.dep_count = g->flow_dep_count[v]; q.gnode = v;
+        q.dep_begin = g->flow_dep_begin[v]; q.dep_count = g->flow_dep_count[v];
       }
     }
     if ((st = upload(g, &g->nodes4, n4)) != SR_OK) return st;
@@ -2217,152 +2099,6 @@ sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds) {
     const int k = g->nodes[v].kind;   // 0 input, 1 tile kernel, 2 direct, 3 head
     kinds[v] = (k == 0) ? 0 : (k == 1 ? (g->tile_version == 2 ? 2 : 1) : (k == 2 ? 3 : 4));
   }
-  return SR_OK;
-}
-
-sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const int32_t* labels,
-                              int32_t out_node, float* loss, float* const* dtheta, float* const* dbias) {
-  if (!g || !inputs || !labels || !loss || !dtheta || W < 1)
-    return gfail(g, SR_ERR_ARG, "bad argument to sr_window_gradients");
-  if (g->dtype != SR_F32) return gfail(g, SR_ERR_ARG, "sr_window_gradients: training windows take SR_F32 graphs only");
-  if (out_node < 0 || out_node >= g->n_nodes || g->an.is_input[out_node] || g->nodes[out_node].d.height != 1 ||
-      g->nodes[out_node].d.width != 1)
-    return gfail(g, SR_ERR_ARG, "sr_window_gradients: out_node must be a 1x1 node with incoming edges (the logits)");
-  for (int e = 0; e < g->n_edges; ++e)
-    if (!dtheta[e]) return gfail(g, SR_ERR_ARG, "sr_window_gradients: dtheta[" + std::to_string(e) + "] is null");
-  for (size_t i = 0; i < g->inputs.size(); ++i)
-    if (!inputs[i]) return gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
-  const int B = g->batch, N = g->n_nodes;
-  auto node_floats = [&](int v) {
-    const sr_node_desc& d = g->nodes[v].d;
-    return (size_t)B * d.height * d.width * d.channels;
-  };
-  auto geom_of = [&](const EdgeRt& e) {
-    const sr_node_desc& s = g->nodes[e.d.src].d;
-    const sr_node_desc& d = g->nodes[e.d.dst].d;
-    SrConvGeom q{};
-    q.B = B; q.Cin = s.channels; q.Cout = d.channels;
-    if (e.d.kind == SR_EDGE_CONV) {
-      q.H = s.height; q.W = s.width; q.kh = e.kh; q.kw = e.kw; q.stride = e.d.stride; q.pad = e.d.pad;
-      q.Ho = d.height / e.d.upsample; q.Wo = d.width / e.d.upsample;
-    } else if (e.d.kind == SR_EDGE_DENSE) {   // a valid convolution whose kernel covers the source
-      q.H = s.height; q.W = s.width; q.kh = s.height; q.kw = s.width; q.stride = 1; q.pad = 0; q.Ho = 1; q.Wo = 1;
-    } else {                                   // GAP + dense: a 1x1 map on the per-image channel means
-      q.H = 1; q.W = 1; q.kh = 1; q.kw = 1; q.stride = 1; q.pad = 0; q.Ho = 1; q.Wo = 1;
-    }
-    return q;
-  };
-  // arena layout
-  size_t at = 0;
-  auto take = [&](size_t n) { size_t r = at; at += (n + 63) / 64 * 64; return r; };
-  std::vector<size_t> x_at(N, 0), dx_at[2];
-  dx_at[0].assign(N, 0); dx_at[1].assign(N, 0);
-  for (int v = 0; v < N; ++v) {
-    if (g->an.is_input[v]) continue;
-    x_at[v] = take(node_floats(v) * (size_t)(W + 1));
-    dx_at[0][v] = take(node_floats(v));
-    dx_at[1][v] = take(node_floats(v));
-  }
-  size_t pooled_n = 0, mean_n = 0, part_n = 0;
-  for (const EdgeRt& e : g->edges) {
-    const SrConvGeom q = geom_of(e);
-    part_n = std::max(part_n, (size_t)sr_train_wgrad_slices(q) * e.w_count);
-    if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) pooled_n = std::max(pooled_n, (size_t)B * q.Ho * q.Wo * q.Cout);
-    if (e.d.kind == SR_EDGE_GAP_DENSE) mean_n = std::max(mean_n, (size_t)B * q.Cin);
-  }
-  const size_t pooled_at = take(pooled_n), mean_at = take(mean_n), dmean_at = take(mean_n), part_at = take(part_n);
-  const size_t terms_at = take((size_t)W * B);
-  if (at > g->train_arena_floats) {
-    SR_HIP(g, hipStreamSynchronize(g->stream));
-    if (g->train_arena) SR_HIP(g, hipFree(g->train_arena));
-    g->train_arena = nullptr;
-    g->train_arena_floats = 0;
-    void* p = nullptr;
-    SR_HIP(g, hipMalloc(&p, at * sizeof(float)));
-    g->train_arena = (float*)p;
-    g->train_arena_floats = at;
-  }
-  float* A = g->train_arena;
-  hipStream_t s = g->stream;
-
-  // forward over the window from the zero state, keeping every frame's states
-  std::vector<const void*> ptrs(g->inputs.size());
-  std::vector<size_t> in_stride(g->inputs.size());
-  for (size_t k = 0; k < g->inputs.size(); ++k) {
-    in_stride[k] = node_floats(g->inputs[k]);
-    ptrs[k] = inputs[k];
-  }
-  sr_status st = sr_reset(g, ptrs.data());
-  if (st != SR_OK) return st;
-  for (int v = 0; v < N; ++v)
-    if (!g->an.is_input[v]) SR_HIP(g, sr_launch_fill_zero(s, A + x_at[v], node_floats(v) * sizeof(float)));
-  for (int i = 1; i <= W; ++i) {
-    for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = (const float*)inputs[k] + (size_t)i * in_stride[k];
-    st = sr_frame_step(g, ptrs.data());
-    if (st != SR_OK) return st;
-    for (int v = 0; v < N; ++v)
-      if (!g->an.is_input[v])
-        SR_HIP(g, hipMemcpyAsync(A + x_at[v] + (size_t)i * node_floats(v), g->nodes[v].state[g->host_frame & 1],
-                                 node_floats(v) * sizeof(float), hipMemcpyDeviceToDevice, s));
-  }
-
-  // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
-  // (frame, node) has the gradient of all its readers before it is processed
-  std::vector<int> order;
-  for (int v = 0; v < N; ++v)
-    if (!g->an.is_input[v]) order.push_back(v);
-  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] > g->an.level[b]; });
-  for (int v : order)
-    for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[c][v], node_floats(v) * sizeof(float)));
-  for (int e = 0; e < g->n_edges; ++e) SR_HIP(g, sr_launch_fill_zero(s, dtheta[e], g->edges[e].w_count * sizeof(float)));
-  if (dbias)
-    for (int v : order)
-      if (dbias[v]) SR_HIP(g, sr_launch_fill_zero(s, dbias[v], (size_t)g->nodes[v].d.channels * sizeof(float)));
-  std::vector<int> slot_of(N, -1);
-  for (size_t k = 0; k < g->inputs.size(); ++k) slot_of[g->inputs[k]] = (int)k;
-  const int classes = g->nodes[out_node].d.channels;
-  const float scale = 1.0f / ((float)B * (float)W);
-  for (int i = W; i >= 1; --i) {
-    const int cur = i & 1;
-    SR_HIP(g, sr_train_ce(s, A + x_at[out_node] + (size_t)i * node_floats(out_node), labels, B, classes, scale,
-                          A + terms_at + (size_t)(i - 1) * B, A + dx_at[cur][out_node]));
-    for (int v : order) {
-      const sr_node_desc& d = g->nodes[v].d;
-      float* da = A + dx_at[cur][v];
-      if (d.act == SR_ACT_RELU) SR_HIP(g, sr_train_relu_mask(s, da, A + x_at[v] + (size_t)i * node_floats(v), node_floats(v)));
-      if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(s, da, B * d.height * d.width, d.channels, dbias[v]));
-      for (int ei = 0; ei < g->n_edges; ++ei) {
-        const EdgeRt& e = g->edges[ei];
-        if (e.d.dst != v) continue;
-        const int u = e.d.src, fi = i - (int)e.d.bridge;
-        const float* xsrc = g->an.is_input[u] ? (const float*)inputs[slot_of[u]] + (size_t)fi * in_stride[slot_of[u]]
-                                              : A + x_at[u] + (size_t)fi * node_floats(u);
-        // frame 0 and the input nodes are given: no gradient is kept for them
-        float* dxsrc = (g->an.is_input[u] || fi == 0) ? nullptr : A + dx_at[fi & 1][u];
-        const SrConvGeom q = geom_of(e);
-        if (e.d.kind == SR_EDGE_GAP_DENSE) {
-          const sr_node_desc& sd = g->nodes[u].d;
-          SR_HIP(g, sr_train_gap_mean(s, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at));
-          SR_HIP(g, sr_train_wgrad(s, q, A + mean_at, da, A + part_at, dtheta[ei]));
-          if (dxsrc) {
-            SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, da, A + dmean_at, 0));
-            SR_HIP(g, sr_train_gap_spread(s, A + dmean_at, B, sd.height * sd.width, sd.channels, dxsrc));
-          }
-          continue;
-        }
-        const float* dy = da;
-        if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) {
-          SR_HIP(g, sr_train_pool_sum(s, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_at));
-          dy = A + pooled_at;
-        }
-        SR_HIP(g, sr_train_wgrad(s, q, xsrc, dy, A + part_at, dtheta[ei]));
-        if (dxsrc) SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, dy, dxsrc, 1));
-      }
-    }
-    // this copy next holds frame i - 2
-    for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[cur][v], node_floats(v) * sizeof(float)));
-  }
-  SR_HIP(g, sr_train_sum_terms(s, A + terms_at, W * B, scale, loss));
   return SR_OK;
 }
 

@@ -1,0 +1,162 @@
+// Host side of one training window (Sec. 3: rollout window of size W; Sec. 2: backpropagation through
+// the rolled-out network; App. A2: loss): drives the frame path forward, keeps every frame's states,
+// and runs the reverse sweep with the kernels of sr_train.hip.
+#include <hip/hip_runtime_api.h>
+
+#include <algorithm>
+#include <string>
+#include <vector>
+
+#include "../../include/sr.h"
+#include "sr_internal.h"
+#include "sr_graph.h"
+
+extern "C" {
+
+sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const int32_t* labels,
+                              int32_t out_node, float* loss, float* const* dtheta, float* const* dbias) {
+  if (!g || !inputs || !labels || !loss || !dtheta || W < 1)
+    return sr_gfail(g, SR_ERR_ARG, "bad argument to sr_window_gradients");
+  if (g->dtype != SR_F32) return sr_gfail(g, SR_ERR_ARG, "sr_window_gradients: training windows take SR_F32 graphs only");
+  if (out_node < 0 || out_node >= g->n_nodes || g->an.is_input[out_node] || g->nodes[out_node].d.height != 1 ||
+      g->nodes[out_node].d.width != 1)
+    return sr_gfail(g, SR_ERR_ARG, "sr_window_gradients: out_node must be a 1x1 node with incoming edges (the logits)");
+  for (int e = 0; e < g->n_edges; ++e)
+    if (!dtheta[e]) return sr_gfail(g, SR_ERR_ARG, "sr_window_gradients: dtheta[" + std::to_string(e) + "] is null");
+  for (size_t i = 0; i < g->inputs.size(); ++i)
+    if (!inputs[i]) return sr_gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
+  const int B = g->batch, N = g->n_nodes;
+  auto node_floats = [&](int v) {
+    const sr_node_desc& d = g->nodes[v].d;
+    return (size_t)B * d.height * d.width * d.channels;
+  };
+  auto geom_of = [&](const EdgeRt& e) {
+    const sr_node_desc& s = g->nodes[e.d.src].d;
+    const sr_node_desc& d = g->nodes[e.d.dst].d;
+    SrConvGeom q{};
+    q.B = B; q.Cin = s.channels; q.Cout = d.channels;
+    if (e.d.kind == SR_EDGE_CONV) {
+      q.H = s.height; q.W = s.width; q.kh = e.kh; q.kw = e.kw; q.stride = e.d.stride; q.pad = e.d.pad;
+      q.Ho = d.height / e.d.upsample; q.Wo = d.width / e.d.upsample;
+    } else if (e.d.kind == SR_EDGE_DENSE) {   // a valid convolution whose kernel covers the source
+      q.H = s.height; q.W = s.width; q.kh = s.height; q.kw = s.width; q.stride = 1; q.pad = 0; q.Ho = 1; q.Wo = 1;
+    } else {                                   // GAP + dense: a 1x1 map on the per-image channel means
+      q.H = 1; q.W = 1; q.kh = 1; q.kw = 1; q.stride = 1; q.pad = 0; q.Ho = 1; q.Wo = 1;
+    }
+    return q;
+  };
+  // arena layout
+  size_t at = 0;
+  auto take = [&](size_t n) { size_t r = at; at += (n + 63) / 64 * 64; return r; };
+  std::vector<size_t> x_at(N, 0), dx_at[2];
+  dx_at[0].assign(N, 0); dx_at[1].assign(N, 0);
+  for (int v = 0; v < N; ++v) {
+    if (g->an.is_input[v]) continue;
+    x_at[v] = take(node_floats(v) * (size_t)(W + 1));
+    dx_at[0][v] = take(node_floats(v));
+    dx_at[1][v] = take(node_floats(v));
+  }
+  size_t pooled_n = 0, mean_n = 0, part_n = 0;
+  for (const EdgeRt& e : g->edges) {
+    const SrConvGeom q = geom_of(e);
+    part_n = std::max(part_n, (size_t)sr_train_wgrad_slices(q) * e.w_count);
+    if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) pooled_n = std::max(pooled_n, (size_t)B * q.Ho * q.Wo * q.Cout);
+    if (e.d.kind == SR_EDGE_GAP_DENSE) mean_n = std::max(mean_n, (size_t)B * q.Cin);
+  }
+  const size_t pooled_at = take(pooled_n), mean_at = take(mean_n), dmean_at = take(mean_n), part_at = take(part_n);
+  const size_t terms_at = take((size_t)W * B);
+  if (at > g->train_arena_floats) {
+    SR_HIP(g, hipStreamSynchronize(g->stream));
+    if (g->train_arena) SR_HIP(g, hipFree(g->train_arena));
+    g->train_arena = nullptr;
+    g->train_arena_floats = 0;
+    void* p = nullptr;
+    SR_HIP(g, hipMalloc(&p, at * sizeof(float)));
+    g->train_arena = (float*)p;
+    g->train_arena_floats = at;
+  }
+  float* A = g->train_arena;
+  hipStream_t s = g->stream;
+
+  // forward over the window from the zero state, keeping every frame's states
+  std::vector<const void*> ptrs(g->inputs.size());
+  std::vector<size_t> in_stride(g->inputs.size());
+  for (size_t k = 0; k < g->inputs.size(); ++k) {
+    in_stride[k] = node_floats(g->inputs[k]);
+    ptrs[k] = inputs[k];
+  }
+  sr_status st = sr_reset(g, ptrs.data());
+  if (st != SR_OK) return st;
+  for (int v = 0; v < N; ++v)
+    if (!g->an.is_input[v]) SR_HIP(g, sr_launch_fill_zero(s, A + x_at[v], node_floats(v) * sizeof(float)));
+  for (int i = 1; i <= W; ++i) {
+    for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = (const float*)inputs[k] + (size_t)i * in_stride[k];
+    st = sr_frame_step(g, ptrs.data());
+    if (st != SR_OK) return st;
+    for (int v = 0; v < N; ++v)
+      if (!g->an.is_input[v])
+        SR_HIP(g, hipMemcpyAsync(A + x_at[v] + (size_t)i * node_floats(v), g->nodes[v].state[g->host_frame & 1],
+                                 node_floats(v) * sizeof(float), hipMemcpyDeviceToDevice, s));
+  }
+
+  // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
+  // (frame, node) has the gradient of all its readers before it is processed
+  std::vector<int> order;
+  for (int v = 0; v < N; ++v)
+    if (!g->an.is_input[v]) order.push_back(v);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] > g->an.level[b]; });
+  for (int v : order)
+    for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[c][v], node_floats(v) * sizeof(float)));
+  for (int e = 0; e < g->n_edges; ++e) SR_HIP(g, sr_launch_fill_zero(s, dtheta[e], g->edges[e].w_count * sizeof(float)));
+  if (dbias)
+    for (int v : order)
+      if (dbias[v]) SR_HIP(g, sr_launch_fill_zero(s, dbias[v], (size_t)g->nodes[v].d.channels * sizeof(float)));
+  std::vector<int> slot_of(N, -1);
+  for (size_t k = 0; k < g->inputs.size(); ++k) slot_of[g->inputs[k]] = (int)k;
+  const int classes = g->nodes[out_node].d.channels;
+  const float scale = 1.0f / ((float)B * (float)W);
+  for (int i = W; i >= 1; --i) {
+    const int cur = i & 1;
+    SR_HIP(g, sr_train_ce(s, A + x_at[out_node] + (size_t)i * node_floats(out_node), labels, B, classes, scale,
+                          A + terms_at + (size_t)(i - 1) * B, A + dx_at[cur][out_node]));
+    for (int v : order) {
+      const sr_node_desc& d = g->nodes[v].d;
+      float* da = A + dx_at[cur][v];
+      if (d.act == SR_ACT_RELU) SR_HIP(g, sr_train_relu_mask(s, da, A + x_at[v] + (size_t)i * node_floats(v), node_floats(v)));
+      if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(s, da, B * d.height * d.width, d.channels, dbias[v]));
+      for (int ei = 0; ei < g->n_edges; ++ei) {
+        const EdgeRt& e = g->edges[ei];
+        if (e.d.dst != v) continue;
+        const int u = e.d.src, fi = i - (int)e.d.bridge;
+        const float* xsrc = g->an.is_input[u] ? (const float*)inputs[slot_of[u]] + (size_t)fi * in_stride[slot_of[u]]
+                                              : A + x_at[u] + (size_t)fi * node_floats(u);
+        // frame 0 and the input nodes are given: no gradient is kept for them
+        float* dxsrc = (g->an.is_input[u] || fi == 0) ? nullptr : A + dx_at[fi & 1][u];
+        const SrConvGeom q = geom_of(e);
+        if (e.d.kind == SR_EDGE_GAP_DENSE) {
+          const sr_node_desc& sd = g->nodes[u].d;
+          SR_HIP(g, sr_train_gap_mean(s, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at));
+          SR_HIP(g, sr_train_wgrad(s, q, A + mean_at, da, A + part_at, dtheta[ei]));
+          if (dxsrc) {
+            SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, da, A + dmean_at, 0));
+            SR_HIP(g, sr_train_gap_spread(s, A + dmean_at, B, sd.height * sd.width, sd.channels, dxsrc));
+          }
+          continue;
+        }
+        const float* dy = da;
+        if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) {
+          SR_HIP(g, sr_train_pool_sum(s, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_at));
+          dy = A + pooled_at;
+        }
+        SR_HIP(g, sr_train_wgrad(s, q, xsrc, dy, A + part_at, dtheta[ei]));
+        if (dxsrc) SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, dy, dxsrc, 1));
+      }
+    }
+    // this copy next holds frame i - 2
+    for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[cur][v], node_floats(v) * sizeof(float)));
+  }
+  SR_HIP(g, sr_train_sum_terms(s, A + terms_at, W * B, scale, loss));
+  return SR_OK;
+}
+
+}  // extern "C"
