@@ -388,9 +388,13 @@ EdgeStaging choose_staging(const sr_graph* g, int v, const EdgeRt& e, int BM, in
   return best;
 }
 
-// Does the 4-wave tile kernel have a tile shape for node v whose UNSPLIT source patches fit its LDS
-// budget?  (Decides the default tile kernel: graphs with edges of a large stride onto small images
-// go to the 8-wave kernel, whose stages are cut by row phase throughout.)
+// Does the 4-wave tile kernel have a tile shape for node v all of whose edges can be staged (unsplit or
+// cut into phase planes) within its LDS budget?  (Decides the default tile kernel: only a graph with a
+// node that fails this goes to the 8-wave kernel.  The paper's DSR networks, whose 4x4 node reads 16x16
+// states over stride-4 edges, pass since strided edges are staged as phase planes: 16 images' worth of
+// every fourth row and column is a few KiB.  On them the 4-wave kernel is as fast or faster per streaming
+// frame, 31-51 against 32-61 us, and their sequential pattern runs dependency-driven, 52-137 against
+// 82-270 us per frame.)
 bool four_wave_kernel_fits(const sr_graph* g, int v, int lds_cap) {
   const NodeRt& n = g->nodes[v];
   const int Cout = (n.d.channels + 31) / 32 * 32;   // channel tiles are 32 wide; the rest of the last one is padding
@@ -398,18 +402,11 @@ bool four_wave_kernel_fits(const sr_graph* g, int v, int lds_cap) {
     for (int wn : {4, 2, 1}) {
       if (Cout % (32 * wt * wn) != 0) continue;
       const int BM = 128 * (4 / wn);
+      if (BM / ((int64_t)n.d.height * n.d.width) + 2 > 127) continue;
       bool ok = true;
       for (const EdgeRt& e : g->edges) {
         if (e.d.dst != v) continue;
-        const NodeRt& sn = g->nodes[e.d.src];
-        const int PW = sn.d.width + 2 * e.d.pad, PWs = (PW + e.d.stride - 1) / e.d.stride, RP = e.d.stride * PWs;
-        const int64_t rows = max_patch_rows(g, v, e, BM);
-        bool fits = false;
-        for (int cand : {64, 32, 16})
-          if (sn.Cp % cand == 0 &&
-              rows * row_pitch16(RP, cand / 8 + 1, e.d.stride, e.d.upsample, n.d.width) * 16 <= lds_cap)
-            fits = true;
-        ok = ok && fits;
+        if (e.d.kh * e.d.kw > 64 || choose_staging(g, v, e, BM, lds_cap).KC == 0) ok = false;
       }
       if (ok) return true;
     }

@@ -251,9 +251,9 @@ def test_eight_wave_tile_kernel_rollout_in_hipgraph_matches_steps():
 
 def test_tile_kernel_choice_is_reported():
     import paper_1806_04965_amd as sr
-    # CIFAR-shaped: every patch fits the 4-wave kernel; DSR0 at its batch of 64: the stride-4 edges into the 4x4 node do not;
-    # fp32 graphs have no MFMA node; an explicit choice is reported back
-    for g, options, want in ((W.cifar_sr(batch=2, frames=2), None, 1), (W.dsr_net(0, batch=64, frames=2), None, 2),
+    # CIFAR-shaped: every patch fits the 4-wave kernel; DSR0 at its batch of 64: the stride-4 edges into the 4x4 node
+    # fit as phase planes; fp32 graphs have no MFMA node; an explicit choice is reported back
+    for g, options, want in ((W.cifar_sr(batch=2, frames=2), None, 1), (W.dsr_net(0, batch=64, frames=2), None, 1),
                              (W.tiny_sr(), None, 0), (W.cifar_sr(batch=2, frames=2), OPT_WIDE, 2)):
         dev = sr.SrGraph(g, options=options)
         w, b, _ = W.make_case(g, seed=1)
