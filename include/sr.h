@@ -92,8 +92,9 @@ typedef enum {
   SR_OPT_K_SPLIT = 3,          /* 1 (default): long tiles are cut along the contraction and reduced by the last part; 0: never */
   SR_OPT_TILE_KERNEL = 4,      /* tile kernel of bf16 graphs: 1 = 4 waves per workgroup, weights from registers;
                                   2 = 8 waves, both operands through LDS, next stage loaded during the current one;
-                                  0 (default) = 1 unless a node's source patches do not fit its LDS budget, then 2 */
-  SR_OPT_DATAFLOW = 5          /* dependency-driven execution of graphs whose nodes all run on the 4-wave tile kernel or as
+                                  0 (default) = 1 unless some node has an edge that fits its LDS budget neither whole nor cut into phase
+                                  planes, then 2 */
+  SR_OPT_DATAFLOW = 5,         /* dependency-driven execution of graphs whose nodes all run on the 4-wave tile kernel or as
                                   head items: one launch covers every update step of a frame, and of several frames in
                                   sr_rollout; a work item starts when the nodes it reads have completed the frame it
                                   reads (Eq. 2: frame t - R(e) of the edge's source), not when a whole update step or
@@ -101,6 +102,10 @@ typedef enum {
                                   2 (default): for patterns with more than one update step per frame (F(R) > 1, Eq. 6);
                                   1: whenever possible, also for the streaming pattern; 0: never (one launch per
                                   update step) */
+  SR_OPT_DEP_SPIN_LIMIT = 6    /* polls (with back-off) before a dependency wait of a dependency-driven graph gives up
+                                  (default 2^18, about 0.3 s; 0..2^24).  A wait that gives up lets its work item go
+                                  on with whatever is in memory and is counted by sr_graph_health; every kernel
+                                  still ends normally.  For tests of that path. */
 } sr_option;
 
 /* ---------------------------------------------------------------------------

@@ -97,6 +97,7 @@ struct sr_graph {
   // dependency-driven execution (see SrDep): one launch covers all update steps of several frames
   int dataflow_option = 2;   // 0 never, 1 whenever possible, 2 (default) when a frame has more than one update step
   bool dataflow = false;
+  int dep_spin_limit = 1 << 18;   // polls before a dependency wait gives up: ~0.3 s
   SrDep* deps = nullptr;
   int32_t* done_counters = nullptr;   // one per graph node
   SrTile4* flow_items = nullptr;      // a frame's work items in dependency order: tiles, and aux items as node = -2 - index

@@ -1351,7 +1351,7 @@ sr_status ensure_split_scratch(sr_graph* g) {
 
 // Dependency-driven graphs: `frames` frames, every update step of each, in one launch.
 sr_status enqueue_flow(sr_graph* g, int frames, bool advance, SrSplitScratch split) {
-  const SrFlow flow{g->deps, g->done_counters, 1 << 18, 0};   // ~0.3 s of polling before a wait gives up
+  const SrFlow flow{g->deps, g->done_counters, g->dep_spin_limit, 0};
   SR_HIP(g, sr_launch_mfma(g->stream, g->ctx,
                            SrTables4{g->nodes4, g->planes4, (const SrPlanRef*)g->plan_index, g->plan_tables, g->tap_table},
                            flow, frames, g->flow_items, g->n_flow_items, g->lds_bytes, g->aux, 0, g->heads, g->head_edges,
@@ -1874,6 +1874,10 @@ sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value) {
     case SR_OPT_DATAFLOW:
       if (value < 0 || value > 2) return gfail(g, SR_ERR_ARG, "dependency-driven execution: 0 (off), 1 (on) or 2 (default)");
       g->dataflow_option = (int)value;
+      return SR_OK;
+    case SR_OPT_DEP_SPIN_LIMIT:
+      if (value < 0 || value > (1 << 24)) return gfail(g, SR_ERR_ARG, "spin limit of dependency waits must be in 0..2^24");
+      g->dep_spin_limit = (int)value;
       return SR_OK;
     case SR_OPT_TILE_KERNEL:
       if (value < 0 || value > 2) return gfail(g, SR_ERR_ARG, "tile kernel must be 0 (choose), 1 or 2");

@@ -372,3 +372,25 @@ def test_two_graphs_alive_interleaved_and_recreated():
                 assert max_abs_rel(got, ref[t - 1]) <= 2e-2
         for d, _, _ in devs:
             d.close()
+
+
+def test_dependency_wait_that_gives_up_is_counted_and_every_kernel_ends():
+    # failure path of the dependency-driven launch, forced from the host: with a spin limit of 0 a wait
+    # gives up at its first unsatisfied poll; the work item goes on (results undefined), the kernels
+    # end normally, and the graph reports the waits that gave up.  sr_reset clears the count.
+    import paper_1806_04965_amd as sr
+    g0 = W.cifar_sr(batch=4, frames=4)
+    g = g0.with_pattern(W.sequential_pattern(g0))
+    w, b, x = W.make_case(g, seed=3, bias_scale=0.1, frames=4)
+    dev = sr.SrGraph(g, options={6: 0})
+    dev.set_parameters(w, b)
+    xd = [to_device_(x[v], g.dtype) for v in g.input_nodes()]
+    dev.rollout(xd, 4)
+    dev.synchronize()
+    h = dev.health()
+    assert h["dependency_driven"] and h["dependency_timeouts"] > 0, h
+    dev.reset([xi[0] for xi in xd])
+    assert dev.health()["dependency_timeouts"] == 0
+    dev.close()
+    with pytest.raises(sr.SrError):
+        sr.SrGraph(g, options={6: -1})
