@@ -69,6 +69,76 @@ PEAK_BF16_TFLOPS = 2500.0      # MI355X dense bf16 MFMA peak
 PEAK_FP32_VALU_TFLOPS = 157.3  # fp32 vector peak (the fp32 graph runs on plain ALUs)
 
 
+def train_window_bench(args, g):
+    """One step = one training window (Sec. 3 rollout window of size W; loss of App. A2): forward over
+    W frames, loss, gradients of every weight and bias, through sr_window_gradients on the fp32 graph.
+    The roofline is the fp32 vector one; the algorithmic work of a window is taken as 3 x the forward
+    FLOP of its W frames (forward, state gradients, weight gradients: the state gradients of edges that
+    leave an input are not needed and not computed, so this over-counts slightly)."""
+    import dataclasses
+    import numpy as np
+    import torch
+    import workloads as W
+    import paper_1806_04965_amd as sr
+    Wn = args.train_window
+    g = dataclasses.replace(g, dtype="f32", frames=Wn)
+    B = g.batch
+    w, b, x = W.make_case(g, seed=0, frames=Wn, bias_scale=0.1)
+    labels_h = np.random.default_rng(1).integers(0, g.nodes[g.out_node].channels, B).astype(np.int32)
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    ins = g.input_nodes()
+    xin = [torch.from_numpy(x[v][:Wn + 1]).to("cuda").float().contiguous() for v in ins]
+    labels = torch.from_numpy(labels_h).to("cuda")
+    work = dev.work()
+    for _ in range(max(1, args.warmup)):
+        res = dev.window_gradients(xin, labels, Wn)
+    dev.synchronize()
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(dev.stream)
+    for _ in range(args.steps):
+        res = dev.window_gradients(xin, labels, Wn)
+    ev1.record(dev.stream)
+    dev.synchronize()
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+    ms_per_step = dt / args.steps * 1e3
+    flop = 3.0 * work["flops_per_frame"] * Wn
+    achieved = flop / (ev0.elapsed_time(ev1) / args.steps * 1e-3) / 1e12
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import training as otr
+        Bs = min(B, 4)          # bounded sample: the same window on a few samples of the batch
+        gs = dataclasses.replace(g, batch=Bs)
+        c0 = time.perf_counter()
+        otr.window_gradients(gs, w, b, {v: x[v][:Wn + 1, :Bs] for v in x}, labels_h[:Bs], Wn)
+        cdt = time.perf_counter() - c0
+        try:
+            from threadpoolctl import threadpool_info
+            cores = max([p.get("num_threads", 1) for p in threadpool_info()] or [os.cpu_count()])
+        except Exception:
+            cores = os.cpu_count()
+        cpu = {"value": round(Bs * Wn / cdt, 3), "unit": "frames/s", "cores": int(cores), "kind": "oracle",
+               "sample": f"one window of {Wn} frames on {Bs} of the {B} samples (float64), {cdt:.1f} s"}
+    line = {
+        "metric": "training-window frames/sec (batch x window frames / s; forward + loss + all gradients)",
+        "value": round(B * Wn * args.steps / dt, 1), "unit": "frames/s", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "f32", "data": "synthetic",
+        "config": {"workload": f"{args.workload} ({args.pattern} rollout), training window W={Wn}", "batch": B,
+                   "nodes": len(g.nodes), "edges": len(g.edges)},
+        "loss": round(float(res[0].cpu()[0]), 6),
+        "roofline": {"bound": "alu", "achieved": round(achieved, 4), "peak": PEAK_FP32_VALU_TFLOPS, "unit": "TFLOP/s",
+                     "frac": round(achieved / PEAK_FP32_VALU_TFLOPS, 5), "traffic": None,
+                     "kernel": "sr_window_gradients (all kernels of a window)", "flop_per_step": flop},
+        "cpu_baseline": cpu,
+    }
+    dev.close()
+    print(json.dumps(line))
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -84,6 +154,9 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 512 MiB device copy (a kernel of known HBM traffic, for scaling "
                          "FETCH_SIZE / WRITE_SIZE counters)")
+    ap.add_argument("--train-window", type=int, default=0, metavar="W",
+                    help="time sr_window_gradients on a rollout window of W frames of the workload (as an fp32 "
+                         "graph) instead of the rollout; a step is then one window: forward, loss, all gradients")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -101,6 +174,8 @@ def main():
     bits = {"streaming": W.streaming_pattern, "sequential": W.sequential_pattern,
             "hybrid": W.hybrid_pattern}[args.pattern](g)
     g = g.with_pattern(bits)
+    if args.train_window > 0:
+        return train_window_bench(args, g)
     T, B = g.frames, g.batch
     w, b, x = W.make_case(g, seed=0)
 

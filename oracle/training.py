@@ -25,7 +25,8 @@ closed-form gradient; the adjoint identity <f_e(x), y> = <x, f_e^T(y)> of every 
 Sec. 4 fixes: a window shorter than the shortest input-to-output path gives the weights of edges
 that leave an input no gradient at all under the streaming pattern; and the gradient with the
 rectifier's derivative toggled at chosen elements (see Window.near_kink) against torch.autograd on a
-window whose rectifiers carry that derivative.
+window whose rectifiers carry that derivative.  rmsprop_step: closed form of the first step, a constant
+gradient's limit, and torch.optim.RMSprop over several steps.
 """
 from __future__ import annotations
 
@@ -232,3 +233,20 @@ def window_gradients(graph, weights, biases, inputs, labels, W, out_node=None):
     loss = win.loss(labels, out_node)
     dtheta, dbias, _ = win.backward(labels, out_node)
     return loss, dtheta, dbias
+
+
+# ----------------------------------------------------------------------------
+# optimiser
+# ----------------------------------------------------------------------------
+
+def rmsprop_step(theta, mean_square, grad, lr, rho=0.9, eps=1e-7):
+    """One RMSprop update (the optimiser of App. A2, training details; Tieleman & Hinton 2012):
+         a     <- rho * a + (1 - rho) * g^2
+         theta <- theta - lr * g / (sqrt(a) + eps)
+    with a the running mean of the squared gradient (zero before the first step).  The paper gives the
+    initial learning rate (1e-4) and its decay (1e-6 per update: lr_t = lr / (1 + decay * t), the
+    caller's business); rho and eps are not stated: the defaults of the authors' framework are taken.
+    Returns (theta, a) as new float64 arrays."""
+    g = np.asarray(grad, dtype=np.float64)
+    a = rho * np.asarray(mean_square, dtype=np.float64) + (1.0 - rho) * g * g
+    return np.asarray(theta, dtype=np.float64) - lr * g / (np.sqrt(a) + eps), a

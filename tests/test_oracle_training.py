@@ -294,3 +294,32 @@ def test_kink_matching_recovers_planted_toggles():
         assert gpu_util.match_kinks(win, labels, clean, base) == []
     finally:
         gpu_util.KINK_TAU = old
+
+
+def test_rmsprop_step_closed_forms_and_torch():
+    import torch
+    rng = np.random.default_rng(1)
+    theta = rng.standard_normal((3, 4))
+    g = rng.standard_normal((3, 4))
+    lr, rho, eps = 1e-2, 0.9, 1e-7
+    # first step from a = 0: theta - lr * g / (sqrt(1 - rho) |g| + eps)
+    t1, a1 = tr.rmsprop_step(theta, np.zeros_like(theta), g, lr, rho, eps)
+    np.testing.assert_allclose(a1, (1 - rho) * g * g, rtol=1e-15)
+    np.testing.assert_allclose(t1, theta - lr * g / (np.sqrt(1 - rho) * np.abs(g) + eps), rtol=1e-14)
+    # a constant gradient: a -> g^2, the step tends to lr * sign(g)
+    t, a = theta, np.zeros_like(theta)
+    for _ in range(400):
+        prev = t
+        t, a = tr.rmsprop_step(t, a, g, lr, rho, eps)
+    np.testing.assert_allclose(a, g * g, rtol=1e-12)
+    np.testing.assert_allclose(prev - t, lr * np.sign(g), rtol=1e-5)
+    # several steps with changing gradients against torch's optimiser
+    p = torch.tensor(theta, dtype=torch.float64, requires_grad=True)
+    opt = torch.optim.RMSprop([p], lr=lr, alpha=rho, eps=eps)
+    t, a = theta, np.zeros_like(theta)
+    for k in range(5):
+        gk = rng.standard_normal((3, 4))
+        p.grad = torch.tensor(gk, dtype=torch.float64)
+        opt.step()
+        t, a = tr.rmsprop_step(t, a, gk, lr, rho, eps)
+        np.testing.assert_allclose(t, p.detach().numpy(), rtol=1e-13, atol=1e-15)
