@@ -306,13 +306,13 @@ def test_rmsprop_step_closed_forms_and_torch():
     t1, a1 = tr.rmsprop_step(theta, np.zeros_like(theta), g, lr, rho, eps)
     np.testing.assert_allclose(a1, (1 - rho) * g * g, rtol=1e-15)
     np.testing.assert_allclose(t1, theta - lr * g / (np.sqrt(1 - rho) * np.abs(g) + eps), rtol=1e-14)
-    # a constant gradient: a -> g^2, the step tends to lr * sign(g)
+    # a constant gradient: a -> g^2, the step tends to lr * g / (|g| + eps), i.e. lr * sign(g)
     t, a = theta, np.zeros_like(theta)
     for _ in range(400):
         prev = t
         t, a = tr.rmsprop_step(t, a, g, lr, rho, eps)
     np.testing.assert_allclose(a, g * g, rtol=1e-12)
-    np.testing.assert_allclose(prev - t, lr * np.sign(g), rtol=1e-5)
+    np.testing.assert_allclose(prev - t, lr * g / (np.abs(g) + eps), rtol=1e-10)
     # several steps with changing gradients against torch's optimiser
     p = torch.tensor(theta, dtype=torch.float64, requires_grad=True)
     opt = torch.optim.RMSprop([p], lr=lr, alpha=rho, eps=eps)
