@@ -305,6 +305,27 @@ sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
 sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const int32_t* labels,
                               int32_t out_node, float* loss, float* const* dtheta, float* const* dbias);
 
+/* One RMSprop update of every weight and bias of an SR_F32 graph, in place on the device (App. A2,
+ * training details: RMSprop; Tieleman & Hinton 2012):
+ *     a <- rho * a + (1 - rho) * g^2,     theta <- theta - lr * g / (sqrt(a) + eps)
+ * with g the gradients as sr_window_gradients returns them (dtheta: n_edges device pointers; dbias:
+ * n_nodes device pointers or NULL, NULL entries and input nodes skipped) and a the running mean of
+ * the squared gradient, kept by the graph per parameter and zero before the first update.  The paper
+ * gives lr = 1e-4 with a decay of 1e-6 per update (the caller passes the current lr); rho and eps are
+ * not stated there (0.9 and 1e-7 are the defaults of the authors' framework).  The next frame or
+ * window uses the new parameters; sr_graph_set_weights / sr_graph_set_bias overwrite them but leave a.
+ * Asynchronous.  Errors: SR_ERR_ARG (bf16 graph, null gradient, lr < 0, rho outside [0,1], eps <= 0),
+ * SR_ERR_STATE (weights missing), SR_ERR_OOM, SR_ERR_DEVICE. */
+sr_status sr_rmsprop_step(sr_graph* g, float lr, float rho, float eps, const float* const* dtheta,
+                          const float* const* dbias);
+
+/* Current theta_e / b_v of the graph as the device holds them (after updates), into host float arrays
+ * laid out as for sr_graph_set_weights / sr_graph_set_bias; count must match.  For bf16 graphs these are
+ * the bf16-rounded values as floats.  Synchronises with the graph's stream.
+ * Errors: SR_ERR_ARG, SR_ERR_STATE (no weights set), SR_ERR_DEVICE. */
+sr_status sr_graph_get_weights(sr_graph* g, int32_t edge, float* host_w, size_t count);
+sr_status sr_graph_get_bias(sr_graph* g, int32_t node, float* host_b, size_t count);
+
 void sr_graph_destroy(sr_graph* g);
 
 const char* sr_status_str(sr_status s);

@@ -17,7 +17,7 @@ EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_mo
            "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
            "sr_frame_step_static", "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
-           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_health", "sr_window_gradients", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
+           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_health", "sr_window_gradients", "sr_rmsprop_step", "sr_graph_get_weights", "sr_graph_get_bias", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
 
 
 class NodeDesc(C.Structure):
@@ -76,6 +76,9 @@ def load_library():
     lib.sr_graph_node_kernels.argtypes = [vp, P(i32)]
     lib.sr_graph_health.argtypes = [vp, P(i64), P(i32)]
     lib.sr_window_gradients.argtypes = [vp, i32, P(vp), vp, i32, vp, P(vp), P(vp)]
+    lib.sr_rmsprop_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, P(vp), P(vp)]
+    lib.sr_graph_get_weights.argtypes = [vp, i32, P(C.c_float), C.c_size_t]
+    lib.sr_graph_get_bias.argtypes = [vp, i32, P(C.c_float), C.c_size_t]
     lib.sr_graph_destroy.argtypes = [vp]
     lib.sr_graph_destroy.restype = None
     lib.sr_status_str.argtypes = [i32]
@@ -231,6 +234,13 @@ class SrGraph:
                 if t is not None:
                     t.record_stream(self.stream)
 
+    def _publish(self):
+        """The other direction: torch work enqueued from now on (on torch's current stream) runs after what
+        the library has enqueued so far, so tensors the library has just been asked to fill can be used."""
+        cur = self.torch.cuda.current_stream()
+        if cur != self.stream:
+            cur.wait_stream(self.stream)
+
     def _ptrs(self, tensors):
         arr = (C.c_void_p * max(1, len(self.inputs)))()
         for i, t in enumerate(tensors):
@@ -267,6 +277,8 @@ class SrGraph:
             optr = C.c_void_p(outputs.data_ptr())
             self._order(outputs)
         _check(self.lib, self.lib.sr_rollout(self.h, self._ptrs(inputs), T, out_node, optr), self.h)
+        if outputs is not None:
+            self._publish()
 
     def window_gradients(self, inputs, labels, W: int, out_node: Optional[int] = None):
         """inputs: one float tensor [W+1,B,H,W,C] per input node; labels: int32 tensor [B] on the device.
@@ -297,7 +309,37 @@ class SrGraph:
         self._order(labels, loss, *dth, *dbs)
         _check(self.lib, self.lib.sr_window_gradients(self.h, W, self._ptrs(inputs), C.c_void_p(labels.data_ptr()), out,
                                                        C.c_void_p(loss.data_ptr()), tarr, barr), self.h)
+        self._publish()
         return loss, dth, dbs
+
+    def rmsprop_step(self, dtheta, dbias, lr: float, rho: float = 0.9, eps: float = 1e-7):
+        """One RMSprop update of the graph's parameters from the gradients of window_gradients."""
+        tarr = (C.c_void_p * len(dtheta))()
+        for i, t in enumerate(dtheta):
+            assert t.is_cuda and t.is_contiguous() and t.dtype == self.torch.float32
+            tarr[i] = t.data_ptr()
+        barr = (C.c_void_p * len(self.g.nodes))()
+        for v, t in enumerate(dbias):
+            barr[v] = None if t is None else t.data_ptr()
+        self._order(*dtheta, *dbias)
+        _check(self.lib, self.lib.sr_rmsprop_step(self.h, lr, rho, eps, tarr, barr), self.h)
+
+    def get_parameters(self):
+        """(weights, biases) as the device holds them now, as float32 numpy arrays."""
+        g = self.g
+        ws, bs = [], []
+        for ei, e in enumerate(g.edges):
+            s, d = g.nodes[e.src], g.nodes[e.dst]
+            shape = {"conv": (e.kh, e.kw, s.channels, d.channels), "dense": (s.height, s.width, s.channels, d.channels),
+                     "gap_dense": (1, 1, s.channels, d.channels)}[e.kind]
+            a = np.empty(shape, dtype=np.float32)
+            _check(self.lib, self.lib.sr_graph_get_weights(self.h, ei, a.ctypes.data_as(C.POINTER(C.c_float)), a.size), self.h)
+            ws.append(a)
+        for v, n in enumerate(g.nodes):
+            a = np.empty(n.channels, dtype=np.float32)
+            _check(self.lib, self.lib.sr_graph_get_bias(self.h, v, a.ctypes.data_as(C.POINTER(C.c_float)), a.size), self.h)
+            bs.append(a)
+        return ws, bs
 
     def get_state(self, node: int):
         n = self.g.nodes[node]

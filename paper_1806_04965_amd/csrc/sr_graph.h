@@ -123,6 +123,7 @@ struct sr_graph {
   // training window: one arena holding every node's states of the frames 0..W, two gradient copies per
   // node (frames i and i-1 of the reverse sweep) and the scratch of the gradient kernels
   float* train_arena = nullptr;
+  std::vector<float*> rms_w, rms_b;   // RMSprop's running mean of the squared gradient, per edge / node (on first use)
   size_t train_arena_floats = 0;
 
   hipGraph_t graph1 = nullptr, graphN = nullptr;

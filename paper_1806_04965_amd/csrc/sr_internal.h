@@ -321,6 +321,8 @@ int sr_train_wgrad_slices(const SrConvGeom& q);
 hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, const float* dy, float* part,
                           float* dtheta);
 hipError_t sr_train_gap_mean(hipStream_t s, const float* x, int B, int HW, int C, float* out);
+hipError_t sr_train_rmsprop(hipStream_t s, float* theta, float* a, const float* g, size_t n, float lr, float rho,
+                            float eps);
 hipError_t sr_train_gap_spread(hipStream_t s, const float* dmean, int B, int HW, int C, float* dx);
 // 8-wave kernel: bytes of one of its two stage buffers, and floats of one part's K-split slab
 #define SR8_BUF_BYTES (80 * 1024)

@@ -174,7 +174,25 @@ __global__ void sr_gap_spread_kernel(const float* __restrict__ dmean, int B, int
   dx[i] += dmean[(size_t)b * C + c] / (float)HW;
 }
 
+// RMSprop: a <- rho a + (1 - rho) g^2;  theta <- theta - lr g / (sqrt(a) + eps)
+__global__ void sr_rmsprop_kernel(float* __restrict__ theta, float* __restrict__ a, const float* __restrict__ g,
+                                  size_t n, float lr, float rho, float eps) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float gi = g[i];
+  const float ai = rho * a[i] + (1.f - rho) * gi * gi;
+  a[i] = ai;
+  theta[i] -= lr * gi / (sqrtf(ai) + eps);
+}
+
 }  // namespace
+
+hipError_t sr_train_rmsprop(hipStream_t s, float* theta, float* a, const float* g, size_t n, float lr, float rho,
+                            float eps) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(sr_rmsprop_kernel, dim3(grid_for((long long)n, 256)), dim3(256), 0, s, theta, a, g, n, lr, rho, eps);
+  return hipGetLastError();
+}
 
 hipError_t sr_train_ce(hipStream_t s, const float* z, const int32_t* labels, int B, int C, float scale, float* terms,
                        float* dz) {

@@ -159,4 +159,60 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   return SR_OK;
 }
 
+sr_status sr_rmsprop_step(sr_graph* g, float lr, float rho, float eps, const float* const* dtheta,
+                          const float* const* dbias) {
+  if (!g || !dtheta || !(lr >= 0.f) || !(rho >= 0.f && rho <= 1.f) || !(eps > 0.f))
+    return sr_gfail(g, SR_ERR_ARG, "bad argument to sr_rmsprop_step");
+  if (g->dtype != SR_F32) return sr_gfail(g, SR_ERR_ARG, "sr_rmsprop_step: SR_F32 graphs only");
+  for (int e = 0; e < g->n_edges; ++e) {
+    if (!dtheta[e]) return sr_gfail(g, SR_ERR_ARG, "sr_rmsprop_step: dtheta[" + std::to_string(e) + "] is null");
+    if (!g->edges[e].has_w) return sr_gfail(g, SR_ERR_STATE, "edge " + std::to_string(e) + " has no weights");
+  }
+  if (g->rms_w.empty()) {
+    g->rms_w.assign(g->n_edges, nullptr);
+    g->rms_b.assign(g->n_nodes, nullptr);
+  }
+  auto running = [&](float** slot, size_t n) -> sr_status {
+    if (*slot) return SR_OK;
+    void* p = nullptr;
+    SR_HIP(g, hipMalloc(&p, std::max<size_t>(n, 4) * sizeof(float)));
+    g->dev_allocs.push_back(p);
+    *slot = (float*)p;
+    SR_HIP(g, sr_launch_fill_zero(g->stream, p, n * sizeof(float)));
+    return SR_OK;
+  };
+  for (int e = 0; e < g->n_edges; ++e) {
+    sr_status st = running(&g->rms_w[e], g->edges[e].w_count);
+    if (st != SR_OK) return st;
+    SR_HIP(g, sr_train_rmsprop(g->stream, g->edges[e].w_dev, g->rms_w[e], dtheta[e], g->edges[e].w_count, lr, rho, eps));
+  }
+  if (dbias)
+    for (int v = 0; v < g->n_nodes; ++v) {
+      if (g->an.is_input[v] || !dbias[v]) continue;
+      const size_t n = (size_t)g->nodes[v].d.channels;
+      sr_status st = running(&g->rms_b[v], n);
+      if (st != SR_OK) return st;
+      SR_HIP(g, sr_train_rmsprop(g->stream, g->nodes[v].bias_dev, g->rms_b[v], dbias[v], n, lr, rho, eps));
+    }
+  return SR_OK;
+}
+
+sr_status sr_graph_get_weights(sr_graph* g, int32_t edge, float* host_w, size_t count) {
+  if (!g || !host_w || edge < 0 || edge >= g->n_edges) return sr_gfail(g, SR_ERR_ARG, "bad argument to sr_graph_get_weights");
+  const EdgeRt& e = g->edges[edge];
+  if (count != e.w_count) return sr_gfail(g, SR_ERR_ARG, "edge " + std::to_string(edge) + ": expected " + std::to_string(e.w_count) + " weights");
+  if (!e.has_w) return sr_gfail(g, SR_ERR_STATE, "edge " + std::to_string(edge) + " has no weights");
+  SR_HIP(g, hipStreamSynchronize(g->stream));
+  SR_HIP(g, hipMemcpy(host_w, e.w_dev, count * sizeof(float), hipMemcpyDeviceToHost));
+  return SR_OK;
+}
+
+sr_status sr_graph_get_bias(sr_graph* g, int32_t node, float* host_b, size_t count) {
+  if (!g || !host_b || node < 0 || node >= g->n_nodes) return sr_gfail(g, SR_ERR_ARG, "bad argument to sr_graph_get_bias");
+  if (count != (size_t)g->nodes[node].d.channels) return sr_gfail(g, SR_ERR_ARG, "bias length differs from the node's channels");
+  SR_HIP(g, hipStreamSynchronize(g->stream));
+  SR_HIP(g, hipMemcpy(host_b, g->nodes[node].bias_dev, count * sizeof(float), hipMemcpyDeviceToHost));
+  return SR_OK;
+}
+
 }  // extern "C"

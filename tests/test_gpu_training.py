@@ -172,3 +172,88 @@ def test_refusals():
     with pytest.raises(sr.SrError):
         dev.window_gradients(xd, labels, 0)
     dev.close()
+
+
+def test_rmsprop_step_on_given_gradients():
+    # the update itself, on seeded gradients handed to both sides (App. A2: RMSprop); three steps so that the
+    # running mean of the squared gradient is carried over
+    import torch
+    import paper_1806_04965_amd as sr
+    g0 = small_sr_graph(batch=2)
+    g = g0.with_pattern(W.streaming_pattern(g0))
+    w, b, _ = W.make_case(g, seed=9, bias_scale=0.1, frames=1)
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    ins = g.input_nodes()
+    rng = np.random.default_rng(10)
+    th = [wi.astype(np.float64) for wi in w]
+    bs = [bi.astype(np.float64) for bi in b]
+    a_w = [np.zeros_like(t) for t in th]
+    a_b = [np.zeros_like(t) for t in bs]
+    lr, rho, eps = 1e-2, 0.9, 1e-7
+    for step in range(3):
+        gw = [(rng.standard_normal(t.shape) * 10.0 ** rng.integers(-6, 1)).astype(np.float32) for t in th]
+        gb = [None if v in ins else rng.standard_normal(t.shape).astype(np.float32) for v, t in enumerate(bs)]
+        dev.rmsprop_step([torch.from_numpy(t).to("cuda") for t in gw],
+                         [None if t is None else torch.from_numpy(t).to("cuda") for t in gb], lr / (1 + 1e-6 * step), rho, eps)
+        for i in range(len(th)):
+            th[i], a_w[i] = tr.rmsprop_step(th[i], a_w[i], gw[i], lr / (1 + 1e-6 * step), rho, eps)
+        for v in range(len(bs)):
+            if gb[v] is not None:
+                bs[v], a_b[v] = tr.rmsprop_step(bs[v], a_b[v], gb[v], lr / (1 + 1e-6 * step), rho, eps)
+        got_w, got_b = dev.get_parameters()
+        for i in range(len(th)):
+            assert np.abs(got_w[i] - th[i]).max() <= 1e-6 * max(1.0, np.abs(th[i]).max()), (step, i)
+        for v in range(len(bs)):
+            assert np.abs(got_b[v] - bs[v]).max() <= 1e-6 * max(1.0, np.abs(bs[v]).max()), (step, v)
+            if v in ins:
+                assert np.array_equal(got_b[v], b[v])          # input nodes have no parameters to update
+    dev.close()
+
+
+def test_training_steps_follow_the_oracle_and_lower_the_loss():
+    # window gradients + RMSprop, five steps on the same batch (the paper's MNIST SR net, B = 16, W = 4):
+    # the loss falls, and the parameters follow the oracle's loop.  RMSprop divides a gradient by its own
+    # running magnitude, so an element whose gradient is below the float32 noise of its tensor moves by
+    # up to lr / sqrt(1 - rho) in either direction: such elements are only held to that bound.
+    import torch
+    import paper_1806_04965_amd as sr
+    g0 = W.mnist_net("SR", batch=16, frames=4)
+    g = g0.with_pattern(W.streaming_pattern(g0))
+    Wn = 4
+    w, b, x = W.make_case(g, seed=12, bias_scale=0.1, frames=Wn, recipe="uniform")
+    labels = np.random.default_rng(13).integers(0, 10, g.batch).astype(np.int32)
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    ins = g.input_nodes()
+    xd = [to_device(x[v][:Wn + 1], "f32") for v in ins]
+    ld = torch.from_numpy(labels).to("cuda")
+    th = [wi.astype(np.float64) for wi in w]
+    bs = [bi.astype(np.float64) for bi in b]
+    a_w = [np.zeros_like(t) for t in th]
+    a_b = [np.zeros_like(t) for t in bs]
+    lr, rho, eps = 1e-3, 0.9, 1e-7
+    losses, ref_losses = [], []
+    for step in range(5):
+        loss, dth, dbs = dev.window_gradients(xd, ld, Wn)
+        dev.rmsprop_step(dth, dbs, lr, rho, eps)
+        losses.append(float(loss.cpu()[0]))
+        rl, rdth, rdb = tr.window_gradients(g, th, bs, {v: x[v][:Wn + 1] for v in x}, labels, Wn)
+        ref_losses.append(rl)
+        noisy = []
+        for i in range(len(th)):
+            noisy.append(np.abs(rdth[i]) < 1e-3 * np.abs(rdth[i]).max())
+            th[i], a_w[i] = tr.rmsprop_step(th[i], a_w[i], rdth[i], lr, rho, eps)
+        for v in range(len(bs)):
+            if v not in ins:
+                bs[v], a_b[v] = tr.rmsprop_step(bs[v], a_b[v], rdb[v], lr, rho, eps)
+        got_w, _ = dev.get_parameters()
+        bound = (step + 1) * 2 * lr / np.sqrt(1 - rho) * 1.01
+        for i in range(len(th)):
+            d = np.abs(got_w[i] - th[i])
+            assert d[~noisy[i]].max() <= 2e-2 * lr * (step + 1), (step, i, d[~noisy[i]].max())
+            assert d.max() <= bound, (step, i, d.max())
+    assert all(abs(a - c) <= 1e-4 * max(1.0, abs(c)) for a, c in zip(losses, ref_losses)), (losses, ref_losses)
+    assert losses[-1] < losses[0] - 0.05, losses
+    print(f"[train] mnist_sr, 5 RMSprop steps: loss {losses[0]:.4f} -> {losses[-1]:.4f} (oracle {ref_losses[0]:.4f} -> {ref_losses[-1]:.4f})", flush=True)
+    dev.close()
