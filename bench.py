@@ -263,7 +263,9 @@ def main():
                     "kernel": "sr_mfma8_kernel" if dev.tile_kernel() == 2 else "sr_mfma_kernel",
                     "launch_ms": round(launch_ms, 4),
                     "launch_ms_single": round(float(np.mean(kind_ms[1])), 4),
-                    "launches_per_frame": tile_launches_per_frame, "flop_per_launch": flop_per_launch}
+                    "launches_per_frame": tile_launches_per_frame, "flop_per_launch": flop_per_launch,
+                    # bytes per frame by class as the planner counts them (no cache modelled)
+                    "traffic_model": {k: int(v) for k, v in dev.traffic_model().items()}}
     else:
         d_ms = float(np.mean(kind_ms.get(2, [float("nan")])))
         achieved = work["flops_per_frame"] / (d_ms * 1e-3) / 1e12

@@ -254,6 +254,18 @@ sr_status sr_frame_step_timed(sr_graph* g, const void* const* inputs_t, float* k
 sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfma_tiles,
                         int64_t* device_bytes);
 
+/* Bytes one frame moves, by class, as the planner counts them (no cache is modelled; for setting the
+ * HBM counters of a profile against): bytes6 (host, 6 doubles) =
+ *   [0] every state that some edge reads, once        [1] every edge reading its whole source once
+ *   [2] what the tiles of the 4-wave kernel load into LDS: per (tile, plane) the distinct source positions
+ *       of its patch, all channel chunks -- [1] plus the halo rows and columns that neighbouring tiles share
+ *       (0 for graphs on other kernels)
+ *   [3] every weight once                              [4] the weights as the tiles read them (per tile the
+ *       packed weights of its channel range; served by the L2 of the tile's XCD after the first tile)
+ *   [5] every computed state written once.
+ * The frame update of App. A1.2 needs [0] + [3] + [5] at least.  Plans the graph if needed. */
+sr_status sr_graph_traffic_model(const sr_graph* g, double* bytes6);
+
 /* Which tile kernel the graph's MFMA nodes run on (what SR_OPT_TILE_KERNEL = 0 chose, Eq. 2 hot
  * path): 1 = 4 waves per workgroup, 2 = 8 waves; 0 if the graph has no MFMA node (fp32 graphs,
  * SR_OPT_FORCE_DIRECT).  Plans the graph if that has not happened yet, as sr_graph_work does. */

@@ -17,7 +17,7 @@ EXPORTS = ["sr_analyze", "sr_count_valid_patterns", "sr_tableau", "sr_equally_mo
            "sr_pattern_count_bounds", "sr_graph_create", "sr_graph_set_weights",
            "sr_graph_set_bias", "sr_graph_configure", "sr_graph_info", "sr_reset", "sr_frame_step",
            "sr_frame_step_static", "sr_rollout", "sr_get_state", "sr_set_state", "sr_frame_index", "sr_frame_step_timed",
-           "sr_graph_work", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_health", "sr_window_gradients", "sr_rmsprop_step", "sr_graph_get_weights", "sr_graph_get_bias", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
+           "sr_graph_work", "sr_graph_traffic_model", "sr_graph_tile_kernel", "sr_graph_node_kernels", "sr_graph_health", "sr_window_gradients", "sr_rmsprop_step", "sr_graph_get_weights", "sr_graph_get_bias", "sr_graph_destroy", "sr_status_str", "sr_last_error"]
 
 
 class NodeDesc(C.Structure):
@@ -72,6 +72,7 @@ def load_library():
     lib.sr_frame_index.argtypes = [vp, P(i64)]
     lib.sr_frame_step_timed.argtypes = [vp, P(vp), P(C.c_float), P(i32), i32, P(i32)]
     lib.sr_graph_work.argtypes = [vp, P(C.c_double), P(i64), P(i64)]
+    lib.sr_graph_traffic_model.argtypes = [vp, P(C.c_double)]
     lib.sr_graph_tile_kernel.argtypes = [vp, P(i32)]
     lib.sr_graph_node_kernels.argtypes = [vp, P(i32)]
     lib.sr_graph_health.argtypes = [vp, P(i64), P(i32)]
@@ -204,6 +205,13 @@ class SrGraph:
         fl, t, b = C.c_double(), C.c_int64(), C.c_int64()
         _check(self.lib, self.lib.sr_graph_work(self.h, C.byref(fl), C.byref(t), C.byref(b)), self.h)
         return {"flops_per_frame": fl.value, "mfma_tiles": t.value, "device_bytes": b.value}
+
+    def traffic_model(self):
+        """sr_graph_traffic_model: bytes per frame by class (no cache modelled)."""
+        a = (C.c_double * 6)()
+        _check(self.lib, self.lib.sr_graph_traffic_model(self.h, a), self.h)
+        keys = ["states_read_once", "edge_source_reads", "tile_patch_loads", "weights_once", "tile_weight_reads", "states_written"]
+        return dict(zip(keys, [float(x) for x in a]))
 
     def tile_kernel(self):
         k = C.c_int32()

@@ -114,6 +114,7 @@ struct sr_graph {
   int lds_bytes = 0;
   int64_t n_mfma_tiles = 0;
   double flops = 0;
+  double traffic[6] = {0, 0, 0, 0, 0, 0};   // see sr_graph_traffic_model
   int64_t device_bytes = 0;
   int launches_per_frame = 0;
 

@@ -524,6 +524,19 @@ sr_status finalize(sr_graph* g) {
   const int lds_cap = sr_mfma_max_lds_bytes();
   g->lds_bytes = 0;
   g->flops = 0;
+  for (double& t : g->traffic) t = 0;
+  for (int v = 0; v < g->n_nodes; ++v) {
+    bool read = false;
+    for (const EdgeRt& e : g->edges) read |= (e.d.src == v);
+    const double bytes = (double)B * g->nodes[v].d.height * g->nodes[v].d.width * g->nodes[v].Cp * elem_size(g);
+    if (read) g->traffic[0] += bytes;                       // every state that has a reader, once
+    if (!g->an.is_input[v]) g->traffic[5] += bytes;         // every computed state, written once
+  }
+  for (const EdgeRt& e : g->edges) {
+    const NodeRt& sn = g->nodes[e.d.src];
+    g->traffic[1] += (double)B * sn.d.height * sn.d.width * sn.Cp * elem_size(g);   // one full read per edge
+    g->traffic[3] += (double)e.w_count * elem_size(g);
+  }
   g->n_mfma_tiles = 0;
 
   for (const EdgeRt& e : g->edges) {
@@ -907,6 +920,13 @@ sr_status finalize(sr_graph* g) {
                   const PatchRows r = patch_rows(t.m0, std::min<int64_t>((int64_t)t.m0 + BM, M) - 1,
                                                  n.d.height * n.d.width, n.d.width, m.PHr, 1 << m.lgRS, m.up, m.ta_max + 1);
                   build_plan(&plan_tmp, m, r);
+                  {   // traffic model: the plane's distinct source positions, all channel chunks; the tile's weights
+                    int64_t pos = 0;
+                    for (size_t i = 0; i < plan_tmp.size(); ++i)
+                      pos += (plan_tmp[i] >= 0 && (i == 0 || plan_tmp[i] != plan_tmp[i - 1])) ? 1 : 0;
+                    g->traffic[2] += (double)pos * 16.0 * m.nchunk;
+                    g->traffic[4] += (double)m.ntaps * m.Csp * BN * 2.0;
+                  }
                   uint64_t h = 1469598103934665603ull ^ (uint64_t)(node.edge_begin + ei);
                   for (int32_t x : plan_tmp) h = (h ^ (uint32_t)x) * 1099511628211ull;
                   int found = -1;
@@ -2065,6 +2085,14 @@ sr_status sr_graph_work(const sr_graph* g, double* flops_per_frame, int64_t* mfm
   if (flops_per_frame) *flops_per_frame = g->flops;
   if (mfma_tiles) *mfma_tiles = g->n_mfma_tiles;
   if (device_bytes) *device_bytes = g->device_bytes;
+  return SR_OK;
+}
+
+sr_status sr_graph_traffic_model(const sr_graph* g, double* bytes6) {
+  if (!g || !bytes6) return fail(nullptr, SR_ERR_ARG, "bad argument to sr_graph_traffic_model");
+  sr_status st = finalize(const_cast<sr_graph*>(g));
+  if (st != SR_OK) return st;
+  for (int i = 0; i < 6; ++i) bytes6[i] = g->traffic[i];
   return SR_OK;
 }
 
