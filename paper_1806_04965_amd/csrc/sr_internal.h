@@ -306,7 +306,12 @@ hipError_t sr_static_scratch(void** ptr);
 // ---------------------------------------------------------------------------
 struct SrConvGeom {   // y[b][ho][wo][co] = sum x[b][ho*stride + i - pad][wo*stride + j - pad][ci] * theta[i][j][ci][co]
   int B, H, W, Cin, Ho, Wo, Cout, kh, kw, stride, pad;
+  // state gradient of a strided edge, one launch per phase (ph, pw) of the source pixels: rows are the pixels
+  // h = hh*stride + ph, w = ww*stride + pw of a Hp x Wp grid, which pair only with the taps i = ti0 + a*stride,
+  // j = tj0 + c*stride (a < nti, c < ntj).  Stride 1: one phase, the whole image, all taps.
+  int ph, pw, Hp, Wp, ti0, tj0, nti, ntj;
 };
+#define SR_TRAIN_TILED_MIN_MACS 4.0e6   // smaller contractions stay on the one-thread-per-output kernels
 #define SR_TRAIN_MAX_SLICES 64   // a weight gradient's pixel sum is cut into at most this many partial sums
 hipError_t sr_train_ce(hipStream_t s, const float* z, const int32_t* labels, int B, int C, float scale, float* terms,
                        float* dz);

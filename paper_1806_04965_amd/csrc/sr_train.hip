@@ -6,6 +6,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <algorithm>
+
 #include "sr_internal.h"
 
 namespace {
@@ -174,6 +176,188 @@ __global__ void sr_gap_spread_kernel(const float* __restrict__ dmean, int B, int
   dx[i] += dmean[(size_t)b * C + c] / (float)HW;
 }
 
+// ---------------------------------------------------------------------------
+// The two gradient contractions of a convolution as tiled matrix products on the fp32 matrix cores
+// (v_mfma_f32_32x32x2_f32): C[i][j] (+)= sum_r A[i][r] * B[r][j], operands gathered on the fly.
+//   state gradient  (MODE 0): i = source pixel (b, h, w), j = ci, r = (tap, co);
+//                             A = dy at the output pixel that tap pairs with (h, w), B = theta[tap][j][co]
+//   weight gradient (MODE 1): i = (tap, ci), j = co, r = output pixel m = (b, ho, wo);
+//                             A = x at the source pixel that tap pairs with m, B = dy[m][j]
+// One workgroup (4 waves) owns a 128 x 128 tile of C, a wave 64 x 64 of it (2 x 2 MFMA tiles); the
+// reduction runs in steps of 16 through LDS (A and B tiles stored r-major, so a wave's operand read is
+// 32 consecutive floats); blockIdx.z cuts the reduction into slices (weight gradient: partial sums
+// that a second kernel adds in slice order).  Every sum has a fixed order: same call, same bits.
+typedef float sr_f32x16 __attribute__((ext_vector_type(16)));
+#define SR_GT 128   // tile edge
+#define SR_GR 16    // reduction step
+#define SR_GP 132   // LDS row pitch in floats
+
+template <int MODE>
+__global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, const float* __restrict__ pa,
+                                                              const float* __restrict__ pb, float* __restrict__ pc,
+                                                              int I, int J, int R, int r_per_slice, int accumulate) {
+  __shared__ float As[SR_GR][SR_GP];
+  __shared__ float Bs[SR_GR][SR_GP];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int i0 = blockIdx.x * SR_GT, j0 = blockIdx.y * SR_GT;
+  if (MODE == 0) {
+    // blockIdx.z = phase (ph, pw) of the source pixels: a stride-s edge pairs a pixel only with the taps of its
+    // own residues, so each phase is a contraction of its own (without the split all but 1/s^2 of the products
+    // would be zeros).  I, R: the caller passes those of phase (0, 0), the largest.
+    q.ph = blockIdx.z / q.stride;
+    q.pw = blockIdx.z % q.stride;
+    q.Hp = (q.H - q.ph + q.stride - 1) / q.stride;
+    q.Wp = (q.W - q.pw + q.stride - 1) / q.stride;
+    q.ti0 = (q.ph + q.pad) % q.stride;
+    q.tj0 = (q.pw + q.pad) % q.stride;
+    q.nti = q.ti0 < q.kh ? (q.kh - q.ti0 + q.stride - 1) / q.stride : 0;
+    q.ntj = q.tj0 < q.kw ? (q.kw - q.tj0 + q.stride - 1) / q.stride : 0;
+    I = q.B * max(q.Hp, 0) * max(q.Wp, 0);
+    R = q.nti * q.ntj * q.Cout;
+    r_per_slice = R;
+    if (i0 >= I || (R == 0 && accumulate)) return;   // the whole workgroup: this phase has fewer pixels, or no tap reaches it
+  }
+  const int r_begin = (MODE == 0) ? 0 : blockIdx.z * r_per_slice;
+  const int r_end = min(R, r_begin + r_per_slice);
+  const int wi = wave >> 1, wj = wave & 1;
+
+  // what does not change over the reduction: the rows / columns this thread gathers
+  // MODE 0: A and B are gathered r-fastest (r = t % 16, eight rows t / 16 + 16 n)
+  // MODE 1: A and B are gathered i- / j-fastest (i = t % 128, eight r values t / 128 + 2 n)
+  int ab[8], ah[8], aw[8];          // MODE 0: source pixel (b, h, w) of the thread's 8 A rows (b < 0: row past the end)
+  int ati = 0, atj = 0, aci = 0;    // MODE 1: tap and channel of the thread's A row
+  bool a_row_ok = false;
+  if (MODE == 0) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int i = i0 + (t >> 4) + 16 * n;
+      if (i < I) {   // pixel (hh, ww) of the phase grid
+        aw[n] = (i % q.Wp) * q.stride + q.pw;
+        ah[n] = ((i / q.Wp) % q.Hp) * q.stride + q.ph;
+        ab[n] = i / (q.Wp * q.Hp);
+      } else {
+        ab[n] = -1; ah[n] = 0; aw[n] = 0;
+      }
+    }
+  } else {
+    const int i = i0 + (t & 127);
+    a_row_ok = i < I;
+    aci = i % q.Cin;
+    const int tap = i / q.Cin;
+    atj = tap % q.kw;
+    ati = tap / q.kw;
+  }
+
+  sr_f32x16 acc[2][2];
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+
+  // stride 1, 2, 4 without divisions
+  const int lgs = (q.stride == 1) ? 0 : (q.stride == 2 ? 1 : (q.stride == 4 ? 2 : -1));
+  float va[8], vb[8];
+  // the operands of one reduction step, from global memory into registers
+  auto gather = [&](int rs) {
+    if (MODE == 0) {
+      const int r = rs + (t & 15);
+      const bool r_ok = r < r_end;
+      const int co = r % q.Cout, vt = r / q.Cout;          // vt: index among the phase's taps
+      const int tj = q.tj0 + (vt % q.ntj) * q.stride, ti = q.ti0 + (vt / q.ntj) * q.stride;
+      const int tap = ti * q.kw + tj;
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        float v = 0.f;
+        if (r_ok && ab[n] >= 0) {
+          // the phase's taps pair with its pixels exactly: (h + pad - ti) is a multiple of the stride
+          const int th = ah[n] + q.pad - ti, tw = aw[n] + q.pad - tj;
+          int ho, wo;
+          if (lgs >= 0) { ho = th >> lgs; wo = tw >> lgs; }
+          else { ho = th / q.stride; wo = tw / q.stride; }
+          if (th >= 0 && tw >= 0 && ho < q.Ho && wo < q.Wo) v = pa[(((size_t)ab[n] * q.Ho + ho) * q.Wo + wo) * q.Cout + co];
+        }
+        va[n] = v;
+        const int j = j0 + (t >> 4) + 16 * n;
+        vb[n] = (r_ok && j < J) ? pb[((size_t)tap * q.Cin + j) * q.Cout + co] : 0.f;
+      }
+    } else {
+      // the thread's eight output pixels r, r + 2, ...: decoded once, then stepped
+      int r = rs + (t >> 7);
+      int wo = r % q.Wo, ho = (r / q.Wo) % q.Ho, b = r / (q.Wo * q.Ho);
+      const int j = j0 + (t & 127);
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        float v = 0.f, u = 0.f;
+        if (r < r_end) {
+          if (a_row_ok) {
+            const int hi = ho * q.stride + ati - q.pad, wi2 = wo * q.stride + atj - q.pad;
+            if (hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W) v = pa[(((size_t)b * q.H + hi) * q.W + wi2) * q.Cin + aci];
+          }
+          if (j < J) u = pb[(size_t)r * q.Cout + j];
+        }
+        va[n] = v;
+        vb[n] = u;
+        r += 2;
+        wo += 2;
+        while (wo >= q.Wo) {
+          wo -= q.Wo;
+          if (++ho == q.Ho) { ho = 0; ++b; }
+        }
+      }
+    }
+  };
+
+  if (r_begin < r_end) gather(r_begin);
+  for (int rs = r_begin; rs < r_end; rs += SR_GR) {
+    __syncthreads();   // the previous step's operand reads are done
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      if (MODE == 0) {
+        As[t & 15][(t >> 4) + 16 * n] = va[n];
+        Bs[t & 15][(t >> 4) + 16 * n] = vb[n];
+      } else {
+        As[(t >> 7) + 2 * n][t & 127] = va[n];
+        Bs[(t >> 7) + 2 * n][t & 127] = vb[n];
+      }
+    }
+    __syncthreads();
+    // the next step's loads are in flight while this step's products run
+    if (rs + SR_GR < r_end) gather(rs + SR_GR);
+#pragma unroll
+    for (int kk = 0; kk < SR_GR / 2; ++kk) {
+      const int rr = 2 * kk + (lane >> 5);
+      const float a0 = As[rr][wi * 64 + (lane & 31)], a1 = As[rr][wi * 64 + 32 + (lane & 31)];
+      const float b0 = Bs[rr][wj * 64 + (lane & 31)], b1 = Bs[rr][wj * 64 + 32 + (lane & 31)];
+      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
+      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
+      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
+      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+    }
+  }
+  // register v of lane l holds row 8 * (v / 4) + 4 * (l / 32) + v % 4 (of the A operand's 32), column l % 32
+  float* out = pc + ((MODE == 0) ? (size_t)0 : (size_t)blockIdx.z * I * J);
+#pragma unroll
+  for (int x = 0; x < 2; ++x)
+#pragma unroll
+    for (int y = 0; y < 2; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = i0 + wi * 64 + x * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int j = j0 + wj * 64 + y * 32 + (lane & 31);
+        if (i < I && j < J) {
+          size_t row = (size_t)i;
+          if (MODE == 0) {   // row of the phase grid -> source pixel
+            const int ww = i % q.Wp, hh = (i / q.Wp) % q.Hp, b = i / (q.Wp * q.Hp);
+            row = ((size_t)b * q.H + hh * q.stride + q.ph) * q.W + ww * q.stride + q.pw;
+          }
+          float* dst = out + row * J + j;
+          *dst = accumulate ? *dst + acc[x][y][v] : acc[x][y][v];
+        }
+      }
+}
+
 // RMSprop: a <- rho a + (1 - rho) g^2;  theta <- theta - lr g / (sqrt(a) + eps)
 __global__ void sr_rmsprop_kernel(float* __restrict__ theta, float* __restrict__ a, const float* __restrict__ g,
                                   size_t n, float lr, float rho, float eps) {
@@ -222,9 +406,36 @@ hipError_t sr_train_pool_sum(hipStream_t s, const float* d, int B, int Hs, int W
   return hipGetLastError();
 }
 
+// Which contractions go to the tiled matrix-core kernel: those with enough multiply-adds whose 128 x 128 tiles are
+// reasonably full and numerous (else the one-thread-per-output kernels, which spread over the chip whatever the shape)
+static bool sr_train_big(const SrConvGeom& q) {
+  return (double)q.B * q.Ho * q.Wo * q.Cout * q.Cin * q.kh * q.kw >= SR_TRAIN_TILED_MIN_MACS;
+}
+static long long sr_wgrad_tiles(const SrConvGeom& q) {
+  return ((long long)q.kh * q.kw * q.Cin + SR_GT - 1) / SR_GT * ((q.Cout + SR_GT - 1) / SR_GT);
+}
+static long long sr_wgrad_max_slices(const SrConvGeom& q) {   // slices of at least 256 pixels
+  const long long M = (long long)q.B * q.Ho * q.Wo;
+  return std::min<long long>(SR_TRAIN_MAX_SLICES, std::max<long long>(1, M / 256));
+}
+static bool sr_dgrad_tiled(const SrConvGeom& q) {
+  return sr_train_big(q) && q.Cin >= 32 && ((long long)q.B * q.H * q.W + SR_GT - 1) / SR_GT >= 16;
+}
+static bool sr_wgrad_tiled(const SrConvGeom& q) {
+  return sr_train_big(q) && q.Cout >= 32 && sr_wgrad_tiles(q) * sr_wgrad_max_slices(q) >= 16;
+}
+
 hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta, const float* dy, float* dx,
                           int accumulate) {
   const long long n = (long long)q.B * q.H * q.W * q.Cin;
+  if (sr_dgrad_tiled(q)) {
+    // grid z: the stride^2 phases of the source pixels; x is sized for phase (0, 0), which has the most pixels
+    const int Hp = (q.H + q.stride - 1) / q.stride, Wp = (q.W + q.stride - 1) / q.stride;
+    const int I = q.B * Hp * Wp, J = q.Cin;
+    hipLaunchKernelGGL(sr_conv_gemm_kernel<0>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, q.stride * q.stride),
+                       dim3(256), 0, s, q, dy, theta, dx, I, J, 0, 0, accumulate);
+    return hipGetLastError();
+  }
   hipLaunchKernelGGL(sr_dgrad_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, q, theta, dy, dx, accumulate);
   return hipGetLastError();
 }
@@ -232,6 +443,11 @@ hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta
 int sr_train_wgrad_slices(const SrConvGeom& q) {
   const long long nw = (long long)q.kh * q.kw * q.Cin * q.Cout;
   const long long M = (long long)q.B * q.Ho * q.Wo;
+  if (sr_wgrad_tiled(q)) {   // about 1024 workgroups
+    const long long tiles = sr_wgrad_tiles(q);
+    const long long want = std::min<long long>((1024 + tiles - 1) / tiles, sr_wgrad_max_slices(q));
+    return (int)std::max<long long>(1, want);
+  }
   long long want = (2048LL * 256 + nw - 1) / nw;   // about 2048 workgroups in all
   if (want > SR_TRAIN_MAX_SLICES) want = SR_TRAIN_MAX_SLICES;
   if (want > M) want = M;
@@ -243,6 +459,17 @@ hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, co
   const long long nw = (long long)q.kh * q.kw * q.Cin * q.Cout;
   const int M = q.B * q.Ho * q.Wo;
   const int slices = sr_train_wgrad_slices(q);
+  if (sr_wgrad_tiled(q)) {
+    const int I = q.kh * q.kw * q.Cin, J = q.Cout;
+    const int per = ((M + slices - 1) / slices + SR_GR - 1) / SR_GR * SR_GR;
+    const int used = (M + per - 1) / per;
+    hipLaunchKernelGGL(sr_conv_gemm_kernel<1>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, used), dim3(256), 0, s,
+                       q, x, dy, part, I, J, M, per, 0);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 256)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);
+    return hipGetLastError();
+  }
   const int per = (M + slices - 1) / slices;
   const int used = (M + per - 1) / per;
   hipLaunchKernelGGL(sr_wgrad_kernel, dim3(grid_for(nw, 256), used), dim3(256), 0, s, q, x, dy, per, part);

@@ -31,9 +31,14 @@ def cases():
     return {
         # every edge kind: strided and plain convolutions, skip, self-recurrence, 1x1 + up-sampling, dense, GAP+dense
         "small_sr": (lambda: small_sr_graph(batch=3), 4),
+        # the same wiring wide enough for the tiled matrix-core gradient kernels (32 and 64 channels at 16x16 / 8x8,
+        # batch 8); its input and 1x1 edges stay on the one-thread-per-output kernels
+        "mid_sr": (lambda: small_sr_graph(batch=8, classes=10, channels=(8, 32, 64), hw=16), 4),
         "tiny_sr": (lambda: W.tiny_sr(batch=2, frames=5), 5),
         # App. A2: MNIST net with skip and self-recurrence, 7x7 stride-4 convolution and dense edges
         "mnist_sr": (lambda: W.mnist_net("SR", batch=16, frames=4), 4),
+        # ... at the paper's batch size (Tab. A1): its strided 7x7 convolution and dense edges on the tiled kernels
+        "mnist_sr_b128": (lambda: W.mnist_net("SR", batch=128, frames=3), 3),
         # App. A2: CIFAR10 family member (10 nodes, 64-channel 3x3 convolutions at 32x32 and 16x16)
         "dsr2": (lambda: replace(W.dsr_net(2, batch=2, frames=6), dtype="f32"), 6),
     }

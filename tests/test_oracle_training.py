@@ -12,12 +12,14 @@ from oracle import training as tr
 from oracle import theory as th
 
 
-def small_sr_graph(batch=2, classes=5):
-    """in(2ch 6x6) -> a(3ch 6x6) -> b(4ch 3x3, stride 2) -> out(classes, dense); skip in -> b (stride 2),
-    self-recurrent a -> a, top-down b -> a (1x1 + x2 up-sampling), GAP+dense skip a -> out."""
-    nodes = [Node("in", 2, 6, 6, ACT_IDENTITY), Node("a", 3, 6, 6), Node("b", 4, 3, 3),
+def small_sr_graph(batch=2, classes=5, channels=(2, 3, 4), hw=6):
+    """in(c0 @ hw x hw) -> a(c1 @ hw x hw) -> b(c2 @ hw/2 x hw/2, stride 2) -> out(classes, dense); skip in -> b
+    (stride 2), self-recurrent a -> a, top-down b -> a (1x1 + x2 up-sampling), GAP+dense skip a -> out."""
+    c0, c1, c2 = channels
+    h2 = hw // 2
+    nodes = [Node("in", c0, hw, hw, ACT_IDENTITY), Node("a", c1, hw, hw), Node("b", c2, h2, h2),
              Node("out", classes, 1, 1, ACT_IDENTITY)]
-    edges = [Edge(0, 1, "conv", 3, 3, 1, 1), Edge(1, 2, "conv", 3, 3, 2, 1), Edge(2, 3, "dense", 3, 3, 1, 0),
+    edges = [Edge(0, 1, "conv", 3, 3, 1, 1), Edge(1, 2, "conv", 3, 3, 2, 1), Edge(2, 3, "dense", h2, h2, 1, 0),
              Edge(0, 2, "conv", 3, 3, 2, 1), Edge(1, 1, "conv", 3, 3, 1, 1), Edge(2, 1, "conv", 1, 1, 1, 0, 2),
              Edge(1, 3, "gap_dense", 1, 1, 1, 0)]
     return Graph("small_sr", nodes, edges, batch, 4, "f32", out_node=3)
