@@ -1055,11 +1055,12 @@ sr_status finalize(sr_graph* g) {
       const double slots = (g->tile_version == 2 ? 1.0 : 2.0) * 256;   // resident workgroups of the chip
       const double share = level_cost / slots;
       for (TileGroup& grp : groups) {
-        // only tiles longer than an even share of the level are cut, into parts of about half a
-        // share but not shorter than ~25 us (a part pays for its own staging and for the reduction)
-        // (a part leaves 128 KiB of partial sums in uncached memory and the last one reads them all:
-        // measured, parts shorter than this cost more than the better balance gains)
-        const double part_cost = std::max(0.5 * share, 60000.0);
+        // only tiles longer than an even share of the level are cut, into parts of about 0.9 of a
+        // share but not shorter than ~25 us (a part pays for its own staging and for the reduction:
+        // it leaves 128 KiB of partial sums and the last one reads them all).  Measured on the hi-res
+        // graph: parts of 0.5 of a share 163 us per frame, 0.65 .. 1.25 of a share 158-160, no cutting 204;
+        // shorter parts than 25 us lose on every graph (CIFAR-shaped 33 -> 36 .. 49 us)
+        const double part_cost = std::max(0.9 * share, 60000.0);
         int parts = (grp.cost > share) ? (int)std::ceil(grp.cost / part_cost) : 1;
         parts = std::max(1, std::min(std::min(parts, 16), grp.n_stages));
         if (parts <= 1 || !g->allow_split) continue;
