@@ -310,6 +310,9 @@ struct SrConvGeom {   // y[b][ho][wo][co] = sum x[b][ho*stride + i - pad][wo*str
   // h = hh*stride + ph, w = ww*stride + pw of a Hp x Wp grid, which pair only with the taps i = ti0 + a*stride,
   // j = tj0 + c*stride (a < nti, c < ntj).  Stride 1: one phase, the whole image, all taps.
   int ph, pw, Hp, Wp, ti0, tj0, nti, ntj;
+  // divisions by Wo, Ho*Wo and Cout as multiply-high, add, shift (exact for dividends below 2^31); filled by
+  // the launchers of the tiled kernels
+  uint32_t mul_wo, sh_wo, mul_howo, sh_howo, mul_cout, sh_cout;
 };
 #define SR_TRAIN_TILED_MIN_MACS 4.0e6   // smaller contractions stay on the one-thread-per-output kernels
 #define SR_TRAIN_MAX_SLICES 64   // a weight gradient's pixel sum is cut into at most this many partial sums
@@ -317,7 +320,9 @@ hipError_t sr_train_ce(hipStream_t s, const float* z, const int32_t* labels, int
                        float* dz);
 hipError_t sr_train_sum_terms(hipStream_t s, const float* terms, int n, float scale, float* out);
 hipError_t sr_train_relu_mask(hipStream_t s, float* d, const float* x, size_t n);
-hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float* db);
+int sr_train_bias_slices(int M);
+// part: sr_train_bias_slices(M) * C floats of scratch; db += the gradient
+hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float* part, float* db);
 hipError_t sr_train_pool_sum(hipStream_t s, const float* d, int B, int Hs, int Ws, int C, int up, float* out);
 hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta, const float* dy, float* dx,
                           int accumulate);

@@ -56,8 +56,8 @@ __global__ void sr_relu_mask_kernel(float* __restrict__ d, const float* __restri
   if (i < n && !(x[i] > 0.f)) d[i] = 0.f;
 }
 
-// db[c] += sum over the M pixels of d[m][c]; one workgroup per channel
-__global__ void sr_bias_grad_kernel(const float* __restrict__ d, int M, int C, float* __restrict__ db) {
+// db[c] += sum over the M pixels of d[m][c]; one workgroup per channel (few pixels: one launch, no scratch)
+__global__ void sr_bias_grad_small_kernel(const float* __restrict__ d, int M, int C, float* __restrict__ db) {
   __shared__ float part[256];
   const int c = blockIdx.x;
   float acc = 0.f;
@@ -69,6 +69,22 @@ __global__ void sr_bias_grad_kernel(const float* __restrict__ d, int M, int C, f
     __syncthreads();
   }
   if (threadIdx.x == 0) db[c] += part[0];
+}
+
+// part[s][c] = sum over the pixels m of slice s of d[m][c]: a workgroup takes 64 channels x one slice of pixels,
+// four pixel lanes per channel (each adds every fourth pixel of the slice in order, then the four in order)
+__global__ void sr_bias_grad_kernel(const float* __restrict__ d, int M, int C, int m_per_slice, float* __restrict__ part) {
+  __shared__ float lanes[4][64];
+  const int c = blockIdx.x * 64 + (threadIdx.x & 63), pl = threadIdx.x >> 6;
+  const int m0 = blockIdx.y * m_per_slice;
+  const int m1 = min(M, m0 + m_per_slice);
+  float acc = 0.f;
+  if (c < C)
+    for (int m = m0 + pl; m < m1; m += 4) acc += d[(size_t)m * C + c];
+  lanes[pl][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (pl == 0 && c < C)
+    part[(size_t)blockIdx.y * C + c] = ((lanes[0][threadIdx.x] + lanes[1][threadIdx.x]) + lanes[2][threadIdx.x]) + lanes[3][threadIdx.x];
 }
 
 // adjoint of nearest up-sampling: out[b][h][w][c] = sum of the up x up block of d
@@ -188,6 +204,12 @@ __global__ void sr_gap_spread_kernel(const float* __restrict__ dmean, int B, int
 // 32 consecutive floats); blockIdx.z cuts the reduction into slices (weight gradient: partial sums
 // that a second kernel adds in slice order).  Every sum has a fixed order: same call, same bits.
 typedef float sr_f32x16 __attribute__((ext_vector_type(16)));
+
+// n / d for n < 2^31 with the pair the host made for d (Granlund & Montgomery: l = ceil(log2 d),
+// m = floor(2^32 (2^l - d) / d) + 1, q = (mulhi(m, n) + n) >> l; no overflow while n < 2^31)
+__device__ __forceinline__ int sr_fdiv(int n, uint32_t mul, uint32_t sh) {
+  return (int)((__umulhi((uint32_t)n, mul) + (uint32_t)n) >> sh);
+}
 #define SR_GT 128   // tile edge
 #define SR_GR 16    // reduction step
 #define SR_GP 132   // LDS row pitch in floats
@@ -264,7 +286,7 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
     if (MODE == 0) {
       const int r = rs + (t & 15);
       const bool r_ok = r < r_end;
-      const int co = r % q.Cout, vt = r / q.Cout;          // vt: index among the phase's taps
+      const int vt = sr_fdiv(r, q.mul_cout, q.sh_cout), co = r - vt * q.Cout;   // vt: index among the phase's taps
       const int tj = q.tj0 + (vt % q.ntj) * q.stride, ti = q.ti0 + (vt / q.ntj) * q.stride;
       const int tap = ti * q.kw + tj;
 #pragma unroll
@@ -276,35 +298,39 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
           int ho, wo;
           if (lgs >= 0) { ho = th >> lgs; wo = tw >> lgs; }
           else { ho = th / q.stride; wo = tw / q.stride; }
-          if (th >= 0 && tw >= 0 && ho < q.Ho && wo < q.Wo) v = pa[(((size_t)ab[n] * q.Ho + ho) * q.Wo + wo) * q.Cout + co];
+          // the load is unconditional (element 0 when out of range): no branch per element
+          const bool ok = th >= 0 && tw >= 0 && ho < q.Ho && wo < q.Wo;
+          const size_t at = ok ? (((size_t)ab[n] * q.Ho + ho) * q.Wo + wo) * q.Cout + co : 0;
+          v = pa[at];
+          v = ok ? v : 0.f;
         }
         va[n] = v;
         const int j = j0 + (t >> 4) + 16 * n;
-        vb[n] = (r_ok && j < J) ? pb[((size_t)tap * q.Cin + j) * q.Cout + co] : 0.f;
+        {
+          const bool okb = r_ok && j < J;
+          const float u = pb[okb ? ((size_t)tap * q.Cin + j) * q.Cout + co : 0];
+          vb[n] = okb ? u : 0.f;
+        }
       }
     } else {
-      // the thread's eight output pixels r, r + 2, ...: decoded once, then stepped
-      int r = rs + (t >> 7);
-      int wo = r % q.Wo, ho = (r / q.Wo) % q.Ho, b = r / (q.Wo * q.Ho);
       const int j = j0 + (t & 127);
+      const int r0 = rs + (t >> 7);
 #pragma unroll
       for (int n = 0; n < 8; ++n) {
-        float v = 0.f, u = 0.f;
-        if (r < r_end) {
-          if (a_row_ok) {
-            const int hi = ho * q.stride + ati - q.pad, wi2 = wo * q.stride + atj - q.pad;
-            if (hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W) v = pa[(((size_t)b * q.H + hi) * q.W + wi2) * q.Cin + aci];
-          }
-          if (j < J) u = pb[(size_t)r * q.Cout + j];
-        }
-        va[n] = v;
-        vb[n] = u;
-        r += 2;
-        wo += 2;
-        while (wo >= q.Wo) {
-          wo -= q.Wo;
-          if (++ho == q.Ho) { ho = 0; ++b; }
-        }
+        const int r = r0 + 2 * n;
+        const bool r_ok = r < r_end;
+        // output pixel (b, ho, wo) of r, without divisions; unconditional loads (element 0 when out of range)
+        const int b = sr_fdiv(r, q.mul_howo, q.sh_howo);
+        const int rem = r - b * (q.Ho * q.Wo);
+        const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo);
+        const int wo = rem - ho * q.Wo;
+        const int hi = ho * q.stride + ati - q.pad, wi2 = wo * q.stride + atj - q.pad;
+        const bool oka = r_ok && a_row_ok && hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W;
+        const float v = pa[oka ? (((size_t)b * q.H + hi) * q.W + wi2) * q.Cin + aci : 0];
+        va[n] = oka ? v : 0.f;
+        const bool okb = r_ok && j < J;
+        const float u = pb[okb ? (size_t)r * q.Cout + j : 0];
+        vb[n] = okb ? u : 0.f;
       }
     }
   };
@@ -395,8 +421,23 @@ hipError_t sr_train_relu_mask(hipStream_t s, float* d, const float* x, size_t n)
   return hipGetLastError();
 }
 
-hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float* db) {
-  hipLaunchKernelGGL(sr_bias_grad_kernel, dim3(C), dim3(256), 0, s, d, M, C, db);
+int sr_train_bias_slices(int M) {
+  const int want = (M + 1023) / 1024;   // about a thousand pixels per slice
+  return want < 1 ? 1 : (want > SR_TRAIN_MAX_SLICES ? SR_TRAIN_MAX_SLICES : want);
+}
+
+hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float* part, float* db) {
+  if (M <= 16384) {
+    hipLaunchKernelGGL(sr_bias_grad_small_kernel, dim3(C), dim3(256), 0, s, d, M, C, db);
+    return hipGetLastError();
+  }
+  const int slices = sr_train_bias_slices(M);
+  const int per = (M + slices - 1) / slices;
+  const int used = (M + per - 1) / per;
+  hipLaunchKernelGGL(sr_bias_grad_kernel, dim3((C + 63) / 64, used), dim3(256), 0, s, d, M, C, per, part);
+  hipError_t e = hipGetLastError();
+  if (e != hipSuccess) return e;
+  hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(C, 256)), dim3(256), 0, s, part, (size_t)C, used, db);
   return hipGetLastError();
 }
 
@@ -404,6 +445,20 @@ hipError_t sr_train_pool_sum(hipStream_t s, const float* d, int B, int Hs, int W
   const long long n = (long long)B * Hs * Ws * C;
   hipLaunchKernelGGL(sr_pool_sum_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, d, B, Hs, Ws, C, up, out);
   return hipGetLastError();
+}
+
+static void sr_fastdiv(uint32_t d, uint32_t* mul, uint32_t* sh) {
+  uint32_t l = 0;
+  while ((1ull << l) < d) ++l;
+  *mul = (uint32_t)(((1ull << 32) * ((1ull << l) - d)) / d + 1);
+  *sh = l;
+}
+static SrConvGeom sr_with_divisors(const SrConvGeom& q) {
+  SrConvGeom p = q;
+  sr_fastdiv((uint32_t)q.Wo, &p.mul_wo, &p.sh_wo);
+  sr_fastdiv((uint32_t)(q.Ho * q.Wo), &p.mul_howo, &p.sh_howo);
+  sr_fastdiv((uint32_t)q.Cout, &p.mul_cout, &p.sh_cout);
+  return p;
 }
 
 // Which contractions go to the tiled matrix-core kernel: those with enough multiply-adds whose 128 x 128 tiles are
@@ -433,7 +488,7 @@ hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta
     const int Hp = (q.H + q.stride - 1) / q.stride, Wp = (q.W + q.stride - 1) / q.stride;
     const int I = q.B * Hp * Wp, J = q.Cin;
     hipLaunchKernelGGL(sr_conv_gemm_kernel<0>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, q.stride * q.stride),
-                       dim3(256), 0, s, q, dy, theta, dx, I, J, 0, 0, accumulate);
+                       dim3(256), 0, s, sr_with_divisors(q), dy, theta, dx, I, J, 0, 0, accumulate);
     return hipGetLastError();
   }
   hipLaunchKernelGGL(sr_dgrad_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, q, theta, dy, dx, accumulate);
@@ -464,7 +519,7 @@ hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, co
     const int per = ((M + slices - 1) / slices + SR_GR - 1) / SR_GR * SR_GR;
     const int used = (M + per - 1) / per;
     hipLaunchKernelGGL(sr_conv_gemm_kernel<1>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, used), dim3(256), 0, s,
-                       q, x, dy, part, I, J, M, per, 0);
+                       sr_with_divisors(q), x, dy, part, I, J, M, per, 0);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 256)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);

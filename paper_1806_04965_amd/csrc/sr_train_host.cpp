@@ -60,6 +60,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   for (const EdgeRt& e : g->edges) {
     const SrConvGeom q = geom_of(e);
     part_n = std::max(part_n, (size_t)sr_train_wgrad_slices(q) * e.w_count);
+    part_n = std::max(part_n, (size_t)SR_TRAIN_MAX_SLICES * g->nodes[e.d.dst].d.channels);   // bias gradient slices
     if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) pooled_n = std::max(pooled_n, (size_t)B * q.Ho * q.Wo * q.Cout);
     if (e.d.kind == SR_EDGE_GAP_DENSE) mean_n = std::max(mean_n, (size_t)B * q.Cin);
   }
@@ -123,7 +124,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
       const sr_node_desc& d = g->nodes[v].d;
       float* da = A + dx_at[cur][v];
       if (d.act == SR_ACT_RELU) SR_HIP(g, sr_train_relu_mask(s, da, A + x_at[v] + (size_t)i * node_floats(v), node_floats(v)));
-      if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(s, da, B * d.height * d.width, d.channels, dbias[v]));
+      if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(s, da, B * d.height * d.width, d.channels, A + part_at, dbias[v]));
       for (int ei = 0; ei < g->n_edges; ++ei) {
         const EdgeRt& e = g->edges[ei];
         if (e.d.dst != v) continue;
