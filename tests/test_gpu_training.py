@@ -262,3 +262,33 @@ def test_training_steps_follow_the_oracle_and_lower_the_loss():
     assert losses[-1] < losses[0] - 0.05, losses
     print(f"[train] mnist_sr, 5 RMSprop steps: loss {losses[0]:.4f} -> {losses[-1]:.4f} (oracle {ref_losses[0]:.4f} -> {ref_losses[-1]:.4f})", flush=True)
     dev.close()
+
+
+def test_two_inputs_batch_of_one_odd_channel_counts_and_clamped_labels():
+    # degenerate shapes of a window: two input nodes, a batch of one, channel counts 3 / 2 / 5 / 7, 5x5 states, and
+    # labels outside the class range, which the library clamps to it
+    import torch
+    import paper_1806_04965_amd as sr
+    from workloads.graphs import Node, Edge, Graph, ACT_IDENTITY
+    nodes = [Node("in0", 3, 5, 5, ACT_IDENTITY), Node("in1", 2, 5, 5, ACT_IDENTITY), Node("a", 5, 5, 5),
+             Node("out", 7, 1, 1, ACT_IDENTITY)]
+    edges = [Edge(0, 2, "conv", 3, 3, 1, 1), Edge(1, 2, "conv", 1, 1, 1, 0), Edge(2, 2, "conv", 3, 3, 1, 1),
+             Edge(2, 3, "dense", 5, 5, 1, 0), Edge(1, 3, "gap_dense", 1, 1, 1, 0)]
+    g0 = Graph("two_inputs", nodes, edges, 1, 3, "f32", out_node=3)
+    for pattern in ("streaming", "sequential"):
+        g = g0.with_pattern(PATTERNS[pattern](g0))
+        got, data = run_case(g, 3, seed=77)
+        check_against_oracle(g, 3, got, data, f"two_inputs/{pattern}")
+    g = g0.with_pattern(W.streaming_pattern(g0))
+    g = Graph(g.name, g.nodes, g.edges, 2, 3, "f32", out_node=3)
+    w, b, x = W.make_case(g, seed=78, bias_scale=0.1, frames=3, recipe="uniform")
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    xd = [to_device(x[v][:4], "f32") for v in g.input_nodes()]
+    loss, dth, dbs = dev.window_gradients(xd, torch.tensor([-3, 99], dtype=torch.int32, device="cuda"), 3)
+    dev.synchronize()
+    ref_loss, ref_dth, _ = tr.window_gradients(g, w, b, {v: x[v][:4] for v in x}, np.array([0, 6]), 3)
+    assert abs(float(loss.cpu()[0]) - ref_loss) <= LOSS_TOL * max(1.0, ref_loss)
+    for ei in range(len(g.edges)):
+        assert max_abs_rel(dth[ei].cpu().numpy(), ref_dth[ei]) <= GRAD_TOL, ei
+    dev.close()
