@@ -292,8 +292,9 @@ sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
  * One training window (Sec. 3: rollout window of size W >= 1 of the graph's pattern; Sec. 2: trained
  * by backpropagation through the rolled-out network; App. A2, training details: zero initial state,
  * loss = mean over the window's frames of the single-frame prediction losses, cross-entropy).
- * Runs frames 1..W from the zero state (as sr_reset + W x sr_frame_step, keeping every frame's
- * states), then the reverse sweep over the window: frames W..1, inside a frame the update steps of
+ * Runs frames 1..W from the zero state (the node map of App. A1.2 in fp32, every frame's states kept;
+ * the graph's own frame state and frame counter are unspecified afterwards: sr_reset before stepping
+ * frames again), then the reverse sweep over the window: frames W..1, inside a frame the update steps of
  * the inference tableau in reverse (Eq. 5).  With z(i) = state of out_node at frame i,
  *     loss = 1/(W*B) * sum_{i=1..W} sum_b -log softmax(z_b(i))[labels[b]]
  * and the gradients of that loss with respect to every theta_e and b_v are returned; the W copies
@@ -309,7 +310,7 @@ sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
  *   dbias     host array of n_nodes device pointers or NULL; dbias[v]: [C] floats, overwritten; entries
  *             of input nodes are ignored, a NULL entry skips that node
  * fp32 arithmetic; every sum is taken in a fixed order (no floating-point atomics): the same call
- * gives the same bits.  The graph is left at frame W.  Device memory for the window's states and
+ * gives the same bits.  Device memory for the window's states and
  * gradients (about (W + 3) x the graph's node states) is allocated by the call, kept by the graph and
  * reused by later calls.  Asynchronous on the graph's stream; the host arrays are consumed before
  * the call returns.  No optimiser step is taken.

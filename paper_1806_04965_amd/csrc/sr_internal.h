@@ -301,39 +301,6 @@ hipError_t sr_launch_mfma8(hipStream_t s, SrCtx* ctx, const SrMfmaNode* nodes, c
 #define SR_STATIC_SCRATCH_BYTES (64u << 20)
 #define SR_STATIC_MAX_SLOTS 1024            // counters: 4 KiB at the start of the array
 hipError_t sr_static_scratch(void** ptr);
-// ---------------------------------------------------------------------------
-// training window (fp32 graphs): reverse sweep over the rollout window (Sec. 3; loss of App. A2)
-// ---------------------------------------------------------------------------
-struct SrConvGeom {   // y[b][ho][wo][co] = sum x[b][ho*stride + i - pad][wo*stride + j - pad][ci] * theta[i][j][ci][co]
-  int B, H, W, Cin, Ho, Wo, Cout, kh, kw, stride, pad;
-  // state gradient of a strided edge, one launch per phase (ph, pw) of the source pixels: rows are the pixels
-  // h = hh*stride + ph, w = ww*stride + pw of a Hp x Wp grid, which pair only with the taps i = ti0 + a*stride,
-  // j = tj0 + c*stride (a < nti, c < ntj).  Stride 1: one phase, the whole image, all taps.
-  int ph, pw, Hp, Wp, ti0, tj0, nti, ntj;
-  // divisions by Wo, Ho*Wo and Cout as multiply-high, add, shift (exact for dividends below 2^31); filled by
-  // the launchers of the tiled kernels
-  uint32_t mul_wo, sh_wo, mul_howo, sh_howo, mul_cout, sh_cout;
-};
-#define SR_TRAIN_TILED_MIN_MACS 4.0e6   // smaller contractions stay on the one-thread-per-output kernels
-#define SR_TRAIN_MAX_SLICES 64   // a weight gradient's pixel sum is cut into at most this many partial sums
-hipError_t sr_train_ce(hipStream_t s, const float* z, const int32_t* labels, int B, int C, float scale, float* terms,
-                       float* dz);
-hipError_t sr_train_sum_terms(hipStream_t s, const float* terms, int n, float scale, float* out);
-hipError_t sr_train_relu_mask(hipStream_t s, float* d, const float* x, size_t n);
-int sr_train_bias_slices(int M);
-// part: sr_train_bias_slices(M) * C floats of scratch; db += the gradient
-hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float* part, float* db);
-hipError_t sr_train_pool_sum(hipStream_t s, const float* d, int B, int Hs, int Ws, int C, int up, float* out);
-hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta, const float* dy, float* dx,
-                          int accumulate);
-int sr_train_wgrad_slices(const SrConvGeom& q);
-// part: sr_train_wgrad_slices(q) * (number of weights) floats of scratch; dtheta += the gradient
-hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, const float* dy, float* part,
-                          float* dtheta);
-hipError_t sr_train_gap_mean(hipStream_t s, const float* x, int B, int HW, int C, float* out);
-hipError_t sr_train_rmsprop(hipStream_t s, float* theta, float* a, const float* g, size_t n, float lr, float rho,
-                            float eps);
-hipError_t sr_train_gap_spread(hipStream_t s, const float* dmean, int B, int HW, int C, float* dx);
 // 8-wave kernel: bytes of one of its two stage buffers, and floats of one part's K-split slab
 #define SR8_BUF_BYTES (80 * 1024)
 #define SR_ZERO_TAIL 2048   // zero bytes behind every state copy: where padding pixels are loaded from

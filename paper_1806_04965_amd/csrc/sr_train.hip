@@ -9,6 +9,7 @@
 #include <algorithm>
 
 #include "sr_internal.h"
+#include "sr_train.h"
 
 namespace {
 
@@ -197,6 +198,8 @@ __global__ void sr_gap_spread_kernel(const float* __restrict__ dmean, int B, int
 // (v_mfma_f32_32x32x2_f32): C[i][j] (+)= sum_r A[i][r] * B[r][j], operands gathered on the fly.
 //   state gradient  (MODE 0): i = source pixel (b, h, w), j = ci, r = (tap, co);
 //                             A = dy at the output pixel that tap pairs with (h, w), B = theta[tap][j][co]
+//   forward         (MODE 2): i = output pixel m = (b, ho, wo), j = co, r = (tap, ci);
+//                             A = x at the source pixel that tap pairs with m, B = theta[tap][ci][j]
 //   weight gradient (MODE 1): i = (tap, ci), j = co, r = output pixel m = (b, ho, wo);
 //                             A = x at the source pixel that tap pairs with m, B = dy[m][j]
 // One workgroup (4 waves) owns a 128 x 128 tile of C, a wave 64 x 64 of it (2 x 2 MFMA tiles); the
@@ -239,7 +242,7 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
     r_per_slice = R;
     if (i0 >= I || (R == 0 && accumulate)) return;   // the whole workgroup: this phase has fewer pixels, or no tap reaches it
   }
-  const int r_begin = (MODE == 0) ? 0 : blockIdx.z * r_per_slice;
+  const int r_begin = (MODE == 1) ? blockIdx.z * r_per_slice : 0;
   const int r_end = min(R, r_begin + r_per_slice);
   const int wi = wave >> 1, wj = wave & 1;
 
@@ -249,7 +252,19 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
   int ab[8], ah[8], aw[8];          // MODE 0: source pixel (b, h, w) of the thread's 8 A rows (b < 0: row past the end)
   int ati = 0, atj = 0, aci = 0;    // MODE 1: tap and channel of the thread's A row
   bool a_row_ok = false;
-  if (MODE == 0) {
+  if (MODE == 2) {
+#pragma unroll
+    for (int n = 0; n < 8; ++n) {
+      const int i = i0 + (t >> 4) + 16 * n;
+      if (i < I) {   // output pixel: top-left corner of its window in the source
+        aw[n] = (i % q.Wo) * q.stride - q.pad;
+        ah[n] = ((i / q.Wo) % q.Ho) * q.stride - q.pad;
+        ab[n] = i / (q.Wo * q.Ho);
+      } else {
+        ab[n] = -1; ah[n] = 0; aw[n] = 0;
+      }
+    }
+  } else if (MODE == 0) {
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
       const int i = i0 + (t >> 4) + 16 * n;
@@ -283,7 +298,24 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
   float va[8], vb[8];
   // the operands of one reduction step, from global memory into registers
   auto gather = [&](int rs) {
-    if (MODE == 0) {
+    if (MODE == 2) {
+      const int r = rs + (t & 15);
+      const bool r_ok = r < r_end;
+      const int tap = sr_fdiv(r, q.mul_cout, q.sh_cout), ci = r - tap * q.Cin;   // the divisor pair is Cin's here
+      const int tj = tap % q.kw, ti = tap / q.kw;
+      const int jb = j0 + (t & 127);
+#pragma unroll
+      for (int n = 0; n < 8; ++n) {
+        const int hi = ah[n] + ti, wi2 = aw[n] + tj;
+        const bool ok = r_ok && ab[n] >= 0 && hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W;
+        const float v = pa[ok ? (((size_t)ab[n] * q.H + hi) * q.W + wi2) * q.Cin + ci : 0];
+        va[n] = ok ? v : 0.f;
+        const int rb = rs + (t >> 7) + 2 * n;
+        const bool okb = rb < r_end && jb < J;
+        const float u = pb[okb ? (size_t)rb * q.Cout + jb : 0];
+        vb[n] = okb ? u : 0.f;
+      }
+    } else if (MODE == 0) {
       const int r = rs + (t & 15);
       const bool r_ok = r < r_end;
       const int vt = sr_fdiv(r, q.mul_cout, q.sh_cout), co = r - vt * q.Cout;   // vt: index among the phase's taps
@@ -340,7 +372,10 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
     __syncthreads();   // the previous step's operand reads are done
 #pragma unroll
     for (int n = 0; n < 8; ++n) {
-      if (MODE == 0) {
+      if (MODE == 2) {
+        As[t & 15][(t >> 4) + 16 * n] = va[n];
+        Bs[(t >> 7) + 2 * n][t & 127] = vb[n];
+      } else if (MODE == 0) {
         As[t & 15][(t >> 4) + 16 * n] = va[n];
         Bs[t & 15][(t >> 4) + 16 * n] = vb[n];
       } else {
@@ -363,7 +398,7 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
     }
   }
   // register v of lane l holds row 8 * (v / 4) + 4 * (l / 32) + v % 4 (of the A operand's 32), column l % 32
-  float* out = pc + ((MODE == 0) ? (size_t)0 : (size_t)blockIdx.z * I * J);
+  float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
 #pragma unroll
   for (int x = 0; x < 2; ++x)
 #pragma unroll
@@ -382,6 +417,80 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
           *dst = accumulate ? *dst + acc[x][y][v] : acc[x][y][v];
         }
       }
+}
+
+// forward of one edge, one thread per output element: y[b][ho][wo][co] (+)= sum x * theta
+__global__ void sr_fwd_kernel(SrConvGeom q, const float* __restrict__ x, const float* __restrict__ theta,
+                              float* __restrict__ y, int accumulate) {
+  const size_t idx = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t n = (size_t)q.B * q.Ho * q.Wo * q.Cout;
+  if (idx >= n) return;
+  const int co = (int)(idx % q.Cout);
+  size_t r = idx / q.Cout;
+  const int wo = (int)(r % q.Wo); r /= q.Wo;
+  const int ho = (int)(r % q.Ho);
+  const int b = (int)(r / q.Ho);
+  float acc = 0.f;
+  for (int i = 0; i < q.kh; ++i) {
+    const int hi = ho * q.stride + i - q.pad;
+    if (hi < 0 || hi >= q.H) continue;
+    for (int j = 0; j < q.kw; ++j) {
+      const int wi = wo * q.stride + j - q.pad;
+      if (wi < 0 || wi >= q.W) continue;
+      const float* xs = x + (((size_t)b * q.H + hi) * q.W + wi) * q.Cin;
+      const float* t = theta + (size_t)(i * q.kw + j) * q.Cin * q.Cout + co;
+      for (int ci = 0; ci < q.Cin; ++ci) acc += xs[ci] * t[(size_t)ci * q.Cout];
+    }
+  }
+  y[idx] = accumulate ? y[idx] + acc : acc;
+}
+
+// the same for few outputs with long sums (dense edges): one wave per output element, the lanes take every 64th
+// term of the (tap, ci) sum in order, then a fixed tree over the lanes
+__global__ void sr_fwd_wide_kernel(SrConvGeom q, const float* __restrict__ x, const float* __restrict__ theta,
+                                   float* __restrict__ y, int accumulate) {
+  const size_t idx = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+  const size_t n = (size_t)q.B * q.Ho * q.Wo * q.Cout;
+  if (idx >= n) return;                       // a whole wave
+  const int lane = threadIdx.x & 63;
+  const int co = (int)(idx % q.Cout);
+  size_t r = idx / q.Cout;
+  const int wo = (int)(r % q.Wo); r /= q.Wo;
+  const int ho = (int)(r % q.Ho);
+  const int b = (int)(r / q.Ho);
+  const int K = q.kh * q.kw * q.Cin;
+  float acc = 0.f;
+  for (int k = lane; k < K; k += 64) {
+    const int ci = k % q.Cin, tap = k / q.Cin;
+    const int hi = ho * q.stride + tap / q.kw - q.pad, wi = wo * q.stride + tap % q.kw - q.pad;
+    if (hi >= 0 && hi < q.H && wi >= 0 && wi < q.W)
+      acc += x[(((size_t)b * q.H + hi) * q.W + wi) * q.Cin + ci] * theta[(size_t)k * q.Cout + co];
+  }
+  for (int m = 32; m > 0; m >>= 1) acc += __shfl_xor(acc, m, 64);
+  if (lane == 0) y[idx] = accumulate ? y[idx] + acc : acc;
+}
+
+// nearest up-sampling of an edge's result into its target: dst[b][h][w][c] (+)= y[b][h / up][w / up][c]
+__global__ void sr_upsample_add_kernel(const float* __restrict__ y, int B, int H, int W, int C, int up,
+                                       float* __restrict__ dst, int accumulate) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  const size_t n = (size_t)B * H * W * C;
+  if (i >= n) return;
+  const int c = (int)(i % C);
+  size_t r = i / C;
+  const int w = (int)(r % W); r /= W;
+  const int h = (int)(r % H);
+  const int b = (int)(r / H);
+  const float v = y[(((size_t)b * (H / up) + h / up) * (W / up) + w / up) * C + c];
+  dst[i] = accumulate ? dst[i] + v : v;
+}
+
+// x = sigma(a + b_c) in place (App. A1.2 node map)
+__global__ void sr_bias_act_kernel(float* __restrict__ a, const float* __restrict__ bias, int C, size_t n, int act) {
+  const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  if (i >= n) return;
+  const float v = a[i] + bias[i % C];
+  a[i] = act == 1 ? fmaxf(v, 0.f) : v;
 }
 
 // RMSprop: a <- rho a + (1 - rho) g^2;  theta <- theta - lr g / (sqrt(a) + eps)
@@ -492,6 +601,44 @@ hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta
     return hipGetLastError();
   }
   hipLaunchKernelGGL(sr_dgrad_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, q, theta, dy, dx, accumulate);
+  return hipGetLastError();
+}
+
+static bool sr_fwd_tiled(const SrConvGeom& q) {
+  return sr_train_big(q) && q.Cout >= 32 &&
+         ((long long)q.B * q.Ho * q.Wo + SR_GT - 1) / SR_GT * ((q.Cout + SR_GT - 1) / SR_GT) >= 8;
+}
+int sr_train_fwd_is_tiled(const SrConvGeom& q) { return sr_fwd_tiled(q) ? 1 : 0; }
+
+hipError_t sr_train_fwd(hipStream_t s, const SrConvGeom& q, const float* x, const float* theta, float* y,
+                        int accumulate) {
+  if (sr_fwd_tiled(q)) {
+    SrConvGeom p = q;
+    sr_fastdiv((uint32_t)q.Cin, &p.mul_cout, &p.sh_cout);   // the forward decodes r = (tap, ci): its divisor is Cin
+    const int I = q.B * q.Ho * q.Wo, J = q.Cout, R = q.kh * q.kw * q.Cin;
+    hipLaunchKernelGGL(sr_conv_gemm_kernel<2>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, 1), dim3(256), 0, s,
+                       p, x, theta, y, I, J, R, R, accumulate);
+    return hipGetLastError();
+  }
+  const long long n = (long long)q.B * q.Ho * q.Wo * q.Cout;
+  if (n <= 65536 && (long long)q.kh * q.kw * q.Cin >= 256) {   // few outputs, long sums: a wave per output
+    hipLaunchKernelGGL(sr_fwd_wide_kernel, dim3(grid_for(n, 4)), dim3(256), 0, s, q, x, theta, y, accumulate);
+    return hipGetLastError();
+  }
+  hipLaunchKernelGGL(sr_fwd_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, q, x, theta, y, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t sr_train_upsample_add(hipStream_t s, const float* y, int B, int H, int W, int C, int up, float* dst,
+                                 int accumulate) {
+  const long long n = (long long)B * H * W * C;
+  hipLaunchKernelGGL(sr_upsample_add_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, y, B, H, W, C, up, dst, accumulate);
+  return hipGetLastError();
+}
+
+hipError_t sr_train_bias_act(hipStream_t s, float* a, const float* bias, int C, size_t n, int act) {
+  if (n == 0) return hipSuccess;
+  hipLaunchKernelGGL(sr_bias_act_kernel, dim3(grid_for((long long)n, 256)), dim3(256), 0, s, a, bias, C, n, act);
   return hipGetLastError();
 }
 

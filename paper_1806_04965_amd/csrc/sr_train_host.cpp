@@ -9,6 +9,7 @@
 
 #include "../../include/sr.h"
 #include "sr_internal.h"
+#include "sr_train.h"
 #include "sr_graph.h"
 
 extern "C" {
@@ -25,6 +26,9 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     if (!dtheta[e]) return sr_gfail(g, SR_ERR_ARG, "sr_window_gradients: dtheta[" + std::to_string(e) + "] is null");
   for (size_t i = 0; i < g->inputs.size(); ++i)
     if (!inputs[i]) return sr_gfail(g, SR_ERR_ARG, "input " + std::to_string(i) + " is null");
+  for (int e = 0; e < g->n_edges; ++e)
+    if (!g->edges[e].has_w) return sr_gfail(g, SR_ERR_STATE, "edge " + std::to_string(e) + " has no weights");
+  if (W > 4096) return sr_gfail(g, SR_ERR_ARG, "sr_window_gradients: window size above 4096");
   const int B = g->batch, N = g->n_nodes;
   auto node_floats = [&](int v) {
     const sr_node_desc& d = g->nodes[v].d;
@@ -79,32 +83,69 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   float* A = g->train_arena;
   hipStream_t s = g->stream;
 
-  // forward over the window from the zero state, keeping every frame's states
-  std::vector<const void*> ptrs(g->inputs.size());
+  // forward over the window from the zero state, every frame's states written straight into the arena:
+  // frames 1..W, inside a frame the update steps of the tableau in order (Eq. 5), per node the sum of its
+  // edges' results (the first edge overwrites, the others add), then bias and activation in place
   std::vector<size_t> in_stride(g->inputs.size());
-  for (size_t k = 0; k < g->inputs.size(); ++k) {
-    in_stride[k] = node_floats(g->inputs[k]);
-    ptrs[k] = inputs[k];
-  }
-  sr_status st = sr_reset(g, ptrs.data());
-  if (st != SR_OK) return st;
-  for (int v = 0; v < N; ++v)
-    if (!g->an.is_input[v]) SR_HIP(g, sr_launch_fill_zero(s, A + x_at[v], node_floats(v) * sizeof(float)));
-  for (int i = 1; i <= W; ++i) {
-    for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = (const float*)inputs[k] + (size_t)i * in_stride[k];
-    st = sr_frame_step(g, ptrs.data());
-    if (st != SR_OK) return st;
-    for (int v = 0; v < N; ++v)
-      if (!g->an.is_input[v])
-        SR_HIP(g, hipMemcpyAsync(A + x_at[v] + (size_t)i * node_floats(v), g->nodes[v].state[g->host_frame & 1],
-                                 node_floats(v) * sizeof(float), hipMemcpyDeviceToDevice, s));
-  }
-
-  // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
-  // (frame, node) has the gradient of all its readers before it is processed
+  for (size_t k = 0; k < g->inputs.size(); ++k) in_stride[k] = node_floats(g->inputs[k]);
+  std::vector<int> slot_of(N, -1);
+  for (size_t k = 0; k < g->inputs.size(); ++k) slot_of[g->inputs[k]] = (int)k;
   std::vector<int> order;
   for (int v = 0; v < N; ++v)
     if (!g->an.is_input[v]) order.push_back(v);
+  std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] < g->an.level[b]; });
+  auto state_of = [&](int u, int frame) -> const float* {
+    return g->an.is_input[u] ? (const float*)inputs[slot_of[u]] + (size_t)frame * in_stride[slot_of[u]]
+                             : A + x_at[u] + (size_t)frame * node_floats(u);
+  };
+  for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + x_at[v], node_floats(v) * sizeof(float)));
+  // Two ways to the same states: when some edge is large enough for the tiled matrix-core kernel the window
+  // runs its own forward pass below; a graph of small edges only is better served by the frame path
+  // (sr_reset + W x sr_frame_step, each frame's states copied into the arena), whose kernels take a whole
+  // update step per launch
+  bool own_forward = false;
+  for (const EdgeRt& e : g->edges) own_forward |= sr_train_fwd_is_tiled(geom_of(e)) != 0;
+  if (!own_forward) {
+    std::vector<const void*> ptrs(g->inputs.size());
+    for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = inputs[k];
+    sr_status st = sr_reset(g, ptrs.data());
+    if (st != SR_OK) return st;
+    for (int i = 1; i <= W; ++i) {
+      for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = (const float*)inputs[k] + (size_t)i * in_stride[k];
+      st = sr_frame_step(g, ptrs.data());
+      if (st != SR_OK) return st;
+      for (int v : order)
+        SR_HIP(g, hipMemcpyAsync(A + x_at[v] + (size_t)i * node_floats(v), g->nodes[v].state[g->host_frame & 1],
+                                 node_floats(v) * sizeof(float), hipMemcpyDeviceToDevice, s));
+    }
+  }
+  for (int i = 1; own_forward && i <= W; ++i)
+    for (int v : order) {
+      const sr_node_desc& d = g->nodes[v].d;
+      float* dst = A + x_at[v] + (size_t)i * node_floats(v);
+      int seen = 0;
+      for (int ei = 0; ei < g->n_edges; ++ei) {
+        const EdgeRt& e = g->edges[ei];
+        if (e.d.dst != v) continue;
+        const float* xsrc = state_of(e.d.src, i - (int)e.d.bridge);
+        const SrConvGeom q = geom_of(e);
+        if (e.d.kind == SR_EDGE_GAP_DENSE) {
+          const sr_node_desc& sd = g->nodes[e.d.src].d;
+          SR_HIP(g, sr_train_gap_mean(s, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at));
+          SR_HIP(g, sr_train_fwd(s, q, A + mean_at, e.w_dev, dst, seen));
+        } else if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) {
+          SR_HIP(g, sr_train_fwd(s, q, xsrc, e.w_dev, A + pooled_at, 0));
+          SR_HIP(g, sr_train_upsample_add(s, A + pooled_at, B, d.height, d.width, d.channels, e.d.upsample, dst, seen));
+        } else {
+          SR_HIP(g, sr_train_fwd(s, q, xsrc, e.w_dev, dst, seen));
+        }
+        seen = 1;
+      }
+      SR_HIP(g, sr_train_bias_act(s, dst, g->nodes[v].bias_dev, d.channels, node_floats(v), d.act));
+    }
+
+  // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
+  // (frame, node) has the gradient of all its readers before it is processed
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] > g->an.level[b]; });
   for (int v : order)
     for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[c][v], node_floats(v) * sizeof(float)));
@@ -112,8 +153,6 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   if (dbias)
     for (int v : order)
       if (dbias[v]) SR_HIP(g, sr_launch_fill_zero(s, dbias[v], (size_t)g->nodes[v].d.channels * sizeof(float)));
-  std::vector<int> slot_of(N, -1);
-  for (size_t k = 0; k < g->inputs.size(); ++k) slot_of[g->inputs[k]] = (int)k;
   const int classes = g->nodes[out_node].d.channels;
   const float scale = 1.0f / ((float)B * (float)W);
   for (int i = W; i >= 1; --i) {
@@ -129,8 +168,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         const EdgeRt& e = g->edges[ei];
         if (e.d.dst != v) continue;
         const int u = e.d.src, fi = i - (int)e.d.bridge;
-        const float* xsrc = g->an.is_input[u] ? (const float*)inputs[slot_of[u]] + (size_t)fi * in_stride[slot_of[u]]
-                                              : A + x_at[u] + (size_t)fi * node_floats(u);
+        const float* xsrc = state_of(u, fi);
         // frame 0 and the input nodes are given: no gradient is kept for them
         float* dxsrc = (g->an.is_input[u] || fi == 0) ? nullptr : A + dx_at[fi & 1][u];
         const SrConvGeom q = geom_of(e);
