@@ -25,7 +25,8 @@ closed-form gradient; the adjoint identity <f_e(x), y> = <x, f_e^T(y)> of every 
 Sec. 4 fixes: a window shorter than the shortest input-to-output path gives the weights of edges
 that leave an input no gradient at all under the streaming pattern; and the gradient with the
 rectifier's derivative toggled at chosen elements (see Window.near_kink) against torch.autograd on a
-window whose rectifiers carry that derivative.  rmsprop_step: closed form of the first step, a constant
+window whose rectifiers carry that derivative; dropout masks: finite differences and torch.autograd with
+the same masks, masks of ones change nothing, a zero mask cuts a node off.  rmsprop_step: closed form of the first step, a constant
 gradient's limit, and torch.optim.RMSprop over several steps.
 """
 from __future__ import annotations
@@ -140,10 +141,14 @@ class Window:
         self.inputs = self.schedule[0]
         self.src_edges = [[ei for ei, e in enumerate(graph.edges) if e.dst == v] for v in range(len(graph.nodes))]
 
-    def forward(self, inputs, W, init=None):
+    def forward(self, inputs, W, init=None, masks=None):
         """inputs[v]: (W+1,B,H,W,C) for every input node.  Returns X with X[i][v] the state of node v at
         frame i = 0..W (frame 0: `init[v]` or zeros for nodes with incoming edges).  The pre-activations
-        a_v(i) are kept in self.A."""
+        a_v(i) are kept in self.A.
+        masks (dropout, App. A2 training details): {v: (W+1,B,H,W,C)} multipliers of the node's state,
+        x_v(i) = m_v(i) * sigma_v(a_v(i)); the caller draws them (0 with the dropout rate, 1/(1 - rate)
+        otherwise, afresh for every frame and node: the paper does not say more than the rates).  Frame 0
+        of a mask is not used."""
         g = self.g
         X = [[None] * len(g.nodes) for _ in range(W + 1)]
         A = [[None] * len(g.nodes) for _ in range(W + 1)]
@@ -164,7 +169,9 @@ class Window:
                         a = a + ro.edge_transform(e, self.theta[ei], X[i - e.bridge][e.src])
                     A[i][v] = a
                     X[i][v] = ro.activation(n.act, a)
-        self.X, self.A, self.W = X, A, W
+                    if masks is not None and masks.get(v) is not None:
+                        X[i][v] = X[i][v] * np.asarray(masks[v][i], dtype=np.float64)
+        self.X, self.A, self.W, self.masks = X, A, W, masks
         return X
 
     def near_kink(self, tau_rel):
@@ -216,6 +223,8 @@ class Window:
                         da = dX[i][v] * mask
                     else:
                         da = dX[i][v]
+                    if self.masks is not None and self.masks.get(v) is not None:
+                        da = da * np.asarray(self.masks[v][i], dtype=np.float64)      # x = m * sigma(a)
                     dbias[v] += da.sum(axis=(0, 1, 2))
                     for ei in self.src_edges[v]:
                         e = g.edges[ei]
@@ -226,10 +235,10 @@ class Window:
         return dtheta, dbias, dinputs
 
 
-def window_gradients(graph, weights, biases, inputs, labels, W, out_node=None):
+def window_gradients(graph, weights, biases, inputs, labels, W, out_node=None, masks=None):
     """(loss, dtheta, dbias) of one training window from the zero initial state."""
     win = Window(graph, weights, biases)
-    win.forward(inputs, W)
+    win.forward(inputs, W, masks=masks)
     loss = win.loss(labels, out_node)
     dtheta, dbias, _ = win.backward(labels, out_node)
     return loss, dtheta, dbias

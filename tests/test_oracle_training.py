@@ -69,7 +69,7 @@ def test_gradients_match_central_finite_differences(pattern):
             assert abs(fd - db[v][c]) <= 1e-6 + 1e-5 * abs(fd), (pattern, "bias", v, c, fd, db[v][c])
 
 
-def torch_window_loss(g, w, b, x, labels, Wn, flips=()):
+def torch_window_loss(g, w, b, x, labels, Wn, flips=(), masks=None):
     """The same window built from torch's CPU operators (float64); returns loss and autograd gradients.
     flips: (frame, node, flat index) at which the rectifier keeps its value but passes the other derivative."""
     import torch
@@ -115,6 +115,8 @@ def torch_window_loss(g, w, b, x, labels, Wn, flips=()):
                 X[i][v] = torch.relu(a).detach() + (a - a.detach()) * mask    # value of the rectifier, derivative = mask
             else:
                 X[i][v] = a
+            if masks is not None and masks.get(v) is not None:
+                X[i][v] = X[i][v] * torch.tensor(masks[v][i], dtype=torch.float64)
     lab = torch.tensor(labels, dtype=torch.long)
     loss = sum(F.cross_entropy(X[i][g.out_node].reshape(g.batch, -1), lab) for i in range(1, Wn + 1)) / Wn
     loss.backward()
@@ -325,3 +327,54 @@ def test_rmsprop_step_closed_forms_and_torch():
         opt.step()
         t, a = tr.rmsprop_step(t, a, gk, lr, rho, eps)
         np.testing.assert_allclose(t, p.detach().numpy(), rtol=1e-13, atol=1e-15)
+
+
+def dropout_masks(g, Wn, seed, rates):
+    """{node: (W+1,B,H,W,C)} of 0 or 1/(1 - rate), drawn afresh per frame (the caller's business: the
+    method's random numbers are inputs of both sides)."""
+    rng = np.random.default_rng(seed)
+    out = {}
+    for v, rate in rates.items():
+        n = g.nodes[v]
+        keep = rng.random((Wn + 1, g.batch, n.height, n.width, n.channels)) >= rate
+        out[v] = keep.astype(np.float64) / (1.0 - rate)
+    return out
+
+
+@pytest.mark.parametrize("pattern", ["streaming", "hybrid", "sequential"])
+def test_dropout_masks_against_finite_differences_and_torch(pattern):
+    g = patterns(small_sr_graph(batch=3))[pattern]
+    Wn = 4
+    w, b, x, labels = case(g, 29, Wn)
+    masks = dropout_masks(g, Wn, 30, {1: 0.25, 2: 0.5})        # App. A2: 0.25, and 0.5 on the last hidden layer
+    loss, dth, db = tr.window_gradients(g, w, b, x, labels, Wn, masks=masks)
+    tl, tdw, tdb = torch_window_loss(g, w, b, x, labels, Wn, masks=masks)
+    assert abs(loss - tl) <= 1e-12 * max(1.0, abs(tl))
+    for a, c in zip(dth + db, tdw + tdb):
+        np.testing.assert_allclose(a, c, rtol=1e-9, atol=1e-12)
+    rng = np.random.default_rng(2)
+    h = 1e-5
+
+    def loss_at(ws):
+        win = tr.Window(g, ws, b)
+        win.forward(x, Wn, masks=masks)
+        return win.loss(labels)
+
+    for ei in range(len(w)):
+        for _ in range(3):
+            k = tuple(rng.integers(0, s) for s in w[ei].shape)
+            wp = [t.copy() for t in w]; wm = [t.copy() for t in w]
+            wp[ei][k] += h; wm[ei][k] -= h
+            fd = (loss_at(wp) - loss_at(wm)) / (2 * h)
+            assert abs(fd - dth[ei][k]) <= 1e-6 + 1e-5 * abs(fd), (pattern, ei, k, fd, dth[ei][k])
+    # the masks matter, masks of ones do not, and a node that is dropped entirely passes nothing on
+    base = tr.window_gradients(g, w, b, x, labels, Wn)
+    assert any(np.abs(a - c).max() > 1e-6 for a, c in zip(dth, base[1]))
+    ones = {v: np.ones_like(m) for v, m in masks.items()}
+    same = tr.window_gradients(g, w, b, x, labels, Wn, masks=ones)
+    for a, c in zip(same[1] + same[2], base[1] + base[2]):
+        assert np.array_equal(a, c)
+    cut = tr.window_gradients(g, w, b, x, labels, Wn, masks={2: np.zeros_like(masks[2])})
+    for ei, e in enumerate(g.edges):
+        if e.dst == 2:
+            assert np.all(cut[1][ei] == 0), ei            # edges into the dropped node get no gradient
