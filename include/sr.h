@@ -302,6 +302,10 @@ sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
  *   g         an SR_F32 graph with all weights set (SR_BF16 graphs: SR_ERR_ARG)
  *   inputs    host array, one device pointer per input node: float [W+1][B][H][W][C], frame 0 first
  *             (frame 0 is read by the bridging edges that leave an input node)
+ *   masks     dropout (App. A2, training details: rates 0.25 and 0.5): NULL, or a host array of n_nodes device
+ *             pointers, masks[v] NULL or float [W+1][B][H][W][C] multipliers of node v's state,
+ *             x_v(i) = masks[v][i] * sigma_v(a_v(i)); the caller draws them (0 with the dropout rate,
+ *             1/(1 - rate) otherwise, afresh for every frame and node); frame 0 and input nodes are ignored
  *   labels    device, B int32 class indices in [0, channels of out_node); values outside are clamped
  *   out_node  a 1x1 node with incoming edges whose channels are the class scores
  *   loss      device, 1 float
@@ -315,8 +319,9 @@ sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
  * reused by later calls.  Asynchronous on the graph's stream; the host arrays are consumed before
  * the call returns.  No optimiser step is taken.
  * Errors: SR_ERR_ARG, SR_ERR_STATE (weights missing), SR_ERR_OOM, SR_ERR_DEVICE. */
-sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const int32_t* labels,
-                              int32_t out_node, float* loss, float* const* dtheta, float* const* dbias);
+sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const float* const* masks,
+                              const int32_t* labels, int32_t out_node, float* loss, float* const* dtheta,
+                              float* const* dbias);
 
 /* One RMSprop update of every weight and bias of an SR_F32 graph, in place on the device (App. A2,
  * training details: RMSprop; Tieleman & Hinton 2012):

@@ -76,7 +76,7 @@ def load_library():
     lib.sr_graph_tile_kernel.argtypes = [vp, P(i32)]
     lib.sr_graph_node_kernels.argtypes = [vp, P(i32)]
     lib.sr_graph_health.argtypes = [vp, P(i64), P(i32)]
-    lib.sr_window_gradients.argtypes = [vp, i32, P(vp), vp, i32, vp, P(vp), P(vp)]
+    lib.sr_window_gradients.argtypes = [vp, i32, P(vp), P(vp), vp, i32, vp, P(vp), P(vp)]
     lib.sr_rmsprop_step.argtypes = [vp, C.c_float, C.c_float, C.c_float, P(vp), P(vp)]
     lib.sr_graph_get_weights.argtypes = [vp, i32, P(C.c_float), C.c_size_t]
     lib.sr_graph_get_bias.argtypes = [vp, i32, P(C.c_float), C.c_size_t]
@@ -288,8 +288,9 @@ class SrGraph:
         if outputs is not None:
             self._publish()
 
-    def window_gradients(self, inputs, labels, W: int, out_node: Optional[int] = None):
-        """inputs: one float tensor [W+1,B,H,W,C] per input node; labels: int32 tensor [B] on the device.
+    def window_gradients(self, inputs, labels, W: int, out_node: Optional[int] = None, masks=None):
+        """inputs: one float tensor [W+1,B,H,W,C] per input node; labels: int32 tensor [B] on the device;
+        masks: None or {node: float tensor [W+1,B,H,W,C]} of dropout multipliers.
         Returns (loss tensor [1], dtheta list, dbias list) as device tensors (dbias of input nodes: None)."""
         torch = self.torch
         g = self.g
@@ -314,8 +315,19 @@ class SrGraph:
             t = torch.empty(n.channels, dtype=torch.float32, device="cuda")
             dbs.append(t)
             barr[v] = t.data_ptr()
+        marr = None
+        if masks:
+            marr = (C.c_void_p * len(g.nodes))()
+            for v in range(len(g.nodes)):
+                t = masks.get(v)
+                if t is not None:
+                    n = g.nodes[v]
+                    assert t.is_cuda and t.is_contiguous() and t.dtype == torch.float32
+                    assert tuple(t.shape) == (W + 1, g.batch, n.height, n.width, n.channels), "mask shape"
+                    marr[v] = t.data_ptr()
+            self._order(*masks.values())
         self._order(labels, loss, *dth, *dbs)
-        _check(self.lib, self.lib.sr_window_gradients(self.h, W, self._ptrs(inputs), C.c_void_p(labels.data_ptr()), out,
+        _check(self.lib, self.lib.sr_window_gradients(self.h, W, self._ptrs(inputs), marr, C.c_void_p(labels.data_ptr()), out,
                                                        C.c_void_p(loss.data_ptr()), tarr, barr), self.h)
         self._publish()
         return loss, dth, dbs

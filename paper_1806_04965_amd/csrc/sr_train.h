@@ -24,7 +24,8 @@ struct SrConvGeom {   // y[b][ho][wo][co] = sum x[b][ho*stride + i - pad][wo*str
 hipError_t sr_train_ce(hipStream_t s, const float* z, const int32_t* labels, int B, int C, float scale, float* terms,
                        float* dz);
 hipError_t sr_train_sum_terms(hipStream_t s, const float* terms, int n, float scale, float* out);
-hipError_t sr_train_relu_mask(hipStream_t s, float* d, const float* x, size_t n);
+// d <- d * m * sigma'(a) for x = m * sigma(a) (m may be null)
+hipError_t sr_train_act_grad(hipStream_t s, float* d, const float* x, const float* m, size_t n, int act);
 int sr_train_bias_slices(int M);
 // part: sr_train_bias_slices(M) * C floats of scratch; db += the gradient
 hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float* part, float* db);
@@ -37,7 +38,7 @@ hipError_t sr_train_fwd(hipStream_t s, const SrConvGeom& q, const float* x, cons
 int sr_train_fwd_is_tiled(const SrConvGeom& q);   // would sr_train_fwd take this edge to the tiled kernel?
 hipError_t sr_train_upsample_add(hipStream_t s, const float* y, int B, int H, int W, int C, int up, float* dst,
                                  int accumulate);
-hipError_t sr_train_bias_act(hipStream_t s, float* a, const float* bias, int C, size_t n, int act);
+hipError_t sr_train_bias_act(hipStream_t s, float* a, const float* bias, const float* m, int C, size_t n, int act);
 int sr_train_wgrad_slices(const SrConvGeom& q);
 // part: sr_train_wgrad_slices(q) * (number of weights) floats of scratch; dtheta += the gradient
 hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, const float* dy, float* part,

@@ -51,10 +51,16 @@ __global__ void sr_sum_terms_kernel(const float* __restrict__ terms, int n, floa
   if (threadIdx.x == 0) out[0] = part[0] * scale;
 }
 
-// rectifier: the gradient passes where the state is positive (x = max(a, 0): a > 0 exactly there)
-__global__ void sr_relu_mask_kernel(float* __restrict__ d, const float* __restrict__ x, size_t n) {
+// gradient through the node map x = m * sigma(a): for the rectifier the gradient passes where the state is positive
+// (x = m * max(a, 0) > 0 exactly where a > 0 and m > 0); m: dropout multipliers or null
+__global__ void sr_act_grad_kernel(float* __restrict__ d, const float* __restrict__ x, const float* __restrict__ m,
+                                   size_t n, int act) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (i < n && !(x[i] > 0.f)) d[i] = 0.f;
+  if (i >= n) return;
+  float v = d[i];
+  if (act == 1 && !(x[i] > 0.f)) v = 0.f;
+  if (m) v *= m[i];
+  d[i] = v;
 }
 
 // db[c] += sum over the M pixels of d[m][c]; one workgroup per channel (few pixels: one launch, no scratch)
@@ -485,12 +491,14 @@ __global__ void sr_upsample_add_kernel(const float* __restrict__ y, int B, int H
   dst[i] = accumulate ? dst[i] + v : v;
 }
 
-// x = sigma(a + b_c) in place (App. A1.2 node map)
-__global__ void sr_bias_act_kernel(float* __restrict__ a, const float* __restrict__ bias, int C, size_t n, int act) {
+// x = m * sigma(a + b_c) in place (App. A1.2 node map; m: dropout multipliers or null)
+__global__ void sr_bias_act_kernel(float* __restrict__ a, const float* __restrict__ bias, const float* __restrict__ m,
+                                   int C, size_t n, int act) {
   const size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
   if (i >= n) return;
-  const float v = a[i] + bias[i % C];
-  a[i] = act == 1 ? fmaxf(v, 0.f) : v;
+  float v = a[i] + bias[i % C];
+  if (act == 1) v = fmaxf(v, 0.f);
+  a[i] = m ? v * m[i] : v;
 }
 
 // RMSprop: a <- rho a + (1 - rho) g^2;  theta <- theta - lr g / (sqrt(a) + eps)
@@ -524,9 +532,9 @@ hipError_t sr_train_sum_terms(hipStream_t s, const float* terms, int n, float sc
   return hipGetLastError();
 }
 
-hipError_t sr_train_relu_mask(hipStream_t s, float* d, const float* x, size_t n) {
-  if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(sr_relu_mask_kernel, dim3(grid_for((long long)n, 256)), dim3(256), 0, s, d, x, n);
+hipError_t sr_train_act_grad(hipStream_t s, float* d, const float* x, const float* m, size_t n, int act) {
+  if (n == 0 || (act != 1 && !m)) return hipSuccess;
+  hipLaunchKernelGGL(sr_act_grad_kernel, dim3(grid_for((long long)n, 256)), dim3(256), 0, s, d, x, m, n, act);
   return hipGetLastError();
 }
 
@@ -636,9 +644,9 @@ hipError_t sr_train_upsample_add(hipStream_t s, const float* y, int B, int H, in
   return hipGetLastError();
 }
 
-hipError_t sr_train_bias_act(hipStream_t s, float* a, const float* bias, int C, size_t n, int act) {
+hipError_t sr_train_bias_act(hipStream_t s, float* a, const float* bias, const float* m, int C, size_t n, int act) {
   if (n == 0) return hipSuccess;
-  hipLaunchKernelGGL(sr_bias_act_kernel, dim3(grid_for((long long)n, 256)), dim3(256), 0, s, a, bias, C, n, act);
+  hipLaunchKernelGGL(sr_bias_act_kernel, dim3(grid_for((long long)n, 256)), dim3(256), 0, s, a, bias, m, C, n, act);
   return hipGetLastError();
 }
 

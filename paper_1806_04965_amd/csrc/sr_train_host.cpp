@@ -14,8 +14,9 @@
 
 extern "C" {
 
-sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const int32_t* labels,
-                              int32_t out_node, float* loss, float* const* dtheta, float* const* dbias) {
+sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const float* const* masks,
+                              const int32_t* labels, int32_t out_node, float* loss, float* const* dtheta,
+                              float* const* dbias) {
   if (!g || !inputs || !labels || !loss || !dtheta || W < 1)
     return sr_gfail(g, SR_ERR_ARG, "bad argument to sr_window_gradients");
   if (g->dtype != SR_F32) return sr_gfail(g, SR_ERR_ARG, "sr_window_gradients: training windows take SR_F32 graphs only");
@@ -105,6 +106,11 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   // update step per launch
   bool own_forward = false;
   for (const EdgeRt& e : g->edges) own_forward |= sr_train_fwd_is_tiled(geom_of(e)) != 0;
+  // dropout multipliers of node v at frame i (null: none); the frame path knows no dropout
+  auto mask_of = [&](int v, int frame) -> const float* {
+    return (masks && masks[v] && !g->an.is_input[v]) ? masks[v] + (size_t)frame * node_floats(v) : nullptr;
+  };
+  for (int v = 0; masks && v < N; ++v) own_forward |= (masks[v] != nullptr && !g->an.is_input[v]);
   if (!own_forward) {
     std::vector<const void*> ptrs(g->inputs.size());
     for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = inputs[k];
@@ -141,7 +147,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         }
         seen = 1;
       }
-      SR_HIP(g, sr_train_bias_act(s, dst, g->nodes[v].bias_dev, d.channels, node_floats(v), d.act));
+      SR_HIP(g, sr_train_bias_act(s, dst, g->nodes[v].bias_dev, mask_of(v, i), d.channels, node_floats(v), d.act));
     }
 
   // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
@@ -162,7 +168,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     for (int v : order) {
       const sr_node_desc& d = g->nodes[v].d;
       float* da = A + dx_at[cur][v];
-      if (d.act == SR_ACT_RELU) SR_HIP(g, sr_train_relu_mask(s, da, A + x_at[v] + (size_t)i * node_floats(v), node_floats(v)));
+      SR_HIP(g, sr_train_act_grad(s, da, A + x_at[v] + (size_t)i * node_floats(v), mask_of(v, i), node_floats(v), d.act));
       if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(s, da, B * d.height * d.width, d.channels, A + part_at, dbias[v]));
       for (int ei = 0; ei < g->n_edges; ++ei) {
         const EdgeRt& e = g->edges[ei];

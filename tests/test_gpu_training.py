@@ -291,3 +291,41 @@ def test_two_inputs_batch_of_one_odd_channel_counts_and_clamped_labels():
     for ei in range(len(g.edges)):
         assert max_abs_rel(dth[ei].cpu().numpy(), ref_dth[ei]) <= GRAD_TOL, ei
     dev.close()
+
+
+@pytest.mark.parametrize("name", ["small_sr", "mid_sr", "mnist_sr"])
+def test_window_gradients_with_dropout_masks(name):
+    # App. A2, training details: dropout 0.25, and 0.5 on the last hidden layer; the masks are drawn here, once,
+    # and handed to both sides
+    import torch
+    import paper_1806_04965_amd as sr
+    from test_oracle_training import dropout_masks
+    mk, Wn = cases()[name]
+    g0 = mk()
+    g = g0.with_pattern(W.hybrid_pattern(g0))
+    hidden = [v for v in range(len(g.nodes)) if v not in g.input_nodes() and v != g.out_node]
+    rates = {v: (0.5 if v == hidden[-1] else 0.25) for v in hidden}
+    masks = dropout_masks(g, Wn, 91, rates)
+    w, b, x = W.make_case(g, seed=92, bias_scale=0.1, frames=Wn, recipe="uniform")
+    labels = np.random.default_rng(93).integers(0, g.nodes[g.out_node].channels, g.batch).astype(np.int32)
+    dev = sr.SrGraph(g)
+    dev.set_parameters(w, b)
+    xd = [to_device(x[v][:Wn + 1], "f32") for v in g.input_nodes()]
+    md = {v: torch.from_numpy(m.astype(np.float32)).to("cuda").contiguous() for v, m in masks.items()}
+    loss, dth, dbs = dev.window_gradients(xd, torch.from_numpy(labels).to("cuda"), Wn, masks=md)
+    dev.synchronize()
+    ref_loss, ref_dth, ref_db = tr.window_gradients(g, w, b, {v: x[v][:Wn + 1] for v in x}, labels, Wn, masks=masks)
+    no_drop = tr.window_gradients(g, w, b, {v: x[v][:Wn + 1] for v in x}, labels, Wn)[0]
+    assert abs(ref_loss - no_drop) > 1e-3                      # the masks do change the window
+    assert abs(float(loss.cpu()[0]) - ref_loss) <= LOSS_TOL * max(1.0, ref_loss)
+    worst = 0.0
+    for ei in range(len(g.edges)):
+        assert np.abs(ref_dth[ei]).max() > 0
+        worst = max(worst, max_abs_rel(dth[ei].cpu().numpy(), ref_dth[ei]))
+    for v in range(len(g.nodes)):
+        if dbs[v] is not None:
+            worst = max(worst, max_abs_rel(dbs[v].cpu().numpy(), ref_db[v]))
+    print(f"[train] {name}/hybrid with dropout: loss {float(loss.cpu()[0]):.6f} (oracle {ref_loss:.6f}), worst gradient "
+          f"max-abs-rel {worst:.2e}", flush=True)
+    assert worst <= GRAD_TOL
+    dev.close()

@@ -176,7 +176,7 @@ def test_null_handles_are_errors_not_crashes():
     assert lib.sr_graph_health(None, None, None) == 1
     assert lib.sr_graph_traffic_model(None, None) == 1
     assert lib.sr_frame_step_static(None, None) == 1
-    assert lib.sr_window_gradients(None, 1, None, None, 0, None, None, None) == 1
+    assert lib.sr_window_gradients(None, 1, None, None, None, 0, None, None, None) == 1
     assert lib.sr_rmsprop_step(None, 1e-3, 0.9, 1e-7, None, None) == 1
     assert lib.sr_graph_get_weights(None, 0, None, 0) == 1
     assert lib.sr_graph_get_bias(None, 0, None, 0) == 1
