@@ -102,10 +102,16 @@ typedef enum {
                                   2 (default): for patterns with more than one update step per frame (F(R) > 1, Eq. 6);
                                   1: whenever possible, also for the streaming pattern; 0: never (one launch per
                                   update step) */
-  SR_OPT_DEP_SPIN_LIMIT = 6    /* polls (with back-off) before a dependency wait of a dependency-driven graph gives up
+  SR_OPT_DEP_SPIN_LIMIT = 6,   /* polls (with back-off) before a dependency wait of a dependency-driven graph gives up
                                   (default 2^18, about 0.3 s; 0..2^24).  A wait that gives up lets its work item go
                                   on with whatever is in memory and is counted by sr_graph_health; every kernel
                                   still ends normally.  For tests of that path. */
+  SR_OPT_FLOW_ORDER = 7        /* dependency-driven launches that cover several frames (sr_rollout):
+                                  1 (default): the work items of all their frames are dispatched in the order of
+                                  their depth in the rollout window of those frames (the inference tableau of Eq. 5
+                                  taken over update steps of all the frames), so that update steps of consecutive
+                                  frames that do not depend on one another run side by side;
+                                  0: frame after frame */
 } sr_option;
 
 /* ---------------------------------------------------------------------------

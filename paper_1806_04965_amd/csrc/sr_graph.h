@@ -102,6 +102,9 @@ struct sr_graph {
   int32_t* done_counters = nullptr;   // one per graph node
   SrTile4* flow_items = nullptr;      // a frame's work items in dependency order: tiles, and aux items as node = -2 - index
   int n_flow_items = 0;
+  int32_t* flow_order = nullptr;      // (frame, item) pairs of a launch of flow_order_frames frames, by depth (see SrFlow)
+  int n_flow_order = 0, flow_order_frames = 0;
+  bool flow_depth_order = true;       // SR_OPT_FLOW_ORDER
   std::vector<int> flow_dep_begin, flow_dep_count;
   float* split_scratch = nullptr;
   size_t split_scratch_bytes = 0;

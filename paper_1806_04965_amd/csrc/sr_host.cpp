@@ -1258,19 +1258,80 @@ sr_status finalize(sr_graph* g) {
       std::vector<SrTile4> items;
       SrTile4 none{};
       none.node = -1;
+      std::vector<int> run_begin;   // the list is a sequence of runs: staging, then per update step its tiles and its head items
       auto pad8 = [&]() { while (items.size() % SR_XCDS) items.push_back(none); };
+      auto new_run = [&]() { if (run_begin.empty() || run_begin.back() != (int)items.size()) run_begin.push_back((int)items.size()); };
       auto aux_item = [&](int index) { SrTile4 a{}; a.node = -2 - index; items.push_back(a); };
+      new_run();
       for (int k = 0; k < (int)stage_aux.size(); ++k) aux_item(flow_stage_begin + k);
       pad8();
       for (int L = 1; L <= F; ++L) {
         const LevelPlan& lp = g->levels[L];
+        new_run();
         items.insert(items.end(), t4.begin() + lp.tile_begin, t4.begin() + lp.tile_begin + lp.n_tiles);
         pad8();
+        new_run();
         for (int k = 0; k < lp.n_aux; ++k)
           if (aux[lp.aux_begin + k].kind == SR_AUX_HEAD) aux_item(lp.aux_begin + k);
         pad8();
       }
       g->n_flow_items = (int)items.size();
+      // Launches that cover several frames: their (frame, run) pairs in the order of their depth in the rollout
+      // window of those frames -- a run's depth is one more than the deepest run it waits for (reads and
+      // overwrites alike; what lies before the launch is complete) -- the inference tableau of Eq. 5 taken over
+      // runs.  Every wait still refers to an earlier workgroup, and update steps of consecutive frames that do not
+      // depend on one another are dispatched side by side instead of frame after frame.
+      {
+        const int n_frames = g->frames_per_graph;
+        run_begin.push_back((int)items.size());
+        const int n_runs = (int)run_begin.size() - 1;
+        std::vector<std::vector<int>> run_nodes(n_runs);
+        std::vector<int> run_of(g->n_nodes, -1);
+        for (int r = 0; r < n_runs; ++r)
+          for (int i = run_begin[r]; i < run_begin[r + 1]; ++i) {
+            const SrTile4& q = items[i];
+            int v = -1;
+            if (q.node >= 0) v = mfma_graph_node[q.node];
+            else if (q.node <= -2) {
+              const SrAux& a = aux[-2 - q.node];
+              v = (a.kind == SR_AUX_HEAD) ? g->head_node[a.a] : g->inputs[a.a];
+            }
+            if (v >= 0 && run_of[v] != r) { run_of[v] = r; run_nodes[r].push_back(v); }
+          }
+        bool ok = n_frames >= 2 && n_frames <= 255 && g->n_flow_items < (1 << 24);
+        std::vector<std::vector<int>> depth(n_frames, std::vector<int>(n_runs, 0));
+        for (int t = 0; ok && t < n_frames; ++t)
+          for (int r = 0; ok && r < n_runs; ++r) {
+            int d = 0;
+            for (int v : run_nodes[r]) {
+              const int cnt = (g->flow_dep_count[v] & 0xff) + (g->flow_dep_count[v] >> 8);
+              for (int k = 0; k < cnt; ++k) {
+                const SrDep& dp = deps[g->flow_dep_begin[v] + k];
+                const int tt = t - dp.lag, rr = run_of[dp.node];
+                if (tt < 0 || rr < 0) continue;
+                if (dp.lag == 0 && rr >= r) { ok = false; break; }   // cannot be: same-frame sources lie in earlier runs
+                d = std::max(d, depth[tt][rr] + 1);
+              }
+            }
+            depth[t][r] = d;
+          }
+        if (ok) {
+          struct Key { int depth, t, r; };
+          std::vector<Key> keys;
+          for (int t = 0; t < n_frames; ++t)
+            for (int r = 0; r < n_runs; ++r) keys.push_back(Key{depth[t][r], t, r});
+          std::stable_sort(keys.begin(), keys.end(), [](const Key& a, const Key& b) {
+            return a.depth != b.depth ? a.depth < b.depth : (a.t != b.t ? a.t < b.t : a.r < b.r);
+          });
+          std::vector<int32_t> order;
+          order.reserve((size_t)n_frames * items.size());
+          for (const Key& k : keys)
+            for (int i = run_begin[k.r]; i < run_begin[k.r + 1]; ++i) order.push_back((int32_t)(i | (k.t << 24)));
+          g->n_flow_order = (int)order.size();
+          g->flow_order_frames = n_frames;
+          if ((st = upload(g, &g->flow_order, order)) != SR_OK) return st;
+        }
+      }
       if ((st = upload(g, &g->flow_items, items)) != SR_OK) return st;
       if ((st = upload(g, &g->deps, deps)) != SR_OK) return st;
       void* dc = nullptr;
@@ -1372,10 +1433,11 @@ sr_status ensure_split_scratch(sr_graph* g) {
 
 // Dependency-driven graphs: `frames` frames, every update step of each, in one launch.
 sr_status enqueue_flow(sr_graph* g, int frames, bool advance, SrSplitScratch split) {
-  const SrFlow flow{g->deps, g->done_counters, g->dep_spin_limit, 0};
+  const bool by_depth = g->flow_order && frames == g->flow_order_frames && g->flow_depth_order;
+  const SrFlow flow{g->deps, g->done_counters, g->dep_spin_limit, frames, by_depth ? g->flow_order : nullptr};
   SR_HIP(g, sr_launch_mfma(g->stream, g->ctx,
                            SrTables4{g->nodes4, g->planes4, (const SrPlanRef*)g->plan_index, g->plan_tables, g->tap_table},
-                           flow, frames, g->flow_items, g->n_flow_items, g->lds_bytes, g->aux, 0, g->heads, g->head_edges,
+                           flow, frames, g->n_flow_order, g->flow_items, g->n_flow_items, g->lds_bytes, g->aux, 0, g->heads, g->head_edges,
                            g->stage_nodes, g->aux_smem_bytes, advance ? 1 : 0, split));
   return SR_OK;
 }
@@ -1444,7 +1506,7 @@ sr_status enqueue_frame(sr_graph* g, bool record, FrameTimer* ft, SrSplitScratch
       else
         SR_HIP(g, sr_launch_mfma(s, g->ctx,
                                  SrTables4{g->nodes4, g->planes4, (const SrPlanRef*)g->plan_index, g->plan_tables, g->tap_table},
-                                 SrFlow{nullptr, nullptr, 0, 0}, 1, g->tiles4 + lp.tile_begin, lp.n_tiles, g->lds_bytes,
+                                 SrFlow{nullptr, nullptr, 0, 0, nullptr}, 1, 0, g->tiles4 + lp.tile_begin, lp.n_tiles, g->lds_bytes,
                                  g->aux + lp.aux_begin, lp.n_aux, g->heads, g->head_edges, g->stage_nodes,
                                  g->aux_smem_bytes, is_last, split));
     }
@@ -1895,6 +1957,9 @@ sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value) {
     case SR_OPT_DATAFLOW:
       if (value < 0 || value > 2) return gfail(g, SR_ERR_ARG, "dependency-driven execution: 0 (off), 1 (on) or 2 (default)");
       g->dataflow_option = (int)value;
+      return SR_OK;
+    case SR_OPT_FLOW_ORDER:
+      g->flow_depth_order = value != 0;
       return SR_OK;
     case SR_OPT_DEP_SPIN_LIMIT:
       if (value < 0 || value > (1 << 24)) return gfail(g, SR_ERR_ARG, "spin limit of dependency waits must be in 0..2^24");

@@ -47,7 +47,12 @@ struct SrFlow {
   int32_t* done;       // per graph node, SR_DONE_STRIDE ints apart (a memory line each: they are polled):
                        // work items completed since the last reset (wraps; compared by difference)
   int32_t spin_limit;  // polls before a wait gives up (and counts itself in SrCtx::dep_timeouts)
-  int32_t pad_;
+  int32_t frames;      // with `order`: frames the launch covers
+  // null: workgroup (x, y) is work item x of frame y.  Else the launch is one-dimensional and workgroup i is work
+  // item order[i] & 0xffffff of frame order[i] >> 24: the (frame, item) pairs of all its frames sorted by their
+  // depth in the rollout window of those frames (the inference tableau of Eq. 5 taken over work items), so that
+  // update steps of consecutive frames that do not depend on one another run side by side
+  const int32_t* order;
 };
 
 // ---------------------------------------------------------------------------
@@ -286,7 +291,8 @@ struct SrTables4 {   // 4-wave kernel: the graph's device tables
   const SrTap* tap_table;
 };
 // frames > 1 or flow.deps != null: dependency-driven launch covering `frames` frames (grid y)
-hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, SrTables4 tables, SrFlow flow, int frames,
+// flow.order != null: one-dimensional launch of n_order workgroups (see SrFlow)
+hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, SrTables4 tables, SrFlow flow, int frames, int n_order,
                           const SrTile4* tiles, int n_tiles, int lds_bytes, const SrAux* aux, int n_aux,
                           const SrHead* heads, const SrHeadEdge* head_edges, const SrStageNode* stage_nodes,
                           int aux_smem_bytes, int is_last, SrSplitScratch split);

@@ -521,7 +521,7 @@ __global__ __launch_bounds__(256) void sr_direct_kernel(SrCtx* __restrict__ ctx,
     sr_direct_block<T>(ctx, nodes[blk.node], edges, blk.first, batch);
   } else {
     sr_aux_item<T>(ctx, aux[blockIdx.x - n_blocks], heads, head_edges, stage_nodes, sr_aux_smem, vec_floats, ctx->frame,
-                   SrFlow{nullptr, nullptr, 0, 0});
+                   SrFlow{nullptr, nullptr, 0, 0, nullptr});
   }
   if (is_last) sr_block_done(ctx, gridDim.x, 1);
 }
@@ -999,8 +999,15 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
   // that neither the longest tiles start late nor the launch ends on an auxiliary item
   // A launch covers gridDim.y frames (more than one only when dependency-driven); the hardware hands
   // workgroups out in the order x, then y: frame by frame.
-  const int item = blockIdx.x;
-  const int frame = ctx->frame + (int)blockIdx.y;
+  int item = blockIdx.x, frame = ctx->frame + (int)blockIdx.y;
+  int n_blocks = gridDim.x * gridDim.y, n_frames = gridDim.y;
+  if (flow.order) {
+    const int e = ((const __attribute__((address_space(4))) int*)(unsigned long long)flow.order)[blockIdx.x];
+    item = e & 0xffffff;
+    frame = ctx->frame + (int)((unsigned)e >> 24);
+    n_blocks = gridDim.x;
+    n_frames = flow.frames;
+  }
   const bool is_aux = item >= aux_at && item < aux_at + n_aux;
   if (!is_aux) {
     const SrTileK t = sr_load_tile(tiles, item < aux_at ? item : item - n_aux);
@@ -1016,7 +1023,7 @@ __global__ __launch_bounds__(256, 2) void sr_mfma_kernel(SrCtx* __restrict__ ctx
   } else {
     sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds, vec_floats, frame, flow);
   }
-  if (is_last) sr_block_done(ctx, gridDim.x * gridDim.y, gridDim.y);
+  if (is_last) sr_block_done(ctx, n_blocks, n_frames);
 }
 
 // ---------------------------------------------------------------------------
@@ -1358,7 +1365,7 @@ __global__ __launch_bounds__(512) void sr_mfma8_kernel(SrCtx* __restrict__ ctx, 
   if (item >= aux_at && item < aux_at + n_aux) {
     if (threadIdx.x >= SR_AUX_THREADS) return;
     sr_aux_item<uint16_t>(ctx, aux[item - aux_at], heads, head_edges, stage_nodes, (float*)sr_lds8, vec_floats, ctx->frame,
-                          SrFlow{nullptr, nullptr, 0, 0});
+                          SrFlow{nullptr, nullptr, 0, 0, nullptr});
     if (is_last) sr_block_done(ctx, gridDim.x, 1);
     return;
   }
@@ -1413,7 +1420,7 @@ __global__ void sr_aux_kernel(SrCtx* __restrict__ ctx, const SrAux* __restrict__
                               int vec_floats, int is_last) {
   extern __shared__ float sr_aux_smem2[];
   sr_aux_item<T>(ctx, aux[blockIdx.x], heads, head_edges, stage_nodes, sr_aux_smem2, vec_floats, ctx->frame,
-                 SrFlow{nullptr, nullptr, 0, 0});
+                 SrFlow{nullptr, nullptr, 0, 0, nullptr});
   if (is_last) sr_block_done(ctx, gridDim.x, 1);
 }
 
@@ -1475,7 +1482,8 @@ static hipError_t sr_request_lds(const void* kernel, int bytes, int which) {
   return e;
 }
 
-hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, SrTables4 tables, SrFlow flow, int frames, const SrTile4* tiles,
+hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, SrTables4 tables, SrFlow flow, int frames, int n_order,
+                          const SrTile4* tiles,
                           int n_tiles, int lds_bytes, const SrAux* aux, int n_aux, const SrHead* heads,
                           const SrHeadEdge* head_edges, const SrStageNode* stage_nodes, int aux_smem_bytes, int is_last,
                           SrSplitScratch split) {
@@ -1484,7 +1492,8 @@ hipError_t sr_launch_mfma(hipStream_t s, SrCtx* ctx, SrTables4 tables, SrFlow fl
     hipError_t e = sr_request_lds((const void*)sr_mfma_kernel, sr_mfma_max_lds_bytes(), 0);
     if (e != hipSuccess) return e;
   }
-  hipLaunchKernelGGL(sr_mfma_kernel, dim3(n_tiles + n_aux, frames), dim3(256), lds_bytes, s, ctx, tables, flow, tiles,
+  const dim3 grid = flow.order ? dim3(n_order) : dim3(n_tiles + n_aux, frames);
+  hipLaunchKernelGGL(sr_mfma_kernel, grid, dim3(256), lds_bytes, s, ctx, tables, flow, tiles,
                      n_tiles, aux, n_aux, n_tiles / 2, heads, head_edges, stage_nodes, sr_vec_floats(aux_smem_bytes), is_last,
                      split);
   return hipGetLastError();

@@ -394,3 +394,26 @@ def test_dependency_wait_that_gives_up_is_counted_and_every_kernel_ends():
     dev.close()
     with pytest.raises(sr.SrError):
         sr.SrGraph(g, options={6: -1})
+
+
+@pytest.mark.parametrize("name", ["cifar_seq", "cifar_hybrid", "dsr2_seq", "hires_seq"])
+def test_depth_ordered_multi_frame_launch_equals_frame_after_frame(name):
+    # a dependency-driven rollout dispatches the work items of 8 frames in the order of their depth in the rollout
+    # window of those frames (Eq. 5 over update steps); the arithmetic of every item is the same as when the frames
+    # are dispatched one after the other, so the outputs are bit-identical -- and both match the oracle
+    g0 = {"cifar_seq": lambda: W.cifar_sr(batch=4, frames=19), "cifar_hybrid": lambda: W.cifar_sr(batch=4, frames=19),
+          "dsr2_seq": lambda: W.dsr_net(2, batch=8, frames=17), "hires_seq": lambda: W.hires_sr(batch=1, frames=16)}[name]()
+    pat = W.hybrid_pattern if name.endswith("hybrid") else W.sequential_pattern
+    g = g0.with_pattern(pat(g0))
+    T = g.frames
+    w, b, x = W.make_case(g, seed=61, bias_scale=0.1, frames=T)
+    a, dev = gpu_rollout(g, w, b, x, T, return_dev=True)
+    h = dev.health()
+    dev.close()
+    assert h["dependency_driven"] and h["dependency_timeouts"] == 0
+    c = gpu_rollout(g, w, b, x, T, options={7: 0})
+    assert np.array_equal(a, c)
+    ref = oracle_states(g, w, b, x, T, "bf16", nodes=[g.out_node])
+    for t in range(T):
+        assert np.abs(ref[g.out_node][t]).max() > 0
+        assert max_abs_rel(a[t], ref[g.out_node][t]) <= TOL["bf16"], (name, t)
