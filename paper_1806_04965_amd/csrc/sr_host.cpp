@@ -1267,9 +1267,30 @@ sr_status finalize(sr_graph* g) {
       pad8();
       for (int L = 1; L <= F; ++L) {
         const LevelPlan& lp = g->levels[L];
-        new_run();
-        items.insert(items.end(), t4.begin() + lp.tile_begin, t4.begin() + lp.tile_begin + lp.n_tiles);
-        pad8();
+        // the step's tiles, one run per node (in the order in which the nodes first appear in the step's list:
+        // costliest tiles first), every tile on the XCD the step's list gave it: position p of the list runs on XCD p % 8
+        {
+          std::vector<int> node_order;
+          std::vector<std::vector<std::vector<SrTile4>>> lanes;   // [node slot][XCD] -> tiles
+          std::vector<int> slot_of_node(mn.size(), -1);
+          for (int p = 0; p < lp.n_tiles; ++p) {
+            const SrTile4& q = t4[lp.tile_begin + p];
+            if (q.node < 0) continue;
+            if (slot_of_node[q.node] < 0) {
+              slot_of_node[q.node] = (int)node_order.size();
+              node_order.push_back(q.node);
+              lanes.emplace_back(SR_XCDS);
+            }
+            lanes[slot_of_node[q.node]][p % SR_XCDS].push_back(q);
+          }
+          for (size_t sl = 0; sl < node_order.size(); ++sl) {
+            new_run();
+            size_t longest = 0;
+            for (const auto& ln : lanes[sl]) longest = std::max(longest, ln.size());
+            for (size_t k = 0; k < longest; ++k)
+              for (int x = 0; x < SR_XCDS; ++x) items.push_back(k < lanes[sl][x].size() ? lanes[sl][x][k] : none);
+          }
+        }
         new_run();
         for (int k = 0; k < lp.n_aux; ++k)
           if (aux[lp.aux_begin + k].kind == SR_AUX_HEAD) aux_item(lp.aux_begin + k);
