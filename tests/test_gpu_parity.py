@@ -417,3 +417,16 @@ def test_depth_ordered_multi_frame_launch_equals_frame_after_frame(name):
     for t in range(T):
         assert np.abs(ref[g.out_node][t]).max() > 0
         assert max_abs_rel(a[t], ref[g.out_node][t]) <= TOL["bf16"], (name, t)
+
+
+@pytest.mark.parametrize("frames_per_launch", [1, 2, 5, 16])
+def test_depth_ordered_launches_of_other_lengths(frames_per_launch):
+    # the order table is built for the configured number of frames per launch; a rollout whose length is no
+    # multiple of it finishes with single-frame launches.  All of them equal one launch per update step.
+    g0 = W.cifar_sr(batch=3, frames=13)
+    g = g0.with_pattern(W.sequential_pattern(g0))
+    w, b, x = W.make_case(g, seed=62, bias_scale=0.1, frames=13)
+    a = gpu_rollout(g, w, b, x, 13, options={2: frames_per_launch})
+    c = gpu_rollout(g, w, b, x, 13, options={5: 0})
+    assert np.array_equal(a, c)
+    assert np.abs(a[-1]).max() > 0
