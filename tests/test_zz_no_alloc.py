@@ -67,6 +67,19 @@ def test_static_scratch_matches_own_scratch_two_graphs_second_smaller():
     assert t_c > t_c_ns
 
 
+def test_static_scratch_with_a_dependency_driven_graph():
+    # sequential pattern: all update steps of a frame in one launch, ordered by completion counters
+    import paper_1806_04965_amd as sr
+    g0 = W.cifar_sr(batch=4, frames=3)
+    g = g0.with_pattern(W.sequential_pattern(g0))
+    dev = sr.SrGraph(g)
+    w, b, _ = W.make_case(g, seed=7)
+    dev.set_parameters(w, b)
+    assert dev.health()["dependency_driven"]
+    dev.close()
+    run_pair(g, seed=7, T=3)
+
+
 def test_static_scratch_with_the_eight_wave_kernel():
     run_pair(hires_at(64, 2), seed=6, T=2, options={4: 2})
 
