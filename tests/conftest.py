@@ -10,6 +10,8 @@ if ROOT not in sys.path:
 
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (runs the HIP library)")
+    # enforced by pytest-timeout where that plugin is installed; registered here so that the mark is known without it
+    config.addinivalue_line("markers", "timeout(seconds): upper bound of a test's run time")
 
 
 def _gpu_present():
