@@ -91,15 +91,16 @@ def train_window_bench(args, g):
     xin = [torch.from_numpy(x[v][:Wn + 1]).to("cuda").float().contiguous() for v in ins]
     labels = torch.from_numpy(labels_h).to("cuda")
     work = dev.work()
+    res = None   # every step writes the same output tensors, as a training loop does
     for _ in range(max(1, args.warmup)):
-        res = dev.window_gradients(xin, labels, Wn)
+        res = dev.window_gradients(xin, labels, Wn, into=res)
     dev.synchronize()
     torch.cuda.synchronize()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     t0 = time.perf_counter()
     ev0.record(dev.stream)
     for _ in range(args.steps):
-        res = dev.window_gradients(xin, labels, Wn)
+        res = dev.window_gradients(xin, labels, Wn, into=res)
     ev1.record(dev.stream)
     dev.synchronize()
     torch.cuda.synchronize()

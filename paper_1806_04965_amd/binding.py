@@ -288,14 +288,21 @@ class SrGraph:
         if outputs is not None:
             self._publish()
 
-    def window_gradients(self, inputs, labels, W: int, out_node: Optional[int] = None, masks=None):
+    def window_gradients(self, inputs, labels, W: int, out_node: Optional[int] = None, masks=None, into=None):
         """inputs: one float tensor [W+1,B,H,W,C] per input node; labels: int32 tensor [B] on the device;
-        masks: None or {node: float tensor [W+1,B,H,W,C]} of dropout multipliers.
+        masks: None or {node: float tensor [W+1,B,H,W,C]} of dropout multipliers; into: None, or the tuple an
+        earlier call returned, whose tensors are then written again (a loop that keeps all its buffers lets the
+        library replay the window's launches instead of issuing them one by one).
         Returns (loss tensor [1], dtheta list, dbias list) as device tensors (dbias of input nodes: None)."""
         torch = self.torch
         g = self.g
         out = g.out_node if out_node is None else out_node
         assert labels.is_cuda and labels.dtype == torch.int32 and labels.is_contiguous()
+        if into is not None:
+            loss, dth, dbs = into
+            tarr = (C.c_void_p * len(g.edges))(*[t.data_ptr() for t in dth])
+            barr = (C.c_void_p * len(g.nodes))(*[None if t is None else t.data_ptr() for t in dbs])
+            return self._window_call(inputs, labels, W, out, masks, loss, dth, dbs, tarr, barr)
         loss = torch.empty(1, dtype=torch.float32, device="cuda")
         dth, dbs = [], []
         tarr = (C.c_void_p * len(g.edges))()
@@ -315,6 +322,11 @@ class SrGraph:
             t = torch.empty(n.channels, dtype=torch.float32, device="cuda")
             dbs.append(t)
             barr[v] = t.data_ptr()
+        return self._window_call(inputs, labels, W, out, masks, loss, dth, dbs, tarr, barr)
+
+    def _window_call(self, inputs, labels, W, out, masks, loss, dth, dbs, tarr, barr):
+        g = self.g
+        torch = self.torch
         marr = None
         if masks:
             marr = (C.c_void_p * len(g.nodes))()

@@ -129,6 +129,11 @@ struct sr_graph {
   float* train_arena = nullptr;
   std::vector<float*> rms_w, rms_b;   // RMSprop's running mean of the squared gradient, per edge / node (on first use)
   size_t train_arena_floats = 0;
+  // the launches of one window, captured: replayed while a call names the same window size, output node and
+  // buffers (train_key holds them) and the arena has not moved
+  hipGraph_t train_graph = nullptr;
+  hipGraphExec_t train_exec = nullptr;
+  std::vector<const void*> train_key;
 
   hipGraph_t graph1 = nullptr, graphN = nullptr;
   hipGraphExec_t exec1 = nullptr, execN = nullptr;

@@ -2224,6 +2224,8 @@ void sr_graph_destroy(sr_graph* g) {
   drop_graphs(g);
   for (void* p : g->dev_allocs) hipFree(p);
   if (g->split_scratch) uncached_release(g->split_scratch, g->split_scratch_bytes);
+  if (g->train_exec) hipGraphExecDestroy(g->train_exec);
+  if (g->train_graph) hipGraphDestroy(g->train_graph);
   if (g->train_arena) hipFree(g->train_arena);
   delete g;
 }

@@ -4,6 +4,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstdint>
 #include <string>
 #include <vector>
 
@@ -11,6 +12,19 @@
 #include "sr_internal.h"
 #include "sr_train.h"
 #include "sr_graph.h"
+
+namespace {
+
+void drop_train_graph(sr_graph* g) {
+  if (g->train_exec) hipStreamSynchronize(g->stream);   // a replay may still be running
+  if (g->train_exec) hipGraphExecDestroy(g->train_exec);
+  if (g->train_graph) hipGraphDestroy(g->train_graph);
+  g->train_exec = nullptr;
+  g->train_graph = nullptr;
+  g->train_key.clear();
+}
+
+}  // namespace
 
 extern "C" {
 
@@ -73,6 +87,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   const size_t terms_at = take((size_t)W * B);
   if (at > g->train_arena_floats) {
     SR_HIP(g, hipStreamSynchronize(g->stream));
+    drop_train_graph(g);   // its launches name the old arena
     if (g->train_arena) SR_HIP(g, hipFree(g->train_arena));
     g->train_arena = nullptr;
     g->train_arena_floats = 0;
@@ -99,7 +114,6 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     return g->an.is_input[u] ? (const float*)inputs[slot_of[u]] + (size_t)frame * in_stride[slot_of[u]]
                              : A + x_at[u] + (size_t)frame * node_floats(u);
   };
-  for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + x_at[v], node_floats(v) * sizeof(float)));
   // Two ways to the same states: when some edge is large enough for the tiled matrix-core kernel the window
   // runs its own forward pass below; a graph of small edges only is better served by the frame path
   // (sr_reset + W x sr_frame_step, each frame's states copied into the arena), whose kernels take a whole
@@ -111,6 +125,10 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     return (masks && masks[v] && !g->an.is_input[v]) ? masks[v] + (size_t)frame * node_floats(v) : nullptr;
   };
   for (int v = 0; masks && v < N; ++v) own_forward |= (masks[v] != nullptr && !g->an.is_input[v]);
+
+  // every launch of the window, in stream order
+  auto enqueue = [&]() -> sr_status {
+  for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + x_at[v], node_floats(v) * sizeof(float)));
   if (!own_forward) {
     std::vector<const void*> ptrs(g->inputs.size());
     for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = inputs[k];
@@ -201,6 +219,38 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[cur][v], node_floats(v) * sizeof(float)));
   }
   SR_HIP(g, sr_train_sum_terms(s, A + terms_at, W * B, scale, loss));
+  return SR_OK;
+  };
+
+  // A window of the own forward pass is some hundreds of short dependent launches, none of which reads host
+  // memory: captured once into a graph and replayed while the call names the same buffers.  The frame path
+  // brings its own graphs and host-side frame counter and stays outside.
+  if (!own_forward || !g->use_hipgraph) return enqueue();
+  std::vector<const void*> key;
+  key.push_back((const void*)(uintptr_t)W);
+  key.push_back((const void*)(uintptr_t)out_node);
+  key.push_back(A);
+  for (size_t k = 0; k < g->inputs.size(); ++k) key.push_back(inputs[k]);
+  for (int v = 0; v < N; ++v) key.push_back(masks ? (const void*)masks[v] : nullptr);
+  key.push_back(labels);
+  key.push_back(loss);
+  for (int e = 0; e < g->n_edges; ++e) key.push_back(dtheta[e]);
+  for (int v = 0; v < N; ++v) key.push_back(dbias ? (const void*)dbias[v] : nullptr);
+  if (!g->train_exec || key != g->train_key) {
+    drop_train_graph(g);
+    SR_HIP(g, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+    const sr_status st = enqueue();
+    const hipError_t e = hipStreamEndCapture(s, &g->train_graph);
+    if (st != SR_OK || e != hipSuccess) {
+      if (g->train_graph) hipGraphDestroy(g->train_graph);
+      g->train_graph = nullptr;
+      if (st != SR_OK) return st;
+      SR_HIP(g, e);
+    }
+    SR_HIP(g, hipGraphInstantiate(&g->train_exec, g->train_graph, nullptr, nullptr, 0));
+    g->train_key = key;
+  }
+  SR_HIP(g, hipGraphLaunch(g->train_exec, s));
   return SR_OK;
 }
 
