@@ -208,10 +208,11 @@ __global__ void sr_gap_spread_kernel(const float* __restrict__ dmean, int B, int
 //                             A = x at the source pixel that tap pairs with m, B = theta[tap][ci][j]
 //   weight gradient (MODE 1): i = (tap, ci), j = co, r = output pixel m = (b, ho, wo);
 //                             A = x at the source pixel that tap pairs with m, B = dy[m][j]
-// One workgroup (4 waves) owns a 128 x 128 tile of C, a wave 64 x 64 of it (2 x 2 MFMA tiles); the
-// reduction runs in steps of 16 through LDS (A and B tiles stored r-major, so a wave's operand read is
-// 32 consecutive floats); blockIdx.z cuts the reduction into slices (weight gradient: partial sums
-// that a second kernel adds in slice order).  Every sum has a fixed order: same call, same bits.
+// One workgroup (4 waves) owns a TI x TJ tile of C; the waves lie WJN along j and 4 / WJN along i, each
+// with MI x MJ MFMA tiles of 32 x 32.  The reduction runs in steps of 16 through LDS (A and B tiles stored
+// r-major, so a wave's operand read is 32 consecutive floats); blockIdx.z cuts the reduction into slices
+// (weight gradient: partial sums that a second kernel adds in slice order).  Every sum has a fixed order
+// whatever the tile shape: same call, same bits.
 typedef float sr_f32x16 __attribute__((ext_vector_type(16)));
 
 // n / d for n < 2^31 with the pair the host made for d (Granlund & Montgomery: l = ceil(log2 d),
@@ -219,18 +220,21 @@ typedef float sr_f32x16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ int sr_fdiv(int n, uint32_t mul, uint32_t sh) {
   return (int)((__umulhi((uint32_t)n, mul) + (uint32_t)n) >> sh);
 }
-#define SR_GT 128   // tile edge
+#define SR_GT 128   // edge of the largest tile
 #define SR_GR 16    // reduction step
-#define SR_GP 132   // LDS row pitch in floats
 
-template <int MODE>
+template <int MODE, int TI, int TJ, int WJN>
 __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, const float* __restrict__ pa,
                                                               const float* __restrict__ pb, float* __restrict__ pc,
                                                               int I, int J, int R, int r_per_slice, int accumulate) {
-  __shared__ float As[SR_GR][SR_GP];
-  __shared__ float Bs[SR_GR][SR_GP];
+  constexpr int WIN = 4 / WJN;                                // waves along i
+  constexpr int MI = TI / (32 * WIN), MJ = TJ / (32 * WJN);   // MFMA tiles of a wave
+  constexpr int NA = TI / 16, NB = TJ / 16;                   // operand elements a thread gathers per step
+  static_assert(MI >= 1 && MJ >= 1 && MI * 32 * WIN == TI && MJ * 32 * WJN == TJ, "tile shape");
+  __shared__ float As[SR_GR][TI + 4];
+  __shared__ float Bs[SR_GR][TJ + 4];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int i0 = blockIdx.x * SR_GT, j0 = blockIdx.y * SR_GT;
+  const int i0 = blockIdx.x * TI, j0 = blockIdx.y * TJ;
   if (MODE == 0) {
     // blockIdx.z = phase (ph, pw) of the source pixels: a stride-s edge pairs a pixel only with the taps of its
     // own residues, so each phase is a contraction of its own (without the split all but 1/s^2 of the products
@@ -250,17 +254,17 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
   }
   const int r_begin = (MODE == 1) ? blockIdx.z * r_per_slice : 0;
   const int r_end = min(R, r_begin + r_per_slice);
-  const int wi = wave >> 1, wj = wave & 1;
+  const int wi = wave / WJN, wj = wave % WJN;
 
   // what does not change over the reduction: the rows / columns this thread gathers
-  // MODE 0: A and B are gathered r-fastest (r = t % 16, eight rows t / 16 + 16 n)
-  // MODE 1: A and B are gathered i- / j-fastest (i = t % 128, eight r values t / 128 + 2 n)
-  int ab[8], ah[8], aw[8];          // MODE 0: source pixel (b, h, w) of the thread's 8 A rows (b < 0: row past the end)
+  // MODE 0, 2: A is gathered r-fastest (r = t % 16, rows t / 16 + 16 n)
+  // MODE 1:    A and B are gathered i- / j-fastest (i = t % TI, r = t / TI + (256 / TI) n; B alike with TJ)
+  int ab[NA], ah[NA], aw[NA];       // MODE 0, 2: pixel (b, h, w) of the thread's A rows (b < 0: row past the end)
   int ati = 0, atj = 0, aci = 0;    // MODE 1: tap and channel of the thread's A row
   bool a_row_ok = false;
   if (MODE == 2) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
+    for (int n = 0; n < NA; ++n) {
       const int i = i0 + (t >> 4) + 16 * n;
       if (i < I) {   // output pixel: top-left corner of its window in the source
         aw[n] = (i % q.Wo) * q.stride - q.pad;
@@ -272,7 +276,7 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
     }
   } else if (MODE == 0) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
+    for (int n = 0; n < NA; ++n) {
       const int i = i0 + (t >> 4) + 16 * n;
       if (i < I) {   // pixel (hh, ww) of the phase grid
         aw[n] = (i % q.Wp) * q.stride + q.pw;
@@ -283,7 +287,7 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
       }
     }
   } else {
-    const int i = i0 + (t & 127);
+    const int i = i0 + (t % TI);
     a_row_ok = i < I;
     aci = i % q.Cin;
     const int tap = i / q.Cin;
@@ -291,32 +295,36 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
     ati = tap / q.kw;
   }
 
-  sr_f32x16 acc[2][2];
+  sr_f32x16 acc[MI][MJ];
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < MI; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < MJ; ++y)
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
 
   // stride 1, 2, 4 without divisions
   const int lgs = (q.stride == 1) ? 0 : (q.stride == 2 ? 1 : (q.stride == 4 ? 2 : -1));
-  float va[8], vb[8];
-  // the operands of one reduction step, from global memory into registers
+  float va[NA], vb[NB];
+  // the operands of one reduction step, from global memory into registers; every load is unconditional (element 0
+  // when out of range): no branch per element
   auto gather = [&](int rs) {
     if (MODE == 2) {
       const int r = rs + (t & 15);
       const bool r_ok = r < r_end;
       const int tap = sr_fdiv(r, q.mul_cout, q.sh_cout), ci = r - tap * q.Cin;   // the divisor pair is Cin's here
       const int tj = tap % q.kw, ti = tap / q.kw;
-      const int jb = j0 + (t & 127);
 #pragma unroll
-      for (int n = 0; n < 8; ++n) {
+      for (int n = 0; n < NA; ++n) {
         const int hi = ah[n] + ti, wi2 = aw[n] + tj;
         const bool ok = r_ok && ab[n] >= 0 && hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W;
         const float v = pa[ok ? (((size_t)ab[n] * q.H + hi) * q.W + wi2) * q.Cin + ci : 0];
         va[n] = ok ? v : 0.f;
-        const int rb = rs + (t >> 7) + 2 * n;
+      }
+      const int jb = j0 + (t % TJ);
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        const int rb = rs + t / TJ + (256 / TJ) * n;
         const bool okb = rb < r_end && jb < J;
         const float u = pb[okb ? (size_t)rb * q.Cout + jb : 0];
         vb[n] = okb ? u : 0.f;
@@ -328,7 +336,7 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
       const int tj = q.tj0 + (vt % q.ntj) * q.stride, ti = q.ti0 + (vt / q.ntj) * q.stride;
       const int tap = ti * q.kw + tj;
 #pragma unroll
-      for (int n = 0; n < 8; ++n) {
+      for (int n = 0; n < NA; ++n) {
         float v = 0.f;
         if (r_ok && ab[n] >= 0) {
           // the phase's taps pair with its pixels exactly: (h + pad - ti) is a multiple of the stride
@@ -336,28 +344,26 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
           int ho, wo;
           if (lgs >= 0) { ho = th >> lgs; wo = tw >> lgs; }
           else { ho = th / q.stride; wo = tw / q.stride; }
-          // the load is unconditional (element 0 when out of range): no branch per element
           const bool ok = th >= 0 && tw >= 0 && ho < q.Ho && wo < q.Wo;
           const size_t at = ok ? (((size_t)ab[n] * q.Ho + ho) * q.Wo + wo) * q.Cout + co : 0;
           v = pa[at];
           v = ok ? v : 0.f;
         }
         va[n] = v;
+      }
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
         const int j = j0 + (t >> 4) + 16 * n;
-        {
-          const bool okb = r_ok && j < J;
-          const float u = pb[okb ? ((size_t)tap * q.Cin + j) * q.Cout + co : 0];
-          vb[n] = okb ? u : 0.f;
-        }
+        const bool okb = r_ok && j < J;
+        const float u = pb[okb ? ((size_t)tap * q.Cin + j) * q.Cout + co : 0];
+        vb[n] = okb ? u : 0.f;
       }
     } else {
-      const int j = j0 + (t & 127);
-      const int r0 = rs + (t >> 7);
 #pragma unroll
-      for (int n = 0; n < 8; ++n) {
-        const int r = r0 + 2 * n;
+      for (int n = 0; n < NA; ++n) {
+        const int r = rs + t / TI + (256 / TI) * n;
         const bool r_ok = r < r_end;
-        // output pixel (b, ho, wo) of r, without divisions; unconditional loads (element 0 when out of range)
+        // output pixel (b, ho, wo) of r, without divisions
         const int b = sr_fdiv(r, q.mul_howo, q.sh_howo);
         const int rem = r - b * (q.Ho * q.Wo);
         const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo);
@@ -366,7 +372,12 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
         const bool oka = r_ok && a_row_ok && hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W;
         const float v = pa[oka ? (((size_t)b * q.H + hi) * q.W + wi2) * q.Cin + aci : 0];
         va[n] = oka ? v : 0.f;
-        const bool okb = r_ok && j < J;
+      }
+      const int j = j0 + (t % TJ);
+#pragma unroll
+      for (int n = 0; n < NB; ++n) {
+        const int r = rs + t / TJ + (256 / TJ) * n;
+        const bool okb = r < r_end && j < J;
         const float u = pb[okb ? (size_t)r * q.Cout + j : 0];
         vb[n] = okb ? u : 0.f;
       }
@@ -376,18 +387,19 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
   if (r_begin < r_end) gather(r_begin);
   for (int rs = r_begin; rs < r_end; rs += SR_GR) {
     __syncthreads();   // the previous step's operand reads are done
+    if (MODE == 1) {
 #pragma unroll
-    for (int n = 0; n < 8; ++n) {
-      if (MODE == 2) {
-        As[t & 15][(t >> 4) + 16 * n] = va[n];
-        Bs[(t >> 7) + 2 * n][t & 127] = vb[n];
-      } else if (MODE == 0) {
-        As[t & 15][(t >> 4) + 16 * n] = va[n];
-        Bs[t & 15][(t >> 4) + 16 * n] = vb[n];
-      } else {
-        As[(t >> 7) + 2 * n][t & 127] = va[n];
-        Bs[(t >> 7) + 2 * n][t & 127] = vb[n];
-      }
+      for (int n = 0; n < NA; ++n) As[t / TI + (256 / TI) * n][t % TI] = va[n];
+    } else {
+#pragma unroll
+      for (int n = 0; n < NA; ++n) As[t & 15][(t >> 4) + 16 * n] = va[n];
+    }
+    if (MODE == 0) {
+#pragma unroll
+      for (int n = 0; n < NB; ++n) Bs[t & 15][(t >> 4) + 16 * n] = vb[n];
+    } else {
+#pragma unroll
+      for (int n = 0; n < NB; ++n) Bs[t / TJ + (256 / TJ) * n][t % TJ] = vb[n];
     }
     __syncthreads();
     // the next step's loads are in flight while this step's products run
@@ -395,24 +407,27 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
 #pragma unroll
     for (int kk = 0; kk < SR_GR / 2; ++kk) {
       const int rr = 2 * kk + (lane >> 5);
-      const float a0 = As[rr][wi * 64 + (lane & 31)], a1 = As[rr][wi * 64 + 32 + (lane & 31)];
-      const float b0 = Bs[rr][wj * 64 + (lane & 31)], b1 = Bs[rr][wj * 64 + 32 + (lane & 31)];
-      acc[0][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b0, acc[0][0], 0, 0, 0);
-      acc[0][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a0, b1, acc[0][1], 0, 0, 0);
-      acc[1][0] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b0, acc[1][0], 0, 0, 0);
-      acc[1][1] = __builtin_amdgcn_mfma_f32_32x32x2f32(a1, b1, acc[1][1], 0, 0, 0);
+      float a[MI], b[MJ];
+#pragma unroll
+      for (int x = 0; x < MI; ++x) a[x] = As[rr][wi * 32 * MI + 32 * x + (lane & 31)];
+#pragma unroll
+      for (int y = 0; y < MJ; ++y) b[y] = Bs[rr][wj * 32 * MJ + 32 * y + (lane & 31)];
+#pragma unroll
+      for (int x = 0; x < MI; ++x)
+#pragma unroll
+        for (int y = 0; y < MJ; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
     }
   }
   // register v of lane l holds row 8 * (v / 4) + 4 * (l / 32) + v % 4 (of the A operand's 32), column l % 32
   float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
 #pragma unroll
-  for (int x = 0; x < 2; ++x)
+  for (int x = 0; x < MI; ++x)
 #pragma unroll
-    for (int y = 0; y < 2; ++y)
+    for (int y = 0; y < MJ; ++y)
 #pragma unroll
       for (int v = 0; v < 16; ++v) {
-        const int i = i0 + wi * 64 + x * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int j = j0 + wj * 64 + y * 32 + (lane & 31);
+        const int i = i0 + wi * 32 * MI + x * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int j = j0 + wj * 32 * MJ + y * 32 + (lane & 31);
         if (i < I && j < J) {
           size_t row = (size_t)i;
           if (MODE == 0) {   // row of the phase grid -> source pixel
@@ -578,6 +593,36 @@ static SrConvGeom sr_with_divisors(const SrConvGeom& q) {
   return p;
 }
 
+// Tile shape of a contraction with I rows and J columns in `planes` grid planes: the narrowest column tile that
+// holds J, then the tallest row tile that still gives the chip about two workgroups per compute unit (a launch
+// of few tall tiles is a few long dependent chains on an otherwise idle chip)
+struct SrTileShape { int ti, tj, wjn; };
+static SrTileShape sr_pick_tile(long long I, long long J, long long planes) {
+  static const SrTileShape wide[] = {{128, 128, 2}, {64, 64, 2}}, mid[] = {{128, 64, 2}, {64, 64, 2}},
+                           slim[] = {{256, 32, 1}, {128, 32, 1}};
+  const SrTileShape* c = J <= 32 ? slim : (J <= 64 ? mid : wide);
+  const long long first = (I + c[0].ti - 1) / c[0].ti * ((J + c[0].tj - 1) / c[0].tj) * planes;
+  return first >= 512 ? c[0] : c[1];
+}
+template <int MODE>
+static hipError_t sr_launch_gemm(hipStream_t s, SrTileShape ts, int planes, const SrConvGeom& q, const float* pa,
+                                 const float* pb, float* pc, int I, int J, int R, int per, int accumulate) {
+  const dim3 grid((I + ts.ti - 1) / ts.ti, (J + ts.tj - 1) / ts.tj, planes);
+#define SR_GEMM_CASE(TI, TJ, WJN)                                                                                    \
+  if (ts.ti == TI && ts.tj == TJ && ts.wjn == WJN) {                                                                 \
+    hipLaunchKernelGGL((sr_conv_gemm_kernel<MODE, TI, TJ, WJN>), grid, dim3(256), 0, s, q, pa, pb, pc, I, J, R, per, \
+                       accumulate);                                                                                  \
+    return hipGetLastError();                                                                                        \
+  }
+  SR_GEMM_CASE(128, 128, 2)
+  SR_GEMM_CASE(128, 64, 2)
+  SR_GEMM_CASE(64, 64, 2)
+  SR_GEMM_CASE(256, 32, 1)
+  SR_GEMM_CASE(128, 32, 1)
+#undef SR_GEMM_CASE
+  return hipErrorInvalidValue;
+}
+
 // Which contractions go to the tiled matrix-core kernel: those with enough multiply-adds whose 128 x 128 tiles are
 // reasonably full and numerous (else the one-thread-per-output kernels, which spread over the chip whatever the shape)
 static bool sr_train_big(const SrConvGeom& q) {
@@ -604,9 +649,8 @@ hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta
     // grid z: the stride^2 phases of the source pixels; x is sized for phase (0, 0), which has the most pixels
     const int Hp = (q.H + q.stride - 1) / q.stride, Wp = (q.W + q.stride - 1) / q.stride;
     const int I = q.B * Hp * Wp, J = q.Cin;
-    hipLaunchKernelGGL(sr_conv_gemm_kernel<0>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, q.stride * q.stride),
-                       dim3(256), 0, s, sr_with_divisors(q), dy, theta, dx, I, J, 0, 0, accumulate);
-    return hipGetLastError();
+    const int planes = q.stride * q.stride;
+    return sr_launch_gemm<0>(s, sr_pick_tile(I, J, planes), planes, sr_with_divisors(q), dy, theta, dx, I, J, 0, 0, accumulate);
   }
   hipLaunchKernelGGL(sr_dgrad_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, q, theta, dy, dx, accumulate);
   return hipGetLastError();
@@ -624,9 +668,7 @@ hipError_t sr_train_fwd(hipStream_t s, const SrConvGeom& q, const float* x, cons
     SrConvGeom p = q;
     sr_fastdiv((uint32_t)q.Cin, &p.mul_cout, &p.sh_cout);   // the forward decodes r = (tap, ci): its divisor is Cin
     const int I = q.B * q.Ho * q.Wo, J = q.Cout, R = q.kh * q.kw * q.Cin;
-    hipLaunchKernelGGL(sr_conv_gemm_kernel<2>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, 1), dim3(256), 0, s,
-                       p, x, theta, y, I, J, R, R, accumulate);
-    return hipGetLastError();
+    return sr_launch_gemm<2>(s, sr_pick_tile(I, J, 1), 1, p, x, theta, y, I, J, R, R, accumulate);
   }
   const long long n = (long long)q.B * q.Ho * q.Wo * q.Cout;
   if (n <= 65536 && (long long)q.kh * q.kw * q.Cin >= 256) {   // few outputs, long sums: a wave per output
@@ -673,9 +715,7 @@ hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, co
     const int I = q.kh * q.kw * q.Cin, J = q.Cout;
     const int per = ((M + slices - 1) / slices + SR_GR - 1) / SR_GR * SR_GR;
     const int used = (M + per - 1) / per;
-    hipLaunchKernelGGL(sr_conv_gemm_kernel<1>, dim3((I + SR_GT - 1) / SR_GT, (J + SR_GT - 1) / SR_GT, used), dim3(256), 0, s,
-                       sr_with_divisors(q), x, dy, part, I, J, M, per, 0);
-    hipError_t e = hipGetLastError();
+    hipError_t e = sr_launch_gemm<1>(s, sr_pick_tile(I, J, used), used, sr_with_divisors(q), x, dy, part, I, J, M, per, 0);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 256)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);
     return hipGetLastError();
