@@ -15,9 +15,9 @@ struct SrConvGeom {   // y[b][ho][wo][co] = sum x[b][ho*stride + i - pad][wo*str
   // h = hh*stride + ph, w = ww*stride + pw of a Hp x Wp grid, which pair only with the taps i = ti0 + a*stride,
   // j = tj0 + c*stride (a < nti, c < ntj).  Stride 1: one phase, the whole image, all taps.
   int ph, pw, Hp, Wp, ti0, tj0, nti, ntj;
-  // divisions by Wo, Ho*Wo and Cout as multiply-high, add, shift (exact for dividends below 2^31); filled by
-  // the launchers of the tiled kernels
-  uint32_t mul_wo, sh_wo, mul_howo, sh_howo, mul_cout, sh_cout;
+  // divisions by Wo, Ho*Wo, Cout, Cin and kw as multiply-high, add, shift (exact for dividends below 2^31);
+  // filled by the launchers of the tiled kernels
+  uint32_t mul_wo, sh_wo, mul_howo, sh_howo, mul_cout, sh_cout, mul_cin, sh_cin, mul_kw, sh_kw;
 };
 #define SR_TRAIN_TILED_MIN_MACS 4.0e6   // smaller contractions stay on the one-thread-per-output kernels
 #define SR_TRAIN_MAX_SLICES 64   // a weight gradient's pixel sum is cut into at most this many partial sums

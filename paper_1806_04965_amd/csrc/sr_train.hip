@@ -220,6 +220,12 @@ typedef float sr_f32x16 __attribute__((ext_vector_type(16)));
 __device__ __forceinline__ int sr_fdiv(int n, uint32_t mul, uint32_t sh) {
   return (int)((__umulhi((uint32_t)n, mul) + (uint32_t)n) >> sh);
 }
+// the pair for d >= 1, made on the device (a phase's own divisors)
+__device__ __forceinline__ void sr_fdiv_make(uint32_t d, uint32_t* mul, uint32_t* sh) {
+  const uint32_t l = (d <= 1) ? 0u : 32u - (uint32_t)__clz((int)(d - 1));
+  *mul = (uint32_t)((((1ull << l) - d) << 32) / d + 1);
+  *sh = l;
+}
 #define SR_GT 128   // edge of the largest tile
 #define SR_GR 16    // reduction step
 
@@ -256,43 +262,63 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
   const int r_end = min(R, r_begin + r_per_slice);
   const int wi = wave / WJN, wj = wave % WJN;
 
-  // what does not change over the reduction: the rows / columns this thread gathers
+  // Operand addresses are byte offsets in 32 bits (the launchers send only tensors below 2^30 bytes here), split
+  // into a part fixed per thread and row, made once, and a part per reduction step, made once per thread and
+  // step; an element costs one add for its address and two compares for its bounds.  Every load is unconditional
+  // (offset 0 when out of range): no branch per element.
+  constexpr int FAR = 1 << 20;      // added to a coordinate, puts it out of every range
   // MODE 0, 2: A is gathered r-fastest (r = t % 16, rows t / 16 + 16 n)
   // MODE 1:    A and B are gathered i- / j-fastest (i = t % TI, r = t / TI + (256 / TI) n; B alike with TJ)
-  int ab[NA], ah[NA], aw[NA];       // MODE 0, 2: pixel (b, h, w) of the thread's A rows (b < 0: row past the end)
-  int ati = 0, atj = 0, aci = 0;    // MODE 1: tap and channel of the thread's A row
-  bool a_row_ok = false;
+  int ah[NA], aw[NA], aoff[NA];     // MODE 0, 2: per row, the coordinates the taps move and the byte offset at tap 0
+  int ati = 0, atj = 0, a1off = 0;  // MODE 1: tap and byte offset of the thread's A row
+  uint32_t mul_wp = 0, sh_wp = 0, mul_hpwp = 0, sh_hpwp = 0, mul_ntj = 0, sh_ntj = 0;   // MODE 0: the phase's divisors
   if (MODE == 2) {
 #pragma unroll
     for (int n = 0; n < NA; ++n) {
       const int i = i0 + (t >> 4) + 16 * n;
-      if (i < I) {   // output pixel: top-left corner of its window in the source
-        aw[n] = (i % q.Wo) * q.stride - q.pad;
-        ah[n] = ((i / q.Wo) % q.Ho) * q.stride - q.pad;
-        ab[n] = i / (q.Wo * q.Ho);
-      } else {
-        ab[n] = -1; ah[n] = 0; aw[n] = 0;
-      }
+      const int b = sr_fdiv(i, q.mul_howo, q.sh_howo), rem = i - b * (q.Ho * q.Wo);
+      const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo), wo = rem - ho * q.Wo;
+      // top-left corner of the output pixel's window in the source
+      ah[n] = (i < I) ? ho * q.stride - q.pad : FAR;
+      aw[n] = wo * q.stride - q.pad;
+      aoff[n] = (((b * q.H + ho * q.stride - q.pad) * q.W + aw[n]) * q.Cin) * 4;
     }
   } else if (MODE == 0) {
+    const int lgs = (q.stride == 1) ? 0 : (q.stride == 2 ? 1 : (q.stride == 4 ? 2 : -1));   // strides 1, 2, 4 by shifts
+    sr_fdiv_make((uint32_t)max(q.Wp, 1), &mul_wp, &sh_wp);
+    sr_fdiv_make((uint32_t)max(q.Wp * q.Hp, 1), &mul_hpwp, &sh_hpwp);
+    sr_fdiv_make((uint32_t)max(q.ntj, 1), &mul_ntj, &sh_ntj);
 #pragma unroll
     for (int n = 0; n < NA; ++n) {
       const int i = i0 + (t >> 4) + 16 * n;
-      if (i < I) {   // pixel (hh, ww) of the phase grid
-        aw[n] = (i % q.Wp) * q.stride + q.pw;
-        ah[n] = ((i / q.Wp) % q.Hp) * q.stride + q.ph;
-        ab[n] = i / (q.Wp * q.Hp);
-      } else {
-        ab[n] = -1; ah[n] = 0; aw[n] = 0;
-      }
+      const int b = sr_fdiv(i, mul_hpwp, sh_hpwp), rem = i - b * (q.Wp * q.Hp);
+      const int hh = sr_fdiv(rem, mul_wp, sh_wp), ww = rem - hh * q.Wp;
+      // source pixel (hh*s + ph, ww*s + pw) pairs through the phase's tap (a, c) with output pixel (hq - a, wq - c):
+      // (h + pad - ti0) is a multiple of the stride and not negative
+      const int hn = hh * q.stride + q.ph + q.pad - q.ti0, wn = ww * q.stride + q.pw + q.pad - q.tj0;
+      const int hq = lgs >= 0 ? hn >> lgs : hn / q.stride, wq = lgs >= 0 ? wn >> lgs : wn / q.stride;
+      ah[n] = (i < I) ? hq : -FAR;
+      aw[n] = wq;
+      aoff[n] = (((b * q.Ho + hq) * q.Wo + wq) * q.Cout) * 4;
     }
   } else {
     const int i = i0 + (t % TI);
-    a_row_ok = i < I;
-    aci = i % q.Cin;
-    const int tap = i / q.Cin;
-    atj = tap % q.kw;
-    ati = tap / q.kw;
+    const int tap = sr_fdiv(i, q.mul_cin, q.sh_cin), ci = i - tap * q.Cin;
+    ati = sr_fdiv(tap, q.mul_kw, q.sh_kw);
+    atj = tap - ati * q.kw;
+    a1off = (((ati * q.W + atj) * q.Cin) + ci) * 4;
+    if (i >= I) ati = FAR;
+  }
+  // B: byte offset of the thread's first element at reduction index 0, and whether its column exists
+  int boff = 0;
+  bool b_col_ok = false;
+  if (MODE == 0) {
+    const int j = j0 + (t >> 4);
+    boff = j * q.Cout * 4;                      // theta[tap][j][co]: + 16 n Cout per element, + (tap Cin Cout + co) per step
+  } else {
+    const int j = j0 + (t % TJ);
+    b_col_ok = j < J;
+    boff = ((t / TJ) * q.Cout + j) * 4;         // [r][j] with Cout columns: + (256 / TJ) n Cout per element, + rs Cout per step
   }
 
   sr_f32x16 acc[MI][MJ];
@@ -303,82 +329,71 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
 
-  // stride 1, 2, 4 without divisions
-  const int lgs = (q.stride == 1) ? 0 : (q.stride == 2 ? 1 : (q.stride == 4 ? 2 : -1));
+  auto at = [](const float* base, int byte_off) { return *(const float*)((const char*)base + (uint32_t)byte_off); };
   float va[NA], vb[NB];
-  // the operands of one reduction step, from global memory into registers; every load is unconditional (element 0
-  // when out of range): no branch per element
+  // the operands of one reduction step, from global memory into registers
   auto gather = [&](int rs) {
     if (MODE == 2) {
       const int r = rs + (t & 15);
-      const bool r_ok = r < r_end;
-      const int tap = sr_fdiv(r, q.mul_cout, q.sh_cout), ci = r - tap * q.Cin;   // the divisor pair is Cin's here
-      const int tj = tap % q.kw, ti = tap / q.kw;
+      const int tap = sr_fdiv(r, q.mul_cin, q.sh_cin), ci = r - tap * q.Cin;
+      int ti = sr_fdiv(tap, q.mul_kw, q.sh_kw);
+      const int tj = tap - ti * q.kw;
+      const int toff = ((ti * q.W + tj) * q.Cin + ci) * 4;
+      if (r >= r_end) ti = FAR;
 #pragma unroll
       for (int n = 0; n < NA; ++n) {
-        const int hi = ah[n] + ti, wi2 = aw[n] + tj;
-        const bool ok = r_ok && ab[n] >= 0 && hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W;
-        const float v = pa[ok ? (((size_t)ab[n] * q.H + hi) * q.W + wi2) * q.Cin + ci : 0];
+        const bool ok = (unsigned)(ah[n] + ti) < (unsigned)q.H && (unsigned)(aw[n] + tj) < (unsigned)q.W;
+        const float v = at(pa, ok ? aoff[n] + toff : 0);
         va[n] = ok ? v : 0.f;
       }
-      const int jb = j0 + (t % TJ);
+      const int sb = boff + rs * q.Cout * 4;
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
-        const int rb = rs + t / TJ + (256 / TJ) * n;
-        const bool okb = rb < r_end && jb < J;
-        const float u = pb[okb ? (size_t)rb * q.Cout + jb : 0];
+        const bool okb = b_col_ok && rs + t / TJ + (256 / TJ) * n < r_end;
+        const float u = at(pb, okb ? sb + n * (256 / TJ) * q.Cout * 4 : 0);
         vb[n] = okb ? u : 0.f;
       }
     } else if (MODE == 0) {
       const int r = rs + (t & 15);
       const bool r_ok = r < r_end;
       const int vt = sr_fdiv(r, q.mul_cout, q.sh_cout), co = r - vt * q.Cout;   // vt: index among the phase's taps
-      const int tj = q.tj0 + (vt % q.ntj) * q.stride, ti = q.ti0 + (vt / q.ntj) * q.stride;
-      const int tap = ti * q.kw + tj;
+      int vi = sr_fdiv(vt, mul_ntj, sh_ntj);
+      const int vj = vt - vi * q.ntj;
+      const int tap = (q.ti0 + vi * q.stride) * q.kw + q.tj0 + vj * q.stride;
+      const int toff = (co - (vi * q.Wo + vj) * q.Cout) * 4;
+      if (!r_ok) vi = 2 * FAR;
 #pragma unroll
       for (int n = 0; n < NA; ++n) {
-        float v = 0.f;
-        if (r_ok && ab[n] >= 0) {
-          // the phase's taps pair with its pixels exactly: (h + pad - ti) is a multiple of the stride
-          const int th = ah[n] + q.pad - ti, tw = aw[n] + q.pad - tj;
-          int ho, wo;
-          if (lgs >= 0) { ho = th >> lgs; wo = tw >> lgs; }
-          else { ho = th / q.stride; wo = tw / q.stride; }
-          const bool ok = th >= 0 && tw >= 0 && ho < q.Ho && wo < q.Wo;
-          const size_t at = ok ? (((size_t)ab[n] * q.Ho + ho) * q.Wo + wo) * q.Cout + co : 0;
-          v = pa[at];
-          v = ok ? v : 0.f;
-        }
-        va[n] = v;
+        const bool ok = (unsigned)(ah[n] - vi) < (unsigned)q.Ho && (unsigned)(aw[n] - vj) < (unsigned)q.Wo;
+        const float v = at(pa, ok ? aoff[n] + toff : 0);
+        va[n] = ok ? v : 0.f;
       }
+      const int sb = boff + (tap * q.Cin * q.Cout + co) * 4;
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
-        const int j = j0 + (t >> 4) + 16 * n;
-        const bool okb = r_ok && j < J;
-        const float u = pb[okb ? ((size_t)tap * q.Cin + j) * q.Cout + co : 0];
+        const bool okb = r_ok && j0 + (t >> 4) + 16 * n < J;
+        const float u = at(pb, okb ? sb + n * 16 * q.Cout * 4 : 0);
         vb[n] = okb ? u : 0.f;
       }
     } else {
+      // a wave's threads share their reduction indices: the pixel's decoding runs on the scalar unit
+      const int rl = __builtin_amdgcn_readfirstlane(rs + t / TI);
 #pragma unroll
       for (int n = 0; n < NA; ++n) {
-        const int r = rs + t / TI + (256 / TI) * n;
-        const bool r_ok = r < r_end;
-        // output pixel (b, ho, wo) of r, without divisions
-        const int b = sr_fdiv(r, q.mul_howo, q.sh_howo);
-        const int rem = r - b * (q.Ho * q.Wo);
-        const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo);
-        const int wo = rem - ho * q.Wo;
-        const int hi = ho * q.stride + ati - q.pad, wi2 = wo * q.stride + atj - q.pad;
-        const bool oka = r_ok && a_row_ok && hi >= 0 && hi < q.H && wi2 >= 0 && wi2 < q.W;
-        const float v = pa[oka ? (((size_t)b * q.H + hi) * q.W + wi2) * q.Cin + aci : 0];
-        va[n] = oka ? v : 0.f;
+        const int r = rl + (256 / TI) * n;
+        const int b = sr_fdiv(r, q.mul_howo, q.sh_howo), rem = r - b * (q.Ho * q.Wo);
+        const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo), wo = rem - ho * q.Wo;
+        const int h0 = (r < r_end) ? ho * q.stride - q.pad : FAR, w0 = wo * q.stride - q.pad;
+        const int sbase = (((b * q.H + ho * q.stride - q.pad) * q.W + w0) * q.Cin) * 4;
+        const bool ok = (unsigned)(h0 + ati) < (unsigned)q.H && (unsigned)(w0 + atj) < (unsigned)q.W;
+        const float v = at(pa, ok ? sbase + a1off : 0);
+        va[n] = ok ? v : 0.f;
       }
-      const int j = j0 + (t % TJ);
+      const int sb = boff + rs * q.Cout * 4;
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
-        const int r = rs + t / TJ + (256 / TJ) * n;
-        const bool okb = r < r_end && j < J;
-        const float u = pb[okb ? (size_t)r * q.Cout + j : 0];
+        const bool okb = b_col_ok && rs + t / TJ + (256 / TJ) * n < r_end;
+        const float u = at(pb, okb ? sb + n * (256 / TJ) * q.Cout * 4 : 0);
         vb[n] = okb ? u : 0.f;
       }
     }
@@ -431,7 +446,8 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
         if (i < I && j < J) {
           size_t row = (size_t)i;
           if (MODE == 0) {   // row of the phase grid -> source pixel
-            const int ww = i % q.Wp, hh = (i / q.Wp) % q.Hp, b = i / (q.Wp * q.Hp);
+            const int b = sr_fdiv(i, mul_hpwp, sh_hpwp), rem = i - b * (q.Wp * q.Hp);
+            const int hh = sr_fdiv(rem, mul_wp, sh_wp), ww = rem - hh * q.Wp;
             row = ((size_t)b * q.H + hh * q.stride + q.ph) * q.W + ww * q.stride + q.pw;
           }
           float* dst = out + row * J + j;
@@ -590,6 +606,8 @@ static SrConvGeom sr_with_divisors(const SrConvGeom& q) {
   sr_fastdiv((uint32_t)q.Wo, &p.mul_wo, &p.sh_wo);
   sr_fastdiv((uint32_t)(q.Ho * q.Wo), &p.mul_howo, &p.sh_howo);
   sr_fastdiv((uint32_t)q.Cout, &p.mul_cout, &p.sh_cout);
+  sr_fastdiv((uint32_t)q.Cin, &p.mul_cin, &p.sh_cin);
+  sr_fastdiv((uint32_t)q.kw, &p.mul_kw, &p.sh_kw);
   return p;
 }
 
@@ -626,6 +644,11 @@ static hipError_t sr_launch_gemm(hipStream_t s, SrTileShape ts, int planes, cons
 // Which contractions go to the tiled matrix-core kernel: those with enough multiply-adds whose 128 x 128 tiles are
 // reasonably full and numerous (else the one-thread-per-output kernels, which spread over the chip whatever the shape)
 static bool sr_train_big(const SrConvGeom& q) {
+  // the tiled kernel addresses its operands by byte offsets in 32 bits, with room for a padding row either side
+  const double lim = (double)(1u << 30);
+  if (4.0 * q.B * q.H * q.W * q.Cin >= lim || 4.0 * q.B * q.Ho * q.Wo * q.Cout >= lim ||
+      4.0 * q.kh * q.kw * q.Cin * q.Cout >= lim)
+    return false;
   return (double)q.B * q.Ho * q.Wo * q.Cout * q.Cin * q.kh * q.kw >= SR_TRAIN_TILED_MIN_MACS;
 }
 static long long sr_wgrad_tiles(const SrConvGeom& q) {
@@ -665,8 +688,7 @@ int sr_train_fwd_is_tiled(const SrConvGeom& q) { return sr_fwd_tiled(q) ? 1 : 0;
 hipError_t sr_train_fwd(hipStream_t s, const SrConvGeom& q, const float* x, const float* theta, float* y,
                         int accumulate) {
   if (sr_fwd_tiled(q)) {
-    SrConvGeom p = q;
-    sr_fastdiv((uint32_t)q.Cin, &p.mul_cout, &p.sh_cout);   // the forward decodes r = (tap, ci): its divisor is Cin
+    const SrConvGeom p = sr_with_divisors(q);
     const int I = q.B * q.Ho * q.Wo, J = q.Cout, R = q.kh * q.kw * q.Cin;
     return sr_launch_gemm<2>(s, sr_pick_tile(I, J, 1), 1, p, x, theta, y, I, J, R, R, accumulate);
   }
