@@ -87,7 +87,13 @@ __global__ void sr_bias_grad_kernel(const float* __restrict__ d, int M, int C, i
   const int m1 = min(M, m0 + m_per_slice);
   float acc = 0.f;
   if (c < C)
-    for (int m = m0 + pl; m < m1; m += 4) acc += d[(size_t)m * C + c];
+    for (int m = m0 + pl; m < m1; m += 32) {   // eight loads in flight at a time, added in order
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (m + 4 * u < m1) ? d[(size_t)(m + 4 * u) * C + c] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
   lanes[pl][threadIdx.x & 63] = acc;
   __syncthreads();
   if (pl == 0 && c < C)
@@ -170,13 +176,25 @@ __global__ void sr_wgrad_kernel(SrConvGeom q, const float* __restrict__ x, const
   part[(size_t)blockIdx.y * nw + k] = acc;
 }
 
-// dst[k] += part[0][k] + part[1][k] + ... in slice order
+// dst[k] += the sum over the slices of part[s][k], in a fixed order: a workgroup takes 64 elements, four slice
+// lanes per element (each adds every fourth slice in order, eight loads in flight at a time; then the four in order)
 __global__ void sr_add_slices_kernel(const float* __restrict__ part, size_t n, int slices, float* __restrict__ dst) {
-  const size_t k = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (k >= n) return;
+  __shared__ float lanes[4][64];
+  const size_t k = (size_t)blockIdx.x * 64 + (threadIdx.x & 63);
+  const int pl = threadIdx.x >> 6;
   float acc = 0.f;
-  for (int s = 0; s < slices; ++s) acc += part[(size_t)s * n + k];
-  dst[k] += acc;
+  if (k < n)
+    for (int s0 = pl; s0 < slices; s0 += 32) {
+      float v[8];
+#pragma unroll
+      for (int u = 0; u < 8; ++u) v[u] = (s0 + 4 * u < slices) ? part[(size_t)(s0 + 4 * u) * n + k] : 0.f;
+#pragma unroll
+      for (int u = 0; u < 8; ++u) acc += v[u];
+    }
+  lanes[pl][threadIdx.x & 63] = acc;
+  __syncthreads();
+  if (pl == 0 && k < n)
+    dst[k] += ((lanes[0][threadIdx.x] + lanes[1][threadIdx.x]) + lanes[2][threadIdx.x]) + lanes[3][threadIdx.x];
 }
 
 // mean over the pixels of one image: out[b][c]
@@ -570,7 +588,7 @@ hipError_t sr_train_act_grad(hipStream_t s, float* d, const float* x, const floa
 }
 
 int sr_train_bias_slices(int M) {
-  const int want = (M + 1023) / 1024;   // about a thousand pixels per slice
+  const int want = (M + 255) / 256;   // 256 pixels per slice or more
   return want < 1 ? 1 : (want > SR_TRAIN_MAX_SLICES ? SR_TRAIN_MAX_SLICES : want);
 }
 
@@ -585,7 +603,7 @@ hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float
   hipLaunchKernelGGL(sr_bias_grad_kernel, dim3((C + 63) / 64, used), dim3(256), 0, s, d, M, C, per, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(C, 256)), dim3(256), 0, s, part, (size_t)C, used, db);
+  hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(C, 64)), dim3(256), 0, s, part, (size_t)C, used, db);
   return hipGetLastError();
 }
 
@@ -612,15 +630,16 @@ static SrConvGeom sr_with_divisors(const SrConvGeom& q) {
 }
 
 // Tile shape of a contraction with I rows and J columns in `planes` grid planes: the narrowest column tile that
-// holds J, then the tallest row tile that still gives the chip about two workgroups per compute unit (a launch
-// of few tall tiles is a few long dependent chains on an otherwise idle chip)
+// holds J, then the taller row tile only where the launch still has some thousands of workgroups (a launch of few
+// tall tiles is a few long dependent chains on an otherwise idle chip; on the measured windows the smaller tile
+// was the faster or equal one for every launch below that)
 struct SrTileShape { int ti, tj, wjn; };
 static SrTileShape sr_pick_tile(long long I, long long J, long long planes) {
   static const SrTileShape wide[] = {{128, 128, 2}, {64, 64, 2}}, mid[] = {{128, 64, 2}, {64, 64, 2}},
                            slim[] = {{256, 32, 1}, {128, 32, 1}};
   const SrTileShape* c = J <= 32 ? slim : (J <= 64 ? mid : wide);
   const long long first = (I + c[0].ti - 1) / c[0].ti * ((J + c[0].tj - 1) / c[0].tj) * planes;
-  return first >= 512 ? c[0] : c[1];
+  return first >= 2048 ? c[0] : c[1];
 }
 template <int MODE>
 static hipError_t sr_launch_gemm(hipStream_t s, SrTileShape ts, int planes, const SrConvGeom& q, const float* pa,
@@ -739,7 +758,7 @@ hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, co
     const int used = (M + per - 1) / per;
     hipError_t e = sr_launch_gemm<1>(s, sr_pick_tile(I, J, used), used, sr_with_divisors(q), x, dy, part, I, J, M, per, 0);
     if (e != hipSuccess) return e;
-    hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 256)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);
+    hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 64)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);
     return hipGetLastError();
   }
   const int per = (M + slices - 1) / slices;
@@ -747,7 +766,7 @@ hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, co
   hipLaunchKernelGGL(sr_wgrad_kernel, dim3(grid_for(nw, 256), used), dim3(256), 0, s, q, x, dy, per, part);
   hipError_t e = hipGetLastError();
   if (e != hipSuccess) return e;
-  hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 256)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);
+  hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 64)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);
   return hipGetLastError();
 }
 
