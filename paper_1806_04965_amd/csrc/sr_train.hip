@@ -232,6 +232,7 @@ __global__ void sr_gap_spread_kernel(const float* __restrict__ dmean, int B, int
 // (weight gradient: partial sums that a second kernel adds in slice order).  Every sum has a fixed order
 // whatever the tile shape: same call, same bits.
 typedef float sr_f32x16 __attribute__((ext_vector_type(16)));
+__device__ const float sr_zero_word = 0.f;   // what an operand element outside its tensor reads
 
 // n / d for n < 2^31 with the pair the host made for d (Granlund & Montgomery: l = ceil(log2 d),
 // m = floor(2^32 (2^l - d) / d) + 1, q = (mulhi(m, n) + n) >> l; no overflow while n < 2^31)
@@ -282,8 +283,8 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
 
   // Operand addresses are byte offsets in 32 bits (the launchers send only tensors below 2^30 bytes here), split
   // into a part fixed per thread and row, made once, and a part per reduction step, made once per thread and
-  // step; an element costs one add for its address and two compares for its bounds.  Every load is unconditional
-  // (offset 0 when out of range): no branch per element.
+  // step; an element costs one add for its address and two compares for its bounds.  Every load is unconditional:
+  // no branch per element.
   constexpr int FAR = 1 << 20;      // added to a coordinate, puts it out of every range
   // MODE 0, 2: A is gathered r-fastest (r = t % 16, rows t / 16 + 16 n)
   // MODE 1:    A and B are gathered i- / j-fastest (i = t % TI, r = t / TI + (256 / TI) n; B alike with TJ)
@@ -347,10 +348,15 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
 #pragma unroll
       for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
 
-  auto at = [](const float* base, int byte_off) { return *(const float*)((const char*)base + (uint32_t)byte_off); };
-  float va[NA], vb[NB];
+  // an element out of range is read from a word that holds zero: no use of a loaded value before the step that
+  // stores it (a select after the load would wait for the load right where it was issued)
+  auto at = [](const float* base, bool ok, int byte_off) {
+    typedef const __attribute__((address_space(1))) float* global_ptr;   // both are global memory: say so
+    const global_ptr p = ok ? (global_ptr)((const char*)base + (uint32_t)byte_off) : (global_ptr)&sr_zero_word;
+    return *p;
+  };
   // the operands of one reduction step, from global memory into registers
-  auto gather = [&](int rs) {
+  auto gather = [&](int rs, float (&va)[NA], float (&vb)[NB]) {
     if (MODE == 2) {
       const int r = rs + (t & 15);
       const int tap = sr_fdiv(r, q.mul_cin, q.sh_cin), ci = r - tap * q.Cin;
@@ -361,15 +367,13 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
 #pragma unroll
       for (int n = 0; n < NA; ++n) {
         const bool ok = (unsigned)(ah[n] + ti) < (unsigned)q.H && (unsigned)(aw[n] + tj) < (unsigned)q.W;
-        const float v = at(pa, ok ? aoff[n] + toff : 0);
-        va[n] = ok ? v : 0.f;
+        va[n] = at(pa, ok, aoff[n] + toff);
       }
       const int sb = boff + rs * q.Cout * 4;
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
         const bool okb = b_col_ok && rs + t / TJ + (256 / TJ) * n < r_end;
-        const float u = at(pb, okb ? sb + n * (256 / TJ) * q.Cout * 4 : 0);
-        vb[n] = okb ? u : 0.f;
+        vb[n] = at(pb, okb, sb + n * (256 / TJ) * q.Cout * 4);
       }
     } else if (MODE == 0) {
       const int r = rs + (t & 15);
@@ -383,15 +387,13 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
 #pragma unroll
       for (int n = 0; n < NA; ++n) {
         const bool ok = (unsigned)(ah[n] - vi) < (unsigned)q.Ho && (unsigned)(aw[n] - vj) < (unsigned)q.Wo;
-        const float v = at(pa, ok ? aoff[n] + toff : 0);
-        va[n] = ok ? v : 0.f;
+        va[n] = at(pa, ok, aoff[n] + toff);
       }
       const int sb = boff + (tap * q.Cin * q.Cout + co) * 4;
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
         const bool okb = r_ok && j0 + (t >> 4) + 16 * n < J;
-        const float u = at(pb, okb ? sb + n * 16 * q.Cout * 4 : 0);
-        vb[n] = okb ? u : 0.f;
+        vb[n] = at(pb, okb, sb + n * 16 * q.Cout * 4);
       }
     } else {
       // a wave's threads share their reduction indices: the pixel's decoding runs on the scalar unit
@@ -404,21 +406,20 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
         const int h0 = (r < r_end) ? ho * q.stride - q.pad : FAR, w0 = wo * q.stride - q.pad;
         const int sbase = (((b * q.H + ho * q.stride - q.pad) * q.W + w0) * q.Cin) * 4;
         const bool ok = (unsigned)(h0 + ati) < (unsigned)q.H && (unsigned)(w0 + atj) < (unsigned)q.W;
-        const float v = at(pa, ok ? sbase + a1off : 0);
-        va[n] = ok ? v : 0.f;
+        va[n] = at(pa, ok, sbase + a1off);
       }
       const int sb = boff + rs * q.Cout * 4;
 #pragma unroll
       for (int n = 0; n < NB; ++n) {
         const bool okb = b_col_ok && rs + t / TJ + (256 / TJ) * n < r_end;
-        const float u = at(pb, okb ? sb + n * (256 / TJ) * q.Cout * 4 : 0);
-        vb[n] = okb ? u : 0.f;
+        vb[n] = at(pb, okb, sb + n * (256 / TJ) * q.Cout * 4);
       }
     }
   };
 
-  if (r_begin < r_end) gather(r_begin);
-  for (int rs = r_begin; rs < r_end; rs += SR_GR) {
+  // one reduction step from the register set that holds its operands; the set is then refilled with the operands
+  // of the step after the next, so that two steps' loads are in flight while a step's products run
+  auto step = [&](int rs, float (&va)[NA], float (&vb)[NB]) {
     __syncthreads();   // the previous step's operand reads are done
     if (MODE == 1) {
 #pragma unroll
@@ -435,8 +436,9 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
       for (int n = 0; n < NB; ++n) Bs[t / TJ + (256 / TJ) * n][t % TJ] = vb[n];
     }
     __syncthreads();
-    // the next step's loads are in flight while this step's products run
-    if (rs + SR_GR < r_end) gather(rs + SR_GR);
+    // unconditional (past the end every element reads the zero word): the count of loads in flight is then the
+    // same at every step, and a step waits only for its own set
+    gather(rs + 2 * SR_GR, va, vb);
 #pragma unroll
     for (int kk = 0; kk < SR_GR / 2; ++kk) {
       const int rr = 2 * kk + (lane >> 5);
@@ -450,6 +452,13 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
 #pragma unroll
         for (int y = 0; y < MJ; ++y) acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x], b[y], acc[x][y], 0, 0, 0);
     }
+  };
+  float va0[NA], vb0[NB], va1[NA], vb1[NB];
+  gather(r_begin, va0, vb0);
+  gather(r_begin + SR_GR, va1, vb1);
+  for (int rs = r_begin; rs < r_end; rs += 2 * SR_GR) {   // every condition here is the same for the whole workgroup
+    step(rs, va0, vb0);
+    if (rs + SR_GR < r_end) step(rs + SR_GR, va1, vb1);
   }
   // register v of lane l holds row 8 * (v / 4) + 4 * (l / 32) + v % 4 (of the A operand's 32), column l % 32
   float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
