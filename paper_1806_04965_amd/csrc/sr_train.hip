@@ -455,11 +455,18 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
   };
   float va0[NA], vb0[NB], va1[NA], vb1[NB];
   gather(r_begin, va0, vb0);
+  // keep the two sets' loads apart in issue order, as they are inside the loop: a step's wait for its own set is
+  // counted from the order of issue
+  __builtin_amdgcn_sched_barrier(0);
   gather(r_begin + SR_GR, va1, vb1);
-  for (int rs = r_begin; rs < r_end; rs += 2 * SR_GR) {   // every condition here is the same for the whole workgroup
+  // pairs of steps, then the odd one: a loop with one way round, so that the order in which the two sets' loads
+  // were issued is the same whenever a step is reached (every condition here is the same for the whole workgroup)
+  int rs = r_begin;
+  for (; rs + SR_GR < r_end; rs += 2 * SR_GR) {
     step(rs, va0, vb0);
-    if (rs + SR_GR < r_end) step(rs + SR_GR, va1, vb1);
+    step(rs + SR_GR, va1, vb1);
   }
+  if (rs < r_end) step(rs, va0, vb0);
   // register v of lane l holds row 8 * (v / 4) + 4 * (l / 32) + v % 4 (of the A operand's 32), column l % 32
   float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
 #pragma unroll
