@@ -541,6 +541,50 @@ __global__ void sr_fwd_wide_kernel(SrConvGeom q, const float* __restrict__ x, co
   if (lane == 0) y[idx] = accumulate ? y[idx] + acc : acc;
 }
 
+// the same for a narrow target (at most 32 channels, long sums: the edge into the logits): one workgroup per output
+// pixel; a thread takes every 256th term of the (tap, ci) sum in order for up to 16 output channels at a time,
+// reading its source element once for all of them; then a fixed tree over the lanes and the four waves in order
+__global__ __launch_bounds__(256) void sr_fwd_pixel_kernel(SrConvGeom q, const float* __restrict__ x,
+                                                            const float* __restrict__ theta, float* __restrict__ y,
+                                                            int accumulate) {
+  __shared__ float part[4][16];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int m = blockIdx.x;   // output pixel (b, ho, wo)
+  const int b = sr_fdiv(m, q.mul_howo, q.sh_howo), rem = m - b * (q.Ho * q.Wo);
+  const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo), wo = rem - ho * q.Wo;
+  const int K = q.kh * q.kw * q.Cin;
+  for (int c0 = 0; c0 < q.Cout; c0 += 16) {
+    float acc[16];
+#pragma unroll
+    for (int c = 0; c < 16; ++c) acc[c] = 0.f;
+    for (int k = t; k < K; k += 256) {
+      const int tap = sr_fdiv(k, q.mul_cin, q.sh_cin), ci = k - tap * q.Cin;
+      const int ti = sr_fdiv(tap, q.mul_kw, q.sh_kw), tj = tap - ti * q.kw;
+      const int hi = ho * q.stride + ti - q.pad, wi = wo * q.stride + tj - q.pad;
+      if ((unsigned)hi < (unsigned)q.H && (unsigned)wi < (unsigned)q.W) {
+        const float xv = x[(((size_t)b * q.H + hi) * q.W + wi) * q.Cin + ci];
+        const float* row = theta + (size_t)k * q.Cout + c0;
+#pragma unroll
+        for (int c = 0; c < 16; ++c)
+          if (c0 + c < q.Cout) acc[c] += xv * row[c];
+      }
+    }
+#pragma unroll
+    for (int c = 0; c < 16; ++c) {
+      float v = acc[c];
+      for (int w = 32; w > 0; w >>= 1) v += __shfl_xor(v, w, 64);
+      if (lane == 0) part[wave][c] = v;
+    }
+    __syncthreads();
+    if (t < 16 && c0 + t < q.Cout) {
+      const float v = ((part[0][t] + part[1][t]) + part[2][t]) + part[3][t];
+      float* dst = y + (size_t)m * q.Cout + c0 + t;
+      *dst = accumulate ? *dst + v : v;
+    }
+    __syncthreads();
+  }
+}
+
 // nearest up-sampling of an edge's result into its target: dst[b][h][w][c] (+)= y[b][h / up][w / up][c]
 __global__ void sr_upsample_add_kernel(const float* __restrict__ y, int B, int H, int W, int C, int up,
                                        float* __restrict__ dst, int accumulate) {
@@ -609,7 +653,7 @@ int sr_train_bias_slices(int M) {
 }
 
 hipError_t sr_train_bias_grad(hipStream_t s, const float* d, int M, int C, float* part, float* db) {
-  if (M <= 16384) {
+  if (M <= 2048) {
     hipLaunchKernelGGL(sr_bias_grad_small_kernel, dim3(C), dim3(256), 0, s, d, M, C, db);
     return hipGetLastError();
   }
@@ -728,6 +772,11 @@ hipError_t sr_train_fwd(hipStream_t s, const SrConvGeom& q, const float* x, cons
     return sr_launch_gemm<2>(s, sr_pick_tile(I, J, 1), 1, p, x, theta, y, I, J, R, R, accumulate);
   }
   const long long n = (long long)q.B * q.Ho * q.Wo * q.Cout;
+  if (q.Cout <= 32 && n / q.Cout <= 65536 && (long long)q.kh * q.kw * q.Cin >= 1024) {   // a workgroup per output pixel
+    hipLaunchKernelGGL(sr_fwd_pixel_kernel, dim3((unsigned)(n / q.Cout)), dim3(256), 0, s, sr_with_divisors(q), x, theta, y,
+                       accumulate);
+    return hipGetLastError();
+  }
   if (n <= 65536 && (long long)q.kh * q.kw * q.Cin >= 256) {   // few outputs, long sums: a wave per output
     hipLaunchKernelGGL(sr_fwd_wide_kernel, dim3(grid_for(n, 4)), dim3(256), 0, s, q, x, theta, y, accumulate);
     return hipGetLastError();
