@@ -19,7 +19,7 @@ struct SrConvGeom {   // y[b][ho][wo][co] = sum x[b][ho*stride + i - pad][wo*str
   // filled by the launchers of the tiled kernels
   uint32_t mul_wo, sh_wo, mul_howo, sh_howo, mul_cout, sh_cout, mul_cin, sh_cin, mul_kw, sh_kw;
 };
-#define SR_TRAIN_TILED_MIN_MACS 4.0e6   // smaller contractions stay on the one-thread-per-output kernels
+#define SR_TRAIN_TILED_MIN_MACS 1.0e6   // smaller contractions stay on the one-thread-per-output kernels
 #define SR_TRAIN_MAX_SLICES 256  // a weight gradient's pixel sum is cut into at most this many partial sums
 hipError_t sr_train_ce(hipStream_t s, const float* z, const int32_t* labels, int B, int C, float scale, float* terms,
                        float* dz);

@@ -738,10 +738,10 @@ static long long sr_wgrad_max_slices(const SrConvGeom& q) {   // slices of at le
   return std::min<long long>(SR_TRAIN_MAX_SLICES, std::max<long long>(1, M / 256));
 }
 static bool sr_dgrad_tiled(const SrConvGeom& q) {
-  return sr_train_big(q) && q.Cin >= 32 && ((long long)q.B * q.H * q.W + SR_GT - 1) / SR_GT >= 16;
+  return sr_train_big(q) && q.Cin >= 16 && ((long long)q.B * q.H * q.W + 63) / 64 >= 2;
 }
 static bool sr_wgrad_tiled(const SrConvGeom& q) {
-  return sr_train_big(q) && q.Cout >= 32 && sr_wgrad_tiles(q) * sr_wgrad_max_slices(q) >= 16;
+  return sr_train_big(q) && q.Cout >= 16;
 }
 
 hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta, const float* dy, float* dx,
@@ -759,8 +759,7 @@ hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta
 }
 
 static bool sr_fwd_tiled(const SrConvGeom& q) {
-  return sr_train_big(q) && q.Cout >= 32 &&
-         ((long long)q.B * q.Ho * q.Wo + SR_GT - 1) / SR_GT * ((q.Cout + SR_GT - 1) / SR_GT) >= 8;
+  return sr_train_big(q) && q.Cout >= 16 && ((long long)q.B * q.Ho * q.Wo + 63) / 64 >= 2;
 }
 int sr_train_fwd_is_tiled(const SrConvGeom& q) { return sr_fwd_tiled(q) ? 1 : 0; }
 

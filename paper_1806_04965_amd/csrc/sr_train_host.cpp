@@ -57,8 +57,11 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     if (e.d.kind == SR_EDGE_CONV) {
       q.H = s.height; q.W = s.width; q.kh = e.kh; q.kw = e.kw; q.stride = e.d.stride; q.pad = e.d.pad;
       q.Ho = d.height / e.d.upsample; q.Wo = d.width / e.d.upsample;
-    } else if (e.d.kind == SR_EDGE_DENSE) {   // a valid convolution whose kernel covers the source
-      q.H = s.height; q.W = s.width; q.kh = s.height; q.kw = s.width; q.stride = 1; q.pad = 0; q.Ho = 1; q.Wo = 1;
+    } else if (e.d.kind == SR_EDGE_DENSE) {
+      // a 1x1 map on a 1x1 image whose channels are all the source's elements: x[b][h][w][ci] and
+      // theta[h][w][ci][co] lie in memory as x[b][(h, w, ci)] and theta[(h, w, ci)][co]
+      q.Cin = s.height * s.width * s.channels;
+      q.H = 1; q.W = 1; q.kh = 1; q.kw = 1; q.stride = 1; q.pad = 0; q.Ho = 1; q.Wo = 1;
     } else {                                   // GAP + dense: a 1x1 map on the per-image channel means
       q.H = 1; q.W = 1; q.kh = 1; q.kw = 1; q.stride = 1; q.pad = 0; q.Ho = 1; q.Wo = 1;
     }
