@@ -820,6 +820,8 @@ hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, co
     const int I = q.kh * q.kw * q.Cin, J = q.Cout;
     const int per = ((M + slices - 1) / slices + SR_GR - 1) / SR_GR * SR_GR;
     const int used = (M + per - 1) / per;
+    if (used == 1)   // one slice: straight onto the gradient
+      return sr_launch_gemm<1>(s, sr_pick_tile(I, J, 1), 1, sr_with_divisors(q), x, dy, dtheta, I, J, M, per, 1);
     hipError_t e = sr_launch_gemm<1>(s, sr_pick_tile(I, J, used), used, sr_with_divisors(q), x, dy, part, I, J, M, per, 0);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 64)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);

@@ -70,14 +70,19 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   // arena layout
   size_t at = 0;
   auto take = [&](size_t n) { size_t r = at; at += (n + 63) / 64 * 64; return r; };
-  std::vector<size_t> x_at(N, 0), dx_at[2];
-  dx_at[0].assign(N, 0); dx_at[1].assign(N, 0);
+  // states frame by frame, inside a frame node by node (frame 0, the zero state, is then one stretch), and the two
+  // gradient copies laid out like a frame each (a copy is cleared by one fill)
+  std::vector<size_t> in_frame(N, 0);
+  size_t frame_floats = 0;
   for (int v = 0; v < N; ++v) {
     if (g->an.is_input[v]) continue;
-    x_at[v] = take(node_floats(v) * (size_t)(W + 1));
-    dx_at[0][v] = take(node_floats(v));
-    dx_at[1][v] = take(node_floats(v));
+    in_frame[v] = frame_floats;
+    frame_floats += (node_floats(v) + 63) / 64 * 64;
   }
+  const size_t x_base = take(frame_floats * (size_t)(W + 1));
+  const size_t dx_base[2] = {take(frame_floats), take(frame_floats)};
+  auto x_of = [&](int v, int frame) { return x_base + (size_t)frame * frame_floats + in_frame[v]; };
+  auto dx_of = [&](int c, int v) { return dx_base[c] + in_frame[v]; };
   size_t pooled_n = 0, mean_n = 0, part_n = 0;
   for (const EdgeRt& e : g->edges) {
     const SrConvGeom q = geom_of(e);
@@ -115,7 +120,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] < g->an.level[b]; });
   auto state_of = [&](int u, int frame) -> const float* {
     return g->an.is_input[u] ? (const float*)inputs[slot_of[u]] + (size_t)frame * in_stride[slot_of[u]]
-                             : A + x_at[u] + (size_t)frame * node_floats(u);
+                             : A + x_of(u, frame);
   };
   // Two ways to the same states: when some edge is large enough for the tiled matrix-core kernel the window
   // runs its own forward pass below; a graph of small edges only is better served by the frame path
@@ -131,7 +136,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
 
   // every launch of the window, in stream order
   auto enqueue = [&]() -> sr_status {
-  for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + x_at[v], node_floats(v) * sizeof(float)));
+  SR_HIP(g, sr_launch_fill_zero(s, A + x_base, frame_floats * sizeof(float)));   // frame 0
   if (!own_forward) {
     std::vector<const void*> ptrs(g->inputs.size());
     for (size_t k = 0; k < g->inputs.size(); ++k) ptrs[k] = inputs[k];
@@ -142,14 +147,14 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
       st = sr_frame_step(g, ptrs.data());
       if (st != SR_OK) return st;
       for (int v : order)
-        SR_HIP(g, hipMemcpyAsync(A + x_at[v] + (size_t)i * node_floats(v), g->nodes[v].state[g->host_frame & 1],
+        SR_HIP(g, hipMemcpyAsync(A + x_of(v, i), g->nodes[v].state[g->host_frame & 1],
                                  node_floats(v) * sizeof(float), hipMemcpyDeviceToDevice, s));
     }
   }
   for (int i = 1; own_forward && i <= W; ++i)
     for (int v : order) {
       const sr_node_desc& d = g->nodes[v].d;
-      float* dst = A + x_at[v] + (size_t)i * node_floats(v);
+      float* dst = A + x_of(v, i);
       int seen = 0;
       for (int ei = 0; ei < g->n_edges; ++ei) {
         const EdgeRt& e = g->edges[ei];
@@ -174,8 +179,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
   // (frame, node) has the gradient of all its readers before it is processed
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] > g->an.level[b]; });
-  for (int v : order)
-    for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[c][v], node_floats(v) * sizeof(float)));
+  for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_base[c], frame_floats * sizeof(float)));
   for (int e = 0; e < g->n_edges; ++e) SR_HIP(g, sr_launch_fill_zero(s, dtheta[e], g->edges[e].w_count * sizeof(float)));
   if (dbias)
     for (int v : order)
@@ -184,12 +188,12 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   const float scale = 1.0f / ((float)B * (float)W);
   for (int i = W; i >= 1; --i) {
     const int cur = i & 1;
-    SR_HIP(g, sr_train_ce(s, A + x_at[out_node] + (size_t)i * node_floats(out_node), labels, B, classes, scale,
-                          A + terms_at + (size_t)(i - 1) * B, A + dx_at[cur][out_node]));
+    SR_HIP(g, sr_train_ce(s, A + x_of(out_node, i), labels, B, classes, scale,
+                          A + terms_at + (size_t)(i - 1) * B, A + dx_of(cur, out_node)));
     for (int v : order) {
       const sr_node_desc& d = g->nodes[v].d;
-      float* da = A + dx_at[cur][v];
-      SR_HIP(g, sr_train_act_grad(s, da, A + x_at[v] + (size_t)i * node_floats(v), mask_of(v, i), node_floats(v), d.act));
+      float* da = A + dx_of(cur, v);
+      SR_HIP(g, sr_train_act_grad(s, da, A + x_of(v, i), mask_of(v, i), node_floats(v), d.act));
       if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(s, da, B * d.height * d.width, d.channels, A + part_at, dbias[v]));
       for (int ei = 0; ei < g->n_edges; ++ei) {
         const EdgeRt& e = g->edges[ei];
@@ -197,7 +201,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         const int u = e.d.src, fi = i - (int)e.d.bridge;
         const float* xsrc = state_of(u, fi);
         // frame 0 and the input nodes are given: no gradient is kept for them
-        float* dxsrc = (g->an.is_input[u] || fi == 0) ? nullptr : A + dx_at[fi & 1][u];
+        float* dxsrc = (g->an.is_input[u] || fi == 0) ? nullptr : A + dx_of(fi & 1, u);
         const SrConvGeom q = geom_of(e);
         if (e.d.kind == SR_EDGE_GAP_DENSE) {
           const sr_node_desc& sd = g->nodes[u].d;
@@ -219,7 +223,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
       }
     }
     // this copy next holds frame i - 2
-    for (int v : order) SR_HIP(g, sr_launch_fill_zero(s, A + dx_at[cur][v], node_floats(v) * sizeof(float)));
+    SR_HIP(g, sr_launch_fill_zero(s, A + dx_base[cur], frame_floats * sizeof(float)));
   }
   SR_HIP(g, sr_train_sum_terms(s, A + terms_at, W * B, scale, loss));
   return SR_OK;
