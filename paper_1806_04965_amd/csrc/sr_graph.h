@@ -131,6 +131,10 @@ struct sr_graph {
   size_t train_arena_floats = 0;
   // the launches of one window, captured: replayed while a call names the same window size, output node and
   // buffers (train_key holds them) and the arena has not moved
+  // second stream of the reverse sweep (bias and weight gradients run beside the state gradients) and the two
+  // events that order it against the graph's stream
+  hipStream_t train_side = nullptr;
+  hipEvent_t train_ev_main = nullptr, train_ev_side = nullptr;
   hipGraph_t train_graph = nullptr;
   hipGraphExec_t train_exec = nullptr;
   std::vector<const void*> train_key;

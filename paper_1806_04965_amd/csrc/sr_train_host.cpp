@@ -92,6 +92,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     if (e.d.kind == SR_EDGE_GAP_DENSE) mean_n = std::max(mean_n, (size_t)B * q.Cin);
   }
   const size_t pooled_at = take(pooled_n), mean_at = take(mean_n), dmean_at = take(mean_n), part_at = take(part_n);
+  const size_t pooled_side_at = take(pooled_n);   // the second stream's own copy
   const size_t terms_at = take((size_t)W * B);
   if (at > g->train_arena_floats) {
     SR_HIP(g, hipStreamSynchronize(g->stream));
@@ -106,6 +107,12 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   }
   float* A = g->train_arena;
   hipStream_t s = g->stream;
+  if (!g->train_side) {
+    SR_HIP(g, hipStreamCreateWithFlags(&g->train_side, hipStreamNonBlocking));
+    SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_main, hipEventDisableTiming));
+    SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_side, hipEventDisableTiming));
+  }
+  hipStream_t w = g->train_side;
 
   // forward over the window from the zero state, every frame's states written straight into the arena:
   // frames 1..W, inside a frame the update steps of the tableau in order (Eq. 5), per node the sum of its
@@ -177,13 +184,19 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     }
 
   // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
-  // (frame, node) has the gradient of all its readers before it is processed
+  // (frame, node) has the gradient of all its readers before it is processed.  Two streams: the chain of state
+  // gradients (loss, activation gradient, one state gradient per edge) runs on the graph's stream; what hangs off
+  // it (a node's bias gradient and its edges' weight gradients, which nothing later in the sweep reads) runs on a
+  // second stream, started per node once the node's gradient is final and joined at the end of each frame, before
+  // the gradient copy it read is cleared.  The second stream has its own scratch.
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] > g->an.level[b]; });
   for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_base[c], frame_floats * sizeof(float)));
-  for (int e = 0; e < g->n_edges; ++e) SR_HIP(g, sr_launch_fill_zero(s, dtheta[e], g->edges[e].w_count * sizeof(float)));
+  SR_HIP(g, hipEventRecord(g->train_ev_main, s));          // the forward pass is done with the scratch
+  SR_HIP(g, hipStreamWaitEvent(w, g->train_ev_main, 0));
+  for (int e = 0; e < g->n_edges; ++e) SR_HIP(g, sr_launch_fill_zero(w, dtheta[e], g->edges[e].w_count * sizeof(float)));
   if (dbias)
     for (int v : order)
-      if (dbias[v]) SR_HIP(g, sr_launch_fill_zero(s, dbias[v], (size_t)g->nodes[v].d.channels * sizeof(float)));
+      if (dbias[v]) SR_HIP(g, sr_launch_fill_zero(w, dbias[v], (size_t)g->nodes[v].d.channels * sizeof(float)));
   const int classes = g->nodes[out_node].d.channels;
   const float scale = 1.0f / ((float)B * (float)W);
   for (int i = W; i >= 1; --i) {
@@ -194,7 +207,10 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
       const sr_node_desc& d = g->nodes[v].d;
       float* da = A + dx_of(cur, v);
       SR_HIP(g, sr_train_act_grad(s, da, A + x_of(v, i), mask_of(v, i), node_floats(v), d.act));
-      if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(s, da, B * d.height * d.width, d.channels, A + part_at, dbias[v]));
+      // da is final: its writers (readers of v in this frame and the next) came earlier in the sweep
+      SR_HIP(g, hipEventRecord(g->train_ev_main, s));
+      SR_HIP(g, hipStreamWaitEvent(w, g->train_ev_main, 0));
+      if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(w, da, B * d.height * d.width, d.channels, A + part_at, dbias[v]));
       for (int ei = 0; ei < g->n_edges; ++ei) {
         const EdgeRt& e = g->edges[ei];
         if (e.d.dst != v) continue;
@@ -205,8 +221,8 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         const SrConvGeom q = geom_of(e);
         if (e.d.kind == SR_EDGE_GAP_DENSE) {
           const sr_node_desc& sd = g->nodes[u].d;
-          SR_HIP(g, sr_train_gap_mean(s, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at));
-          SR_HIP(g, sr_train_wgrad(s, q, A + mean_at, da, A + part_at, dtheta[ei]));
+          SR_HIP(g, sr_train_gap_mean(w, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at));
+          SR_HIP(g, sr_train_wgrad(w, q, A + mean_at, da, A + part_at, dtheta[ei]));
           if (dxsrc) {
             SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, da, A + dmean_at, 0));
             SR_HIP(g, sr_train_gap_spread(s, A + dmean_at, B, sd.height * sd.width, sd.channels, dxsrc));
@@ -214,15 +230,20 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
           continue;
         }
         const float* dy = da;
+        const float* dy_side = da;
         if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) {
-          SR_HIP(g, sr_train_pool_sum(s, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_at));
+          SR_HIP(g, sr_train_pool_sum(w, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_side_at));
+          dy_side = A + pooled_side_at;
+          if (dxsrc) SR_HIP(g, sr_train_pool_sum(s, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_at));
           dy = A + pooled_at;
         }
-        SR_HIP(g, sr_train_wgrad(s, q, xsrc, dy, A + part_at, dtheta[ei]));
+        SR_HIP(g, sr_train_wgrad(w, q, xsrc, dy_side, A + part_at, dtheta[ei]));
         if (dxsrc) SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, dy, dxsrc, 1));
       }
     }
-    // this copy next holds frame i - 2
+    // the second stream has read this frame's gradients: the copy can be cleared; it next holds frame i - 2
+    SR_HIP(g, hipEventRecord(g->train_ev_side, w));
+    SR_HIP(g, hipStreamWaitEvent(s, g->train_ev_side, 0));
     SR_HIP(g, sr_launch_fill_zero(s, A + dx_base[cur], frame_floats * sizeof(float)));
   }
   SR_HIP(g, sr_train_sum_terms(s, A + terms_at, W * B, scale, loss));
