@@ -92,7 +92,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     if (e.d.kind == SR_EDGE_GAP_DENSE) mean_n = std::max(mean_n, (size_t)B * q.Cin);
   }
   const size_t pooled_at = take(pooled_n), mean_at = take(mean_n), dmean_at = take(mean_n), part_at = take(part_n);
-  const size_t pooled_side_at = take(pooled_n);   // the second stream's own copy
+  const size_t pooled_side_at = take(pooled_n), mean_side_at = take(mean_n);   // the second stream's own copies
   const size_t terms_at = take((size_t)W * B);
   if (at > g->train_arena_floats) {
     SR_HIP(g, hipStreamSynchronize(g->stream));
@@ -158,29 +158,50 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
                                  node_floats(v) * sizeof(float), hipMemcpyDeviceToDevice, s));
     }
   }
+  // the nodes of one update step do not depend on each other: they alternate between the graph's stream and the
+  // second one, which is forked before the step and joined after it
   for (int i = 1; own_forward && i <= W; ++i)
-    for (int v : order) {
-      const sr_node_desc& d = g->nodes[v].d;
-      float* dst = A + x_of(v, i);
-      int seen = 0;
-      for (int ei = 0; ei < g->n_edges; ++ei) {
-        const EdgeRt& e = g->edges[ei];
-        if (e.d.dst != v) continue;
-        const float* xsrc = state_of(e.d.src, i - (int)e.d.bridge);
-        const SrConvGeom q = geom_of(e);
-        if (e.d.kind == SR_EDGE_GAP_DENSE) {
-          const sr_node_desc& sd = g->nodes[e.d.src].d;
-          SR_HIP(g, sr_train_gap_mean(s, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at));
-          SR_HIP(g, sr_train_fwd(s, q, A + mean_at, e.w_dev, dst, seen));
-        } else if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) {
-          SR_HIP(g, sr_train_fwd(s, q, xsrc, e.w_dev, A + pooled_at, 0));
-          SR_HIP(g, sr_train_upsample_add(s, A + pooled_at, B, d.height, d.width, d.channels, e.d.upsample, dst, seen));
-        } else {
-          SR_HIP(g, sr_train_fwd(s, q, xsrc, e.w_dev, dst, seen));
-        }
-        seen = 1;
+    for (size_t o = 0; o < order.size();) {
+      size_t o_end = o;
+      while (o_end < order.size() && g->an.level[order[o_end]] == g->an.level[order[o]]) ++o_end;
+      const bool fork = o_end - o > 1;
+      if (fork) {
+        SR_HIP(g, hipEventRecord(g->train_ev_main, s));
+        SR_HIP(g, hipStreamWaitEvent(w, g->train_ev_main, 0));
       }
-      SR_HIP(g, sr_train_bias_act(s, dst, g->nodes[v].bias_dev, mask_of(v, i), d.channels, node_floats(v), d.act));
+      for (size_t k = o; k < o_end; ++k) {
+        const int v = order[k];
+        const bool side = fork && ((k - o) & 1);
+        hipStream_t st = side ? w : s;
+        float* pooled = A + (side ? pooled_side_at : pooled_at);
+        float* mean = A + (side ? mean_side_at : mean_at);
+        const sr_node_desc& d = g->nodes[v].d;
+        float* dst = A + x_of(v, i);
+        int seen = 0;
+        for (int ei = 0; ei < g->n_edges; ++ei) {
+          const EdgeRt& e = g->edges[ei];
+          if (e.d.dst != v) continue;
+          const float* xsrc = state_of(e.d.src, i - (int)e.d.bridge);
+          const SrConvGeom q = geom_of(e);
+          if (e.d.kind == SR_EDGE_GAP_DENSE) {
+            const sr_node_desc& sd = g->nodes[e.d.src].d;
+            SR_HIP(g, sr_train_gap_mean(st, xsrc, B, sd.height * sd.width, sd.channels, mean));
+            SR_HIP(g, sr_train_fwd(st, q, mean, e.w_dev, dst, seen));
+          } else if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) {
+            SR_HIP(g, sr_train_fwd(st, q, xsrc, e.w_dev, pooled, 0));
+            SR_HIP(g, sr_train_upsample_add(st, pooled, B, d.height, d.width, d.channels, e.d.upsample, dst, seen));
+          } else {
+            SR_HIP(g, sr_train_fwd(st, q, xsrc, e.w_dev, dst, seen));
+          }
+          seen = 1;
+        }
+        SR_HIP(g, sr_train_bias_act(st, dst, g->nodes[v].bias_dev, mask_of(v, i), d.channels, node_floats(v), d.act));
+      }
+      if (fork) {
+        SR_HIP(g, hipEventRecord(g->train_ev_side, w));
+        SR_HIP(g, hipStreamWaitEvent(s, g->train_ev_side, 0));
+      }
+      o = o_end;
     }
 
   // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
@@ -221,8 +242,8 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         const SrConvGeom q = geom_of(e);
         if (e.d.kind == SR_EDGE_GAP_DENSE) {
           const sr_node_desc& sd = g->nodes[u].d;
-          SR_HIP(g, sr_train_gap_mean(w, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at));
-          SR_HIP(g, sr_train_wgrad(w, q, A + mean_at, da, A + part_at, dtheta[ei]));
+          SR_HIP(g, sr_train_gap_mean(w, xsrc, B, sd.height * sd.width, sd.channels, A + mean_side_at));
+          SR_HIP(g, sr_train_wgrad(w, q, A + mean_side_at, da, A + part_at, dtheta[ei]));
           if (dxsrc) {
             SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, da, A + dmean_at, 0));
             SR_HIP(g, sr_train_gap_spread(s, A + dmean_at, B, sd.height * sd.width, sd.channels, dxsrc));
