@@ -131,10 +131,11 @@ struct sr_graph {
   size_t train_arena_floats = 0;
   // the launches of one window, captured: replayed while a call names the same window size, output node and
   // buffers (train_key holds them) and the arena has not moved
-  // second stream of the reverse sweep (bias and weight gradients run beside the state gradients) and the two
-  // events that order it against the graph's stream
-  hipStream_t train_side = nullptr;
-  hipEvent_t train_ev_main = nullptr, train_ev_side = nullptr;
+  // side streams of the training window (nodes of one update step of the forward pass; bias and weight gradients
+  // of the reverse sweep beside the chain of state gradients) and the events that order them against the graph's stream
+  static constexpr int kTrainSides = 3;
+  hipStream_t train_side[kTrainSides] = {nullptr, nullptr, nullptr};
+  hipEvent_t train_ev_main = nullptr, train_ev_side[kTrainSides] = {nullptr, nullptr, nullptr};
   hipGraph_t train_graph = nullptr;
   hipGraphExec_t train_exec = nullptr;
   std::vector<const void*> train_key;

@@ -2226,9 +2226,11 @@ void sr_graph_destroy(sr_graph* g) {
   if (g->split_scratch) uncached_release(g->split_scratch, g->split_scratch_bytes);
   if (g->train_exec) hipGraphExecDestroy(g->train_exec);
   if (g->train_graph) hipGraphDestroy(g->train_graph);
-  if (g->train_side) { hipStreamSynchronize(g->train_side); hipStreamDestroy(g->train_side); }
+  for (int k = 0; k < sr_graph::kTrainSides; ++k) {
+    if (g->train_side[k]) { hipStreamSynchronize(g->train_side[k]); hipStreamDestroy(g->train_side[k]); }
+    if (g->train_ev_side[k]) hipEventDestroy(g->train_ev_side[k]);
+  }
   if (g->train_ev_main) hipEventDestroy(g->train_ev_main);
-  if (g->train_ev_side) hipEventDestroy(g->train_ev_side);
   if (g->train_arena) hipFree(g->train_arena);
   delete g;
 }

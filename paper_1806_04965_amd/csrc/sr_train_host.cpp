@@ -91,8 +91,15 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) pooled_n = std::max(pooled_n, (size_t)B * q.Ho * q.Wo * q.Cout);
     if (e.d.kind == SR_EDGE_GAP_DENSE) mean_n = std::max(mean_n, (size_t)B * q.Cin);
   }
-  const size_t pooled_at = take(pooled_n), mean_at = take(mean_n), dmean_at = take(mean_n), part_at = take(part_n);
-  const size_t pooled_side_at = take(pooled_n), mean_side_at = take(mean_n);   // the second stream's own copies
+  // scratch: copy 0 belongs to the graph's stream, copy 1 + k to side stream k
+  constexpr int NS = sr_graph::kTrainSides;
+  size_t pooled_at[1 + NS], mean_at[1 + NS], part_at[1 + NS];
+  for (int k = 0; k <= NS; ++k) {
+    pooled_at[k] = take(pooled_n);
+    mean_at[k] = take(mean_n);
+    part_at[k] = take(k == 0 ? 0 : part_n);   // partial sums of bias and weight gradients: side streams only
+  }
+  const size_t dmean_at = take(mean_n);
   const size_t terms_at = take((size_t)W * B);
   if (at > g->train_arena_floats) {
     SR_HIP(g, hipStreamSynchronize(g->stream));
@@ -107,12 +114,26 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   }
   float* A = g->train_arena;
   hipStream_t s = g->stream;
-  if (!g->train_side) {
-    SR_HIP(g, hipStreamCreateWithFlags(&g->train_side, hipStreamNonBlocking));
-    SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_main, hipEventDisableTiming));
-    SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_side, hipEventDisableTiming));
+  if (!g->train_ev_main) SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_main, hipEventDisableTiming));
+  for (int k = 0; k < NS; ++k) {
+    if (!g->train_side[k]) SR_HIP(g, hipStreamCreateWithFlags(&g->train_side[k], hipStreamNonBlocking));
+    if (!g->train_ev_side[k]) SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_side[k], hipEventDisableTiming));
   }
-  hipStream_t w = g->train_side;
+  // stream 0 is the graph's, 1 + k side stream k; fork: the side streams take up after what the graph's stream
+  // holds so far; join: the graph's stream takes up after all of them
+  auto stream_of = [&](int k) { return k == 0 ? s : g->train_side[k - 1]; };
+  auto fork = [&]() -> sr_status {
+    SR_HIP(g, hipEventRecord(g->train_ev_main, s));
+    for (int k = 0; k < NS; ++k) SR_HIP(g, hipStreamWaitEvent(g->train_side[k], g->train_ev_main, 0));
+    return SR_OK;
+  };
+  auto join = [&]() -> sr_status {
+    for (int k = 0; k < NS; ++k) {
+      SR_HIP(g, hipEventRecord(g->train_ev_side[k], g->train_side[k]));
+      SR_HIP(g, hipStreamWaitEvent(s, g->train_ev_side[k], 0));
+    }
+    return SR_OK;
+  };
 
   // forward over the window from the zero state, every frame's states written straight into the arena:
   // frames 1..W, inside a frame the update steps of the tableau in order (Eq. 5), per node the sum of its
@@ -158,23 +179,20 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
                                  node_floats(v) * sizeof(float), hipMemcpyDeviceToDevice, s));
     }
   }
-  // the nodes of one update step do not depend on each other: they alternate between the graph's stream and the
-  // second one, which is forked before the step and joined after it
+  // the nodes of one update step do not depend on each other: they go round the streams, forked before the step
+  // and joined after it
   for (int i = 1; own_forward && i <= W; ++i)
     for (size_t o = 0; o < order.size();) {
       size_t o_end = o;
       while (o_end < order.size() && g->an.level[order[o_end]] == g->an.level[order[o]]) ++o_end;
-      const bool fork = o_end - o > 1;
-      if (fork) {
-        SR_HIP(g, hipEventRecord(g->train_ev_main, s));
-        SR_HIP(g, hipStreamWaitEvent(w, g->train_ev_main, 0));
-      }
+      const bool forked = o_end - o > 1;
+      if (forked && fork() != SR_OK) return SR_ERR_DEVICE;
       for (size_t k = o; k < o_end; ++k) {
         const int v = order[k];
-        const bool side = fork && ((k - o) & 1);
-        hipStream_t st = side ? w : s;
-        float* pooled = A + (side ? pooled_side_at : pooled_at);
-        float* mean = A + (side ? mean_side_at : mean_at);
+        const int lane = forked ? (int)((k - o) % (1 + NS)) : 0;
+        hipStream_t st = stream_of(lane);
+        float* pooled = A + pooled_at[lane];
+        float* mean = A + mean_at[lane];
         const sr_node_desc& d = g->nodes[v].d;
         float* dst = A + x_of(v, i);
         int seen = 0;
@@ -197,27 +215,28 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         }
         SR_HIP(g, sr_train_bias_act(st, dst, g->nodes[v].bias_dev, mask_of(v, i), d.channels, node_floats(v), d.act));
       }
-      if (fork) {
-        SR_HIP(g, hipEventRecord(g->train_ev_side, w));
-        SR_HIP(g, hipStreamWaitEvent(s, g->train_ev_side, 0));
-      }
+      if (forked && join() != SR_OK) return SR_ERR_DEVICE;
       o = o_end;
     }
 
   // reverse sweep: frames W..1, inside a frame the update steps in reverse (Eq. 5), so every
-  // (frame, node) has the gradient of all its readers before it is processed.  Two streams: the chain of state
-  // gradients (loss, activation gradient, one state gradient per edge) runs on the graph's stream; what hangs off
-  // it (a node's bias gradient and its edges' weight gradients, which nothing later in the sweep reads) runs on a
-  // second stream, started per node once the node's gradient is final and joined at the end of each frame, before
-  // the gradient copy it read is cleared.  The second stream has its own scratch.
+  // (frame, node) has the gradient of all its readers before it is processed.  The chain of state gradients
+  // (loss, activation gradient, one state gradient per edge) runs on the graph's stream; what hangs off it (a
+  // node's bias gradient and its edges' weight gradients, which nothing later in the sweep reads) runs on the side
+  // streams, started per node once the node's gradient is final and joined at the end of each frame, before the
+  // gradient copy they read is cleared.  A node's bias and an edge's weights always go to the same side stream, so
+  // their sums over the frames keep their order; every side stream has its own scratch.
   std::stable_sort(order.begin(), order.end(), [&](int a, int b) { return g->an.level[a] > g->an.level[b]; });
   for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_base[c], frame_floats * sizeof(float)));
-  SR_HIP(g, hipEventRecord(g->train_ev_main, s));          // the forward pass is done with the scratch
-  SR_HIP(g, hipStreamWaitEvent(w, g->train_ev_main, 0));
-  for (int e = 0; e < g->n_edges; ++e) SR_HIP(g, sr_launch_fill_zero(w, dtheta[e], g->edges[e].w_count * sizeof(float)));
+  auto side_of_edge = [&](int ei) { return 1 + ei % NS; };
+  auto side_of_node = [&](int v) { return 1 + v % NS; };
+  if (fork() != SR_OK) return SR_ERR_DEVICE;   // the forward pass is done with the scratch
+  for (int e = 0; e < g->n_edges; ++e)
+    SR_HIP(g, sr_launch_fill_zero(stream_of(side_of_edge(e)), dtheta[e], g->edges[e].w_count * sizeof(float)));
   if (dbias)
     for (int v : order)
-      if (dbias[v]) SR_HIP(g, sr_launch_fill_zero(w, dbias[v], (size_t)g->nodes[v].d.channels * sizeof(float)));
+      if (dbias[v])
+        SR_HIP(g, sr_launch_fill_zero(stream_of(side_of_node(v)), dbias[v], (size_t)g->nodes[v].d.channels * sizeof(float)));
   const int classes = g->nodes[out_node].d.channels;
   const float scale = 1.0f / ((float)B * (float)W);
   for (int i = W; i >= 1; --i) {
@@ -229,9 +248,10 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
       float* da = A + dx_of(cur, v);
       SR_HIP(g, sr_train_act_grad(s, da, A + x_of(v, i), mask_of(v, i), node_floats(v), d.act));
       // da is final: its writers (readers of v in this frame and the next) came earlier in the sweep
-      SR_HIP(g, hipEventRecord(g->train_ev_main, s));
-      SR_HIP(g, hipStreamWaitEvent(w, g->train_ev_main, 0));
-      if (dbias && dbias[v]) SR_HIP(g, sr_train_bias_grad(w, da, B * d.height * d.width, d.channels, A + part_at, dbias[v]));
+      if (fork() != SR_OK) return SR_ERR_DEVICE;
+      if (dbias && dbias[v])
+        SR_HIP(g, sr_train_bias_grad(stream_of(side_of_node(v)), da, B * d.height * d.width, d.channels,
+                                     A + part_at[side_of_node(v)], dbias[v]));
       for (int ei = 0; ei < g->n_edges; ++ei) {
         const EdgeRt& e = g->edges[ei];
         if (e.d.dst != v) continue;
@@ -240,10 +260,12 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         // frame 0 and the input nodes are given: no gradient is kept for them
         float* dxsrc = (g->an.is_input[u] || fi == 0) ? nullptr : A + dx_of(fi & 1, u);
         const SrConvGeom q = geom_of(e);
+        const int lane = side_of_edge(ei);
+        hipStream_t w = stream_of(lane);
         if (e.d.kind == SR_EDGE_GAP_DENSE) {
           const sr_node_desc& sd = g->nodes[u].d;
-          SR_HIP(g, sr_train_gap_mean(w, xsrc, B, sd.height * sd.width, sd.channels, A + mean_side_at));
-          SR_HIP(g, sr_train_wgrad(w, q, A + mean_side_at, da, A + part_at, dtheta[ei]));
+          SR_HIP(g, sr_train_gap_mean(w, xsrc, B, sd.height * sd.width, sd.channels, A + mean_at[lane]));
+          SR_HIP(g, sr_train_wgrad(w, q, A + mean_at[lane], da, A + part_at[lane], dtheta[ei]));
           if (dxsrc) {
             SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, da, A + dmean_at, 0));
             SR_HIP(g, sr_train_gap_spread(s, A + dmean_at, B, sd.height * sd.width, sd.channels, dxsrc));
@@ -253,18 +275,17 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         const float* dy = da;
         const float* dy_side = da;
         if (e.d.kind == SR_EDGE_CONV && e.d.upsample > 1) {
-          SR_HIP(g, sr_train_pool_sum(w, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_side_at));
-          dy_side = A + pooled_side_at;
-          if (dxsrc) SR_HIP(g, sr_train_pool_sum(s, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_at));
-          dy = A + pooled_at;
+          SR_HIP(g, sr_train_pool_sum(w, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_at[lane]));
+          dy_side = A + pooled_at[lane];
+          if (dxsrc) SR_HIP(g, sr_train_pool_sum(s, da, B, q.Ho, q.Wo, q.Cout, e.d.upsample, A + pooled_at[0]));
+          dy = A + pooled_at[0];
         }
-        SR_HIP(g, sr_train_wgrad(w, q, xsrc, dy_side, A + part_at, dtheta[ei]));
+        SR_HIP(g, sr_train_wgrad(w, q, xsrc, dy_side, A + part_at[lane], dtheta[ei]));
         if (dxsrc) SR_HIP(g, sr_train_dgrad(s, q, e.w_dev, dy, dxsrc, 1));
       }
     }
-    // the second stream has read this frame's gradients: the copy can be cleared; it next holds frame i - 2
-    SR_HIP(g, hipEventRecord(g->train_ev_side, w));
-    SR_HIP(g, hipStreamWaitEvent(s, g->train_ev_side, 0));
+    // the side streams have read this frame's gradients: the copy can be cleared; it next holds frame i - 2
+    if (join() != SR_OK) return SR_ERR_DEVICE;
     SR_HIP(g, sr_launch_fill_zero(s, A + dx_base[cur], frame_floats * sizeof(float)));
   }
   SR_HIP(g, sr_train_sum_terms(s, A + terms_at, W * B, scale, loss));
