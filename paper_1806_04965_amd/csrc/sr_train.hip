@@ -733,9 +733,9 @@ static bool sr_train_big(const SrConvGeom& q) {
 static long long sr_wgrad_tiles(const SrConvGeom& q) {
   return ((long long)q.kh * q.kw * q.Cin + SR_GT - 1) / SR_GT * ((q.Cout + SR_GT - 1) / SR_GT);
 }
-static long long sr_wgrad_max_slices(const SrConvGeom& q) {   // slices of at least 256 pixels
+static long long sr_wgrad_max_slices(const SrConvGeom& q) {   // slices of at least 128 pixels
   const long long M = (long long)q.B * q.Ho * q.Wo;
-  return std::min<long long>(SR_TRAIN_MAX_SLICES, std::max<long long>(1, M / 256));
+  return std::min<long long>(SR_TRAIN_MAX_SLICES, std::max<long long>(1, M / 128));
 }
 static bool sr_dgrad_tiled(const SrConvGeom& q) {
   return sr_train_big(q) && q.Cin >= 16 && ((long long)q.B * q.H * q.W + 63) / 64 >= 2;
