@@ -124,26 +124,16 @@ struct sr_graph {
   // rollout output recording (set per call)
   int rec_node = -1;
 
-  // training window: one arena holding every node's states of the frames 0..W, two gradient copies per
-  // node (frames i and i-1 of the reverse sweep) and the scratch of the gradient kernels
-  float* train_arena = nullptr;
-  std::vector<float*> rms_w, rms_b;   // RMSprop's running mean of the squared gradient, per edge / node (on first use)
-  size_t train_arena_floats = 0;
-  // the launches of one window, captured: replayed while a call names the same window size, output node and
-  // buffers (train_key holds them) and the arena has not moved
-  // side streams of the training window (nodes of one update step of the forward pass; bias and weight gradients
-  // of the reverse sweep beside the chain of state gradients) and the events that order them against the graph's stream
-  static constexpr int kTrainSides = 3;
-  hipStream_t train_side[kTrainSides] = {nullptr, nullptr, nullptr};
-  hipEvent_t train_ev_main = nullptr, train_ev_side[kTrainSides] = {nullptr, nullptr, nullptr};
-  hipGraph_t train_graph = nullptr;
-  hipGraphExec_t train_exec = nullptr;
-  std::vector<const void*> train_key;
+  // what the training window keeps between calls (arena, side streams, captured graph, RMSprop's running means):
+  // made on first use and released by sr_train_state_release, both in sr_train_host.cpp
+  struct SrTrainState* train = nullptr;
 
   hipGraph_t graph1 = nullptr, graphN = nullptr;
   hipGraphExec_t exec1 = nullptr, execN = nullptr;
   int graph_rec_node = -2;   // out_node the captured graphs record
 };
+
+void sr_train_state_release(struct SrTrainState* t);
 
 // records the message in the graph (sr_last_error) and returns st
 sr_status sr_gfail(sr_graph* g, sr_status st, const std::string& msg);

@@ -2224,14 +2224,7 @@ void sr_graph_destroy(sr_graph* g) {
   drop_graphs(g);
   for (void* p : g->dev_allocs) hipFree(p);
   if (g->split_scratch) uncached_release(g->split_scratch, g->split_scratch_bytes);
-  if (g->train_exec) hipGraphExecDestroy(g->train_exec);
-  if (g->train_graph) hipGraphDestroy(g->train_graph);
-  for (int k = 0; k < sr_graph::kTrainSides; ++k) {
-    if (g->train_side[k]) { hipStreamSynchronize(g->train_side[k]); hipStreamDestroy(g->train_side[k]); }
-    if (g->train_ev_side[k]) hipEventDestroy(g->train_ev_side[k]);
-  }
-  if (g->train_ev_main) hipEventDestroy(g->train_ev_main);
-  if (g->train_arena) hipFree(g->train_arena);
+  sr_train_state_release(g->train);
   delete g;
 }
 

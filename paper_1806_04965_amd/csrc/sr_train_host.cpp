@@ -13,15 +13,53 @@
 #include "sr_train.h"
 #include "sr_graph.h"
 
+// what a graph keeps for its training windows between calls
+struct SrTrainState {
+  // one arena: the states of the frames 0..W, two gradient copies (frames i and i-1 of the reverse sweep) and
+  // the scratch of the gradient kernels
+  float* arena = nullptr;
+  size_t arena_floats = 0;
+  std::vector<float*> rms_w, rms_b;   // RMSprop's running mean of the squared gradient, per edge / node (on first use)
+  // side streams (nodes of one update step of the forward pass; bias and weight gradients of the reverse sweep
+  // beside the chain of state gradients) and the events that order them against the graph's stream
+  static constexpr int kSides = 3;
+  hipStream_t side[kSides] = {nullptr, nullptr, nullptr};
+  hipEvent_t ev_main = nullptr, ev_side[kSides] = {nullptr, nullptr, nullptr};
+  // the launches of one window, captured: replayed while a call names the same window size, output node and
+  // buffers (key holds them) and the arena has not moved
+  hipGraph_t graph = nullptr;
+  hipGraphExec_t exec = nullptr;
+  std::vector<const void*> key;
+};
+
+void sr_train_state_release(SrTrainState* t) {
+  if (!t) return;
+  if (t->exec) hipGraphExecDestroy(t->exec);
+  if (t->graph) hipGraphDestroy(t->graph);
+  for (int k = 0; k < SrTrainState::kSides; ++k) {
+    if (t->side[k]) { hipStreamSynchronize(t->side[k]); hipStreamDestroy(t->side[k]); }
+    if (t->ev_side[k]) hipEventDestroy(t->ev_side[k]);
+  }
+  if (t->ev_main) hipEventDestroy(t->ev_main);
+  if (t->arena) hipFree(t->arena);
+  delete t;
+}
+
 namespace {
 
+SrTrainState& train_state(sr_graph* g) {
+  if (!g->train) g->train = new SrTrainState();
+  return *g->train;
+}
+
 void drop_train_graph(sr_graph* g) {
-  if (g->train_exec) hipStreamSynchronize(g->stream);   // a replay may still be running
-  if (g->train_exec) hipGraphExecDestroy(g->train_exec);
-  if (g->train_graph) hipGraphDestroy(g->train_graph);
-  g->train_exec = nullptr;
-  g->train_graph = nullptr;
-  g->train_key.clear();
+  SrTrainState& T = train_state(g);
+  if (T.exec) hipStreamSynchronize(g->stream);   // a replay may still be running
+  if (T.exec) hipGraphExecDestroy(T.exec);
+  if (T.graph) hipGraphDestroy(T.graph);
+  T.exec = nullptr;
+  T.graph = nullptr;
+  T.key.clear();
 }
 
 }  // namespace
@@ -44,6 +82,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   for (int e = 0; e < g->n_edges; ++e)
     if (!g->edges[e].has_w) return sr_gfail(g, SR_ERR_STATE, "edge " + std::to_string(e) + " has no weights");
   if (W > 4096) return sr_gfail(g, SR_ERR_ARG, "sr_window_gradients: window size above 4096");
+  SrTrainState& T = train_state(g);
   const int B = g->batch, N = g->n_nodes;
   auto node_floats = [&](int v) {
     const sr_node_desc& d = g->nodes[v].d;
@@ -92,7 +131,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     if (e.d.kind == SR_EDGE_GAP_DENSE) mean_n = std::max(mean_n, (size_t)B * q.Cin);
   }
   // scratch: copy 0 belongs to the graph's stream, copy 1 + k to side stream k
-  constexpr int NS = sr_graph::kTrainSides;
+  constexpr int NS = SrTrainState::kSides;
   size_t pooled_at[1 + NS], mean_at[1 + NS], part_at[1 + NS];
   for (int k = 0; k <= NS; ++k) {
     pooled_at[k] = take(pooled_n);
@@ -101,36 +140,36 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   }
   const size_t dmean_at = take(mean_n);
   const size_t terms_at = take((size_t)W * B);
-  if (at > g->train_arena_floats) {
+  if (at > T.arena_floats) {
     SR_HIP(g, hipStreamSynchronize(g->stream));
     drop_train_graph(g);   // its launches name the old arena
-    if (g->train_arena) SR_HIP(g, hipFree(g->train_arena));
-    g->train_arena = nullptr;
-    g->train_arena_floats = 0;
+    if (T.arena) SR_HIP(g, hipFree(T.arena));
+    T.arena = nullptr;
+    T.arena_floats = 0;
     void* p = nullptr;
     SR_HIP(g, hipMalloc(&p, at * sizeof(float)));
-    g->train_arena = (float*)p;
-    g->train_arena_floats = at;
+    T.arena = (float*)p;
+    T.arena_floats = at;
   }
-  float* A = g->train_arena;
+  float* A = T.arena;
   hipStream_t s = g->stream;
-  if (!g->train_ev_main) SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_main, hipEventDisableTiming));
+  if (!T.ev_main) SR_HIP(g, hipEventCreateWithFlags(&T.ev_main, hipEventDisableTiming));
   for (int k = 0; k < NS; ++k) {
-    if (!g->train_side[k]) SR_HIP(g, hipStreamCreateWithFlags(&g->train_side[k], hipStreamNonBlocking));
-    if (!g->train_ev_side[k]) SR_HIP(g, hipEventCreateWithFlags(&g->train_ev_side[k], hipEventDisableTiming));
+    if (!T.side[k]) SR_HIP(g, hipStreamCreateWithFlags(&T.side[k], hipStreamNonBlocking));
+    if (!T.ev_side[k]) SR_HIP(g, hipEventCreateWithFlags(&T.ev_side[k], hipEventDisableTiming));
   }
   // stream 0 is the graph's, 1 + k side stream k; fork: the side streams take up after what the graph's stream
   // holds so far; join: the graph's stream takes up after all of them
-  auto stream_of = [&](int k) { return k == 0 ? s : g->train_side[k - 1]; };
+  auto stream_of = [&](int k) { return k == 0 ? s : T.side[k - 1]; };
   auto fork = [&]() -> sr_status {
-    SR_HIP(g, hipEventRecord(g->train_ev_main, s));
-    for (int k = 0; k < NS; ++k) SR_HIP(g, hipStreamWaitEvent(g->train_side[k], g->train_ev_main, 0));
+    SR_HIP(g, hipEventRecord(T.ev_main, s));
+    for (int k = 0; k < NS; ++k) SR_HIP(g, hipStreamWaitEvent(T.side[k], T.ev_main, 0));
     return SR_OK;
   };
   auto join = [&]() -> sr_status {
     for (int k = 0; k < NS; ++k) {
-      SR_HIP(g, hipEventRecord(g->train_ev_side[k], g->train_side[k]));
-      SR_HIP(g, hipStreamWaitEvent(s, g->train_ev_side[k], 0));
+      SR_HIP(g, hipEventRecord(T.ev_side[k], T.side[k]));
+      SR_HIP(g, hipStreamWaitEvent(s, T.ev_side[k], 0));
     }
     return SR_OK;
   };
@@ -306,21 +345,21 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   key.push_back(loss);
   for (int e = 0; e < g->n_edges; ++e) key.push_back(dtheta[e]);
   for (int v = 0; v < N; ++v) key.push_back(dbias ? (const void*)dbias[v] : nullptr);
-  if (!g->train_exec || key != g->train_key) {
+  if (!T.exec || key != T.key) {
     drop_train_graph(g);
     SR_HIP(g, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
     const sr_status st = enqueue();
-    const hipError_t e = hipStreamEndCapture(s, &g->train_graph);
+    const hipError_t e = hipStreamEndCapture(s, &T.graph);
     if (st != SR_OK || e != hipSuccess) {
-      if (g->train_graph) hipGraphDestroy(g->train_graph);
-      g->train_graph = nullptr;
+      if (T.graph) hipGraphDestroy(T.graph);
+      T.graph = nullptr;
       if (st != SR_OK) return st;
       SR_HIP(g, e);
     }
-    SR_HIP(g, hipGraphInstantiate(&g->train_exec, g->train_graph, nullptr, nullptr, 0));
-    g->train_key = key;
+    SR_HIP(g, hipGraphInstantiate(&T.exec, T.graph, nullptr, nullptr, 0));
+    T.key = key;
   }
-  SR_HIP(g, hipGraphLaunch(g->train_exec, s));
+  SR_HIP(g, hipGraphLaunch(T.exec, s));
   return SR_OK;
 }
 
@@ -333,9 +372,10 @@ sr_status sr_rmsprop_step(sr_graph* g, float lr, float rho, float eps, const flo
     if (!dtheta[e]) return sr_gfail(g, SR_ERR_ARG, "sr_rmsprop_step: dtheta[" + std::to_string(e) + "] is null");
     if (!g->edges[e].has_w) return sr_gfail(g, SR_ERR_STATE, "edge " + std::to_string(e) + " has no weights");
   }
-  if (g->rms_w.empty()) {
-    g->rms_w.assign(g->n_edges, nullptr);
-    g->rms_b.assign(g->n_nodes, nullptr);
+  SrTrainState& T = train_state(g);
+  if (T.rms_w.empty()) {
+    T.rms_w.assign(g->n_edges, nullptr);
+    T.rms_b.assign(g->n_nodes, nullptr);
   }
   auto running = [&](float** slot, size_t n) -> sr_status {
     if (*slot) return SR_OK;
@@ -347,17 +387,17 @@ sr_status sr_rmsprop_step(sr_graph* g, float lr, float rho, float eps, const flo
     return SR_OK;
   };
   for (int e = 0; e < g->n_edges; ++e) {
-    sr_status st = running(&g->rms_w[e], g->edges[e].w_count);
+    sr_status st = running(&T.rms_w[e], g->edges[e].w_count);
     if (st != SR_OK) return st;
-    SR_HIP(g, sr_train_rmsprop(g->stream, g->edges[e].w_dev, g->rms_w[e], dtheta[e], g->edges[e].w_count, lr, rho, eps));
+    SR_HIP(g, sr_train_rmsprop(g->stream, g->edges[e].w_dev, T.rms_w[e], dtheta[e], g->edges[e].w_count, lr, rho, eps));
   }
   if (dbias)
     for (int v = 0; v < g->n_nodes; ++v) {
       if (g->an.is_input[v] || !dbias[v]) continue;
       const size_t n = (size_t)g->nodes[v].d.channels;
-      sr_status st = running(&g->rms_b[v], n);
+      sr_status st = running(&T.rms_b[v], n);
       if (st != SR_OK) return st;
-      SR_HIP(g, sr_train_rmsprop(g->stream, g->nodes[v].bias_dev, g->rms_b[v], dbias[v], n, lr, rho, eps));
+      SR_HIP(g, sr_train_rmsprop(g->stream, g->nodes[v].bias_dev, T.rms_b[v], dbias[v], n, lr, rho, eps));
     }
   return SR_OK;
 }
