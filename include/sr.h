@@ -106,12 +106,17 @@ typedef enum {
                                   (default 2^18, about 0.3 s; 0..2^24).  A wait that gives up lets its work item go
                                   on with whatever is in memory and is counted by sr_graph_health; every kernel
                                   still ends normally.  For tests of that path. */
-  SR_OPT_FLOW_ORDER = 7        /* dependency-driven launches that cover several frames (sr_rollout):
+  SR_OPT_FLOW_ORDER = 7,       /* dependency-driven launches that cover several frames (sr_rollout):
                                   1 (default): the work items of all their frames are dispatched in the order of
                                   their depth in the rollout window of those frames (the inference tableau of Eq. 5
                                   taken over update steps of all the frames), so that update steps of consecutive
                                   frames that do not depend on one another run side by side;
                                   0: frame after frame */
+  SR_OPT_TRAIN_TALL_TILES_FROM = 8
+                               /* training window (sr_window_gradients): a contraction takes the taller of its two
+                                  tile shapes when that launch has at least this many workgroups, else the shorter
+                                  one (default 2048; 0: always the taller, 2^30: never).  Same results either way
+                                  up to the order of no sum; for tests of both shapes and for tuning. */
 } sr_option;
 
 /* ---------------------------------------------------------------------------

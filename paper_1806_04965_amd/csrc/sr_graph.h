@@ -127,6 +127,7 @@ struct sr_graph {
   // what the training window keeps between calls (arena, side streams, captured graph, RMSprop's running means):
   // made on first use and released by sr_train_state_release, both in sr_train_host.cpp
   struct SrTrainState* train = nullptr;
+  int train_tall_from = 2048;   // SR_OPT_TRAIN_TALL_TILES_FROM
 
   hipGraph_t graph1 = nullptr, graphN = nullptr;
   hipGraphExec_t exec1 = nullptr, execN = nullptr;

@@ -1982,6 +1982,10 @@ sr_status sr_graph_configure(sr_graph* g, int32_t option, int64_t value) {
     case SR_OPT_FLOW_ORDER:
       g->flow_depth_order = value != 0;
       return SR_OK;
+    case SR_OPT_TRAIN_TALL_TILES_FROM:
+      if (value < 0 || value > (1 << 30)) return gfail(g, SR_ERR_ARG, "tall-tile threshold must be in 0..2^30");
+      g->train_tall_from = (int)value;
+      return SR_OK;
     case SR_OPT_DEP_SPIN_LIMIT:
       if (value < 0 || value > (1 << 24)) return gfail(g, SR_ERR_ARG, "spin limit of dependency waits must be in 0..2^24");
       g->dep_spin_limit = (int)value;

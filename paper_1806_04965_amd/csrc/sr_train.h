@@ -18,6 +18,7 @@ struct SrConvGeom {   // y[b][ho][wo][co] = sum x[b][ho*stride + i - pad][wo*str
   // divisions by Wo, Ho*Wo, Cout, Cin and kw as multiply-high, add, shift (exact for dividends below 2^31);
   // filled by the launchers of the tiled kernels
   uint32_t mul_wo, sh_wo, mul_howo, sh_howo, mul_cout, sh_cout, mul_cin, sh_cin, mul_kw, sh_kw;
+  int tall_from;   // host side only: workgroups from which a launch takes the taller tile shape
 };
 #define SR_TRAIN_TILED_MIN_MACS 1.0e6   // smaller contractions stay on the one-thread-per-output kernels
 #define SR_TRAIN_MAX_SLICES 256  // a weight gradient's pixel sum is cut into at most this many partial sums

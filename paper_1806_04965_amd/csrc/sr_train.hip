@@ -690,16 +690,16 @@ static SrConvGeom sr_with_divisors(const SrConvGeom& q) {
 }
 
 // Tile shape of a contraction with I rows and J columns in `planes` grid planes: the narrowest column tile that
-// holds J, then the taller row tile only where the launch still has some thousands of workgroups (a launch of few
-// tall tiles is a few long dependent chains on an otherwise idle chip; on the measured windows the smaller tile
-// was the faster or equal one for every launch below that)
+// holds J, then the taller row tile only where the launch still has tall_from workgroups, some thousands by
+// default (a launch of few tall tiles is a few long dependent chains on an otherwise idle chip; on the measured
+// windows the smaller tile was the faster or equal one for every launch below that)
 struct SrTileShape { int ti, tj, wjn; };
-static SrTileShape sr_pick_tile(long long I, long long J, long long planes) {
+static SrTileShape sr_pick_tile(long long I, long long J, long long planes, int tall_from) {
   static const SrTileShape wide[] = {{128, 128, 2}, {64, 64, 2}}, mid[] = {{128, 64, 2}, {64, 64, 2}},
                            slim[] = {{256, 32, 1}, {128, 32, 1}};
   const SrTileShape* c = J <= 32 ? slim : (J <= 64 ? mid : wide);
   const long long first = (I + c[0].ti - 1) / c[0].ti * ((J + c[0].tj - 1) / c[0].tj) * planes;
-  return first >= 2048 ? c[0] : c[1];
+  return first >= tall_from ? c[0] : c[1];
 }
 template <int MODE>
 static hipError_t sr_launch_gemm(hipStream_t s, SrTileShape ts, int planes, const SrConvGeom& q, const float* pa,
@@ -752,7 +752,7 @@ hipError_t sr_train_dgrad(hipStream_t s, const SrConvGeom& q, const float* theta
     const int Hp = (q.H + q.stride - 1) / q.stride, Wp = (q.W + q.stride - 1) / q.stride;
     const int I = q.B * Hp * Wp, J = q.Cin;
     const int planes = q.stride * q.stride;
-    return sr_launch_gemm<0>(s, sr_pick_tile(I, J, planes), planes, sr_with_divisors(q), dy, theta, dx, I, J, 0, 0, accumulate);
+    return sr_launch_gemm<0>(s, sr_pick_tile(I, J, planes, q.tall_from), planes, sr_with_divisors(q), dy, theta, dx, I, J, 0, 0, accumulate);
   }
   hipLaunchKernelGGL(sr_dgrad_kernel, dim3(grid_for(n, 256)), dim3(256), 0, s, q, theta, dy, dx, accumulate);
   return hipGetLastError();
@@ -768,7 +768,7 @@ hipError_t sr_train_fwd(hipStream_t s, const SrConvGeom& q, const float* x, cons
   if (sr_fwd_tiled(q)) {
     const SrConvGeom p = sr_with_divisors(q);
     const int I = q.B * q.Ho * q.Wo, J = q.Cout, R = q.kh * q.kw * q.Cin;
-    return sr_launch_gemm<2>(s, sr_pick_tile(I, J, 1), 1, p, x, theta, y, I, J, R, R, accumulate);
+    return sr_launch_gemm<2>(s, sr_pick_tile(I, J, 1, q.tall_from), 1, p, x, theta, y, I, J, R, R, accumulate);
   }
   const long long n = (long long)q.B * q.Ho * q.Wo * q.Cout;
   if (q.Cout <= 32 && n / q.Cout <= 65536 && (long long)q.kh * q.kw * q.Cin >= 1024) {   // a workgroup per output pixel
@@ -821,8 +821,8 @@ hipError_t sr_train_wgrad(hipStream_t s, const SrConvGeom& q, const float* x, co
     const int per = ((M + slices - 1) / slices + SR_GR - 1) / SR_GR * SR_GR;
     const int used = (M + per - 1) / per;
     if (used == 1)   // one slice: straight onto the gradient
-      return sr_launch_gemm<1>(s, sr_pick_tile(I, J, 1), 1, sr_with_divisors(q), x, dy, dtheta, I, J, M, per, 1);
-    hipError_t e = sr_launch_gemm<1>(s, sr_pick_tile(I, J, used), used, sr_with_divisors(q), x, dy, part, I, J, M, per, 0);
+      return sr_launch_gemm<1>(s, sr_pick_tile(I, J, 1, q.tall_from), 1, sr_with_divisors(q), x, dy, dtheta, I, J, M, per, 1);
+    hipError_t e = sr_launch_gemm<1>(s, sr_pick_tile(I, J, used, q.tall_from), used, sr_with_divisors(q), x, dy, part, I, J, M, per, 0);
     if (e != hipSuccess) return e;
     hipLaunchKernelGGL(sr_add_slices_kernel, dim3(grid_for(nw, 64)), dim3(256), 0, s, part, (size_t)nw, used, dtheta);
     return hipGetLastError();

@@ -92,7 +92,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     const sr_node_desc& s = g->nodes[e.d.src].d;
     const sr_node_desc& d = g->nodes[e.d.dst].d;
     SrConvGeom q{};
-    q.B = B; q.Cin = s.channels; q.Cout = d.channels;
+    q.B = B; q.Cin = s.channels; q.Cout = d.channels; q.tall_from = g->train_tall_from;
     if (e.d.kind == SR_EDGE_CONV) {
       q.H = s.height; q.W = s.width; q.kh = e.kh; q.kw = e.kw; q.stride = e.d.stride; q.pad = e.d.pad;
       q.Ho = d.height / e.d.upsample; q.Wo = d.width / e.d.upsample;
