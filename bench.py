@@ -85,7 +85,11 @@ def train_window_bench(args, g):
     B = g.batch
     w, b, x = W.make_case(g, seed=0, frames=Wn, bias_scale=0.1)
     labels_h = np.random.default_rng(1).integers(0, g.nodes[g.out_node].channels, B).astype(np.int32)
-    dev = sr.SrGraph(g)
+    opts = {0: 0} if args.no_hipgraph else {}
+    for kv in args.option:
+        k, v = kv.split("=")
+        opts[int(k)] = int(v)
+    dev = sr.SrGraph(g, options=opts or None)
     dev.set_parameters(w, b)
     ins = g.input_nodes()
     xin = [torch.from_numpy(x[v][:Wn + 1]).to("cuda").float().contiguous() for v in ins]

@@ -490,6 +490,259 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
       }
 }
 
+// The same contraction for channel counts that are multiples of four: every operand is gathered 16 bytes at a
+// time along its channel axis (a quarter of the loads and of the address arithmetic).  Operands whose channel
+// axis is the reduction index (A of the forward and of the state gradient, B of the state gradient) lie in LDS row
+// by row, a row's 16 reduction indices side by side, so a gather is one 16-byte LDS write and a wave reads its
+// operand for a whole step with two 16-byte reads; the others (channel axis = tile row or column) lie reduction
+// index by reduction index as above.  Reduction index of MFMA kk in lane half h: 8 h + kk.
+typedef float sr_f32x4 __attribute__((ext_vector_type(4)));
+__device__ __align__(16) const float sr_zero_quad[4] = {0.f, 0.f, 0.f, 0.f};
+
+template <int MODE, int TI, int TJ, int WJN>
+__global__ __launch_bounds__(256, 2) void sr_conv_gemm4_kernel(SrConvGeom q, const float* __restrict__ pa,
+                                                               const float* __restrict__ pb, float* __restrict__ pc,
+                                                               int I, int J, int R, int r_per_slice, int accumulate) {
+  constexpr int WIN = 4 / WJN;
+  constexpr int MI = TI / (32 * WIN), MJ = TJ / (32 * WJN);
+  constexpr int NAV = TI / 64;                    // 16-byte pieces of A a thread gathers per step
+  constexpr int NBV = TJ >= 64 ? TJ / 64 : 1;     // ... of B (a 32-wide tile: half the threads, one piece each)
+  constexpr bool A_ROWS = MODE != 1, B_ROWS = MODE == 0;
+  constexpr int RP = SR_GR + 4;                   // pitch of a row-by-row operand: eight lanes' 16-byte reads hit eight columns
+  static_assert(MI >= 1 && MJ >= 1 && MI * 32 * WIN == TI && MJ * 32 * WJN == TJ && NAV >= 1, "tile shape");
+  __shared__ __align__(16) float As[A_ROWS ? TI * RP : SR_GR * (TI + 4)];
+  __shared__ __align__(16) float Bs[B_ROWS ? TJ * RP : SR_GR * (TJ + 4)];
+  const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
+  const int i0 = blockIdx.x * TI, j0 = blockIdx.y * TJ;
+  if (MODE == 0) {   // blockIdx.z = phase of the source pixels, as in sr_conv_gemm_kernel
+    q.ph = blockIdx.z / q.stride;
+    q.pw = blockIdx.z % q.stride;
+    q.Hp = (q.H - q.ph + q.stride - 1) / q.stride;
+    q.Wp = (q.W - q.pw + q.stride - 1) / q.stride;
+    q.ti0 = (q.ph + q.pad) % q.stride;
+    q.tj0 = (q.pw + q.pad) % q.stride;
+    q.nti = q.ti0 < q.kh ? (q.kh - q.ti0 + q.stride - 1) / q.stride : 0;
+    q.ntj = q.tj0 < q.kw ? (q.kw - q.tj0 + q.stride - 1) / q.stride : 0;
+    I = q.B * max(q.Hp, 0) * max(q.Wp, 0);
+    R = q.nti * q.ntj * q.Cout;
+    r_per_slice = R;
+    if (i0 >= I || (R == 0 && accumulate)) return;
+  }
+  const int r_begin = (MODE == 1) ? blockIdx.z * r_per_slice : 0;
+  const int r_end = min(R, r_begin + r_per_slice);
+  const int wi = wave / WJN, wj = wave % WJN;
+
+  constexpr int FAR = 1 << 20;
+  // MODE 0, 2: a thread's A pieces are reduction indices 4 (t % 4) .. + 3 of the rows t / 4 + 64 n
+  // MODE 1:    rows 4 (t % (TI / 4)) .. + 3 at the reduction indices t / (TI / 4) + (1024 / TI) n
+  int ah[NAV], aw[NAV], aoff[NAV];
+  int ati = 0, atj = 0, a1off = 0;
+  uint32_t mul_wp = 0, sh_wp = 0, mul_hpwp = 0, sh_hpwp = 0, mul_ntj = 0, sh_ntj = 0;
+  if (MODE == 2) {
+#pragma unroll
+    for (int n = 0; n < NAV; ++n) {
+      const int i = i0 + (t >> 2) + 64 * n;
+      const int b = sr_fdiv(i, q.mul_howo, q.sh_howo), rem = i - b * (q.Ho * q.Wo);
+      const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo), wo = rem - ho * q.Wo;
+      ah[n] = (i < I) ? ho * q.stride - q.pad : FAR;
+      aw[n] = wo * q.stride - q.pad;
+      aoff[n] = (((b * q.H + ho * q.stride - q.pad) * q.W + aw[n]) * q.Cin) * 4;
+    }
+  } else if (MODE == 0) {
+    const int lgs = (q.stride == 1) ? 0 : (q.stride == 2 ? 1 : (q.stride == 4 ? 2 : -1));
+    sr_fdiv_make((uint32_t)max(q.Wp, 1), &mul_wp, &sh_wp);
+    sr_fdiv_make((uint32_t)max(q.Wp * q.Hp, 1), &mul_hpwp, &sh_hpwp);
+    sr_fdiv_make((uint32_t)max(q.ntj, 1), &mul_ntj, &sh_ntj);
+#pragma unroll
+    for (int n = 0; n < NAV; ++n) {
+      const int i = i0 + (t >> 2) + 64 * n;
+      const int b = sr_fdiv(i, mul_hpwp, sh_hpwp), rem = i - b * (q.Wp * q.Hp);
+      const int hh = sr_fdiv(rem, mul_wp, sh_wp), ww = rem - hh * q.Wp;
+      const int hn = hh * q.stride + q.ph + q.pad - q.ti0, wn = ww * q.stride + q.pw + q.pad - q.tj0;
+      const int hq = lgs >= 0 ? hn >> lgs : hn / q.stride, wq = lgs >= 0 ? wn >> lgs : wn / q.stride;
+      ah[n] = (i < I) ? hq : -FAR;
+      aw[n] = wq;
+      aoff[n] = (((b * q.Ho + hq) * q.Wo + wq) * q.Cout) * 4;
+    }
+  } else {
+    const int i = i0 + 4 * (t % (TI / 4));
+    const int tap = sr_fdiv(i, q.mul_cin, q.sh_cin), ci = i - tap * q.Cin;
+    ati = sr_fdiv(tap, q.mul_kw, q.sh_kw);
+    atj = tap - ati * q.kw;
+    a1off = (((ati * q.W + atj) * q.Cin) + ci) * 4;
+    if (i >= I) ati = FAR;
+  }
+  // B: byte offset of the thread's first piece at reduction index 0, and whether the thread has a piece at all
+  int boff = 0;
+  bool b_ok = false;
+  if (MODE == 0) {
+    const int j = j0 + (t >> 2);                 // theta[tap][j][co .. co + 3]: + 64 n Cout per piece, + (tap Cin Cout + co) per step
+    boff = j * q.Cout * 4;
+    b_ok = (t >> 2) < TJ;
+  } else {
+    const int j = j0 + 4 * (t % (TJ / 4));       // [r][j .. j + 3] with Cout columns
+    b_ok = j < J && t / (TJ / 4) < SR_GR;
+    boff = ((t / (TJ / 4)) * q.Cout + j) * 4;
+  }
+
+  sr_f32x16 acc[MI][MJ];
+#pragma unroll
+  for (int x = 0; x < MI; ++x)
+#pragma unroll
+    for (int y = 0; y < MJ; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[x][y][v] = 0.f;
+
+  auto at4 = [](const float* base, bool ok, int byte_off) {
+    typedef const __attribute__((address_space(1))) sr_f32x4* global_ptr;
+    const global_ptr p = ok ? (global_ptr)((const char*)base + (uint32_t)byte_off) : (global_ptr)sr_zero_quad;
+    return *p;
+  };
+  auto gather = [&](int rs, sr_f32x4 (&va)[NAV], sr_f32x4 (&vb)[NBV]) {
+    if (MODE == 2) {
+      const int r = rs + 4 * (t & 3);
+      const int tap = sr_fdiv(r, q.mul_cin, q.sh_cin), ci = r - tap * q.Cin;
+      int ti = sr_fdiv(tap, q.mul_kw, q.sh_kw);
+      const int tj = tap - ti * q.kw;
+      const int toff = ((ti * q.W + tj) * q.Cin + ci) * 4;
+      if (r >= r_end) ti = FAR;
+#pragma unroll
+      for (int n = 0; n < NAV; ++n) {
+        const bool ok = (unsigned)(ah[n] + ti) < (unsigned)q.H && (unsigned)(aw[n] + tj) < (unsigned)q.W;
+        va[n] = at4(pa, ok, aoff[n] + toff);
+      }
+      const int sb = boff + rs * q.Cout * 4;
+#pragma unroll
+      for (int n = 0; n < NBV; ++n) {
+        const bool okb = b_ok && rs + t / (TJ / 4) + (1024 / TJ) * n < r_end;
+        vb[n] = at4(pb, okb, sb + n * (1024 / TJ) * q.Cout * 4);
+      }
+    } else if (MODE == 0) {
+      const int r = rs + 4 * (t & 3);
+      const bool r_ok = r < r_end;
+      const int vt = sr_fdiv(r, q.mul_cout, q.sh_cout), co = r - vt * q.Cout;
+      int vi = sr_fdiv(vt, mul_ntj, sh_ntj);
+      const int vj = vt - vi * q.ntj;
+      const int tap = (q.ti0 + vi * q.stride) * q.kw + q.tj0 + vj * q.stride;
+      const int toff = (co - (vi * q.Wo + vj) * q.Cout) * 4;
+      if (!r_ok) vi = 2 * FAR;
+#pragma unroll
+      for (int n = 0; n < NAV; ++n) {
+        const bool ok = (unsigned)(ah[n] - vi) < (unsigned)q.Ho && (unsigned)(aw[n] - vj) < (unsigned)q.Wo;
+        va[n] = at4(pa, ok, aoff[n] + toff);
+      }
+      const int sb = boff + (tap * q.Cin * q.Cout + co) * 4;
+#pragma unroll
+      for (int n = 0; n < NBV; ++n) {
+        const bool okb = b_ok && r_ok && j0 + (t >> 2) + 64 * n < J;
+        vb[n] = at4(pb, okb, sb + n * 64 * q.Cout * 4);
+      }
+    } else {
+#pragma unroll
+      for (int n = 0; n < NAV; ++n) {
+        const int r = rs + t / (TI / 4) + (1024 / TI) * n;
+        const int b = sr_fdiv(r, q.mul_howo, q.sh_howo), rem = r - b * (q.Ho * q.Wo);
+        const int ho = sr_fdiv(rem, q.mul_wo, q.sh_wo), wo = rem - ho * q.Wo;
+        const int h0 = (r < r_end) ? ho * q.stride - q.pad : FAR, w0 = wo * q.stride - q.pad;
+        const int sbase = (((b * q.H + ho * q.stride - q.pad) * q.W + w0) * q.Cin) * 4;
+        const bool ok = (unsigned)(h0 + ati) < (unsigned)q.H && (unsigned)(w0 + atj) < (unsigned)q.W;
+        va[n] = at4(pa, ok, sbase + a1off);
+      }
+      const int sb = boff + rs * q.Cout * 4;
+#pragma unroll
+      for (int n = 0; n < NBV; ++n) {
+        const bool okb = b_ok && rs + t / (TJ / 4) + (1024 / TJ) * n < r_end;
+        vb[n] = at4(pb, okb, sb + n * (1024 / TJ) * q.Cout * 4);
+      }
+    }
+  };
+  auto step = [&](int rs, sr_f32x4 (&va)[NAV], sr_f32x4 (&vb)[NBV]) {
+    __syncthreads();
+    if (A_ROWS) {
+#pragma unroll
+      for (int n = 0; n < NAV; ++n) *(sr_f32x4*)&As[((t >> 2) + 64 * n) * RP + 4 * (t & 3)] = va[n];
+    } else {
+#pragma unroll
+      for (int n = 0; n < NAV; ++n) *(sr_f32x4*)&As[(t / (TI / 4) + (1024 / TI) * n) * (TI + 4) + 4 * (t % (TI / 4))] = va[n];
+    }
+    if (B_ROWS) {
+#pragma unroll
+      for (int n = 0; n < NBV; ++n)
+        if ((t >> 2) + 64 * n < TJ) *(sr_f32x4*)&Bs[((t >> 2) + 64 * n) * RP + 4 * (t & 3)] = vb[n];
+    } else {
+#pragma unroll
+      for (int n = 0; n < NBV; ++n)
+        if (t / (TJ / 4) + (1024 / TJ) * n < SR_GR)
+          *(sr_f32x4*)&Bs[(t / (TJ / 4) + (1024 / TJ) * n) * (TJ + 4) + 4 * (t % (TJ / 4))] = vb[n];
+    }
+    __syncthreads();
+    gather(rs + 2 * SR_GR, va, vb);   // unconditional: see sr_conv_gemm_kernel
+    const int h8 = (lane >> 5) * 8;
+    float a[MI][8], b[MJ][8];
+#pragma unroll
+    for (int x = 0; x < MI; ++x) {
+      const int row = wi * 32 * MI + 32 * x + (lane & 31);
+      if (A_ROWS) {
+        const sr_f32x4 lo = *(const sr_f32x4*)&As[row * RP + h8], hi = *(const sr_f32x4*)&As[row * RP + h8 + 4];
+        a[x][0] = lo.x; a[x][1] = lo.y; a[x][2] = lo.z; a[x][3] = lo.w;
+        a[x][4] = hi.x; a[x][5] = hi.y; a[x][6] = hi.z; a[x][7] = hi.w;
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) a[x][kk] = As[(h8 + kk) * (TI + 4) + row];
+      }
+    }
+#pragma unroll
+    for (int y = 0; y < MJ; ++y) {
+      const int col = wj * 32 * MJ + 32 * y + (lane & 31);
+      if (B_ROWS) {
+        const sr_f32x4 lo = *(const sr_f32x4*)&Bs[col * RP + h8], hi = *(const sr_f32x4*)&Bs[col * RP + h8 + 4];
+        b[y][0] = lo.x; b[y][1] = lo.y; b[y][2] = lo.z; b[y][3] = lo.w;
+        b[y][4] = hi.x; b[y][5] = hi.y; b[y][6] = hi.z; b[y][7] = hi.w;
+      } else {
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) b[y][kk] = Bs[(h8 + kk) * (TJ + 4) + col];
+      }
+    }
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+#pragma unroll
+      for (int x = 0; x < MI; ++x)
+#pragma unroll
+        for (int y = 0; y < MJ; ++y)
+          acc[x][y] = __builtin_amdgcn_mfma_f32_32x32x2f32(a[x][kk], b[y][kk], acc[x][y], 0, 0, 0);
+  };
+  sr_f32x4 va0[NAV], vb0[NBV], va1[NAV], vb1[NBV];
+  gather(r_begin, va0, vb0);
+  __builtin_amdgcn_sched_barrier(0);
+  gather(r_begin + SR_GR, va1, vb1);
+  int rs = r_begin;
+  for (; rs + SR_GR < r_end; rs += 2 * SR_GR) {
+    step(rs, va0, vb0);
+    step(rs + SR_GR, va1, vb1);
+  }
+  if (rs < r_end) step(rs, va0, vb0);
+  float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
+#pragma unroll
+  for (int x = 0; x < MI; ++x)
+#pragma unroll
+    for (int y = 0; y < MJ; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = i0 + wi * 32 * MI + x * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int j = j0 + wj * 32 * MJ + y * 32 + (lane & 31);
+        if (i < I && j < J) {
+          size_t row = (size_t)i;
+          if (MODE == 0) {
+            const int b = sr_fdiv(i, mul_hpwp, sh_hpwp), rem = i - b * (q.Wp * q.Hp);
+            const int hh = sr_fdiv(rem, mul_wp, sh_wp), ww = rem - hh * q.Wp;
+            row = ((size_t)b * q.H + hh * q.stride + q.ph) * q.W + ww * q.stride + q.pw;
+          }
+          float* dst = out + row * J + j;
+          *dst = accumulate ? *dst + acc[x][y][v] : acc[x][y][v];
+        }
+      }
+}
+
 // forward of one edge, one thread per output element: y[b][ho][wo][co] (+)= sum x * theta
 __global__ void sr_fwd_kernel(SrConvGeom q, const float* __restrict__ x, const float* __restrict__ theta,
                               float* __restrict__ y, int accumulate) {
@@ -705,10 +958,15 @@ template <int MODE>
 static hipError_t sr_launch_gemm(hipStream_t s, SrTileShape ts, int planes, const SrConvGeom& q, const float* pa,
                                  const float* pb, float* pc, int I, int J, int R, int per, int accumulate) {
   const dim3 grid((I + ts.ti - 1) / ts.ti, (J + ts.tj - 1) / ts.tj, planes);
+  const bool quads = q.Cin % 4 == 0 && q.Cout % 4 == 0;   // every channel axis in 16-byte pieces
 #define SR_GEMM_CASE(TI, TJ, WJN)                                                                                    \
   if (ts.ti == TI && ts.tj == TJ && ts.wjn == WJN) {                                                                 \
-    hipLaunchKernelGGL((sr_conv_gemm_kernel<MODE, TI, TJ, WJN>), grid, dim3(256), 0, s, q, pa, pb, pc, I, J, R, per, \
-                       accumulate);                                                                                  \
+    if (quads)                                                                                                       \
+      hipLaunchKernelGGL((sr_conv_gemm4_kernel<MODE, TI, TJ, WJN>), grid, dim3(256), 0, s, q, pa, pb, pc, I, J, R,   \
+                         per, accumulate);                                                                           \
+    else                                                                                                             \
+      hipLaunchKernelGGL((sr_conv_gemm_kernel<MODE, TI, TJ, WJN>), grid, dim3(256), 0, s, q, pa, pb, pc, I, J, R,    \
+                         per, accumulate);                                                                           \
     return hipGetLastError();                                                                                        \
   }
   SR_GEMM_CASE(128, 128, 2)

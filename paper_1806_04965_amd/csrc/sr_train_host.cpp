@@ -23,24 +23,41 @@ struct SrTrainState {
   // side streams (nodes of one update step of the forward pass; bias and weight gradients of the reverse sweep
   // beside the chain of state gradients) and the events that order them against the graph's stream
   static constexpr int kSides = 3;
+  struct Events {
+    hipEvent_t main = nullptr, side[kSides] = {nullptr, nullptr, nullptr};
+  };
   hipStream_t side[kSides] = {nullptr, nullptr, nullptr};
-  hipEvent_t ev_main = nullptr, ev_side[kSides] = {nullptr, nullptr, nullptr};
-  // the launches of one window, captured: replayed while a call names the same window size, output node and
-  // buffers (key holds them) and the arena has not moved
-  hipGraph_t graph = nullptr;
-  hipGraphExec_t exec = nullptr;
-  std::vector<const void*> key;
+  Events plain;   // of calls that launch every kernel themselves
+  // The launches of one window, captured: replayed while a call names the same window size, output node and
+  // buffers (key) and the arena has not moved (live).  A capture has events of its own, and nothing captured is
+  // destroyed before the graph object is: an event recorded during a capture stays tied to that capture.  After
+  // kMaxCaptured captures further new keys are launched plainly.
+  struct Captured {
+    std::vector<const void*> key;
+    hipGraph_t graph = nullptr;
+    hipGraphExec_t exec = nullptr;
+    Events ev;
+    bool live = false;
+  };
+  static constexpr size_t kMaxCaptured = 16;
+  std::vector<Captured> captured;
 };
 
 void sr_train_state_release(SrTrainState* t) {
   if (!t) return;
-  if (t->exec) hipGraphExecDestroy(t->exec);
-  if (t->graph) hipGraphDestroy(t->graph);
-  for (int k = 0; k < SrTrainState::kSides; ++k) {
-    if (t->side[k]) { hipStreamSynchronize(t->side[k]); hipStreamDestroy(t->side[k]); }
-    if (t->ev_side[k]) hipEventDestroy(t->ev_side[k]);
+  auto drop_events = [](SrTrainState::Events& e) {
+    if (e.main) hipEventDestroy(e.main);
+    for (int k = 0; k < SrTrainState::kSides; ++k)
+      if (e.side[k]) hipEventDestroy(e.side[k]);
+  };
+  for (SrTrainState::Captured& c : t->captured) {
+    if (c.exec) hipGraphExecDestroy(c.exec);
+    if (c.graph) hipGraphDestroy(c.graph);
+    drop_events(c.ev);
   }
-  if (t->ev_main) hipEventDestroy(t->ev_main);
+  drop_events(t->plain);
+  for (int k = 0; k < SrTrainState::kSides; ++k)
+    if (t->side[k]) { hipStreamSynchronize(t->side[k]); hipStreamDestroy(t->side[k]); }
   if (t->arena) hipFree(t->arena);
   delete t;
 }
@@ -52,14 +69,16 @@ SrTrainState& train_state(sr_graph* g) {
   return *g->train;
 }
 
-void drop_train_graph(sr_graph* g) {
-  SrTrainState& T = train_state(g);
-  if (T.exec) hipStreamSynchronize(g->stream);   // a replay may still be running
-  if (T.exec) hipGraphExecDestroy(T.exec);
-  if (T.graph) hipGraphDestroy(T.graph);
-  T.exec = nullptr;
-  T.graph = nullptr;
-  T.key.clear();
+// the arena has moved: what was captured names the old one and is never launched again
+void retire_captured(sr_graph* g) {
+  for (SrTrainState::Captured& c : train_state(g).captured) c.live = false;
+}
+
+sr_status make_events(sr_graph* g, SrTrainState::Events* e) {
+  if (!e->main) SR_HIP(g, hipEventCreateWithFlags(&e->main, hipEventDisableTiming));
+  for (int k = 0; k < SrTrainState::kSides; ++k)
+    if (!e->side[k]) SR_HIP(g, hipEventCreateWithFlags(&e->side[k], hipEventDisableTiming));
+  return SR_OK;
 }
 
 }  // namespace
@@ -142,7 +161,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   const size_t terms_at = take((size_t)W * B);
   if (at > T.arena_floats) {
     SR_HIP(g, hipStreamSynchronize(g->stream));
-    drop_train_graph(g);   // its launches name the old arena
+    retire_captured(g);
     if (T.arena) SR_HIP(g, hipFree(T.arena));
     T.arena = nullptr;
     T.arena_floats = 0;
@@ -153,23 +172,21 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   }
   float* A = T.arena;
   hipStream_t s = g->stream;
-  if (!T.ev_main) SR_HIP(g, hipEventCreateWithFlags(&T.ev_main, hipEventDisableTiming));
-  for (int k = 0; k < NS; ++k) {
+  for (int k = 0; k < NS; ++k)
     if (!T.side[k]) SR_HIP(g, hipStreamCreateWithFlags(&T.side[k], hipStreamNonBlocking));
-    if (!T.ev_side[k]) SR_HIP(g, hipEventCreateWithFlags(&T.ev_side[k], hipEventDisableTiming));
-  }
+  SrTrainState::Events* ev = &T.plain;   // the events of this call's launches (a capture brings its own)
   // stream 0 is the graph's, 1 + k side stream k; fork: the side streams take up after what the graph's stream
   // holds so far; join: the graph's stream takes up after all of them
   auto stream_of = [&](int k) { return k == 0 ? s : T.side[k - 1]; };
   auto fork = [&]() -> sr_status {
-    SR_HIP(g, hipEventRecord(T.ev_main, s));
-    for (int k = 0; k < NS; ++k) SR_HIP(g, hipStreamWaitEvent(T.side[k], T.ev_main, 0));
+    SR_HIP(g, hipEventRecord(ev->main, s));
+    for (int k = 0; k < NS; ++k) SR_HIP(g, hipStreamWaitEvent(T.side[k], ev->main, 0));
     return SR_OK;
   };
   auto join = [&]() -> sr_status {
     for (int k = 0; k < NS; ++k) {
-      SR_HIP(g, hipEventRecord(T.ev_side[k], T.side[k]));
-      SR_HIP(g, hipStreamWaitEvent(s, T.ev_side[k], 0));
+      SR_HIP(g, hipEventRecord(ev->side[k], T.side[k]));
+      SR_HIP(g, hipStreamWaitEvent(s, ev->side[k], 0));
     }
     return SR_OK;
   };
@@ -331,10 +348,13 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   return SR_OK;
   };
 
-  // A window of the own forward pass is some hundreds of short dependent launches, none of which reads host
-  // memory: captured once into a graph and replayed while the call names the same buffers.  The frame path
-  // brings its own graphs and host-side frame counter and stays outside.
-  if (!own_forward || !g->use_hipgraph) return enqueue();
+  // A window of the own forward pass is some hundreds of short launches, none of which reads host memory:
+  // captured once into a graph and replayed while the call names the same buffers.  The frame path brings its
+  // own graphs and host-side frame counter and stays outside.
+  if (!own_forward || !g->use_hipgraph) {
+    if (make_events(g, ev) != SR_OK) return SR_ERR_DEVICE;
+    return enqueue();
+  }
   std::vector<const void*> key;
   key.push_back((const void*)(uintptr_t)W);
   key.push_back((const void*)(uintptr_t)out_node);
@@ -345,21 +365,28 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   key.push_back(loss);
   for (int e = 0; e < g->n_edges; ++e) key.push_back(dtheta[e]);
   for (int v = 0; v < N; ++v) key.push_back(dbias ? (const void*)dbias[v] : nullptr);
-  if (!T.exec || key != T.key) {
-    drop_train_graph(g);
-    SR_HIP(g, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
-    const sr_status st = enqueue();
-    const hipError_t e = hipStreamEndCapture(s, &T.graph);
-    if (st != SR_OK || e != hipSuccess) {
-      if (T.graph) hipGraphDestroy(T.graph);
-      T.graph = nullptr;
-      if (st != SR_OK) return st;
-      SR_HIP(g, e);
+  for (SrTrainState::Captured& c : T.captured)
+    if (c.live && c.exec && c.key == key) {
+      SR_HIP(g, hipGraphLaunch(c.exec, s));
+      return SR_OK;
     }
-    SR_HIP(g, hipGraphInstantiate(&T.exec, T.graph, nullptr, nullptr, 0));
-    T.key = key;
+  if (T.captured.size() >= SrTrainState::kMaxCaptured) {   // a caller that never passes the same buffers twice
+    if (make_events(g, ev) != SR_OK) return SR_ERR_DEVICE;
+    return enqueue();
   }
-  SR_HIP(g, hipGraphLaunch(T.exec, s));
+  T.captured.emplace_back();
+  SrTrainState::Captured& c = T.captured.back();
+  if (make_events(g, &c.ev) != SR_OK) return SR_ERR_DEVICE;
+  ev = &c.ev;
+  SR_HIP(g, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
+  const sr_status st = enqueue();
+  const hipError_t e = hipStreamEndCapture(s, &c.graph);
+  if (st != SR_OK) return st;   // the entry stays, not live
+  SR_HIP(g, e);
+  SR_HIP(g, hipGraphInstantiate(&c.exec, c.graph, nullptr, nullptr, 0));
+  c.key = key;
+  c.live = true;
+  SR_HIP(g, hipGraphLaunch(c.exec, s));
   return SR_OK;
 }
 
