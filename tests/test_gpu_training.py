@@ -379,29 +379,33 @@ def test_replayed_window_follows_new_contents_of_the_same_buffers(name):
     plain.close()
 
 
-def ragged_graph(batch=5):
+def ragged_graph(batch=5, channels=(24, 40, 136)):
     """Channel counts and pixel counts that are multiples of no tile edge: 24 channels (32-wide column tiles, ragged),
     40 (64-wide), 136 (128-wide plus a ragged second column tile), 19 x 19 images (ragged row tiles), a stride-2 edge
     (phase planes of unequal size), a self-recurrent edge and a dense read-out."""
     from workloads.graphs import Node, Edge, Graph, ACT_IDENTITY
-    nodes = [Node("in", 3, 19, 19, ACT_IDENTITY), Node("a", 24, 19, 19), Node("b", 40, 10, 10), Node("c", 136, 10, 10),
+    ca, cb, cc = channels
+    nodes = [Node("in", 3, 19, 19, ACT_IDENTITY), Node("a", ca, 19, 19), Node("b", cb, 10, 10), Node("c", cc, 10, 10),
              Node("out", 7, 1, 1, ACT_IDENTITY)]
     edges = [Edge(0, 1, "conv", 5, 5, 1, 2), Edge(1, 1, "conv", 3, 3, 1, 1), Edge(1, 2, "conv", 3, 3, 2, 1),
              Edge(2, 3, "conv", 3, 3, 1, 1), Edge(3, 2, "conv", 1, 1, 1, 0), Edge(3, 4, "dense", 10, 10, 1, 0)]
     return Graph("ragged", nodes, edges, batch, 3, "f32", out_node=4)
 
 
+@pytest.mark.parametrize("channels", [(24, 40, 136), (22, 42, 134)])
 @pytest.mark.parametrize("tall_from", [0, 2048, 1 << 30])
-def test_every_tile_shape_on_ragged_sizes(tall_from):
+def test_every_tile_shape_on_ragged_sizes(tall_from, channels):
     # SR_OPT_TRAIN_TALL_TILES_FROM (option 8): 0 sends every tiled contraction to the taller of its two tile shapes
-    # (128x128, 128x64, 256x32), 2^30 to the shorter (64x64, 128x32), the default chooses by the launch's size
+    # (128x128, 128x64, 256x32), 2^30 to the shorter (64x64, 128x32), the default chooses by the launch's size.
+    # Channel counts that are multiples of four take the kernel that gathers 16 bytes at a time, the others the
+    # one that gathers element by element.
     import paper_1806_04965_amd as sr
-    g0 = ragged_graph()
+    g0 = ragged_graph(channels=channels)
     g = g0.with_pattern(W.hybrid_pattern(g0))
     Wn = 3
     w, b, _ = W.make_case(g, seed=71, bias_scale=0.1, frames=Wn, recipe="uniform")
     dev = sr.SrGraph(g, options={8: tall_from})
     dev.set_parameters(w, b)
     got, data = run_case(g, Wn, seed=71, dev=dev)
-    check_against_oracle(g, Wn, got, data, f"ragged/hybrid tall_from={tall_from}")
+    check_against_oracle(g, Wn, got, data, f"ragged{channels}/hybrid tall_from={tall_from}")
     dev.close()
