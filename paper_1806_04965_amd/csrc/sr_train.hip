@@ -810,17 +810,20 @@ __global__ __launch_bounds__(256) void sr_fwd_pixel_kernel(SrConvGeom q, const f
     float acc[16];
 #pragma unroll
     for (int c = 0; c < 16; ++c) acc[c] = 0.f;
+    const int nc = min(16, q.Cout - c0);
+    // every load unconditional (a source element outside the image is read from a word that holds zero), so the
+    // unrolled loop has four terms' loads in flight at a time
+#pragma unroll 4
     for (int k = t; k < K; k += 256) {
       const int tap = sr_fdiv(k, q.mul_cin, q.sh_cin), ci = k - tap * q.Cin;
       const int ti = sr_fdiv(tap, q.mul_kw, q.sh_kw), tj = tap - ti * q.kw;
       const int hi = ho * q.stride + ti - q.pad, wi = wo * q.stride + tj - q.pad;
-      if ((unsigned)hi < (unsigned)q.H && (unsigned)wi < (unsigned)q.W) {
-        const float xv = x[(((size_t)b * q.H + hi) * q.W + wi) * q.Cin + ci];
-        const float* row = theta + (size_t)k * q.Cout + c0;
+      const bool ok = (unsigned)hi < (unsigned)q.H && (unsigned)wi < (unsigned)q.W;
+      const float* px = ok ? x + (((size_t)b * q.H + hi) * q.W + wi) * q.Cin + ci : &sr_zero_word;
+      const float xv = *px;
+      const float* row = theta + (size_t)k * q.Cout + c0;
 #pragma unroll
-        for (int c = 0; c < 16; ++c)
-          if (c0 + c < q.Cout) acc[c] += xv * row[c];
-      }
+      for (int c = 0; c < 16; ++c) acc[c] += xv * row[c < nc ? c : 0];   // channels past the last: not written out
     }
 #pragma unroll
     for (int c = 0; c < 16; ++c) {
