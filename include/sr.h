@@ -330,12 +330,8 @@ sr_status sr_graph_node_kernels(const sr_graph* g, int32_t* kinds);
  * the graph and reused by later calls.  Asynchronous: the results are complete in the order of the
  * graph's stream (inside the call three more streams of the library's own, of default priority, run
  * work that does not depend on each other; they are joined to the graph's stream before the call's
- * last kernel); the host arrays are consumed before the call returns.  With SR_OPT_USE_HIPGRAPH on
- * (the default) the call's launches are captured into a graph that later calls replay for as long as
- * they pass the same W, out_node and device pointers (the contents may change); a call that differs
- * captures anew (up to 16 captured windows are kept per graph, until sr_graph_destroy; calls with yet
- * other pointers are then launched plainly), so a training loop should keep its buffers.  No optimiser
- * step is taken.
+ * last kernel); the host arrays are consumed before the call returns.  Every kernel is launched by the
+ * call itself (SR_OPT_USE_HIPGRAPH concerns the frame path only).  No optimiser step is taken.
  * Errors: SR_ERR_ARG, SR_ERR_STATE (weights missing), SR_ERR_OOM, SR_ERR_DEVICE. */
 sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs, const float* const* masks,
                               const int32_t* labels, int32_t out_node, float* loss, float* const* dtheta,

@@ -291,8 +291,7 @@ class SrGraph:
     def window_gradients(self, inputs, labels, W: int, out_node: Optional[int] = None, masks=None, into=None):
         """inputs: one float tensor [W+1,B,H,W,C] per input node; labels: int32 tensor [B] on the device;
         masks: None or {node: float tensor [W+1,B,H,W,C]} of dropout multipliers; into: None, or the tuple an
-        earlier call returned, whose tensors are then written again (a loop that keeps all its buffers lets the
-        library replay the window's launches instead of issuing them one by one).
+        earlier call returned, whose tensors are then written again (no allocation per step).
         Returns (loss tensor [1], dtheta list, dbias list) as device tensors (dbias of input nodes: None)."""
         torch = self.torch
         g = self.g

@@ -27,20 +27,7 @@ struct SrTrainState {
     hipEvent_t main = nullptr, side[kSides] = {nullptr, nullptr, nullptr};
   };
   hipStream_t side[kSides] = {nullptr, nullptr, nullptr};
-  Events plain;   // of calls that launch every kernel themselves
-  // The launches of one window, captured: replayed while a call names the same window size, output node and
-  // buffers (key) and the arena has not moved (live).  A capture has events of its own, and nothing captured is
-  // destroyed before the graph object is: an event recorded during a capture stays tied to that capture.  After
-  // kMaxCaptured captures further new keys are launched plainly.
-  struct Captured {
-    std::vector<const void*> key;
-    hipGraph_t graph = nullptr;
-    hipGraphExec_t exec = nullptr;
-    Events ev;
-    bool live = false;
-  };
-  static constexpr size_t kMaxCaptured = 16;
-  std::vector<Captured> captured;
+  Events ev;
 };
 
 void sr_train_state_release(SrTrainState* t) {
@@ -50,12 +37,7 @@ void sr_train_state_release(SrTrainState* t) {
     for (int k = 0; k < SrTrainState::kSides; ++k)
       if (e.side[k]) hipEventDestroy(e.side[k]);
   };
-  for (SrTrainState::Captured& c : t->captured) {
-    if (c.exec) hipGraphExecDestroy(c.exec);
-    if (c.graph) hipGraphDestroy(c.graph);
-    drop_events(c.ev);
-  }
-  drop_events(t->plain);
+  drop_events(t->ev);
   for (int k = 0; k < SrTrainState::kSides; ++k)
     if (t->side[k]) { hipStreamSynchronize(t->side[k]); hipStreamDestroy(t->side[k]); }
   if (t->arena) hipFree(t->arena);
@@ -67,11 +49,6 @@ namespace {
 SrTrainState& train_state(sr_graph* g) {
   if (!g->train) g->train = new SrTrainState();
   return *g->train;
-}
-
-// the arena has moved: what was captured names the old one and is never launched again
-void retire_captured(sr_graph* g) {
-  for (SrTrainState::Captured& c : train_state(g).captured) c.live = false;
 }
 
 sr_status make_events(sr_graph* g, SrTrainState::Events* e) {
@@ -161,7 +138,6 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   const size_t terms_at = take((size_t)W * B);
   if (at > T.arena_floats) {
     SR_HIP(g, hipStreamSynchronize(g->stream));
-    retire_captured(g);
     if (T.arena) SR_HIP(g, hipFree(T.arena));
     T.arena = nullptr;
     T.arena_floats = 0;
@@ -174,23 +150,32 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   hipStream_t s = g->stream;
   for (int k = 0; k < NS; ++k)
     if (!T.side[k]) SR_HIP(g, hipStreamCreateWithFlags(&T.side[k], hipStreamNonBlocking));
-  SrTrainState::Events* ev = &T.plain;   // the events of this call's launches (a capture brings its own)
+  SrTrainState::Events* ev = &T.ev;
+  if (make_events(g, ev) != SR_OK) return SR_ERR_DEVICE;
   // stream 0 is the graph's, 1 + k side stream k; fork: the side streams take up after what the graph's stream
   // holds so far; join: the graph's stream takes up after all of them
   auto stream_of = [&](int k) { return k == 0 ? s : T.side[k - 1]; };
-  auto fork = [&]() -> sr_status {
+  // fork(lanes): the side streams in the bit set take up after what the graph's stream holds so far (bit 1 + k:
+  // side stream k); join(): the graph's stream takes up after every side stream forked since the last join
+  unsigned forked = 0;
+  auto fork = [&](unsigned lanes) -> sr_status {
+    lanes &= ~1u;
+    if (!lanes) return SR_OK;
     SR_HIP(g, hipEventRecord(ev->main, s));
-    for (int k = 0; k < NS; ++k) SR_HIP(g, hipStreamWaitEvent(T.side[k], ev->main, 0));
+    for (int k = 0; k < NS; ++k)
+      if (lanes & (2u << k)) SR_HIP(g, hipStreamWaitEvent(T.side[k], ev->main, 0));
+    forked |= lanes;
     return SR_OK;
   };
   auto join = [&]() -> sr_status {
-    for (int k = 0; k < NS; ++k) {
-      SR_HIP(g, hipEventRecord(ev->side[k], T.side[k]));
-      SR_HIP(g, hipStreamWaitEvent(s, ev->side[k], 0));
-    }
+    for (int k = 0; k < NS; ++k)
+      if (forked & (2u << k)) {
+        SR_HIP(g, hipEventRecord(ev->side[k], T.side[k]));
+        SR_HIP(g, hipStreamWaitEvent(s, ev->side[k], 0));
+      }
+    forked = 0;
     return SR_OK;
   };
-
   // forward over the window from the zero state, every frame's states written straight into the arena:
   // frames 1..W, inside a frame the update steps of the tableau in order (Eq. 5), per node the sum of its
   // edges' results (the first edge overwrites, the others add), then bias and activation in place
@@ -218,7 +203,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   };
   for (int v = 0; masks && v < N; ++v) own_forward |= (masks[v] != nullptr && !g->an.is_input[v]);
 
-  // every launch of the window, in stream order
+  // every launch of the window
   auto enqueue = [&]() -> sr_status {
   SR_HIP(g, sr_launch_fill_zero(s, A + x_base, frame_floats * sizeof(float)));   // frame 0
   if (!own_forward) {
@@ -241,11 +226,11 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
     for (size_t o = 0; o < order.size();) {
       size_t o_end = o;
       while (o_end < order.size() && g->an.level[order[o_end]] == g->an.level[order[o]]) ++o_end;
-      const bool forked = o_end - o > 1;
-      if (forked && fork() != SR_OK) return SR_ERR_DEVICE;
+      const bool wide = o_end - o > 1;
+      if (wide && fork((1u << std::min<size_t>(o_end - o, 1 + NS)) - 1u) != SR_OK) return SR_ERR_DEVICE;
       for (size_t k = o; k < o_end; ++k) {
         const int v = order[k];
-        const int lane = forked ? (int)((k - o) % (1 + NS)) : 0;
+        const int lane = wide ? (int)((k - o) % (1 + NS)) : 0;
         hipStream_t st = stream_of(lane);
         float* pooled = A + pooled_at[lane];
         float* mean = A + mean_at[lane];
@@ -271,7 +256,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
         }
         SR_HIP(g, sr_train_bias_act(st, dst, g->nodes[v].bias_dev, mask_of(v, i), d.channels, node_floats(v), d.act));
       }
-      if (forked && join() != SR_OK) return SR_ERR_DEVICE;
+      if (wide && join() != SR_OK) return SR_ERR_DEVICE;
       o = o_end;
     }
 
@@ -286,7 +271,7 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   for (int c = 0; c < 2; ++c) SR_HIP(g, sr_launch_fill_zero(s, A + dx_base[c], frame_floats * sizeof(float)));
   auto side_of_edge = [&](int ei) { return 1 + ei % NS; };
   auto side_of_node = [&](int v) { return 1 + v % NS; };
-  if (fork() != SR_OK) return SR_ERR_DEVICE;   // the forward pass is done with the scratch
+  if (fork(~0u) != SR_OK) return SR_ERR_DEVICE;   // the forward pass is done with the scratch
   for (int e = 0; e < g->n_edges; ++e)
     SR_HIP(g, sr_launch_fill_zero(stream_of(side_of_edge(e)), dtheta[e], g->edges[e].w_count * sizeof(float)));
   if (dbias)
@@ -304,7 +289,10 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
       float* da = A + dx_of(cur, v);
       SR_HIP(g, sr_train_act_grad(s, da, A + x_of(v, i), mask_of(v, i), node_floats(v), d.act));
       // da is final: its writers (readers of v in this frame and the next) came earlier in the sweep
-      if (fork() != SR_OK) return SR_ERR_DEVICE;
+      unsigned lanes = (dbias && dbias[v]) ? 1u << side_of_node(v) : 0u;
+      for (int ei = 0; ei < g->n_edges; ++ei)
+        if (g->edges[ei].d.dst == v) lanes |= 1u << side_of_edge(ei);
+      if (fork(lanes) != SR_OK) return SR_ERR_DEVICE;
       if (dbias && dbias[v])
         SR_HIP(g, sr_train_bias_grad(stream_of(side_of_node(v)), da, B * d.height * d.width, d.channels,
                                      A + part_at[side_of_node(v)], dbias[v]));
@@ -348,46 +336,9 @@ sr_status sr_window_gradients(sr_graph* g, int32_t W, const void* const* inputs,
   return SR_OK;
   };
 
-  // A window of the own forward pass is some hundreds of short launches, none of which reads host memory:
-  // captured once into a graph and replayed while the call names the same buffers.  The frame path brings its
-  // own graphs and host-side frame counter and stays outside.
-  if (!own_forward || !g->use_hipgraph) {
-    if (make_events(g, ev) != SR_OK) return SR_ERR_DEVICE;
-    return enqueue();
-  }
-  std::vector<const void*> key;
-  key.push_back((const void*)(uintptr_t)W);
-  key.push_back((const void*)(uintptr_t)out_node);
-  key.push_back(A);
-  for (size_t k = 0; k < g->inputs.size(); ++k) key.push_back(inputs[k]);
-  for (int v = 0; v < N; ++v) key.push_back(masks ? (const void*)masks[v] : nullptr);
-  key.push_back(labels);
-  key.push_back(loss);
-  for (int e = 0; e < g->n_edges; ++e) key.push_back(dtheta[e]);
-  for (int v = 0; v < N; ++v) key.push_back(dbias ? (const void*)dbias[v] : nullptr);
-  for (SrTrainState::Captured& c : T.captured)
-    if (c.live && c.exec && c.key == key) {
-      SR_HIP(g, hipGraphLaunch(c.exec, s));
-      return SR_OK;
-    }
-  if (T.captured.size() >= SrTrainState::kMaxCaptured) {   // a caller that never passes the same buffers twice
-    if (make_events(g, ev) != SR_OK) return SR_ERR_DEVICE;
-    return enqueue();
-  }
-  T.captured.emplace_back();
-  SrTrainState::Captured& c = T.captured.back();
-  if (make_events(g, &c.ev) != SR_OK) return SR_ERR_DEVICE;
-  ev = &c.ev;
-  SR_HIP(g, hipStreamBeginCapture(s, hipStreamCaptureModeThreadLocal));
-  const sr_status st = enqueue();
-  const hipError_t e = hipStreamEndCapture(s, &c.graph);
-  if (st != SR_OK) return st;   // the entry stays, not live
-  SR_HIP(g, e);
-  SR_HIP(g, hipGraphInstantiate(&c.exec, c.graph, nullptr, nullptr, 0));
-  c.key = key;
-  c.live = true;
-  SR_HIP(g, hipGraphLaunch(c.exec, s));
-  return SR_OK;
+  // Plain launches.  (Capturing a window's launches into a graph bought large windows nothing, the time being
+  // inside the kernels, and capture across the four streams ended in segmentation faults inside the runtime.)
+  return enqueue();
 }
 
 sr_status sr_rmsprop_step(sr_graph* g, float lr, float rho, float eps, const float* const* dtheta,

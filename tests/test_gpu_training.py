@@ -332,12 +332,12 @@ def test_window_gradients_with_dropout_masks(name):
 
 
 @pytest.mark.parametrize("name", ["mid_sr", "mnist_sr_b128"])
-def test_replayed_window_follows_new_contents_of_the_same_buffers(name):
-    # A loop that keeps its buffers has the window's launches captured once and replayed.  Three calls into the
-    # same tensors, with new inputs and labels written into them in between (and unrelated torch work and
-    # synchronisations between the replays), then one call with other buffers (a new capture): each must equal
-    # what a graph object that launches every kernel plainly gives for the same data, bit for bit, and the
-    # oracle within the tolerance.
+def test_windows_into_the_same_buffers_follow_their_new_contents(name):
+    # A training loop keeps its buffers.  Three calls into the same tensors, with new inputs and labels written
+    # into them in between (and unrelated torch work and synchronisations between the calls), then one call with
+    # other buffers: each must equal, bit for bit, what a second graph object gives for the same data in fresh
+    # tensors (the launches of a window run on four streams: their sums must not depend on how those interleave),
+    # and the oracle within the tolerance.
     import torch
     import paper_1806_04965_amd as sr
     mk, Wn = cases()[name]
@@ -345,7 +345,7 @@ def test_replayed_window_follows_new_contents_of_the_same_buffers(name):
     g = g0.with_pattern(W.hybrid_pattern(g0))
     w, b, _ = W.make_case(g, seed=61, bias_scale=0.1, frames=Wn, recipe="uniform")
     dev = sr.SrGraph(g)
-    plain = sr.SrGraph(g, options={0: 0})   # SR_OPT_USE_HIPGRAPH off: every kernel launched plainly
+    plain = sr.SrGraph(g)
     for d in (dev, plain):
         d.set_parameters(w, b)
     ins = g.input_nodes()
@@ -355,7 +355,7 @@ def test_replayed_window_follows_new_contents_of_the_same_buffers(name):
         _, _, x = W.make_case(g, seed=seed, bias_scale=0.1, frames=Wn, recipe="uniform")
         labels = np.random.default_rng(seed + 100).integers(0, classes, g.batch).astype(np.int32)
         fresh = [to_device(x[v][:Wn + 1], "f32") for v in ins]
-        if call in (0, 3):           # new buffers: first capture, and a capture that replaces it
+        if call in (0, 3):           # new buffers
             xd, labels_d, res = fresh, torch.from_numpy(labels).to("cuda"), None
         else:                        # same buffers, new contents
             for t, f in zip(xd, fresh):
@@ -364,17 +364,17 @@ def test_replayed_window_follows_new_contents_of_the_same_buffers(name):
         torch.cuda.synchronize()
         res = dev.window_gradients(xd, labels_d, Wn, into=res)
         dev.synchronize()
-        filler = torch.randn(1 << 20, device="cuda").sum().item()   # the program's own work between replays
+        filler = torch.randn(1 << 20, device="cuda").sum().item()   # the program's own work between the calls
         assert np.isfinite(filler)
         want = plain.window_gradients(fresh, torch.from_numpy(labels).to("cuda"), Wn)
         plain.synchronize()
         assert float(res[0].cpu()[0]) == float(want[0].cpu()[0]), f"call {call}: loss"
         for a, c in zip(res[1] + [t for t in res[2] if t is not None], want[1] + [t for t in want[2] if t is not None]):
-            assert torch.equal(a, c), f"call {call}: a replayed gradient differs from the plainly launched one"
+            assert torch.equal(a, c), f"call {call}: the two graph objects' gradients differ"
         if call in (1, 3):
             got = (float(res[0].cpu()[0]), [t.cpu().numpy() for t in res[1]],
                    [None if t is None else t.cpu().numpy() for t in res[2]])
-            check_against_oracle(g, Wn, got, (w, b, x, labels), f"{name} replay call {call}")
+            check_against_oracle(g, Wn, got, (w, b, x, labels), f"{name} same buffers, call {call}")
     dev.close()
     plain.close()
 
