@@ -248,6 +248,50 @@ __device__ __forceinline__ void sr_fdiv_make(uint32_t d, uint32_t* mul, uint32_t
 #define SR_GT 128   // edge of the largest tile
 #define SR_GR 16    // reduction step
 
+// State gradient of a stride-s edge: grid plane z is the phase (ph, pw) of the source pixels.  A stride-s edge
+// pairs a pixel only with the taps of its own residues, so each phase is a contraction of its own (without the
+// split all but 1/s^2 of the products would be zeros).  Fills the phase's fields of q and returns its row count
+// I and reduction length R (the launch is sized for phase (0, 0), the largest).
+__device__ __forceinline__ void sr_phase_of_plane(SrConvGeom& q, int z, int* I, int* R) {
+  q.ph = z / q.stride;
+  q.pw = z % q.stride;
+  q.Hp = (q.H - q.ph + q.stride - 1) / q.stride;
+  q.Wp = (q.W - q.pw + q.stride - 1) / q.stride;
+  q.ti0 = (q.ph + q.pad) % q.stride;
+  q.tj0 = (q.pw + q.pad) % q.stride;
+  q.nti = q.ti0 < q.kh ? (q.kh - q.ti0 + q.stride - 1) / q.stride : 0;
+  q.ntj = q.tj0 < q.kw ? (q.kw - q.tj0 + q.stride - 1) / q.stride : 0;
+  *I = q.B * max(q.Hp, 0) * max(q.Wp, 0);
+  *R = q.nti * q.ntj * q.Cout;
+}
+
+// A wave's accumulators into C (row-major, J columns; MODE 0: a row of the phase grid goes to its source pixel).
+// Register v of lane l holds row 8 * (v / 4) + 4 * (l / 32) + v % 4 of an MFMA tile's 32, column l % 32.
+template <int MODE, int MI, int MJ>
+__device__ __forceinline__ void sr_store_tile(const sr_f32x16 (&acc)[MI][MJ], const SrConvGeom& q, float* out, int i_wave,
+                                              int j_wave, int lane, int I, int J, uint32_t mul_wp, uint32_t sh_wp,
+                                              uint32_t mul_hpwp, uint32_t sh_hpwp, int accumulate) {
+#pragma unroll
+  for (int x = 0; x < MI; ++x)
+#pragma unroll
+    for (int y = 0; y < MJ; ++y)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int i = i_wave + x * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
+        const int j = j_wave + y * 32 + (lane & 31);
+        if (i < I && j < J) {
+          size_t row = (size_t)i;
+          if (MODE == 0) {
+            const int b = sr_fdiv(i, mul_hpwp, sh_hpwp), rem = i - b * (q.Wp * q.Hp);
+            const int hh = sr_fdiv(rem, mul_wp, sh_wp), ww = rem - hh * q.Wp;
+            row = ((size_t)b * q.H + hh * q.stride + q.ph) * q.W + ww * q.stride + q.pw;
+          }
+          float* dst = out + row * J + j;
+          *dst = accumulate ? *dst + acc[x][y][v] : acc[x][y][v];
+        }
+      }
+}
+
 template <int MODE, int TI, int TJ, int WJN>
 __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, const float* __restrict__ pa,
                                                               const float* __restrict__ pb, float* __restrict__ pc,
@@ -261,19 +305,7 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int i0 = blockIdx.x * TI, j0 = blockIdx.y * TJ;
   if (MODE == 0) {
-    // blockIdx.z = phase (ph, pw) of the source pixels: a stride-s edge pairs a pixel only with the taps of its
-    // own residues, so each phase is a contraction of its own (without the split all but 1/s^2 of the products
-    // would be zeros).  I, R: the caller passes those of phase (0, 0), the largest.
-    q.ph = blockIdx.z / q.stride;
-    q.pw = blockIdx.z % q.stride;
-    q.Hp = (q.H - q.ph + q.stride - 1) / q.stride;
-    q.Wp = (q.W - q.pw + q.stride - 1) / q.stride;
-    q.ti0 = (q.ph + q.pad) % q.stride;
-    q.tj0 = (q.pw + q.pad) % q.stride;
-    q.nti = q.ti0 < q.kh ? (q.kh - q.ti0 + q.stride - 1) / q.stride : 0;
-    q.ntj = q.tj0 < q.kw ? (q.kw - q.tj0 + q.stride - 1) / q.stride : 0;
-    I = q.B * max(q.Hp, 0) * max(q.Wp, 0);
-    R = q.nti * q.ntj * q.Cout;
+    sr_phase_of_plane(q, blockIdx.z, &I, &R);
     r_per_slice = R;
     if (i0 >= I || (R == 0 && accumulate)) return;   // the whole workgroup: this phase has fewer pixels, or no tap reaches it
   }
@@ -467,27 +499,9 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, cons
     step(rs + SR_GR, va1, vb1);
   }
   if (rs < r_end) step(rs, va0, vb0);
-  // register v of lane l holds row 8 * (v / 4) + 4 * (l / 32) + v % 4 (of the A operand's 32), column l % 32
   float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
-#pragma unroll
-  for (int x = 0; x < MI; ++x)
-#pragma unroll
-    for (int y = 0; y < MJ; ++y)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = i0 + wi * 32 * MI + x * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int j = j0 + wj * 32 * MJ + y * 32 + (lane & 31);
-        if (i < I && j < J) {
-          size_t row = (size_t)i;
-          if (MODE == 0) {   // row of the phase grid -> source pixel
-            const int b = sr_fdiv(i, mul_hpwp, sh_hpwp), rem = i - b * (q.Wp * q.Hp);
-            const int hh = sr_fdiv(rem, mul_wp, sh_wp), ww = rem - hh * q.Wp;
-            row = ((size_t)b * q.H + hh * q.stride + q.ph) * q.W + ww * q.stride + q.pw;
-          }
-          float* dst = out + row * J + j;
-          *dst = accumulate ? *dst + acc[x][y][v] : acc[x][y][v];
-        }
-      }
+  sr_store_tile<MODE, MI, MJ>(acc, q, out, i0 + wi * 32 * MI, j0 + wj * 32 * MJ, lane, I, J, mul_wp, sh_wp, mul_hpwp,
+                              sh_hpwp, accumulate);
 }
 
 // The same contraction for channel counts that are multiples of four: every operand is gathered 16 bytes at a
@@ -514,19 +528,10 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm4_kernel(SrConvGeom q, con
   __shared__ __align__(16) float Bs[B_ROWS ? TJ * RP : SR_GR * (TJ + 4)];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
   const int i0 = blockIdx.x * TI, j0 = blockIdx.y * TJ;
-  if (MODE == 0) {   // blockIdx.z = phase of the source pixels, as in sr_conv_gemm_kernel
-    q.ph = blockIdx.z / q.stride;
-    q.pw = blockIdx.z % q.stride;
-    q.Hp = (q.H - q.ph + q.stride - 1) / q.stride;
-    q.Wp = (q.W - q.pw + q.stride - 1) / q.stride;
-    q.ti0 = (q.ph + q.pad) % q.stride;
-    q.tj0 = (q.pw + q.pad) % q.stride;
-    q.nti = q.ti0 < q.kh ? (q.kh - q.ti0 + q.stride - 1) / q.stride : 0;
-    q.ntj = q.tj0 < q.kw ? (q.kw - q.tj0 + q.stride - 1) / q.stride : 0;
-    I = q.B * max(q.Hp, 0) * max(q.Wp, 0);
-    R = q.nti * q.ntj * q.Cout;
+  if (MODE == 0) {
+    sr_phase_of_plane(q, blockIdx.z, &I, &R);
     r_per_slice = R;
-    if (i0 >= I || (R == 0 && accumulate)) return;
+    if (i0 >= I || (R == 0 && accumulate)) return;   // the whole workgroup: this phase has fewer pixels, or no tap reaches it
   }
   const int r_begin = (MODE == 1) ? blockIdx.z * r_per_slice : 0;
   const int r_end = min(R, r_begin + r_per_slice);
@@ -722,25 +727,8 @@ __global__ __launch_bounds__(256, 2) void sr_conv_gemm4_kernel(SrConvGeom q, con
   }
   if (rs < r_end) step(rs, va0, vb0);
   float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
-#pragma unroll
-  for (int x = 0; x < MI; ++x)
-#pragma unroll
-    for (int y = 0; y < MJ; ++y)
-#pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int i = i0 + wi * 32 * MI + x * 32 + 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3);
-        const int j = j0 + wj * 32 * MJ + y * 32 + (lane & 31);
-        if (i < I && j < J) {
-          size_t row = (size_t)i;
-          if (MODE == 0) {
-            const int b = sr_fdiv(i, mul_hpwp, sh_hpwp), rem = i - b * (q.Wp * q.Hp);
-            const int hh = sr_fdiv(rem, mul_wp, sh_wp), ww = rem - hh * q.Wp;
-            row = ((size_t)b * q.H + hh * q.stride + q.ph) * q.W + ww * q.stride + q.pw;
-          }
-          float* dst = out + row * J + j;
-          *dst = accumulate ? *dst + acc[x][y][v] : acc[x][y][v];
-        }
-      }
+  sr_store_tile<MODE, MI, MJ>(acc, q, out, i0 + wi * 32 * MI, j0 + wj * 32 * MJ, lane, I, J, mul_wp, sh_wp, mul_hpwp,
+                              sh_hpwp, accumulate);
 }
 
 // forward of one edge, one thread per output element: y[b][ho][wo][co] (+)= sum x * theta
