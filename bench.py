@@ -72,9 +72,9 @@ PEAK_FP32_VALU_TFLOPS = 157.3  # fp32 vector peak (the fp32 graph runs on plain 
 def train_window_bench(args, g):
     """One step = one training window (Sec. 3 rollout window of size W; loss of App. A2): forward over
     W frames, loss, gradients of every weight and bias, through sr_window_gradients on the fp32 graph.
-    The roofline is the fp32 vector one; the algorithmic work of a window is taken as 3 x the forward
-    FLOP of its W frames (forward, state gradients, weight gradients: the state gradients of edges that
-    leave an input are not needed and not computed, so this over-counts slightly)."""
+    The roofline is the fp32 vector one; the algorithmic work of a window is, per edge and frame, the
+    forward contraction, the weight gradient and, where one is kept (not into an input node, not into
+    frame 0), the state gradient."""
     import dataclasses
     import numpy as np
     import torch
@@ -110,7 +110,20 @@ def train_window_bench(args, g):
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
     ms_per_step = dt / args.steps * 1e3
-    flop = 3.0 * work["flops_per_frame"] * Wn
+    # algorithmic work of the window: per edge and frame the forward contraction and the weight gradient, and the
+    # state gradient where one is kept (not into input nodes, not into frame 0)
+    inputs_set = set(ins)
+    flop = 0.0
+    for e in g.edges:
+        sn, dn = g.nodes[e.src], g.nodes[e.dst]
+        if e.kind == "conv":
+            macs = B * (dn.height // e.up) * (dn.width // e.up) * dn.channels * sn.channels * e.kh * e.kw
+        elif e.kind == "dense":
+            macs = B * dn.channels * sn.channels * sn.height * sn.width
+        else:
+            macs = B * dn.channels * sn.channels
+        for i in range(1, Wn + 1):
+            flop += 2.0 * macs * (2 + (1 if e.src not in inputs_set and i - int(e.bridge) >= 1 else 0))
     achieved = flop / (ev0.elapsed_time(ev1) / args.steps * 1e-3) / 1e12
     cpu = None
     if not args.no_cpu_baseline:

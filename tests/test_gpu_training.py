@@ -409,3 +409,15 @@ def test_every_tile_shape_on_ragged_sizes(tall_from, channels):
     got, data = run_case(g, Wn, seed=71, dev=dev)
     check_against_oracle(g, Wn, got, data, f"ragged{channels}/hybrid tall_from={tall_from}")
     dev.close()
+
+
+@pytest.mark.timeout(600)
+def test_gtsrb_shaped_window_at_full_width():
+    # The GTSRB-shaped benchmark graph as an fp32 graph with its real image sizes and channel counts (64 @ 48x48 ...
+    # 256 @ 6x6, 32 edges: skips, self-recurrence, the 1x1 up-sampled feedback edge, GAP + dense head), hybrid
+    # pattern, W = 3, at a batch of 8 so that the float64 oracle takes seconds: contractions of up to 2304 terms
+    # and 18432 rows, where the partial sums of the weight gradients are many and long.
+    g0 = replace(W.gtsrb_sr(batch=8, frames=3), dtype="f32")
+    g = g0.with_pattern(W.hybrid_pattern(g0))
+    got, data = run_case(g, 3, seed=5)
+    check_against_oracle(g, 3, got, data, "gtsrb_sr B=8/hybrid")
