@@ -178,7 +178,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards by batch or by node partition, see DESIGN.md)", file=sys.stderr)
+              "(the path would shard by batch or by node partition)", file=sys.stderr)
         sys.exit(2)
 
     import numpy as np
