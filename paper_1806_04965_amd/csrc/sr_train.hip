@@ -1,11 +1,9 @@
-// Kernels of one training window (Sec. 3: rollout window of size W; App. A2: loss) for fp32 graphs: forward
-// pass and reverse sweep.  Contractions with enough work run as tiles on the fp32 matrix cores, the rest as
-// plain gathers (one thread owns one output element).  Every sum is taken in a fixed order, so gradients are
-// reproducible from run to run; sums that are cut across workgroups go through partial results that a second
-// kernel adds in a fixed order.  States and gradients are dense NHWC floats.
+// Kernels of one training window (Sec. 3: rollout window of size W; App. A2: loss): the reverse sweep
+// over the window for fp32 graphs.  Every kernel is a plain gather: one thread owns one output element
+// and adds its terms in a fixed order, so gradients are reproducible from run to run; sums that are cut
+// across workgroups go through partial results that a second kernel adds in index order.
+// States and gradients are dense NHWC floats.
 #include <hip/hip_runtime.h>
-
-#include <vector>
 #include <stdint.h>
 
 #include <algorithm>
@@ -295,9 +293,9 @@ __device__ __forceinline__ void sr_store_tile(const sr_f32x16 (&acc)[MI][MJ], co
 }
 
 template <int MODE, int TI, int TJ, int WJN>
-__device__ __forceinline__ void sr_conv_gemm_body(SrConvGeom q, const float* __restrict__ pa, const float* __restrict__ pb,
-                                                  float* __restrict__ pc, int I, int J, int R, int r_per_slice,
-                                                  int accumulate, int bx, int by, int bz) {
+__global__ __launch_bounds__(256, 2) void sr_conv_gemm_kernel(SrConvGeom q, const float* __restrict__ pa,
+                                                              const float* __restrict__ pb, float* __restrict__ pc,
+                                                              int I, int J, int R, int r_per_slice, int accumulate) {
   constexpr int WIN = 4 / WJN;                                // waves along i
   constexpr int MI = TI / (32 * WIN), MJ = TJ / (32 * WJN);   // MFMA tiles of a wave
   constexpr int NA = TI / 16, NB = TJ / 16;                   // operand elements a thread gathers per step
@@ -305,13 +303,13 @@ __device__ __forceinline__ void sr_conv_gemm_body(SrConvGeom q, const float* __r
   __shared__ float As[SR_GR][TI + 4];
   __shared__ float Bs[SR_GR][TJ + 4];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int i0 = bx * TI, j0 = by * TJ;
+  const int i0 = blockIdx.x * TI, j0 = blockIdx.y * TJ;
   if (MODE == 0) {
-    sr_phase_of_plane(q, bz, &I, &R);
+    sr_phase_of_plane(q, blockIdx.z, &I, &R);
     r_per_slice = R;
     if (i0 >= I || (R == 0 && accumulate)) return;   // the whole workgroup: this phase has fewer pixels, or no tap reaches it
   }
-  const int r_begin = (MODE == 1) ? bz * r_per_slice : 0;
+  const int r_begin = (MODE == 1) ? blockIdx.z * r_per_slice : 0;
   const int r_end = min(R, r_begin + r_per_slice);
   const int wi = wave / WJN, wj = wave % WJN;
 
@@ -501,7 +499,7 @@ __device__ __forceinline__ void sr_conv_gemm_body(SrConvGeom q, const float* __r
     step(rs + SR_GR, va1, vb1);
   }
   if (rs < r_end) step(rs, va0, vb0);
-  float* out = pc + ((MODE == 1) ? (size_t)bz * I * J : (size_t)0);
+  float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
   sr_store_tile<MODE, MI, MJ>(acc, q, out, i0 + wi * 32 * MI, j0 + wj * 32 * MJ, lane, I, J, mul_wp, sh_wp, mul_hpwp,
                               sh_hpwp, accumulate);
 }
@@ -516,9 +514,9 @@ typedef float sr_f32x4 __attribute__((ext_vector_type(4)));
 __device__ __align__(16) const float sr_zero_quad[4] = {0.f, 0.f, 0.f, 0.f};
 
 template <int MODE, int TI, int TJ, int WJN>
-__device__ __forceinline__ void sr_conv_gemm4_body(SrConvGeom q, const float* __restrict__ pa, const float* __restrict__ pb,
-                                                   float* __restrict__ pc, int I, int J, int R, int r_per_slice,
-                                                   int accumulate, int bx, int by, int bz) {
+__global__ __launch_bounds__(256, 2) void sr_conv_gemm4_kernel(SrConvGeom q, const float* __restrict__ pa,
+                                                               const float* __restrict__ pb, float* __restrict__ pc,
+                                                               int I, int J, int R, int r_per_slice, int accumulate) {
   constexpr int WIN = 4 / WJN;
   constexpr int MI = TI / (32 * WIN), MJ = TJ / (32 * WJN);
   constexpr int NAV = TI / 64;                    // 16-byte pieces of A a thread gathers per step
@@ -529,13 +527,13 @@ __device__ __forceinline__ void sr_conv_gemm4_body(SrConvGeom q, const float* __
   __shared__ __align__(16) float As[A_ROWS ? TI * RP : SR_GR * (TI + 4)];
   __shared__ __align__(16) float Bs[B_ROWS ? TJ * RP : SR_GR * (TJ + 4)];
   const int t = threadIdx.x, lane = t & 63, wave = t >> 6;
-  const int i0 = bx * TI, j0 = by * TJ;
+  const int i0 = blockIdx.x * TI, j0 = blockIdx.y * TJ;
   if (MODE == 0) {
-    sr_phase_of_plane(q, bz, &I, &R);
+    sr_phase_of_plane(q, blockIdx.z, &I, &R);
     r_per_slice = R;
     if (i0 >= I || (R == 0 && accumulate)) return;   // the whole workgroup: this phase has fewer pixels, or no tap reaches it
   }
-  const int r_begin = (MODE == 1) ? bz * r_per_slice : 0;
+  const int r_begin = (MODE == 1) ? blockIdx.z * r_per_slice : 0;
   const int r_end = min(R, r_begin + r_per_slice);
   const int wi = wave / WJN, wj = wave % WJN;
 
@@ -728,40 +726,9 @@ __device__ __forceinline__ void sr_conv_gemm4_body(SrConvGeom q, const float* __
     step(rs + SR_GR, va1, vb1);
   }
   if (rs < r_end) step(rs, va0, vb0);
-  float* out = pc + ((MODE == 1) ? (size_t)bz * I * J : (size_t)0);
+  float* out = pc + ((MODE == 1) ? (size_t)blockIdx.z * I * J : (size_t)0);
   sr_store_tile<MODE, MI, MJ>(acc, q, out, i0 + wi * 32 * MI, j0 + wj * 32 * MJ, lane, I, J, mul_wp, sh_wp, mul_hpwp,
                               sh_hpwp, accumulate);
-}
-
-// One launch takes up to SR_BATCH_MAX contractions of one kind and tile shape that do not depend on each other
-// (different nodes of one update step, different edges): workgroup w belongs to problem k with
-// first_wg[k] <= w < first_wg[k + 1] and is tile (x, y, z) of that problem's own grid, x fastest.
-struct SrProblem {
-  SrConvGeom q;
-  const float* pa;
-  const float* pb;
-  float* pc;
-  int I, J, R, r_per_slice, accumulate, tiles_x, tiles_y;
-};
-#define SR_BATCH_MAX 12
-struct SrBatch {
-  int n;
-  int first_wg[SR_BATCH_MAX + 1];
-  SrProblem p[SR_BATCH_MAX];
-};
-
-template <int MODE, int TI, int TJ, int WJN, int QUADS>
-__global__ __launch_bounds__(256, 2) void sr_conv_gemm_batch_kernel(SrBatch batch) {
-  int k = 0;
-  while (k + 1 < batch.n && (int)blockIdx.x >= batch.first_wg[k + 1]) ++k;
-  const SrProblem& p = batch.p[k];
-  const int local = (int)blockIdx.x - batch.first_wg[k];
-  const int bx = local % p.tiles_x, rest = local / p.tiles_x;
-  const int by = rest % p.tiles_y, bz = rest / p.tiles_y;
-  if (QUADS)
-    sr_conv_gemm4_body<MODE, TI, TJ, WJN>(p.q, p.pa, p.pb, p.pc, p.I, p.J, p.R, p.r_per_slice, p.accumulate, bx, by, bz);
-  else
-    sr_conv_gemm_body<MODE, TI, TJ, WJN>(p.q, p.pa, p.pb, p.pc, p.I, p.J, p.R, p.r_per_slice, p.accumulate, bx, by, bz);
 }
 
 // forward of one edge, one thread per output element: y[b][ho][wo][co] (+)= sum x * theta
@@ -978,69 +945,28 @@ static SrTileShape sr_pick_tile(long long I, long long J, long long planes, int 
   const long long first = (I + c[0].ti - 1) / c[0].ti * ((J + c[0].tj - 1) / c[0].tj) * planes;
   return first >= tall_from ? c[0] : c[1];
 }
-// one contraction ready to launch: its tile shape, whether all its channel counts are multiples of four, its grid
-struct SrGemmJob {
-  SrTileShape ts;
-  bool quads;
-  int planes;
-  SrProblem p;
-};
-static SrGemmJob sr_make_job(SrTileShape ts, int planes, const SrConvGeom& q, const float* pa, const float* pb, float* pc,
-                             int I, int J, int R, int per, int accumulate) {
-  SrGemmJob j;
-  j.ts = ts;
-  j.quads = q.Cin % 4 == 0 && q.Cout % 4 == 0;   // every channel axis in 16-byte pieces
-  j.planes = planes;
-  j.p = SrProblem{q, pa, pb, pc, I, J, R, per, accumulate, (I + ts.ti - 1) / ts.ti, (J + ts.tj - 1) / ts.tj};
-  return j;
-}
-// launches n jobs that do not depend on each other: those of one tile shape and kernel share launches
-template <int MODE>
-static hipError_t sr_launch_gemm_jobs(hipStream_t s, const SrGemmJob* jobs, int n) {
-  std::vector<char> done(n, 0);
-  for (int first = 0; first < n; ++first) {
-    if (done[first]) continue;
-    const SrGemmJob& lead = jobs[first];
-    SrBatch batch;
-    batch.n = 0;
-    int wgs = 0;
-    for (int k = first; k < n && batch.n < SR_BATCH_MAX; ++k) {
-      const SrGemmJob& j = jobs[k];
-      if (done[k] || j.quads != lead.quads || j.ts.ti != lead.ts.ti || j.ts.tj != lead.ts.tj || j.ts.wjn != lead.ts.wjn)
-        continue;
-      batch.first_wg[batch.n] = wgs;
-      batch.p[batch.n] = j.p;
-      wgs += j.p.tiles_x * j.p.tiles_y * j.planes;
-      ++batch.n;
-      done[k] = 1;
-    }
-    batch.first_wg[batch.n] = wgs;
-    bool launched = false;
-#define SR_GEMM_CASE(TI, TJ, WJN)                                                                              \
-  if (!launched && lead.ts.ti == TI && lead.ts.tj == TJ && lead.ts.wjn == WJN) {                               \
-    if (lead.quads)                                                                                            \
-      hipLaunchKernelGGL((sr_conv_gemm_batch_kernel<MODE, TI, TJ, WJN, 1>), dim3(wgs), dim3(256), 0, s, batch); \
-    else                                                                                                       \
-      hipLaunchKernelGGL((sr_conv_gemm_batch_kernel<MODE, TI, TJ, WJN, 0>), dim3(wgs), dim3(256), 0, s, batch); \
-    launched = true;                                                                                           \
-  }
-    SR_GEMM_CASE(128, 128, 2)
-    SR_GEMM_CASE(128, 64, 2)
-    SR_GEMM_CASE(64, 64, 2)
-    SR_GEMM_CASE(256, 32, 1)
-    SR_GEMM_CASE(128, 32, 1)
-#undef SR_GEMM_CASE
-    if (!launched) return hipErrorInvalidValue;
-    const hipError_t e = hipGetLastError();
-    if (e != hipSuccess) return e;
-  }
-  return hipSuccess;
-}
 template <int MODE>
 static hipError_t sr_launch_gemm(hipStream_t s, SrTileShape ts, int planes, const SrConvGeom& q, const float* pa,
                                  const float* pb, float* pc, int I, int J, int R, int per, int accumulate) {
-  const SrGemmJob job = sr_make_job(ts, planes, q, pa, pb, pc, I, J, R, per, accumulate);
-  return sr_launch_gemm_jobs<MODE>(s, &job, 1);
+  const dim3 grid((I + ts.ti - 1) / ts.ti, (J + ts.tj - 1) / ts.tj, planes);
+  const bool quads = q.Cin % 4 == 0 && q.Cout % 4 == 0;   // every channel axis in 16-byte pieces
+#define SR_GEMM_CASE(TI, TJ, WJN)                                                                                    \
+  if (ts.ti == TI && ts.tj == TJ && ts.wjn == WJN) {                                                                 \
+    if (quads)                                                                                                       \
+      hipLaunchKernelGGL((sr_conv_gemm4_kernel<MODE, TI, TJ, WJN>), grid, dim3(256), 0, s, q, pa, pb, pc, I, J, R,   \
+                         per, accumulate);                                                                           \
+    else                                                                                                             \
+      hipLaunchKernelGGL((sr_conv_gemm_kernel<MODE, TI, TJ, WJN>), grid, dim3(256), 0, s, q, pa, pb, pc, I, J, R,    \
+                         per, accumulate);                                                                           \
+    return hipGetLastError();                                                                                        \
+  }
+  SR_GEMM_CASE(128, 128, 2)
+  SR_GEMM_CASE(128, 64, 2)
+  SR_GEMM_CASE(64, 64, 2)
+  SR_GEMM_CASE(256, 32, 1)
+  SR_GEMM_CASE(128, 32, 1)
+#undef SR_GEMM_CASE
+  return hipErrorInvalidValue;
 }
 
 // Which contractions go to the tiled matrix-core kernel: those with enough multiply-adds whose 128 x 128 tiles are
