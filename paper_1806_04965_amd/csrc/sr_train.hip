@@ -1,8 +1,8 @@
-// Kernels of one training window (Sec. 3: rollout window of size W; App. A2: loss): the reverse sweep
-// over the window for fp32 graphs.  Every kernel is a plain gather: one thread owns one output element
-// and adds its terms in a fixed order, so gradients are reproducible from run to run; sums that are cut
-// across workgroups go through partial results that a second kernel adds in index order.
-// States and gradients are dense NHWC floats.
+// Kernels of one training window (Sec. 3: rollout window of size W; App. A2: loss) for fp32 graphs: forward
+// pass and reverse sweep.  Contractions with enough work run as tiles on the fp32 matrix cores, the rest as
+// plain gathers (one thread owns one output element).  Every sum is taken in a fixed order, so gradients are
+// reproducible from run to run; sums that are cut across workgroups go through partial results that a second
+// kernel adds in a fixed order.  States and gradients are dense NHWC floats.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
